@@ -1,0 +1,17 @@
+"""Seeded synthetic inputs for the compact CNN cascade hot path.
+
+This package only *draws inputs*: frames, network weights and the description
+of the three network shapes.  It contains none of the detector's arithmetic
+(no pyramid, no convolution, no thresholding) and is the only code that both
+the CPU oracle's tests and the HIP library's tests import.
+"""
+from .cascade import (ACT_NONE, ACT_RATIONAL, ACT_SCALED_TANH, ACT_TANH, CONV,
+                      FC, POOL, Layer, Stage, default_cascade, draw_weights,
+                      uniform_weights)
+from .frames import CONFIGS, config_seed, make_frame, make_stream
+
+__all__ = [
+    "ACT_NONE", "ACT_RATIONAL", "ACT_SCALED_TANH", "ACT_TANH", "CONV", "FC",
+    "POOL", "Layer", "Stage", "default_cascade", "draw_weights",
+    "uniform_weights", "CONFIGS", "config_seed", "make_frame", "make_stream",
+]

@@ -1,0 +1,132 @@
+"""Shapes of the three cascade networks and seeded weight blobs for them.
+
+The three-stage cascade follows Section 3 of the paper (three CNNs of growing
+size, convolution stride 1, pooling stride 2, the activation of eq. (1) after
+every hidden layer).  The paper's own layer shapes were printed only in its
+Figure 1; the shapes used here are the benchmark's default cascade:
+
+  stage 1: 12x12 -> conv3x3 1->4 -> pool2 -> conv3x3 4->8 -> fc 72->1
+  stage 2: 24x24 -> conv5x5 1->8 -> pool2 -> conv3x3 8->16 -> pool2
+           -> fc 256->32 -> fc 32->1
+  stage 3: 48x48 -> conv5x5 1->16 -> pool2 -> conv5x5 16->32 -> pool2
+           -> conv3x3 32->32 -> fc 1568->64 -> fc 64->1
+
+A fully connected layer is described like a convolution whose kernel covers
+its whole input map (feature order [channel][row][col]), so one record type
+serves all layers.
+
+Weight blob layout (float32, one blob per stage): for every conv / fc layer in
+order, weights [cout][cin][k][k] in C order followed by bias[cout].
+"""
+from dataclasses import dataclass
+from typing import List, Sequence
+
+import numpy as np
+
+CONV, POOL, FC = 0, 1, 2
+ACT_NONE, ACT_RATIONAL, ACT_SCALED_TANH, ACT_TANH = 0, 1, 2, 3
+
+
+@dataclass(frozen=True)
+class Layer:
+    kind: int   # CONV, POOL or FC
+    cin: int    # input channels
+    cout: int   # output channels (POOL: == cin)
+    k: int      # kernel side (POOL: 2; FC: side of the input map)
+    act: int    # ACT_* applied to the layer output
+
+    @property
+    def n_weights(self) -> int:
+        return 0 if self.kind == POOL else self.cout * self.cin * self.k * self.k
+
+    @property
+    def n_params(self) -> int:
+        return 0 if self.kind == POOL else self.n_weights + self.cout
+
+    @property
+    def fan_in(self) -> int:
+        return self.cin * self.k * self.k
+
+
+@dataclass(frozen=True)
+class Stage:
+    in_size: int
+    layers: Sequence[Layer]
+
+    @property
+    def n_params(self) -> int:
+        return sum(l.n_params for l in self.layers)
+
+    def shapes(self):
+        """(channels, side) of the map after every layer, starting with the input."""
+        c, s = 1, self.in_size
+        out = [(c, s)]
+        for l in self.layers:
+            if l.kind == CONV:
+                c, s = l.cout, s - l.k + 1
+            elif l.kind == POOL:
+                assert s % 2 == 0
+                s //= 2
+            else:
+                assert s == l.k and c == l.cin
+                c, s = l.cout, 1
+            out.append((c, s))
+        return out
+
+
+def default_cascade(act: int = ACT_RATIONAL) -> List[Stage]:
+    """The benchmark's default three-stage cascade; `act` is the hidden activation."""
+    s1 = Stage(12, (
+        Layer(CONV, 1, 4, 3, act), Layer(POOL, 4, 4, 2, ACT_NONE),
+        Layer(CONV, 4, 8, 3, act), Layer(FC, 8, 1, 3, ACT_NONE)))
+    s2 = Stage(24, (
+        Layer(CONV, 1, 8, 5, act), Layer(POOL, 8, 8, 2, ACT_NONE),
+        Layer(CONV, 8, 16, 3, act), Layer(POOL, 16, 16, 2, ACT_NONE),
+        Layer(FC, 16, 32, 4, act), Layer(FC, 32, 1, 1, ACT_NONE)))
+    s3 = Stage(48, (
+        Layer(CONV, 1, 16, 5, act), Layer(POOL, 16, 16, 2, ACT_NONE),
+        Layer(CONV, 16, 32, 5, act), Layer(POOL, 32, 32, 2, ACT_NONE),
+        Layer(CONV, 32, 32, 3, act), Layer(FC, 32, 64, 7, act),
+        Layer(FC, 64, 1, 1, ACT_NONE)))
+    return [s1, s2, s3]
+
+
+def draw_weights(cascade: Sequence[Stage], seed: int, bias_sd: float = 0.0) -> List[np.ndarray]:
+    """One float32 blob per stage, weights ~ N(0, 1/fan_in).
+
+    Draw order: stage 1 to 3, layer by layer, each weight array in C order as
+    float64 standard normals scaled by fan_in**-0.5 and rounded to float32.
+    Biases are zero (the benchmark's rule) unless `bias_sd` > 0, which tests use
+    to make the bias terms observable; those are drawn from a second generator
+    so the weights do not depend on `bias_sd`.
+    """
+    rng = np.random.default_rng(seed)
+    brng = np.random.default_rng([seed, 0xB1A5])
+    blobs = []
+    for st in cascade:
+        parts = []
+        for l in st.layers:
+            if l.kind == POOL:
+                continue
+            w = rng.standard_normal(l.n_weights) * (l.fan_in ** -0.5)
+            b = brng.standard_normal(l.cout) * bias_sd if bias_sd > 0 else np.zeros(l.cout)
+            parts += [w.astype(np.float32), b.astype(np.float32)]
+        blobs.append(np.concatenate(parts))
+    return blobs
+
+
+def uniform_weights(cascade: Sequence[Stage], values: Sequence[Sequence[float]]) -> List[np.ndarray]:
+    """Blobs in which every weight of a layer has one value and biases are 0.
+
+    `values[s][j]` is the value for the j-th weighted layer of stage s.
+    """
+    blobs = []
+    for st, vals in zip(cascade, values):
+        parts, j = [], 0
+        for l in st.layers:
+            if l.kind == POOL:
+                continue
+            parts += [np.full(l.n_weights, vals[j], np.float32), np.zeros(l.cout, np.float32)]
+            j += 1
+        blobs.append(np.concatenate(parts))
+    return blobs

@@ -1,0 +1,442 @@
+/*
+ * CPU oracle for the compact CNN cascade detector hot path.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the plain, slow, definition-level
+ * implementation that the HIP library is checked against.  It shares no code,
+ * header, table or helper with the HIP library, and nothing in the product
+ * path may call it.  Only the tests, the smoke check and the benchmark's
+ * "cpu_baseline" leg load it.
+ *
+ * Everything floating point is computed in double (weights are given as
+ * float32 and widened).  Everything that decides an integer (pyramid pixels,
+ * crop samples, survivor sets, box merging) is integer arithmetic or an fp32
+ * comparison, stated at each function.
+ *
+ * What follows the paper and what is a reading of a point the paper leaves
+ * open is said at each function: "paper" cites a section / equation of
+ * Kalinovskii & Spitsyn, "reading" marks a choice made for this build.
+ *
+ * Parity pins (tests/test_oracle_*.py): eq. (1) error bound, closed forms on
+ * constant windows, hand-computed one-hot windows, library convolution,
+ * per-window definition vs dense evaluation, translation equivariance,
+ * threshold monotonicity, exact special cases of the resampling, merge
+ * special cases.  The choice of the readings themselves (resampling
+ * convention, crop rectangle, merge rule) cannot be pinned to the authors'
+ * detector: parity unpinned for those choices.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+enum { ORC_CONV = 0, ORC_POOL = 1, ORC_FC = 2 };
+enum { ORC_ACT_NONE = 0, ORC_ACT_RATIONAL = 1, ORC_ACT_SCALED_TANH = 2, ORC_ACT_TANH = 3 };
+
+typedef struct {
+    int32_t kind; /* ORC_CONV, ORC_POOL, ORC_FC */
+    int32_t cin, cout;
+    int32_t k;   /* kernel side; FC: side of its input map */
+    int32_t act; /* ORC_ACT_* applied to the output */
+} orc_layer;
+
+/* ------------------------------------------------------------------------ */
+/* Activation.  Paper, Section 3.1, eq. (1): f(x) = 1.7159 tanh(2x/3) with   */
+/* tanh(y) ~ sgn(y) (1 - 1/(1 + |y| + y^2 + 1.41645 y^4)).                   */
+/* Kinds 2 and 3 are the same scaled form with the exact tanh, and the plain */
+/* tanh(x), kept so that any reading of the benchmark's "+ tanh" can be run. */
+/* ------------------------------------------------------------------------ */
+double orc_rational_tanh(double y)
+{
+    double a = fabs(y), y2 = y * y;
+    double t = 1.0 - 1.0 / (1.0 + a + y2 + 1.41645 * (y2 * y2));
+    return y < 0 ? -t : t;
+}
+
+double orc_activation(double x, int act)
+{
+    switch (act) {
+    case ORC_ACT_RATIONAL:    return 1.7159 * orc_rational_tanh(x * (2.0 / 3.0));
+    case ORC_ACT_SCALED_TANH: return 1.7159 * tanh(x * (2.0 / 3.0));
+    case ORC_ACT_TANH:        return tanh(x);
+    default:                  return x;
+    }
+}
+
+/* ------------------------------------------------------------------------ */
+/* Image pyramid.  Paper, Sections 2 and 3.3: the only pre-processing is the */
+/* pyramid, parameterised by minSize and scaleFactor (Section 4.1).          */
+/* Reading: scale of level 0 is min_face/12 (a min_face-pixel face fills the */
+/* 12x12 stage-1 window); each next scale is the previous times the step     */
+/* (repeated multiplication); level size is floor(W/s + 1e-9) (the epsilon   */
+/* keeps exact quotients such as 3840/2.4 from rounding down); levels stop   */
+/* at the first one with a side below the stage-1 window.                    */
+/* Returns the number of levels (<= cap), or -1 for bad arguments.           */
+/* ------------------------------------------------------------------------ */
+int orc_pyramid_layout(int w, int h, double min_face, double step, int window, int cap,
+                       int32_t *lvl_w, int32_t *lvl_h, double *lvl_scale)
+{
+    if (w <= 0 || h <= 0 || !(min_face >= window) || !(step > 1.0)) return -1;
+    double s = min_face / (double)window;
+    int n = 0;
+    while (n < cap) {
+        int lw = (int)floor((double)w / s + 1e-9);
+        int lh = (int)floor((double)h / s + 1e-9);
+        if (lw < window || lh < window) break;
+        lvl_w[n] = lw; lvl_h[n] = lh; lvl_scale[n] = s;
+        ++n;
+        s = s * step;
+    }
+    return n;
+}
+
+/* One axis of the bilinear map.  Reading: pixel-centre alignment,            */
+/* f = (i + 0.5) s - 0.5 clamped to [0, n_in-1]; i0 = floor(f);               */
+/* weight of the right/lower neighbour quantised to 1/256:                    */
+/* q = round((f - i0) * 256) in [0,256].                                      */
+static void axis_map(int n_out, int n_in, double s, int32_t *i0, int32_t *i1, int32_t *q)
+{
+    for (int i = 0; i < n_out; ++i) {
+        double f = ((double)i + 0.5) * s - 0.5;
+        if (f < 0.0) f = 0.0;
+        if (f > (double)(n_in - 1)) f = (double)(n_in - 1);
+        int a = (int)floor(f);
+        i0[i] = a;
+        i1[i] = a + 1 < n_in ? a + 1 : n_in - 1;
+        q[i] = (int32_t)floor((f - (double)a) * 256.0 + 0.5);
+    }
+}
+
+/* Bilinear resampling of one pyramid level straight from the frame (not     */
+/* level to level).  Reading: integer blend with 8-bit weights,               */
+/* out = (sum of four pixel*weight products + 32768) >> 16, result uint8.     */
+void orc_resample_level(const uint8_t *frame, int w, int h, int pitch, double s,
+                        int lw, int lh, uint8_t *out)
+{
+    int32_t *x0 = malloc(sizeof(int32_t) * 3 * (size_t)lw), *x1 = x0 + lw, *qx = x1 + lw;
+    int32_t *y0 = malloc(sizeof(int32_t) * 3 * (size_t)lh), *y1 = y0 + lh, *qy = y1 + lh;
+    axis_map(lw, w, s, x0, x1, qx);
+    axis_map(lh, h, s, y0, y1, qy);
+    for (int y = 0; y < lh; ++y) {
+        const uint8_t *r0 = frame + (size_t)y0[y] * pitch, *r1 = frame + (size_t)y1[y] * pitch;
+        uint32_t wy = (uint32_t)qy[y];
+        for (int x = 0; x < lw; ++x) {
+            uint32_t wx = (uint32_t)qx[x];
+            uint32_t acc = r0[x0[x]] * (256u - wx) * (256u - wy) + r0[x1[x]] * wx * (256u - wy)
+                         + r1[x0[x]] * (256u - wx) * wy + r1[x1[x]] * wx * wy;
+            out[(size_t)y * lw + x] = (uint8_t)((acc + 32768u) >> 16);
+        }
+    }
+    free(x0); free(y0);
+}
+
+/* ------------------------------------------------------------------------ */
+/* One network on one window, as a plain stack of layers.                    */
+/* Paper, Section 3.1: convolution stride 1 ("valid", no padding), pooling    */
+/* stride 2 (2x2 max), the activation after hidden layers.  A fully           */
+/* connected layer is the convolution whose kernel covers its whole input,    */
+/* features ordered [channel][row][col].                                      */
+/* in: in_size x in_size doubles (one channel).  out: the last layer's cout   */
+/* values.  Returns 0, or -1 if the layer list does not fit the input.        */
+/* ------------------------------------------------------------------------ */
+static size_t layer_params(const orc_layer *l)
+{
+    return l->kind == ORC_POOL ? 0 : (size_t)l->cout * l->cin * l->k * l->k + (size_t)l->cout;
+}
+
+int orc_net_forward(const orc_layer *layers, int n_layers, const float *weights, int in_size,
+                    const double *in, double *out)
+{
+    int c = 1, s = in_size;
+    size_t cap = (size_t)in_size * in_size;
+    for (int i = 0, cc = 1, ss = in_size; i < n_layers; ++i) { /* largest intermediate map */
+        const orc_layer *l = &layers[i];
+        if (l->kind == ORC_POOL) ss /= 2; else { ss = ss - l->k + 1; cc = l->cout; }
+        if (ss < 1) return -1;
+        if ((size_t)cc * ss * ss > cap) cap = (size_t)cc * ss * ss;
+    }
+    double *cur = malloc(sizeof(double) * cap), *nxt = malloc(sizeof(double) * cap);
+    memcpy(cur, in, sizeof(double) * (size_t)in_size * in_size);
+    const float *wp = weights;
+    int rc = 0;
+    for (int i = 0; i < n_layers && rc == 0; ++i) {
+        const orc_layer *l = &layers[i];
+        if (l->cin != c) { rc = -1; break; }
+        if (l->kind == ORC_POOL) {
+            if (s % 2) { rc = -1; break; }
+            int o = s / 2;
+            for (int ch = 0; ch < c; ++ch)
+                for (int y = 0; y < o; ++y)
+                    for (int x = 0; x < o; ++x) {
+                        const double *p = cur + ((size_t)ch * s + 2 * y) * s + 2 * x;
+                        double m = p[0];
+                        if (p[1] > m) m = p[1];
+                        if (p[s] > m) m = p[s];
+                        if (p[s + 1] > m) m = p[s + 1];
+                        nxt[((size_t)ch * o + y) * o + x] = m;
+                    }
+            s = o;
+        } else {
+            int k = l->k, o = s - k + 1;
+            if (l->kind == ORC_FC && o != 1) { rc = -1; break; }
+            const float *bias = wp + (size_t)l->cout * l->cin * k * k;
+            for (int oc = 0; oc < l->cout; ++oc)
+                for (int y = 0; y < o; ++y)
+                    for (int x = 0; x < o; ++x) {
+                        double acc = (double)bias[oc];
+                        for (int ic = 0; ic < c; ++ic)
+                            for (int a = 0; a < k; ++a)
+                                for (int b = 0; b < k; ++b)
+                                    acc += (double)wp[(((size_t)oc * c + ic) * k + a) * k + b]
+                                         * cur[((size_t)ic * s + y + a) * s + x + b];
+                        nxt[((size_t)oc * o + y) * o + x] = orc_activation(acc, l->act);
+                    }
+            wp += layer_params(l);
+            c = l->cout; s = o;
+        }
+        double *t = cur; cur = nxt; nxt = t;
+    }
+    if (rc == 0) memcpy(out, cur, sizeof(double) * (size_t)c * s * s);
+    free(cur); free(nxt);
+    return rc;
+}
+
+/* Pixel to network input.  Reading: x = (p - 128) / 128.                    */
+static double normalise(double p) { return (p - 128.0) * (1.0 / 128.0); }
+
+/* ------------------------------------------------------------------------ */
+/* Stage 1 by its definition (paper, Section 3.3: the first CNN scans every  */
+/* pyramid image; one response per window position).  Reading: stride 1,      */
+/* only windows that lie fully inside the level.                              */
+/* scores: (lh - in_size + 1) x (lw - in_size + 1), row-major.                */
+/* ------------------------------------------------------------------------ */
+int orc_stage1_windows(const uint8_t *level, int lw, int lh, const orc_layer *layers, int n_layers,
+                       const float *weights, int in_size, double *scores)
+{
+    int ow = lw - in_size + 1, oh = lh - in_size + 1, rc = 0;
+    if (ow < 1 || oh < 1) return -1;
+#pragma omp parallel for schedule(dynamic)
+    for (int y = 0; y < oh; ++y) {
+        double *win = malloc(sizeof(double) * (size_t)in_size * in_size);
+        for (int x = 0; x < ow; ++x) {
+            for (int a = 0; a < in_size; ++a)
+                for (int b = 0; b < in_size; ++b)
+                    win[a * in_size + b] = normalise((double)level[(size_t)(y + a) * lw + x + b]);
+            double r;
+            if (orc_net_forward(layers, n_layers, weights, in_size, win, &r) != 0) {
+#pragma omp atomic write
+                rc = -1;
+            }
+            scores[(size_t)y * ow + x] = r;
+        }
+        free(win);
+    }
+    return rc;
+}
+
+/* ------------------------------------------------------------------------ */
+/* Stage 1 as one fully convolutional pass over the level: the same numbers   */
+/* as orc_stage1_windows, reorganised.  Each stride-2 pool becomes a          */
+/* stride-1 max over taps `d` apart and doubles the tap spacing `d` of every  */
+/* later layer.  Used for the large workloads; checked against the            */
+/* definition on small images.                                                */
+/* ------------------------------------------------------------------------ */
+int orc_stage1_dense(const uint8_t *level, int lw, int lh, const orc_layer *layers, int n_layers,
+                     const float *weights, int in_size, double *scores)
+{
+    int ow = lw - in_size + 1, oh = lh - in_size + 1;
+    if (ow < 1 || oh < 1) return -1;
+    int c = 1, W = lw, H = lh, d = 1;
+    double *cur = malloc(sizeof(double) * (size_t)lw * lh);
+    for (size_t i = 0; i < (size_t)lw * lh; ++i) cur[i] = normalise((double)level[i]);
+    const float *wp = weights;
+    for (int i = 0; i < n_layers; ++i) {
+        const orc_layer *l = &layers[i];
+        int oc_n = l->kind == ORC_POOL ? c : l->cout;
+        int span = l->kind == ORC_POOL ? d : (l->k - 1) * d;
+        int OW = W - span, OH = H - span;
+        double *nxt = malloc(sizeof(double) * (size_t)oc_n * OW * OH);
+        if (l->kind == ORC_POOL) {
+#pragma omp parallel for collapse(2)
+            for (int ch = 0; ch < c; ++ch)
+                for (int y = 0; y < OH; ++y)
+                    for (int x = 0; x < OW; ++x) {
+                        const double *p = cur + ((size_t)ch * H + y) * W + x;
+                        double m = p[0];
+                        if (p[d] > m) m = p[d];
+                        if (p[(size_t)d * W] > m) m = p[(size_t)d * W];
+                        if (p[(size_t)d * W + d] > m) m = p[(size_t)d * W + d];
+                        nxt[((size_t)ch * OH + y) * OW + x] = m;
+                    }
+            d *= 2;
+        } else {
+            int k = l->k;
+            const float *bias = wp + (size_t)l->cout * l->cin * k * k;
+#pragma omp parallel for collapse(2)
+            for (int oc = 0; oc < l->cout; ++oc)
+                for (int y = 0; y < OH; ++y)
+                    for (int x = 0; x < OW; ++x) {
+                        double acc = (double)bias[oc];
+                        for (int ic = 0; ic < c; ++ic)
+                            for (int a = 0; a < k; ++a)
+                                for (int b = 0; b < k; ++b)
+                                    acc += (double)wp[(((size_t)oc * c + ic) * k + a) * k + b]
+                                         * cur[((size_t)ic * H + y + (size_t)a * d) * W + x + (size_t)b * d];
+                        nxt[((size_t)oc * OH + y) * OW + x] = orc_activation(acc, l->act);
+                    }
+            wp += layer_params(l);
+            c = l->cout;
+        }
+        free(cur); cur = nxt; W = OW; H = OH;
+    }
+    int rc = (c == 1 && W == ow && H == oh) ? 0 : -1;
+    if (rc == 0) memcpy(scores, cur, sizeof(double) * (size_t)ow * oh);
+    free(cur);
+    return rc;
+}
+
+/* ------------------------------------------------------------------------ */
+/* Survivors of a stage (paper, Section 3.3: windows whose response exceeded  */
+/* the threshold go on).  The comparison is strict and done in fp32, the      */
+/* precision the paper's implementations compute in (Section 3.4).            */
+/* idx receives the positions i with score[i] > thr in ascending order.       */
+/* Returns the count (may exceed cap; only the first cap are written).        */
+/* ------------------------------------------------------------------------ */
+int64_t orc_survivors(const double *scores, int64_t n, float thr, int64_t cap, int64_t *idx)
+{
+    int64_t m = 0;
+    for (int64_t i = 0; i < n; ++i)
+        if ((float)scores[i] > thr) { if (m < cap) idx[m] = i; ++m; }
+    return m;
+}
+
+/* ------------------------------------------------------------------------ */
+/* Crop for stages 2 and 3 (paper, Section 3.3: the region is read from the   */
+/* original grayscale image and scaled to the network's input size).          */
+/* Reading: the region is the surviving window's own rectangle                */
+/* [x s, (x+12) s) x [y s, (y+12) s) in frame pixels, no extra neighbourhood, */
+/* resampled bilinearly to n x n in 16.16 fixed point:                        */
+/*   S = round(s * 65536); P_i = x S + ((2i+1) * window * S) / (2n) - 32768   */
+/*   clamped to [0, (W-1) * 65536]; i0 = P_i >> 16; weight of the right       */
+/*   neighbour q = ((P_i & 0xFFFF) + 128) >> 8 in [0,256].                    */
+/* The blended value sum / 65536 (sum < 2^24, exact in fp32) is normalised    */
+/* like pyramid pixels.  out: n x n doubles.                                  */
+/* ------------------------------------------------------------------------ */
+static void crop_axis(int64_t origin, int64_t S, int window, int n, int n_in,
+                      int32_t *i0, int32_t *i1, int32_t *q)
+{
+    for (int i = 0; i < n; ++i) {
+        int64_t P = origin * S + ((int64_t)(2 * i + 1) * window * S) / (2 * n) - 32768;
+        int64_t hi = (int64_t)(n_in - 1) * 65536;
+        if (P < 0) P = 0;
+        if (P > hi) P = hi;
+        int32_t a = (int32_t)(P >> 16);
+        i0[i] = a;
+        i1[i] = a + 1 < n_in ? a + 1 : n_in - 1;
+        q[i] = (int32_t)(((P & 0xFFFF) + 128) >> 8);
+    }
+}
+
+void orc_crop(const uint8_t *frame, int w, int h, int pitch, int x, int y, double s, int window,
+              int n, double *out)
+{
+    int64_t S = (int64_t)floor(s * 65536.0 + 0.5);
+    int32_t *x0 = malloc(sizeof(int32_t) * 6 * (size_t)n);
+    int32_t *x1 = x0 + n, *qx = x1 + n, *y0 = qx + n, *y1 = y0 + n, *qy = y1 + n;
+    crop_axis(x, S, window, n, w, x0, x1, qx);
+    crop_axis(y, S, window, n, h, y0, y1, qy);
+    for (int i = 0; i < n; ++i) {
+        const uint8_t *r0 = frame + (size_t)y0[i] * pitch, *r1 = frame + (size_t)y1[i] * pitch;
+        uint32_t wy = (uint32_t)qy[i];
+        for (int j = 0; j < n; ++j) {
+            uint32_t wx = (uint32_t)qx[j];
+            uint32_t acc = r0[x0[j]] * (256u - wx) * (256u - wy) + r0[x1[j]] * wx * (256u - wy)
+                         + r1[x0[j]] * (256u - wx) * wy + r1[x1[j]] * wx * wy;
+            out[i * n + j] = normalise((double)acc / 65536.0);
+        }
+    }
+    free(x0);
+}
+
+/* Stage 2 / 3: the network on the crop of each listed window.               */
+/* xs, ys: window corner in level coordinates; scales: that level's scale.   */
+int orc_eval_crops(const uint8_t *frame, int w, int h, int pitch, const int32_t *xs, const int32_t *ys,
+                   const double *scales, int64_t count, int window, const orc_layer *layers,
+                   int n_layers, const float *weights, int in_size, double *scores)
+{
+    int rc = 0;
+#pragma omp parallel for schedule(dynamic)
+    for (int64_t i = 0; i < count; ++i) {
+        double *crop = malloc(sizeof(double) * (size_t)in_size * in_size);
+        orc_crop(frame, w, h, pitch, xs[i], ys[i], scales[i], window, in_size, crop);
+        if (orc_net_forward(layers, n_layers, weights, in_size, crop, &scores[i]) != 0) {
+#pragma omp atomic write
+            rc = -1;
+        }
+        free(crop);
+    }
+    return rc;
+}
+
+/* ------------------------------------------------------------------------ */
+/* Window (level coordinates) to box in frame pixels.  Reading:               */
+/* X = round(x s), Y = round(y s), side = round(window * s).                  */
+/* ------------------------------------------------------------------------ */
+void orc_window_box(int x, int y, double s, int window, int32_t *bx, int32_t *by, int32_t *bsize)
+{
+    *bx = (int32_t)floor((double)x * s + 0.5);
+    *by = (int32_t)floor((double)y * s + 0.5);
+    *bsize = (int32_t)floor((double)window * s + 0.5);
+}
+
+/* ------------------------------------------------------------------------ */
+/* Merging of accepted windows (paper, Section 3.3: non-maximum suppression   */
+/* aggregates the found regions; Section 4.2: minNeighbors).                  */
+/* Reading: greedy.  Boxes are ordered by score (fp32) descending, ties by    */
+/* ascending `order` key.  The best box not yet suppressed is kept and        */
+/* suppresses every later, not yet suppressed box whose intersection over     */
+/* union with it exceeds `iou` (strict; areas are integers and the test       */
+/* inter > iou * union is evaluated exactly in double with iou an fp32        */
+/* value).  `neighbors` of a kept box = how many it suppressed.  Kept boxes   */
+/* with neighbors + 1 < min_neighbors are dropped.                            */
+/* out_index[j] = input position of the j-th kept box (in kept order),        */
+/* out_neighbors[j] its neighbour count.  Returns the number kept.            */
+/* ------------------------------------------------------------------------ */
+typedef struct { float score; int64_t order; int32_t pos; } merge_key;
+
+static int merge_cmp(const void *a, const void *b)
+{
+    const merge_key *p = a, *q = b;
+    if (p->score > q->score) return -1;
+    if (p->score < q->score) return 1;
+    return (p->order > q->order) - (p->order < q->order);
+}
+
+int32_t orc_merge(const int32_t *bx, const int32_t *by, const int32_t *bsize, const float *score,
+                  const int64_t *order, int32_t n, float iou, int32_t min_neighbors,
+                  int32_t *out_index, int32_t *out_neighbors)
+{
+    merge_key *key = malloc(sizeof(merge_key) * (size_t)(n > 0 ? n : 1));
+    uint8_t *dead = calloc((size_t)(n > 0 ? n : 1), 1);
+    for (int32_t i = 0; i < n; ++i) { key[i].score = score[i]; key[i].order = order[i]; key[i].pos = i; }
+    qsort(key, (size_t)n, sizeof(merge_key), merge_cmp);
+    int32_t kept = 0;
+    for (int32_t i = 0; i < n; ++i) {
+        if (dead[i]) continue;
+        int32_t p = key[i].pos, nb = 0;
+        int64_t ax0 = bx[p], ay0 = by[p], ax1 = ax0 + bsize[p], ay1 = ay0 + bsize[p];
+        int64_t aa = (int64_t)bsize[p] * bsize[p];
+        for (int32_t j = i + 1; j < n; ++j) {
+            if (dead[j]) continue;
+            int32_t r = key[j].pos;
+            int64_t cx0 = bx[r], cy0 = by[r], cx1 = cx0 + bsize[r], cy1 = cy0 + bsize[r];
+            int64_t iw = (ax1 < cx1 ? ax1 : cx1) - (ax0 > cx0 ? ax0 : cx0);
+            int64_t ih = (ay1 < cy1 ? ay1 : cy1) - (ay0 > cy0 ? ay0 : cy0);
+            if (iw <= 0 || ih <= 0) continue;
+            int64_t inter = iw * ih, uni = aa + (int64_t)bsize[r] * bsize[r] - inter;
+            if ((double)inter > (double)iou * (double)uni) { dead[j] = 1; ++nb; }
+        }
+        if (nb + 1 >= min_neighbors) { out_index[kept] = p; out_neighbors[kept] = nb; ++kept; }
+    }
+    free(key); free(dead);
+    return kept;
+}
