@@ -1,0 +1,183 @@
+/*
+ * cnnc - hot path of the compact CNN cascade detector (Kalinovskii & Spitsyn,
+ * "Compact Convolutional Neural Network Cascade for Face Detection") for one
+ * AMD MI355X (gfx950).  C ABI: plain pointers and sizes only.
+ *
+ * The path, in the order of Section 3.3 of the paper:
+ *   cnnc_build_pyramid      image pyramid of the frame             (Sections 2, 3.3)
+ *   cnnc_stage1_scoremap    first CNN on every window of every     (Section 3.3, first
+ *                           pyramid level, fully convolutional      paragraph; Section 3.4)
+ *   cnnc_compact_survivors  windows whose response exceeds T_k     (Section 3.3)
+ *   cnnc_eval_stage(k)      CNN_2 / CNN_3 on the surviving regions (Section 3.3, selective unit)
+ *   cnnc_merge_detections   aggregation of accepted regions        (Section 3.3, last paragraph)
+ *   cnnc_detect[_async]     all of the above on one frame; several contexts on several
+ *                           streams overlap stages of different frames (Section 3.4,
+ *                           asynchronous mode)
+ *
+ * Conventions
+ *   - Every function returns CNNC_OK (0) or a negative CNNC_E_* code; nothing throws or aborts.
+ *     cnnc_last_error() gives a text for the last failure on that context.
+ *   - "device" pointers are HIP device memory on the context's GPU; "host" pointers are ordinary
+ *     memory.  The caller owns the frame and the output arrays; the context owns everything else
+ *     and only lends read-only device pointers through the cnnc_get_* calls (valid until the next
+ *     call that changes the frame size or parameters, or cnnc_destroy).
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Work is enqueued on
+ *     it and not waited for, except where a function says it synchronises.
+ *   - Calls on one context must not overlap in time; use one context per stream / thread.
+ *   - The flat window index g orders all stage-1 windows of a frame by (level, y, x):
+ *     g = score_off[level] + y * (lvl_w[level] - 11) + x.
+ *   - The three networks are the fixed shapes listed at cnnc_create; kernels are specialised for
+ *     them (Section 3.4: no generic layer stack).
+ */
+#ifndef CNNC_H
+#define CNNC_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define CNNC_OK          0
+#define CNNC_E_INVAL    -1  /* bad argument (null pointer, size, stage index, unsupported network shape) */
+#define CNNC_E_NOMEM    -2  /* host or device allocation failed */
+#define CNNC_E_OVERFLOW -3  /* a survivor or detection list did not fit; contents up to the capacity are valid */
+#define CNNC_E_HIP      -4  /* a HIP runtime call failed */
+#define CNNC_E_STATE    -5  /* call out of order (e.g. score map before pyramid) */
+
+#define CNNC_WINDOW      12 /* side of the stage-1 window */
+#define CNNC_MAX_LEVELS  64
+
+enum { CNNC_CONV = 0, CNNC_POOL = 1, CNNC_FC = 2 };
+/* Activations.  1 is the paper's: f(x) = 1.7159 * t(2x/3) with the rational t of eq. (1).
+ * 2 is the same with the exact tanh; 3 is plain tanh(x); 0 is the identity (output layers). */
+enum { CNNC_ACT_NONE = 0, CNNC_ACT_RATIONAL = 1, CNNC_ACT_SCALED_TANH = 2, CNNC_ACT_TANH = 3 };
+
+typedef struct cnnc_ctx cnnc_ctx;
+
+/* One layer.  CONV: k x k "valid" convolution, stride 1.  POOL: 2x2 max, stride 2 (Section 3.1).
+ * FC: fully connected over a cin x k x k input map, features ordered [channel][row][col]. */
+typedef struct {
+    int32_t kind, cin, cout, k, act;
+} cnnc_layer;
+
+/* One network.  weights: host pointer, float32; for every CONV / FC layer in order:
+ * w[cout][cin][k][k] then bias[cout].  Copied by cnnc_create. */
+typedef struct {
+    int32_t in_size;
+    int32_t n_layers;
+    const cnnc_layer *layers;
+    const float *weights;
+} cnnc_stage_desc;
+
+/* Search parameters (Section 4.1: minSize, scaleFactor, T_1, T_2; Section 4.2: minNeighbors). */
+typedef struct {
+    double min_face;        /* smallest face side in frame pixels, >= 12; level-0 scale = min_face / 12 */
+    double scale_step;      /* > 1; scale ratio between consecutive pyramid levels */
+    float thr[3];           /* a window passes stage k iff its score > thr[k-1] (fp32, strict) */
+    float merge_iou;        /* boxes with intersection-over-union above this are merged (0.3) */
+    int32_t min_neighbors;  /* a merged box is reported iff it absorbed >= min_neighbors - 1 others */
+} cnnc_params;
+
+/* One detection in frame pixels.  index = flat window index g of the kept window. */
+typedef struct {
+    int32_t x, y, size;
+    float score;            /* stage-3 score of the kept window */
+    int32_t level;
+    int32_t neighbors;      /* boxes it absorbed */
+    int32_t index;
+    int32_t reserved;
+} cnnc_det;
+
+/* Names of the timed steps for cnnc_get_timings. */
+enum {
+    CNNC_T_PYRAMID = 0, CNNC_T_STAGE1, CNNC_T_COMPACT1, CNNC_T_STAGE2, CNNC_T_COMPACT2,
+    CNNC_T_STAGE3, CNNC_T_COMPACT3, CNNC_T_MERGE, CNNC_T_COUNT
+};
+
+/* Create a context on the current HIP device.
+ * stages[3]: the networks.  Supported shapes (anything else -> CNNC_E_INVAL):
+ *   stage 1: 12x12 | conv3 1->4, pool, conv3 4->8, fc 8x3x3->1
+ *   stage 2: 24x24 | conv5 1->8, pool, conv3 8->16, pool, fc 16x4x4->32, fc 32->1
+ *   stage 3: 48x48 | conv5 1->16, pool, conv5 16->32, pool, conv3 32->32, fc 32x7x7->64, fc 64->1
+ *   hidden layers all use one activation kind (1, 2 or 3), output layers kind 0.
+ * max_w, max_h: largest frame accepted.  max_survivors: capacity of every survivor list
+ * (stage 1, 2 and 3) and of the merge input.  Allocates device memory (hipMalloc). */
+int cnnc_create(cnnc_ctx **out, const cnnc_stage_desc stages[3], int max_w, int max_h, int max_survivors);
+int cnnc_destroy(cnnc_ctx *ctx);
+
+/* Set search parameters.  May reallocate pyramid buffers on the next frame. */
+int cnnc_set_params(cnnc_ctx *ctx, const cnnc_params *p);
+
+/* Host only, no GPU work.  Pyramid geometry for a w x h frame under the current parameters:
+ * scale s_0 = min_face / 12, s_{l+1} = s_l * scale_step; level size floor(w / s_l + 1e-9) by
+ * floor(h / s_l + 1e-9); levels end before the first with a side below 12.
+ * Arrays (host, capacity CNNC_MAX_LEVELS; any may be NULL): lvl_w, lvl_h, lvl_scale,
+ * pyr_off (byte offset of level l in the pyramid buffer, n_levels + 1 entries),
+ * score_off (offset of level l in the flat window index, n_levels + 1 entries).
+ * CNNC_E_INVAL if the frame exceeds max_w x max_h or has no level. */
+int cnnc_pyramid_layout(cnnc_ctx *ctx, int w, int h, int *n_levels, int32_t *lvl_w, int32_t *lvl_h,
+                        double *lvl_scale, int64_t *pyr_off, int64_t *score_off);
+
+/* Resample every pyramid level from the frame (not level to level), bilinear with 8-bit weights:
+ * sample position f = (i + 0.5) * s - 0.5 clamped to the frame, right/lower weight
+ * q = round(frac * 256), pixel = (sum of the four pixel * weight products + 32768) >> 16.
+ * d_frame: device, uint8 [h][pitch] (pitch >= w bytes).  Result: uint8 levels, row pitch = level width. */
+int cnnc_build_pyramid(cnnc_ctx *ctx, const uint8_t *d_frame, int w, int h, int pitch, void *stream);
+
+/* Score of every 12x12 window (stride 1, fully inside a level) of every level, fp32, in flat
+ * window order.  Pixels enter the network as (p - 128) / 128.  Needs cnnc_build_pyramid first. */
+int cnnc_stage1_scoremap(cnnc_ctx *ctx, void *stream);
+
+/* stage = 1, 2 or 3: list the windows with score_stage > thr, in ascending flat index.
+ * Stage 1 reads the score map; stage k > 1 reads the scores cnnc_eval_stage(k) left for the
+ * survivors of stage k - 1.  The count stays on the device; lists longer than max_survivors are
+ * truncated and reported by cnnc_survivor_count / cnnc_merge_detections as CNNC_E_OVERFLOW. */
+int cnnc_compact_survivors(cnnc_ctx *ctx, int stage, float thr, void *stream);
+
+/* k = 2 or 3: for every survivor of stage k - 1 cut its window rectangle
+ * [x s, (x + 12) s) x [y s, (y + 12) s) from the frame given to cnnc_build_pyramid (which must
+ * still be alive and unchanged), resample it to the network's input size (16.16 fixed point,
+ * 8-bit weights) and run network k.  One fp32 score per survivor. */
+int cnnc_eval_stage(cnnc_ctx *ctx, int k, void *stream);
+
+/* Greedy merge of the stage-3 survivors: boxes X = round(x s), Y = round(y s), side = round(12 s);
+ * in order of descending score (ties: ascending flat index) a box not yet absorbed is kept and
+ * absorbs every later box with intersection > merge_iou * union.  Kept boxes with fewer than
+ * min_neighbors - 1 absorbed boxes are dropped.  Synchronises the stream.
+ * out: host array of capacity cap, kept order.  *n_out: number of kept boxes (may exceed cap ->
+ * CNNC_E_OVERFLOW, first cap valid). */
+int cnnc_merge_detections(cnnc_ctx *ctx, cnnc_det *out, int cap, int *n_out, void *stream);
+
+/* The whole path on one frame with the context's thresholds.  cnnc_detect synchronises and
+ * returns the detections; cnnc_detect_async only enqueues on `stream` and
+ * cnnc_fetch_detections later waits for that work and returns its detections. */
+int cnnc_detect(cnnc_ctx *ctx, const uint8_t *d_frame, int w, int h, int pitch, cnnc_det *out, int cap,
+                int *n_out);
+int cnnc_detect_async(cnnc_ctx *ctx, const uint8_t *d_frame, int w, int h, int pitch, void *stream);
+int cnnc_fetch_detections(cnnc_ctx *ctx, cnnc_det *out, int cap, int *n_out);
+
+/* Read-only device views for tests and callers that chain their own kernels. */
+int cnnc_get_pyramid(cnnc_ctx *ctx, const uint8_t **d_pyramid, int64_t *n_bytes);
+int cnnc_get_scoremap(cnnc_ctx *ctx, const float **d_scores, int64_t *n_windows);
+/* stage = 1..3: d_index[i] = flat window index, d_score[i] = that stage's score, ascending index. */
+int cnnc_get_survivors(cnnc_ctx *ctx, int stage, const uint32_t **d_index, const float **d_score);
+/* Scores cnnc_eval_stage(k) produced, aligned with the survivor list of stage k - 1. */
+int cnnc_get_stage_scores(cnnc_ctx *ctx, int k, const float **d_score);
+/* Waits for `stream`, then returns the survivor count of a stage (CNNC_E_OVERFLOW if it was truncated;
+ * *n then holds the untruncated count). */
+int cnnc_survivor_count(cnnc_ctx *ctx, int stage, int *n, void *stream);
+
+/* Per-step GPU time.  With timing on, every path call brackets its kernels with HIP events on the
+ * caller's stream; cnnc_get_timings waits for them and returns milliseconds summed since the last
+ * reset and the number of calls per step (host arrays of CNNC_T_COUNT entries), then resets. */
+int cnnc_set_timing(cnnc_ctx *ctx, int on);
+int cnnc_get_timings(cnnc_ctx *ctx, double *ms_sum, int32_t *calls);
+
+const char *cnnc_last_error(const cnnc_ctx *ctx);
+const char *cnnc_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CNNC_H */

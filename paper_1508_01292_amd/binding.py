@@ -1,0 +1,289 @@
+"""ctypes binding of libcnnc.so: argument marshalling only.
+
+Frames are torch uint8 CUDA (ROCm) tensors; streams are torch streams (or None for the default
+stream).  Every method maps to the C entry point of the same name in include/cnnc.h.
+"""
+import ctypes as C
+import os
+from typing import List, Optional, Sequence
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libcnnc.so")
+
+# every symbol include/cnnc.h declares
+EXPORTS = [
+    "cnnc_create", "cnnc_destroy", "cnnc_set_params", "cnnc_pyramid_layout", "cnnc_build_pyramid",
+    "cnnc_stage1_scoremap", "cnnc_compact_survivors", "cnnc_eval_stage", "cnnc_merge_detections",
+    "cnnc_detect", "cnnc_detect_async", "cnnc_fetch_detections", "cnnc_get_pyramid", "cnnc_get_scoremap",
+    "cnnc_get_survivors", "cnnc_get_stage_scores", "cnnc_survivor_count", "cnnc_set_timing",
+    "cnnc_get_timings", "cnnc_last_error", "cnnc_version",
+]
+STEP_NAMES = ["pyramid", "stage1", "compact1", "stage2", "compact2", "stage3", "compact3", "merge"]
+MAX_LEVELS = 64
+E_OVERFLOW = -3
+
+
+class CnncError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__("cnnc error %d: %s" % (code, msg))
+        self.code = code
+
+
+class _Layer(C.Structure):
+    _fields_ = [("kind", C.c_int32), ("cin", C.c_int32), ("cout", C.c_int32), ("k", C.c_int32), ("act", C.c_int32)]
+
+
+class _StageDesc(C.Structure):
+    _fields_ = [("in_size", C.c_int32), ("n_layers", C.c_int32), ("layers", C.POINTER(_Layer)),
+                ("weights", C.POINTER(C.c_float))]
+
+
+class _Params(C.Structure):
+    _fields_ = [("min_face", C.c_double), ("scale_step", C.c_double), ("thr", C.c_float * 3),
+                ("merge_iou", C.c_float), ("min_neighbors", C.c_int32)]
+
+
+class Detection(C.Structure):
+    _fields_ = [("x", C.c_int32), ("y", C.c_int32), ("size", C.c_int32), ("score", C.c_float),
+                ("level", C.c_int32), ("neighbors", C.c_int32), ("index", C.c_int32), ("reserved", C.c_int32)]
+
+    def as_dict(self):
+        return dict(x=self.x, y=self.y, size=self.size, score=self.score, level=self.level,
+                    neighbors=self.neighbors, index=self.index)
+
+
+_lib = None
+_hip = None
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def lib():
+    """The loaded library.  There is no fallback: a missing build is an error."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise ImportError("libcnnc.so is not built: run `python -m paper_1508_01292_amd.build` "
+                              "(or __graft_entry__.build())")
+        L = C.CDLL(_LIB_PATH)
+        L.cnnc_last_error.restype = C.c_char_p
+        L.cnnc_last_error.argtypes = [C.c_void_p]
+        L.cnnc_version.restype = C.c_char_p
+        _lib = L
+    return _lib
+
+
+def _hiprt():
+    global _hip
+    if _hip is None:
+        _hip = C.CDLL("libamdhip64.so")
+    return _hip
+
+
+def _stream(s) -> C.c_void_p:
+    if s is None:
+        return C.c_void_p(0)
+    return C.c_void_p(int(s.cuda_stream))
+
+
+def _d2h(ptr: int, nbytes: int, dtype) -> np.ndarray:
+    out = np.empty(nbytes // np.dtype(dtype).itemsize, dtype)
+    if nbytes:
+        rc = _hiprt().hipMemcpy(out.ctypes.data_as(C.c_void_p), C.c_void_p(ptr), C.c_size_t(nbytes), C.c_int(2))
+        if rc != 0:
+            raise RuntimeError("hipMemcpy failed: %d" % rc)
+    return out
+
+
+class Context:
+    """One detector context (cnnc_ctx).  Calls on one context must not overlap."""
+
+    def __init__(self, cascade: Sequence, weights: Sequence[np.ndarray], max_w: int, max_h: int,
+                 max_survivors: int):
+        self._h = C.c_void_p(0)
+        self._keep = []
+        descs = (_StageDesc * 3)()
+        for s, (st, wt) in enumerate(zip(cascade, weights)):
+            layers = (_Layer * len(st.layers))(*[_Layer(l.kind, l.cin, l.cout, l.k, l.act) for l in st.layers])
+            w = np.ascontiguousarray(wt, np.float32)
+            if w.size != st.n_params:
+                raise ValueError("weight blob of stage %d has %d values, expected %d" % (s + 1, w.size, st.n_params))
+            self._keep += [layers, w]
+            descs[s] = _StageDesc(st.in_size, len(st.layers), layers, w.ctypes.data_as(C.POINTER(C.c_float)))
+        rc = lib().cnnc_create(C.byref(self._h), descs, C.c_int(max_w), C.c_int(max_h), C.c_int(max_survivors))
+        if rc != 0:
+            self._h = C.c_void_p(0)
+            raise CnncError(rc, "cnnc_create failed")
+        self.max_survivors = max_survivors
+        self._frame = None
+
+    # -- plumbing ---------------------------------------------------------------------------
+    def _check(self, rc: int, allow_overflow: bool = False) -> int:
+        if rc != 0 and not (allow_overflow and rc == E_OVERFLOW):
+            raise CnncError(rc, (lib().cnnc_last_error(self._h) or b"").decode())
+        return rc
+
+    def close(self):
+        if self._h:
+            lib().cnnc_destroy(self._h)
+            self._h = C.c_void_p(0)
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _frame_args(self, frame):
+        if frame.dtype.__str__() != "torch.uint8" or frame.dim() != 2 or not frame.is_cuda or frame.stride(1) != 1:
+            raise ValueError("frame must be a 2-D uint8 device tensor with unit column stride")
+        self._frame = frame          # the library reads it again in cnnc_eval_stage
+        return (C.c_void_p(frame.data_ptr()), C.c_int(frame.shape[1]), C.c_int(frame.shape[0]),
+                C.c_int(frame.stride(0)))
+
+    # -- the C entry points -----------------------------------------------------------------
+    def set_params(self, min_face: float, scale_step: float, thr=(0.0, 0.0, 0.0), merge_iou: float = 0.3,
+                   min_neighbors: int = 1):
+        p = _Params(min_face, scale_step, (C.c_float * 3)(*[float(t) for t in thr]), merge_iou, min_neighbors)
+        self._check(lib().cnnc_set_params(self._h, C.byref(p)))
+
+    def pyramid_layout(self, w: int, h: int):
+        n = C.c_int(0)
+        lw = np.zeros(MAX_LEVELS, np.int32)
+        lh = np.zeros(MAX_LEVELS, np.int32)
+        sc = np.zeros(MAX_LEVELS, np.float64)
+        po = np.zeros(MAX_LEVELS + 1, np.int64)
+        so = np.zeros(MAX_LEVELS + 1, np.int64)
+        vp = lambda a: a.ctypes.data_as(C.c_void_p)
+        self._check(lib().cnnc_pyramid_layout(self._h, C.c_int(w), C.c_int(h), C.byref(n), vp(lw), vp(lh), vp(sc),
+                                              vp(po), vp(so)))
+        k = n.value
+        return dict(n_levels=k, lvl_w=lw[:k].tolist(), lvl_h=lh[:k].tolist(), scale=sc[:k].tolist(),
+                    pyr_off=po[:k + 1].tolist(), score_off=so[:k + 1].tolist())
+
+    def build_pyramid(self, frame, stream=None):
+        self._check(lib().cnnc_build_pyramid(self._h, *self._frame_args(frame), _stream(stream)))
+
+    def stage1_scoremap(self, stream=None):
+        self._check(lib().cnnc_stage1_scoremap(self._h, _stream(stream)))
+
+    def compact_survivors(self, stage: int, thr: float, stream=None):
+        self._check(lib().cnnc_compact_survivors(self._h, C.c_int(stage), C.c_float(thr), _stream(stream)))
+
+    def eval_stage(self, k: int, stream=None):
+        self._check(lib().cnnc_eval_stage(self._h, C.c_int(k), _stream(stream)))
+
+    def merge_detections(self, cap: int = 4096, stream=None) -> List[Detection]:
+        out = (Detection * cap)()
+        n = C.c_int(0)
+        self._check(lib().cnnc_merge_detections(self._h, out, C.c_int(cap), C.byref(n), _stream(stream)))
+        return list(out[:n.value])
+
+    def detect(self, frame, cap: int = 4096) -> List[Detection]:
+        out = (Detection * cap)()
+        n = C.c_int(0)
+        self._check(lib().cnnc_detect(self._h, *self._frame_args(frame), out, C.c_int(cap), C.byref(n)))
+        return list(out[:n.value])
+
+    def detect_async(self, frame, stream=None):
+        self._check(lib().cnnc_detect_async(self._h, *self._frame_args(frame), _stream(stream)))
+
+    def fetch_detections(self, cap: int = 4096) -> List[Detection]:
+        out = (Detection * cap)()
+        n = C.c_int(0)
+        self._check(lib().cnnc_fetch_detections(self._h, out, C.c_int(cap), C.byref(n)))
+        return list(out[:n.value])
+
+    # -- views (copied to the host) -----------------------------------------------------------
+    def get_pyramid(self) -> np.ndarray:
+        _hiprt().hipDeviceSynchronize()
+        p, n = C.c_void_p(0), C.c_int64(0)
+        self._check(lib().cnnc_get_pyramid(self._h, C.byref(p), C.byref(n)))
+        return _d2h(p.value, n.value, np.uint8)
+
+    def get_scoremap(self) -> np.ndarray:
+        _hiprt().hipDeviceSynchronize()
+        p, n = C.c_void_p(0), C.c_int64(0)
+        self._check(lib().cnnc_get_scoremap(self._h, C.byref(p), C.byref(n)))
+        return _d2h(p.value, n.value * 4, np.float32)
+
+    def survivor_count(self, stage: int, stream=None) -> int:
+        n = C.c_int(0)
+        self._check(lib().cnnc_survivor_count(self._h, C.c_int(stage), C.byref(n), _stream(stream)))
+        return n.value
+
+    def get_survivors(self, stage: int, stream=None):
+        """(flat window indices, scores of that stage) of the survivors of `stage`."""
+        n = self.survivor_count(stage, stream)
+        pi, ps = C.c_void_p(0), C.c_void_p(0)
+        self._check(lib().cnnc_get_survivors(self._h, C.c_int(stage), C.byref(pi), C.byref(ps)))
+        return _d2h(pi.value, n * 4, np.uint32), _d2h(ps.value, n * 4, np.float32)
+
+    def get_stage_scores(self, k: int, stream=None) -> np.ndarray:
+        """Scores of stage k (2 or 3) for every survivor of stage k - 1."""
+        n = self.survivor_count(k - 1, stream)
+        p = C.c_void_p(0)
+        self._check(lib().cnnc_get_stage_scores(self._h, C.c_int(k), C.byref(p)))
+        return _d2h(p.value, n * 4, np.float32)
+
+    def set_timing(self, on: bool):
+        self._check(lib().cnnc_set_timing(self._h, C.c_int(1 if on else 0)))
+
+    def get_timings(self):
+        ms = (C.c_double * len(STEP_NAMES))()
+        calls = (C.c_int32 * len(STEP_NAMES))()
+        self._check(lib().cnnc_get_timings(self._h, ms, calls))
+        return {n: (ms[i], calls[i]) for i, n in enumerate(STEP_NAMES)}
+
+
+# Same-named thin functions for callers that prefer the C spelling.
+def cnnc_create(cascade, weights, max_w, max_h, max_survivors) -> Context:
+    return Context(cascade, weights, max_w, max_h, max_survivors)
+
+
+def cnnc_destroy(ctx: Context):
+    ctx.close()
+
+
+def cnnc_set_params(ctx: Context, *a, **k):
+    return ctx.set_params(*a, **k)
+
+
+def cnnc_pyramid_layout(ctx: Context, w, h):
+    return ctx.pyramid_layout(w, h)
+
+
+def cnnc_build_pyramid(ctx: Context, frame, stream=None):
+    return ctx.build_pyramid(frame, stream)
+
+
+def cnnc_stage1_scoremap(ctx: Context, stream=None):
+    return ctx.stage1_scoremap(stream)
+
+
+def cnnc_compact_survivors(ctx: Context, stage, thr, stream=None):
+    return ctx.compact_survivors(stage, thr, stream)
+
+
+def cnnc_eval_stage(ctx: Context, k, stream=None):
+    return ctx.eval_stage(k, stream)
+
+
+def cnnc_merge_detections(ctx: Context, cap=4096, stream=None):
+    return ctx.merge_detections(cap, stream)
+
+
+def cnnc_detect(ctx: Context, frame, cap=4096):
+    return ctx.detect(frame, cap)
+
+
+def cnnc_detect_async(ctx: Context, frame, stream=None):
+    return ctx.detect_async(frame, stream)
+
+
+def cnnc_fetch_detections(ctx: Context, cap=4096):
+    return ctx.fetch_detections(cap)

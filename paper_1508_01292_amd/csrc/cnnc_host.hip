@@ -1,0 +1,529 @@
+// Host side of libcnnc: context, geometry tables, buffer management and the C entry points.
+#include <math.h>
+#include <string.h>
+
+#include <algorithm>
+#include <new>
+
+#include "cnnc_internal.h"
+
+using namespace cnnc;
+
+namespace {
+
+enum { DONE_PYR = 1, DONE_S1 = 2, DONE_C1 = 4, DONE_E2 = 8, DONE_C2 = 16, DONE_E3 = 32, DONE_C3 = 64, DONE_MERGE = 128 };
+
+constexpr int kFastDets = 2048;   // detections copied to the host together with the counters
+
+int fail(cnnc_ctx *c, int code, const std::string &msg)
+{
+    if (c) c->err = msg;
+    return code;
+}
+
+int hip_fail(cnnc_ctx *c, hipError_t e, const char *what)
+{
+    return fail(c, e == hipErrorOutOfMemory ? CNNC_E_NOMEM : CNNC_E_HIP, std::string(what) + ": " + hipGetErrorString(e));
+}
+
+#define HIP_TRY(c, expr)                                         \
+    do {                                                         \
+        hipError_t e_ = (expr);                                  \
+        if (e_ != hipSuccess) return hip_fail((c), e_, #expr);   \
+    } while (0)
+
+struct LayerSpec { int kind, cin, cout, k; bool hidden; };
+
+const LayerSpec kStage1[] = {{CNNC_CONV, 1, 4, 3, true}, {CNNC_POOL, 4, 4, 2, false}, {CNNC_CONV, 4, 8, 3, true},
+                             {CNNC_FC, 8, 1, 3, false}};
+const LayerSpec kStage2[] = {{CNNC_CONV, 1, 8, 5, true}, {CNNC_POOL, 8, 8, 2, false}, {CNNC_CONV, 8, 16, 3, true},
+                             {CNNC_POOL, 16, 16, 2, false}, {CNNC_FC, 16, 32, 4, true}, {CNNC_FC, 32, 1, 1, false}};
+const LayerSpec kStage3[] = {{CNNC_CONV, 1, 16, 5, true}, {CNNC_POOL, 16, 16, 2, false}, {CNNC_CONV, 16, 32, 5, true},
+                             {CNNC_POOL, 32, 32, 2, false}, {CNNC_CONV, 32, 32, 3, true}, {CNNC_FC, 32, 64, 7, true},
+                             {CNNC_FC, 64, 1, 1, false}};
+
+// The descriptor must name one of the built-in shapes; returns the hidden activation or -1.
+int check_stage(const cnnc_stage_desc &d, const LayerSpec *spec, int n_spec, int in_size)
+{
+    if (d.in_size != in_size || d.n_layers != n_spec || !d.layers || !d.weights) return -1;
+    int act = 0;
+    for (int i = 0; i < n_spec; ++i) {
+        const cnnc_layer &l = d.layers[i];
+        if (l.kind != spec[i].kind || l.cin != spec[i].cin || l.cout != spec[i].cout || l.k != spec[i].k) return -1;
+        if (spec[i].hidden) {
+            if (l.act < CNNC_ACT_RATIONAL || l.act > CNNC_ACT_TANH) return -1;
+            if (act && l.act != act) return -1;
+            act = l.act;
+        } else if (l.act != CNNC_ACT_NONE) {
+            return -1;
+        }
+    }
+    return act;
+}
+
+template <typename T>
+int ensure(cnnc_ctx *c, T *&ptr, int64_t &cap, int64_t need)
+{
+    if (need <= cap) return CNNC_OK;
+    if (ptr) { HIP_TRY(c, hipFree(ptr)); ptr = nullptr; cap = 0; }
+    HIP_TRY(c, hipMalloc((void **)&ptr, sizeof(T) * (size_t)need));
+    cap = need;
+    return CNNC_OK;
+}
+
+// One axis of the pyramid's bilinear map; entry = (left index << 9) | weight of the right neighbour.
+void axis_taps(int n_out, int n_in, double s, uint32_t *out)
+{
+    for (int i = 0; i < n_out; ++i) {
+        double f = ((double)i + 0.5) * s - 0.5;
+        if (f < 0.0) f = 0.0;
+        if (f > (double)(n_in - 1)) f = (double)(n_in - 1);
+        const int a = (int)floor(f);
+        const int q = (int)floor((f - (double)a) * 256.0 + 0.5);
+        out[i] = ((uint32_t)a << 9) | (uint32_t)q;
+    }
+}
+
+// Pyramid geometry for a frame size under the current parameters (host arithmetic only).
+int compute_levels(const cnnc_ctx *c, int w, int h, std::vector<LevelDev> &lv, int64_t &pyr_bytes, int64_t &n_windows)
+{
+    lv.clear();
+    double s = c->params.min_face / (double)kWin;
+    int64_t poff = 0, soff = 0, toff = 0;
+    while ((int)lv.size() < CNNC_MAX_LEVELS) {
+        const int lw = (int)floor((double)w / s + 1e-9), lh = (int)floor((double)h / s + 1e-9);
+        if (lw < kWin || lh < kWin) break;
+        LevelDev L{};
+        L.w = lw; L.h = lh; L.ow = lw - kWin + 1; L.oh = lh - kWin + 1;
+        L.pyr_off = (int32_t)poff; L.score_off = (int32_t)soff;
+        L.xmap_off = (int32_t)toff; L.ymap_off = (int32_t)(toff + lw);
+        L.scale_q16 = (int64_t)floor(s * 65536.0 + 0.5);
+        L.scale = s;
+        lv.push_back(L);
+        poff += (int64_t)lw * lh; soff += (int64_t)L.ow * L.oh; toff += lw + lh;
+        if (poff > INT32_MAX || soff > INT32_MAX) return CNNC_E_INVAL;
+        s = s * c->params.scale_step;
+    }
+    pyr_bytes = poff; n_windows = soff;
+    return lv.empty() ? CNNC_E_INVAL : CNNC_OK;
+}
+
+int prepare_layout(cnnc_ctx *c, int w, int h)
+{
+    if (c->layout_valid && c->lay_w == w && c->lay_h == h) return CNNC_OK;
+    if (w < kWin || h < kWin || w > c->max_w || h > c->max_h) return fail(c, CNNC_E_INVAL, "frame size outside [12, max]");
+    std::vector<LevelDev> lv;
+    int64_t pyr_bytes = 0, n_windows = 0;
+    if (compute_levels(c, w, h, lv, pyr_bytes, n_windows) != CNNC_OK)
+        return fail(c, CNNC_E_INVAL, "frame has no pyramid level at these parameters");
+
+    std::vector<uint32_t> taps, tiles_pyr, tiles_s1;
+    for (size_t l = 0; l < lv.size(); ++l) {
+        const LevelDev &L = lv[l];
+        const size_t base = taps.size();
+        taps.resize(base + L.w + L.h);
+        axis_taps(L.w, w, L.scale, taps.data() + base);
+        axis_taps(L.h, h, L.scale, taps.data() + base + L.w);
+        for (int ty = 0; ty * kPyrTileH < L.h; ++ty)
+            for (int tx = 0; tx * kPyrTileW < L.w; ++tx) tiles_pyr.push_back(pack_tile((int)l, ty, tx));
+        for (int ty = 0; ty * kS1TileH < L.oh; ++ty)
+            for (int tx = 0; tx * kS1TileW < L.ow; ++tx) tiles_s1.push_back(pack_tile((int)l, ty, tx));
+    }
+
+    // buffers may be in use by work still queued on the last stream
+    HIP_TRY(c, hipStreamSynchronize(c->last_stream));
+    int rc;
+    int64_t cap_levels = c->d_levels ? CNNC_MAX_LEVELS : 0;
+    if ((rc = ensure(c, c->d_levels, cap_levels, CNNC_MAX_LEVELS))) return rc;
+    if ((rc = ensure(c, c->d_taps, c->cap_taps, (int64_t)taps.size()))) return rc;
+    if ((rc = ensure(c, c->d_tiles_pyr, c->cap_tiles_pyr, (int64_t)tiles_pyr.size()))) return rc;
+    if ((rc = ensure(c, c->d_tiles_s1, c->cap_tiles_s1, (int64_t)tiles_s1.size()))) return rc;
+    if ((rc = ensure(c, c->d_pyr, c->cap_pyr, pyr_bytes))) return rc;
+    if ((rc = ensure(c, c->d_score1, c->cap_score1, n_windows))) return rc;
+    const int64_t nblocks = std::max<int64_t>((n_windows + kCompactPerBlock - 1) / kCompactPerBlock,
+                                              (c->max_surv + kCompactPerBlock - 1) / kCompactPerBlock) + 1;
+    int64_t cap_blocks = c->cap_blocks;
+    if ((rc = ensure(c, c->d_blockcnt, cap_blocks, nblocks))) return rc;
+    c->cap_blocks = (int32_t)cap_blocks;
+
+    HIP_TRY(c, hipMemcpy(c->d_levels, lv.data(), sizeof(LevelDev) * lv.size(), hipMemcpyHostToDevice));
+    HIP_TRY(c, hipMemcpy(c->d_taps, taps.data(), sizeof(uint32_t) * taps.size(), hipMemcpyHostToDevice));
+    HIP_TRY(c, hipMemcpy(c->d_tiles_pyr, tiles_pyr.data(), sizeof(uint32_t) * tiles_pyr.size(), hipMemcpyHostToDevice));
+    HIP_TRY(c, hipMemcpy(c->d_tiles_s1, tiles_s1.data(), sizeof(uint32_t) * tiles_s1.size(), hipMemcpyHostToDevice));
+
+    c->levels = lv;
+    c->n_levels = (int)lv.size();
+    c->pyr_bytes = pyr_bytes; c->n_windows = n_windows;
+    c->n_tiles_pyr = (int)tiles_pyr.size(); c->n_tiles_s1 = (int)tiles_s1.size();
+    c->lay_w = w; c->lay_h = h; c->layout_valid = true;
+    return CNNC_OK;
+}
+
+// ---- per-step timing with events on the caller's stream ---------------------------------------
+hipEvent_t take_event(StepTimer &t)
+{
+    hipEvent_t e = nullptr;
+    if (!t.pool.empty()) { e = t.pool.back(); t.pool.pop_back(); return e; }
+    if (hipEventCreate(&e) != hipSuccess) return nullptr;
+    return e;
+}
+
+struct Timed {
+    cnnc_ctx *c; int step; hipStream_t st; hipEvent_t b = nullptr;
+    Timed(cnnc_ctx *c_, int step_, hipStream_t st_) : c(c_), step(step_), st(st_)
+    {
+        if (c->timing && (b = take_event(c->timers[step]))) (void)hipEventRecord(b, st);
+    }
+    ~Timed()
+    {
+        if (!b) return;
+        StepTimer &t = c->timers[step];
+        hipEvent_t e = take_event(t);
+        if (!e) { t.pool.push_back(b); return; }
+        (void)hipEventRecord(e, st);
+        t.begin.push_back(b); t.end.push_back(e);
+    }
+};
+
+int fetch(cnnc_ctx *c, cnnc_det *out, int cap, int *n_out)
+{
+    HIP_TRY(c, hipStreamSynchronize(c->last_stream));
+    const Counters &k = *c->h_cnt;
+    for (int s = 0; s < 3; ++s)
+        if (k.n[s] > c->max_surv) {
+            if (n_out) *n_out = 0;
+            return fail(c, CNNC_E_OVERFLOW, "survivor list of stage " + std::to_string(s + 1) + " needs " +
+                                                std::to_string(k.n[s]) + " entries");
+        }
+    if (k.n[2] > c->merge_cap) return fail(c, CNNC_E_OVERFLOW, "merge input exceeds its capacity");
+    const int n = k.n[3];
+    if (n_out) *n_out = n;
+    const int m = std::min(std::min(n, cap), c->merge_cap);
+    if (m > kFastDets)   // the enqueued copy only brought the first kFastDets
+        HIP_TRY(c, hipMemcpy(c->h_det + kFastDets, c->d_det + kFastDets, sizeof(cnnc_det) * (size_t)(m - kFastDets),
+                             hipMemcpyDeviceToHost));
+    if (m > 0) memcpy(out, c->h_det, sizeof(cnnc_det) * (size_t)m);
+    return n > cap ? fail(c, CNNC_E_OVERFLOW, "detection array too small") : CNNC_OK;
+}
+
+// Enqueue the copy of the counters and of the detections to pinned host memory.
+int enqueue_readback(cnnc_ctx *c, hipStream_t st)
+{
+    HIP_TRY(c, hipMemcpyAsync(c->h_cnt, c->d_cnt, sizeof(Counters), hipMemcpyDeviceToHost, st));
+    HIP_TRY(c, hipMemcpyAsync(c->h_det, c->d_det, sizeof(cnnc_det) * (size_t)std::min(c->merge_cap, kFastDets),
+                              hipMemcpyDeviceToHost, st));
+    return CNNC_OK;
+}
+
+}  // namespace
+
+// ------------------------------------------------------------------------------------------------
+extern "C" {
+
+const char *cnnc_version(void) { return "cnnc 0.1 (gfx950)"; }
+
+const char *cnnc_last_error(const cnnc_ctx *ctx) { return ctx ? ctx->err.c_str() : "null context"; }
+
+int cnnc_create(cnnc_ctx **out, const cnnc_stage_desc stages[3], int max_w, int max_h, int max_survivors)
+{
+    if (!out) return CNNC_E_INVAL;
+    *out = nullptr;
+    if (!stages || max_w < kWin || max_h < kWin || max_w > 16384 || max_h > 16384 || max_survivors < 1 ||
+        max_survivors > (1 << 24))
+        return CNNC_E_INVAL;
+    const int a1 = check_stage(stages[0], kStage1, 4, 12);
+    const int a2 = check_stage(stages[1], kStage2, 6, kS2In);
+    const int a3 = check_stage(stages[2], kStage3, 7, kS3In);
+    if (a1 < 1 || a2 != a1 || a3 != a1) return CNNC_E_INVAL;
+
+    cnnc_ctx *c = new (std::nothrow) cnnc_ctx();
+    if (!c) return CNNC_E_NOMEM;
+    c->act = a1;
+    c->max_w = max_w; c->max_h = max_h; c->max_surv = max_survivors;
+    c->merge_cap = std::min(max_survivors, 32768);
+    c->params.min_face = 60; c->params.scale_step = 1.25;
+    c->params.thr[0] = c->params.thr[1] = c->params.thr[2] = 0.0f;
+    c->params.merge_iou = 0.3f; c->params.min_neighbors = 1;
+
+    auto bail = [&](int rc) { cnnc_destroy(c); return rc; };
+    if (hipGetDevice(&c->device) != hipSuccess) return bail(CNNC_E_HIP);
+    const int n_params[3] = {kS1Params, kS2Params, kS3Params};
+    for (int s = 0; s < 3; ++s) {
+        if (hipMalloc((void **)&c->d_wt[s], sizeof(float) * n_params[s]) != hipSuccess) return bail(CNNC_E_NOMEM);
+        if (hipMemcpy(c->d_wt[s], stages[s].weights, sizeof(float) * n_params[s], hipMemcpyHostToDevice) != hipSuccess)
+            return bail(CNNC_E_HIP);
+    }
+    for (int s = 0; s < 3; ++s) {
+        if (hipMalloc((void **)&c->d_idx[s], sizeof(uint32_t) * (size_t)max_survivors) != hipSuccess) return bail(CNNC_E_NOMEM);
+        if (hipMalloc((void **)&c->d_sc[s], sizeof(float) * (size_t)max_survivors) != hipSuccess) return bail(CNNC_E_NOMEM);
+    }
+    for (int s = 0; s < 2; ++s)
+        if (hipMalloc((void **)&c->d_eval[s], sizeof(float) * (size_t)max_survivors) != hipSuccess) return bail(CNNC_E_NOMEM);
+    if (hipMalloc((void **)&c->d_cnt, sizeof(Counters)) != hipSuccess) return bail(CNNC_E_NOMEM);
+    if (hipMemset(c->d_cnt, 0, sizeof(Counters)) != hipSuccess) return bail(CNNC_E_HIP);
+    if (hipHostMalloc((void **)&c->h_cnt, sizeof(Counters), hipHostMallocDefault) != hipSuccess) return bail(CNNC_E_NOMEM);
+    memset(c->h_cnt, 0, sizeof(Counters));
+    if (hipMalloc(&c->d_merge_ws, merge_workspace_bytes(c->merge_cap)) != hipSuccess) return bail(CNNC_E_NOMEM);
+    if (hipMalloc((void **)&c->d_det, sizeof(cnnc_det) * (size_t)c->merge_cap) != hipSuccess) return bail(CNNC_E_NOMEM);
+    if (hipHostMalloc((void **)&c->h_det, sizeof(cnnc_det) * (size_t)c->merge_cap, hipHostMallocDefault) != hipSuccess)
+        return bail(CNNC_E_NOMEM);
+    *out = c;
+    return CNNC_OK;
+}
+
+int cnnc_destroy(cnnc_ctx *c)
+{
+    if (!c) return CNNC_E_INVAL;
+    (void)hipDeviceSynchronize();
+    for (int s = 0; s < 3; ++s) { (void)hipFree(c->d_wt[s]); (void)hipFree(c->d_idx[s]); (void)hipFree(c->d_sc[s]); }
+    for (int s = 0; s < 2; ++s) (void)hipFree(c->d_eval[s]);
+    (void)hipFree(c->d_levels); (void)hipFree(c->d_taps); (void)hipFree(c->d_tiles_pyr); (void)hipFree(c->d_tiles_s1);
+    (void)hipFree(c->d_pyr); (void)hipFree(c->d_score1); (void)hipFree(c->d_blockcnt); (void)hipFree(c->d_cnt);
+    (void)hipFree(c->d_merge_ws); (void)hipFree(c->d_det);
+    if (c->h_cnt) (void)hipHostFree(c->h_cnt);
+    if (c->h_det) (void)hipHostFree(c->h_det);
+    for (auto &t : c->timers) {
+        for (auto e : t.begin) (void)hipEventDestroy(e);
+        for (auto e : t.end) (void)hipEventDestroy(e);
+        for (auto e : t.pool) (void)hipEventDestroy(e);
+    }
+    delete c;
+    return CNNC_OK;
+}
+
+int cnnc_set_params(cnnc_ctx *c, const cnnc_params *p)
+{
+    if (!c) return CNNC_E_INVAL;
+    if (!p) return fail(c, CNNC_E_INVAL, "null parameters");
+    if (!(p->min_face >= kWin) || !(p->scale_step > 1.0) || !(p->merge_iou >= 0.0f) || !(p->merge_iou <= 1.0f) ||
+        p->min_neighbors < 1)
+        return fail(c, CNNC_E_INVAL, "parameter out of range");
+    for (float t : p->thr)
+        if (t != t) return fail(c, CNNC_E_INVAL, "threshold is NaN");
+    if (p->min_face != c->params.min_face || p->scale_step != c->params.scale_step) { c->layout_valid = false; c->progress = 0; }
+    c->params = *p;
+    return CNNC_OK;
+}
+
+int cnnc_pyramid_layout(cnnc_ctx *c, int w, int h, int *n_levels, int32_t *lvl_w, int32_t *lvl_h, double *lvl_scale,
+                        int64_t *pyr_off, int64_t *score_off)
+{
+    if (!c) return CNNC_E_INVAL;
+    if (w < kWin || h < kWin || w > c->max_w || h > c->max_h) return fail(c, CNNC_E_INVAL, "frame size outside [12, max]");
+    std::vector<LevelDev> lv;
+    int64_t pb = 0, nw = 0;
+    if (compute_levels(c, w, h, lv, pb, nw) != CNNC_OK) return fail(c, CNNC_E_INVAL, "frame has no pyramid level");
+    if (n_levels) *n_levels = (int)lv.size();
+    for (size_t l = 0; l < lv.size(); ++l) {
+        if (lvl_w) lvl_w[l] = lv[l].w;
+        if (lvl_h) lvl_h[l] = lv[l].h;
+        if (lvl_scale) lvl_scale[l] = lv[l].scale;
+        if (pyr_off) pyr_off[l] = lv[l].pyr_off;
+        if (score_off) score_off[l] = lv[l].score_off;
+    }
+    if (pyr_off) pyr_off[lv.size()] = pb;
+    if (score_off) score_off[lv.size()] = nw;
+    return CNNC_OK;
+}
+
+int cnnc_build_pyramid(cnnc_ctx *c, const uint8_t *d_frame, int w, int h, int pitch, void *stream)
+{
+    if (!c) return CNNC_E_INVAL;
+    if (!d_frame || pitch < w) return fail(c, CNNC_E_INVAL, "null frame or pitch < width");
+    int rc = prepare_layout(c, w, h);
+    if (rc) return rc;
+    hipStream_t st = (hipStream_t)stream;
+    c->d_frame = d_frame; c->fw = w; c->fh = h; c->fpitch = pitch;
+    c->last_stream = st;
+    c->progress = 0;
+    {
+        Timed t(c, CNNC_T_PYRAMID, st);
+        HIP_TRY(c, launch_pyramid(c, st));
+    }
+    c->progress = DONE_PYR;
+    return CNNC_OK;
+}
+
+int cnnc_stage1_scoremap(cnnc_ctx *c, void *stream)
+{
+    if (!c) return CNNC_E_INVAL;
+    if (!(c->progress & DONE_PYR)) return fail(c, CNNC_E_STATE, "stage 1 needs a pyramid");
+    hipStream_t st = (hipStream_t)stream;
+    c->last_stream = st;
+    {
+        Timed t(c, CNNC_T_STAGE1, st);
+        HIP_TRY(c, launch_stage1(c, st));
+    }
+    c->progress = DONE_PYR | DONE_S1;
+    return CNNC_OK;
+}
+
+int cnnc_compact_survivors(cnnc_ctx *c, int stage, float thr, void *stream)
+{
+    if (!c) return CNNC_E_INVAL;
+    if (stage < 1 || stage > 3) return fail(c, CNNC_E_INVAL, "stage must be 1, 2 or 3");
+    if (thr != thr) return fail(c, CNNC_E_INVAL, "threshold is NaN");
+    const int need[3] = {DONE_S1, DONE_E2, DONE_E3};
+    if (!(c->progress & need[stage - 1])) return fail(c, CNNC_E_STATE, "compaction needs that stage's scores");
+    hipStream_t st = (hipStream_t)stream;
+    c->last_stream = st;
+    {
+        Timed t(c, CNNC_T_COMPACT1 + 2 * (stage - 1), st);
+        if (stage == 1)
+            HIP_TRY(c, launch_compact(c, c->d_score1, nullptr, nullptr, c->n_windows, thr, c->d_idx[0], c->d_sc[0],
+                                      &c->d_cnt->n[0], st));
+        else
+            HIP_TRY(c, launch_compact(c, c->d_eval[stage - 2], c->d_idx[stage - 2], &c->d_cnt->n[stage - 2], 0, thr,
+                                      c->d_idx[stage - 1], c->d_sc[stage - 1], &c->d_cnt->n[stage - 1], st));
+    }
+    const int done[3] = {DONE_C1, DONE_C2, DONE_C3};
+    const int keep[3] = {DONE_PYR | DONE_S1, DONE_PYR | DONE_S1 | DONE_C1 | DONE_E2,
+                         DONE_PYR | DONE_S1 | DONE_C1 | DONE_E2 | DONE_C2 | DONE_E3};
+    c->progress = (c->progress & keep[stage - 1]) | done[stage - 1];
+    return CNNC_OK;
+}
+
+int cnnc_eval_stage(cnnc_ctx *c, int k, void *stream)
+{
+    if (!c) return CNNC_E_INVAL;
+    if (k != 2 && k != 3) return fail(c, CNNC_E_INVAL, "stage must be 2 or 3");
+    if (!(c->progress & (k == 2 ? DONE_C1 : DONE_C2))) return fail(c, CNNC_E_STATE, "evaluation needs the previous stage's survivors");
+    hipStream_t st = (hipStream_t)stream;
+    c->last_stream = st;
+    {
+        Timed t(c, k == 2 ? CNNC_T_STAGE2 : CNNC_T_STAGE3, st);
+        HIP_TRY(c, k == 2 ? launch_eval2(c, st) : launch_eval3(c, st));
+    }
+    const int keep = k == 2 ? (DONE_PYR | DONE_S1 | DONE_C1) : (DONE_PYR | DONE_S1 | DONE_C1 | DONE_E2 | DONE_C2);
+    c->progress = (c->progress & keep) | (k == 2 ? DONE_E2 : DONE_E3);
+    return CNNC_OK;
+}
+
+static int merge_enqueue(cnnc_ctx *c, hipStream_t st)
+{
+    if (!(c->progress & DONE_C3)) return fail(c, CNNC_E_STATE, "merging needs the stage-3 survivors");
+    c->last_stream = st;
+    {
+        Timed t(c, CNNC_T_MERGE, st);
+        HIP_TRY(c, launch_merge(c, st));
+    }
+    c->progress |= DONE_MERGE;
+    return enqueue_readback(c, st);
+}
+
+int cnnc_merge_detections(cnnc_ctx *c, cnnc_det *out, int cap, int *n_out, void *stream)
+{
+    if (!c) return CNNC_E_INVAL;
+    if ((!out && cap > 0) || cap < 0 || !n_out) return fail(c, CNNC_E_INVAL, "null output");
+    int rc = merge_enqueue(c, (hipStream_t)stream);
+    if (rc) return rc;
+    return fetch(c, out, cap, n_out);
+}
+
+int cnnc_detect_async(cnnc_ctx *c, const uint8_t *d_frame, int w, int h, int pitch, void *stream)
+{
+    int rc;
+    if ((rc = cnnc_build_pyramid(c, d_frame, w, h, pitch, stream))) return rc;
+    if ((rc = cnnc_stage1_scoremap(c, stream))) return rc;
+    if ((rc = cnnc_compact_survivors(c, 1, c->params.thr[0], stream))) return rc;
+    if ((rc = cnnc_eval_stage(c, 2, stream))) return rc;
+    if ((rc = cnnc_compact_survivors(c, 2, c->params.thr[1], stream))) return rc;
+    if ((rc = cnnc_eval_stage(c, 3, stream))) return rc;
+    if ((rc = cnnc_compact_survivors(c, 3, c->params.thr[2], stream))) return rc;
+    return merge_enqueue(c, (hipStream_t)stream);
+}
+
+int cnnc_fetch_detections(cnnc_ctx *c, cnnc_det *out, int cap, int *n_out)
+{
+    if (!c) return CNNC_E_INVAL;
+    if ((!out && cap > 0) || cap < 0 || !n_out) return fail(c, CNNC_E_INVAL, "null output");
+    if (!(c->progress & DONE_MERGE)) return fail(c, CNNC_E_STATE, "no detection pass was enqueued");
+    return fetch(c, out, cap, n_out);
+}
+
+int cnnc_detect(cnnc_ctx *c, const uint8_t *d_frame, int w, int h, int pitch, cnnc_det *out, int cap, int *n_out)
+{
+    if (!c) return CNNC_E_INVAL;
+    if ((!out && cap > 0) || cap < 0 || !n_out) return fail(c, CNNC_E_INVAL, "null output");
+    int rc = cnnc_detect_async(c, d_frame, w, h, pitch, nullptr);
+    if (rc) return rc;
+    return fetch(c, out, cap, n_out);
+}
+
+int cnnc_get_pyramid(cnnc_ctx *c, const uint8_t **d_pyramid, int64_t *n_bytes)
+{
+    if (!c) return CNNC_E_INVAL;
+    if (!(c->progress & DONE_PYR)) return fail(c, CNNC_E_STATE, "no pyramid yet");
+    if (d_pyramid) *d_pyramid = c->d_pyr;
+    if (n_bytes) *n_bytes = c->pyr_bytes;
+    return CNNC_OK;
+}
+
+int cnnc_get_scoremap(cnnc_ctx *c, const float **d_scores, int64_t *n_windows)
+{
+    if (!c) return CNNC_E_INVAL;
+    if (!(c->progress & DONE_S1)) return fail(c, CNNC_E_STATE, "no score map yet");
+    if (d_scores) *d_scores = c->d_score1;
+    if (n_windows) *n_windows = c->n_windows;
+    return CNNC_OK;
+}
+
+int cnnc_get_survivors(cnnc_ctx *c, int stage, const uint32_t **d_index, const float **d_score)
+{
+    if (!c) return CNNC_E_INVAL;
+    if (stage < 1 || stage > 3) return fail(c, CNNC_E_INVAL, "stage must be 1, 2 or 3");
+    if (d_index) *d_index = c->d_idx[stage - 1];
+    if (d_score) *d_score = c->d_sc[stage - 1];
+    return CNNC_OK;
+}
+
+int cnnc_get_stage_scores(cnnc_ctx *c, int k, const float **d_score)
+{
+    if (!c) return CNNC_E_INVAL;
+    if (k != 2 && k != 3) return fail(c, CNNC_E_INVAL, "stage must be 2 or 3");
+    if (d_score) *d_score = c->d_eval[k - 2];
+    return CNNC_OK;
+}
+
+int cnnc_survivor_count(cnnc_ctx *c, int stage, int *n, void *stream)
+{
+    if (!c) return CNNC_E_INVAL;
+    if (stage < 1 || stage > 3 || !n) return fail(c, CNNC_E_INVAL, "bad stage or null output");
+    const int done[3] = {DONE_C1, DONE_C2, DONE_C3};
+    if (!(c->progress & done[stage - 1])) return fail(c, CNNC_E_STATE, "that stage was not compacted");
+    hipStream_t st = (hipStream_t)stream;
+    HIP_TRY(c, hipMemcpyAsync(c->h_cnt, c->d_cnt, sizeof(Counters), hipMemcpyDeviceToHost, st));
+    HIP_TRY(c, hipStreamSynchronize(st));
+    *n = c->h_cnt->n[stage - 1];
+    return *n > c->max_surv ? fail(c, CNNC_E_OVERFLOW, "survivor list truncated") : CNNC_OK;
+}
+
+int cnnc_set_timing(cnnc_ctx *c, int on)
+{
+    if (!c) return CNNC_E_INVAL;
+    c->timing = on != 0;
+    return CNNC_OK;
+}
+
+int cnnc_get_timings(cnnc_ctx *c, double *ms_sum, int32_t *calls)
+{
+    if (!c) return CNNC_E_INVAL;
+    HIP_TRY(c, hipStreamSynchronize(c->last_stream));
+    for (int s = 0; s < CNNC_T_COUNT; ++s) {
+        StepTimer &t = c->timers[s];
+        for (size_t i = 0; i < t.begin.size(); ++i) {
+            float ms = 0;
+            HIP_TRY(c, hipEventSynchronize(t.end[i]));
+            HIP_TRY(c, hipEventElapsedTime(&ms, t.begin[i], t.end[i]));
+            t.ms += ms; t.calls += 1;
+            t.pool.push_back(t.begin[i]); t.pool.push_back(t.end[i]);
+        }
+        t.begin.clear(); t.end.clear();
+        if (ms_sum) ms_sum[s] = t.ms;
+        if (calls) calls[s] = t.calls;
+        t.ms = 0; t.calls = 0;
+    }
+    return CNNC_OK;
+}
+
+}  // extern "C"

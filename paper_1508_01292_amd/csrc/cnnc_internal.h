@@ -1,0 +1,135 @@
+// Internal declarations of libcnnc: context, device-side tables and kernel launchers.
+// Not part of the public interface (include/cnnc.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <string>
+#include <vector>
+
+#include "cnnc.h"
+
+namespace cnnc {
+
+// Network shapes the kernels are specialised for (Section 3.4 of the paper: code written per
+// architecture instead of a generic layer stack).
+constexpr int kWin = CNNC_WINDOW;          // stage-1 window
+constexpr int kS1Params = 409;
+constexpr int kS2In = 24, kS2Params = 9633;
+constexpr int kS3In = 48, kS3Params = 122977;
+
+// Offsets (in floats) of each layer's weights / biases inside a stage's blob.
+namespace s1 { constexpr int W1 = 0, B1 = 36, W2 = 40, B2 = 328, W3 = 336, B3 = 408; }
+namespace s2 {
+constexpr int W1 = 0, B1 = 200, W2 = 208, B2 = 1360, W3 = 1376, B3 = 9568, W4 = 9600, B4 = 9632;
+}
+namespace s3 {
+constexpr int W1 = 0, B1 = 400, W2 = 416, B2 = 13216, W3 = 13248, B3 = 22464, W4 = 22496, B4 = 122848,
+              W5 = 122912, B5 = 122976;
+}
+
+// One pyramid level as the kernels see it.
+struct LevelDev {
+    int32_t w, h;          // level size
+    int32_t ow, oh;        // score-map size (w - 11, h - 11)
+    int32_t pyr_off;       // first byte of the level in the pyramid buffer
+    int32_t score_off;     // first flat window index of the level
+    int32_t xmap_off;      // first entry of the level's column table in the tap table
+    int32_t ymap_off;      // first entry of the level's row table
+    int64_t scale_q16;     // round(scale * 65536)
+    double scale;          // scale of the level (frame pixels per level pixel)
+};
+
+// Small device-resident counters.
+struct Counters {
+    int32_t n[4];          // survivors of stage 1, 2, 3 and merged detections (untruncated counts)
+};
+
+struct StepTimer {
+    std::vector<hipEvent_t> begin, end;   // recorded pairs not yet read
+    std::vector<hipEvent_t> pool;         // events free for reuse
+    double ms = 0;
+    int calls = 0;
+};
+
+}  // namespace cnnc
+
+struct cnnc_ctx {
+    int device = 0;
+    int act = CNNC_ACT_RATIONAL;
+    int max_w = 0, max_h = 0, max_surv = 0;
+    cnnc_params params{};
+    std::string err;
+
+    // weights on the device: the caller's blobs
+    float *d_wt[3] = {nullptr, nullptr, nullptr};
+
+    // geometry of the current frame size / parameters
+    bool layout_valid = false;
+    int lay_w = 0, lay_h = 0;
+    int n_levels = 0;
+    std::vector<cnnc::LevelDev> levels;
+    int64_t pyr_bytes = 0, n_windows = 0;
+    int n_tiles_pyr = 0, n_tiles_s1 = 0;
+
+    // device buffers that depend on the layout
+    cnnc::LevelDev *d_levels = nullptr;
+    uint32_t *d_taps = nullptr;      // column / row tap tables of all levels
+    uint32_t *d_tiles_pyr = nullptr; // (level, tile) table of the pyramid kernel
+    uint32_t *d_tiles_s1 = nullptr;  // (level, tile) table of the stage-1 kernel
+    uint8_t *d_pyr = nullptr;
+    float *d_score1 = nullptr;
+    int64_t cap_pyr = 0, cap_score1 = 0, cap_taps = 0, cap_tiles_pyr = 0, cap_tiles_s1 = 0;
+
+    // survivor lists (capacity max_surv each)
+    uint32_t *d_idx[3] = {nullptr, nullptr, nullptr};
+    float *d_sc[3] = {nullptr, nullptr, nullptr};
+    float *d_eval[2] = {nullptr, nullptr};   // scores of stage 2 / 3, aligned with the previous list
+    int32_t *d_blockcnt = nullptr;           // compaction: per-block counts and offsets
+    int32_t cap_blocks = 0;
+    cnnc::Counters *d_cnt = nullptr;
+    cnnc::Counters *h_cnt = nullptr;         // pinned
+
+    // merge
+    int merge_cap = 0;
+    void *d_merge_ws = nullptr;              // sorted boxes, flags
+    cnnc_det *d_det = nullptr;
+    cnnc_det *h_det = nullptr;               // pinned
+
+    // current frame
+    const uint8_t *d_frame = nullptr;
+    int fw = 0, fh = 0, fpitch = 0;
+    int progress = 0;                        // bit mask of completed steps for CNNC_E_STATE checks
+    hipStream_t last_stream = nullptr;
+
+    bool timing = false;
+    cnnc::StepTimer timers[CNNC_T_COUNT];
+};
+
+namespace cnnc {
+
+// Kernel launchers (one translation unit each).  All enqueue on `st` and return the launch status.
+hipError_t launch_pyramid(const cnnc_ctx *c, hipStream_t st);
+hipError_t launch_stage1(const cnnc_ctx *c, hipStream_t st);
+// Compaction of `vals[0 .. n)`; n = *d_n clamped to n_max if d_n != nullptr, else n_literal.
+// src_idx == nullptr: the position itself is the index written.
+hipError_t launch_compact(const cnnc_ctx *c, const float *vals, const uint32_t *src_idx, const int32_t *d_n,
+                          int64_t n_literal, float thr, uint32_t *out_idx, float *out_sc, int32_t *d_count,
+                          hipStream_t st);
+hipError_t launch_eval2(const cnnc_ctx *c, hipStream_t st);
+hipError_t launch_eval3(const cnnc_ctx *c, hipStream_t st);
+hipError_t launch_merge(const cnnc_ctx *c, hipStream_t st);
+size_t merge_workspace_bytes(int merge_cap);
+
+constexpr int kCompactBlock = 256;
+constexpr int kCompactPerBlock = 2048;   // values handled by one workgroup
+
+// Stage-1 tile (outputs per workgroup) and pyramid tile.
+constexpr int kS1TileW = 32, kS1TileH = 24;
+constexpr int kPyrTileW = 64, kPyrTileH = 4;
+
+// tile table entry: level in the top 8 bits, tile row in the next 12, tile column in the low 12
+inline uint32_t pack_tile(int level, int ty, int tx) { return (uint32_t(level) << 24) | (uint32_t(ty) << 12) | uint32_t(tx); }
+
+}  // namespace cnnc

@@ -1,0 +1,134 @@
+// Survivor compaction (paper, Section 3.3: the coordinates of the windows whose response exceeded
+// the threshold are handed on).  Deterministic: the output keeps ascending input order, so no
+// atomics on the output position.  Three small launches: per-workgroup counts, a scan of the
+// counts, and the scatter; inside a workgroup each wave owns a contiguous run of the input and
+// ranks its survivors with ballots.
+#include "cnnc_internal.h"
+
+namespace cnnc {
+
+namespace {
+constexpr int kWaves = kCompactBlock / 64;
+constexpr int kPerWave = kCompactPerBlock / kWaves;   // contiguous values per wave
+constexpr int kIters = kPerWave / 64;
+
+__device__ __forceinline__ int64_t source_count(const int32_t *d_n, int64_t n_literal, int64_t n_max)
+{
+    if (d_n == nullptr) return n_literal;
+    const int64_t n = *d_n;
+    return n < n_max ? n : n_max;
+}
+}  // namespace
+
+__global__ __launch_bounds__(kCompactBlock)
+void compact_count_kernel(const float *__restrict__ vals, const int32_t *__restrict__ d_n, int64_t n_literal,
+                          int64_t n_max, float thr, int32_t *__restrict__ blockcnt)
+{
+    __shared__ int wsum[kWaves];
+    const int64_t n = source_count(d_n, n_literal, n_max);
+    const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
+    const int64_t base = (int64_t)blockIdx.x * kCompactPerBlock + (int64_t)wave * kPerWave;
+    int cnt = 0;
+    for (int it = 0; it < kIters; ++it) {
+        const int64_t e = base + it * 64 + lane;
+        const bool pass = e < n && vals[e] > thr;
+        cnt += __popcll(__ballot(pass));
+    }
+    if (lane == 0) wsum[wave] = cnt;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int s = 0;
+        for (int w = 0; w < kWaves; ++w) s += wsum[w];
+        blockcnt[blockIdx.x] = s;
+    }
+}
+
+// Exclusive scan of the per-workgroup counts (one workgroup, chunks of 1024 with a carry) and the
+// total into *d_count.
+__global__ __launch_bounds__(1024)
+void compact_scan_kernel(int32_t *__restrict__ blockcnt, int nblocks, int32_t *__restrict__ d_count)
+{
+    __shared__ int wtot[16];
+    __shared__ int carry_s;
+    const int lane = threadIdx.x % 64, wave = threadIdx.x / 64;
+    if (threadIdx.x == 0) carry_s = 0;
+    __syncthreads();
+    for (int base = 0; base < nblocks; base += 1024) {
+        const int i = base + threadIdx.x;
+        const int v = i < nblocks ? blockcnt[i] : 0;
+        int incl = v;
+        for (int d = 1; d < 64; d <<= 1) {
+            const int o = __shfl_up(incl, d, 64);
+            if (lane >= d) incl += o;
+        }
+        if (lane == 63) wtot[wave] = incl;
+        __syncthreads();
+        int woff = 0, total = 0;
+        for (int w = 0; w < 16; ++w) {
+            if (w < wave) woff += wtot[w];
+            total += wtot[w];
+        }
+        const int carry = carry_s;
+        if (i < nblocks) blockcnt[i] = carry + woff + incl - v;
+        __syncthreads();
+        if (threadIdx.x == 0) carry_s = carry + total;
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) *d_count = carry_s;
+}
+
+__global__ __launch_bounds__(kCompactBlock)
+void compact_scatter_kernel(const float *__restrict__ vals, const uint32_t *__restrict__ src_idx,
+                            const int32_t *__restrict__ d_n, int64_t n_literal, int64_t n_max, float thr,
+                            const int32_t *__restrict__ blockoff, uint32_t *__restrict__ out_idx,
+                            float *__restrict__ out_sc, int cap)
+{
+    __shared__ int wsum[kWaves];
+    const int64_t n = source_count(d_n, n_literal, n_max);
+    const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
+    const int64_t base = (int64_t)blockIdx.x * kCompactPerBlock + (int64_t)wave * kPerWave;
+    float v[kIters];
+    uint64_t mask[kIters];
+    int cnt = 0;
+#pragma unroll
+    for (int it = 0; it < kIters; ++it) {
+        const int64_t e = base + it * 64 + lane;
+        v[it] = e < n ? vals[e] : 0.0f;
+        mask[it] = __ballot(e < n && v[it] > thr);
+        cnt += __popcll(mask[it]);
+    }
+    if (lane == 0) wsum[wave] = cnt;
+    __syncthreads();
+    int pos = blockoff[blockIdx.x];
+    for (int w = 0; w < wave; ++w) pos += wsum[w];
+#pragma unroll
+    for (int it = 0; it < kIters; ++it) {
+        const uint64_t m = mask[it];
+        if ((m >> lane) & 1ull) {
+            const int p = pos + __popcll(m & ((1ull << lane) - 1ull));
+            if (p < cap) {
+                const int64_t e = base + it * 64 + lane;
+                out_idx[p] = src_idx ? src_idx[e] : (uint32_t)e;
+                out_sc[p] = v[it];
+            }
+        }
+        pos += __popcll(m);
+    }
+}
+
+hipError_t launch_compact(const cnnc_ctx *c, const float *vals, const uint32_t *src_idx, const int32_t *d_n,
+                          int64_t n_literal, float thr, uint32_t *out_idx, float *out_sc, int32_t *d_count,
+                          hipStream_t st)
+{
+    const int64_t n_max = d_n ? (int64_t)c->max_surv : n_literal;
+    int nblocks = (int)((n_max + kCompactPerBlock - 1) / kCompactPerBlock);
+    if (nblocks < 1) nblocks = 1;   // an empty input still has to write a zero count
+    hipLaunchKernelGGL(compact_count_kernel, dim3(nblocks), dim3(kCompactBlock), 0, st, vals, d_n, n_literal, n_max,
+                       thr, c->d_blockcnt);
+    hipLaunchKernelGGL(compact_scan_kernel, dim3(1), dim3(1024), 0, st, c->d_blockcnt, nblocks, d_count);
+    hipLaunchKernelGGL(compact_scatter_kernel, dim3(nblocks), dim3(kCompactBlock), 0, st, vals, src_idx, d_n,
+                       n_literal, n_max, thr, c->d_blockcnt, out_idx, out_sc, c->max_surv);
+    return hipGetLastError();
+}
+
+}  // namespace cnnc

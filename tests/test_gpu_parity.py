@@ -1,0 +1,309 @@
+"""GPU parity tests: the HIP path, called through the C ABI (ctypes binding), against the CPU oracle
+on the same seeded inputs, element by element."""
+import numpy as np
+import pytest
+
+import cnnc_inputs as I
+from oracle import oracle as O
+
+from parity import (assert_scores, assert_survivors, boxes_of, compare_with_trace, greedy_merge_check,
+                    run_gpu_steps)
+
+pytestmark = pytest.mark.gpu
+
+
+def _torch():
+    import torch
+    return torch
+
+
+def _ctx(cascade, weights, w, h, max_surv=200000):
+    import paper_1508_01292_amd as P
+    return P.Context(cascade, weights, w, h, max_surv)
+
+
+def _full_case(frame, cascade, weights, min_face, step, quantiles=(0.02, 0.2), name=""):
+    torch = _torch()
+    print("case", name, frame.shape, "min_face", min_face, "step", step, flush=True)
+    tr = O.detect(frame, cascade, weights, min_face, step, quantiles=quantiles)
+    ctx = _ctx(cascade, weights, frame.shape[1], frame.shape[0])
+    ctx.set_params(min_face, step, tr.thr)
+    g = run_gpu_steps(ctx, torch.from_numpy(frame).cuda(), tr.thr)
+    info = compare_with_trace(g, tr, frame, cascade, weights)
+    # the one-call wrapper gives the same detections as the step-by-step calls
+    det = [d.as_dict() for d in ctx.detect(torch.from_numpy(frame).cuda(), 8192)]
+    assert det == g["det"]
+    ctx.close()
+    print("   windows %d -> %d -> %d -> %d -> %d detections; band %s merge_exact %s"
+          % (tr.score1.size, len(g["idx1"]), len(g["idx2"]), len(g["idx3"]), len(g["det"]), info["band"],
+             info["merge_exact"]), flush=True)
+    return tr, g, info
+
+
+@pytest.mark.parametrize("act", [I.ACT_RATIONAL, I.ACT_SCALED_TANH, I.ACT_TANH])
+def test_vga_workload_every_activation(act):
+    c = I.CONFIGS[0]
+    casc = I.default_cascade(act)
+    W = I.draw_weights(casc, I.config_seed(0), bias_sd=0.0 if act == I.ACT_RATIONAL else 0.15)
+    frame = I.make_frame(c["width"], c["height"], I.config_seed(0))
+    tr, g, _ = _full_case(frame, casc, W, c["min_face"], c["scale_step"], name="vga act %d" % act)
+    assert tr.score1.size == 23659 and len(tr.idx1) == 473 and len(tr.idx2) == 94
+
+
+def test_fhd_workload():
+    c = I.CONFIGS[1]
+    casc = I.default_cascade()
+    W = I.draw_weights(casc, I.config_seed(1))
+    frame = I.make_frame(c["width"], c["height"], I.config_seed(1))
+    tr, g, _ = _full_case(frame, casc, W, c["min_face"], c["scale_step"], name="fhd")
+    assert tr.score1.size == 199030 and len(tr.idx1) == 3980 and len(tr.idx2) == 796
+
+
+def test_ragged_sizes_and_nonzero_biases():
+    """Odd frame sizes: level sizes that leave ragged tile tails in every kernel, small scale steps,
+    a pitch larger than the width."""
+    torch = _torch()
+    casc = I.default_cascade()
+    W = I.draw_weights(casc, 77, bias_sd=0.2)
+    for (w, h, mf, step) in ((333, 257, 24, 1.2), (131, 97, 12, 1.5), (257, 45, 14, 1.1)):
+        frame = I.make_frame(w, h, 1000 + w)
+        _full_case(frame, casc, W, mf, step, quantiles=(0.05, 0.3), name="ragged %dx%d" % (w, h))
+    # pitched frame (a view into a wider tensor)
+    big = I.make_frame(400, 200, 5)
+    view = big[10:190, 20:350]
+    tr = O.detect(np.ascontiguousarray(view), casc, W, 30, 1.25)
+    ctx = _ctx(casc, W, 400, 200)
+    ctx.set_params(30, 1.25, tr.thr)
+    g = run_gpu_steps(ctx, torch.from_numpy(big).cuda()[10:190, 20:350], tr.thr)
+    compare_with_trace(g, tr, np.ascontiguousarray(view), casc, W)
+    ctx.close()
+
+
+def test_degenerate_cases():
+    torch = _torch()
+    casc = I.default_cascade()
+    W = I.draw_weights(casc, 3, bias_sd=0.1)
+    # the smallest frame: one level, one window
+    frame = I.make_frame(12, 12, 9, n_ellipses=0)
+    tr = O.detect(frame, casc, W, 12, 2.0, thr=(-1e30, -1e30, -1e30))
+    assert tr.score1.size == 1 and len(tr.det) == 1
+    ctx = _ctx(casc, W, 64, 64, 16)
+    ctx.set_params(12, 2.0, tr.thr)
+    g = run_gpu_steps(ctx, torch.from_numpy(frame).cuda(), tr.thr)
+    compare_with_trace(g, tr, frame, casc, W)
+    # thresholds nothing passes: every later list is empty, no detections
+    frame = I.make_frame(64, 48, 10)
+    ctx.set_params(12, 1.5, (1e30, 0.0, 0.0))
+    g = run_gpu_steps(ctx, torch.from_numpy(frame).cuda(), (1e30, 0.0, 0.0))
+    assert len(g["idx1"]) == 0 and len(g["idx2"]) == 0 and len(g["idx3"]) == 0 and g["det"] == []
+    assert ctx.detect(torch.from_numpy(frame).cuda()) == []
+    ctx.close()
+
+
+def test_every_window_survives_and_capacity_overflow():
+    """Thresholds at -inf: the cascade degenerates to 'evaluate everything'; then a context whose lists
+    are too small must report the overflow and still hold valid truncated lists."""
+    import paper_1508_01292_amd as P
+    torch = _torch()
+    casc = I.default_cascade()
+    W = I.draw_weights(casc, 4)
+    frame = I.make_frame(48, 40, 12)
+    thr = (-1e30, -1e30, -1e30)
+    tr = O.detect(frame, casc, W, 12, 1.5, thr=thr)
+    n1 = tr.score1.size
+    assert len(tr.idx1) == n1 == len(tr.idx3)
+    ctx = _ctx(casc, W, 48, 40, 4096)
+    ctx.set_params(12, 1.5, thr)
+    g = run_gpu_steps(ctx, torch.from_numpy(frame).cuda(), thr)
+    compare_with_trace(g, tr, frame, casc, W)
+    ctx.close()
+    small = _ctx(casc, W, 48, 40, 100)
+    small.set_params(12, 1.5, thr)
+    ft = torch.from_numpy(frame).cuda()
+    small.build_pyramid(ft)
+    small.stage1_scoremap()
+    small.compact_survivors(1, thr[0])
+    with pytest.raises(P.CnncError) as e:
+        small.survivor_count(1)
+    assert e.value.code == -3
+    with pytest.raises(P.CnncError) as e:
+        small.detect(ft)
+    assert e.value.code == -3
+    # the first 100 entries are the first 100 windows
+    import ctypes as C
+    pi, ps = C.c_void_p(0), C.c_void_p(0)
+    P.lib().cnnc_get_survivors(small._h, C.c_int(1), C.byref(pi), C.byref(ps))
+    from paper_1508_01292_amd.binding import _d2h
+    assert _d2h(pi.value, 400, np.uint32).tolist() == list(range(100))
+    small.close()
+
+
+def test_detection_array_too_small_reports_overflow():
+    import paper_1508_01292_amd as P
+    torch = _torch()
+    casc = I.default_cascade()
+    W = I.draw_weights(casc, 1508)
+    frame = I.make_frame(320, 240, 33)
+    tr = O.detect(frame, casc, W, 60, 1.25)
+    assert len(tr.det) > 3
+    ctx = _ctx(casc, W, 320, 240)
+    ctx.set_params(60, 1.25, tr.thr)
+    with pytest.raises(P.CnncError) as e:
+        ctx.detect(torch.from_numpy(frame).cuda(), cap=3)
+    assert e.value.code == -3
+    ctx.close()
+
+
+def test_call_order_and_argument_errors():
+    import paper_1508_01292_amd as P
+    torch = _torch()
+    casc = I.default_cascade()
+    W = I.draw_weights(casc, 1)
+    ctx = _ctx(casc, W, 128, 128, 1000)
+    for call in (lambda: ctx.stage1_scoremap(), lambda: ctx.compact_survivors(1, 0.0), lambda: ctx.eval_stage(2),
+                 lambda: ctx.merge_detections(), lambda: ctx.fetch_detections(), lambda: ctx.get_scoremap()):
+        with pytest.raises(P.CnncError) as e:
+            call()
+        assert e.value.code == -5
+    for call in (lambda: ctx.compact_survivors(4, 0.0), lambda: ctx.eval_stage(1), lambda: ctx.set_params(6, 1.25),
+                 lambda: ctx.set_params(24, 1.0), lambda: ctx.compact_survivors(1, float("nan")),
+                 lambda: ctx.build_pyramid(torch.zeros(200, 200, dtype=torch.uint8, device="cuda")),
+                 lambda: ctx.build_pyramid(torch.zeros(8, 100, dtype=torch.uint8, device="cuda"))):
+        with pytest.raises(P.CnncError) as e:
+            call()
+        assert e.value.code == -1
+    ft = torch.from_numpy(I.make_frame(128, 100, 2)).cuda()
+    ctx.set_params(24, 1.25)
+    ctx.build_pyramid(ft)
+    with pytest.raises(P.CnncError) as e:
+        ctx.eval_stage(2)
+    assert e.value.code == -5
+    ctx.stage1_scoremap()
+    with pytest.raises(P.CnncError) as e:
+        ctx.compact_survivors(2, 0.0)
+    assert e.value.code == -5
+    ctx.close()
+    # unsupported network shape
+    bad = I.default_cascade()
+    bad[0] = I.Stage(12, (I.Layer(I.CONV, 1, 4, 3, 1), I.Layer(I.POOL, 4, 4, 2, 0), I.Layer(I.CONV, 4, 6, 3, 1),
+                          I.Layer(I.FC, 6, 1, 3, 0)))
+    with pytest.raises(P.CnncError) as e:
+        P.Context(bad, [np.zeros(bad[0].n_params, np.float32), W[1], W[2]], 128, 128, 100)
+    assert e.value.code == -1
+
+
+def test_layout_matches_oracle_for_all_workloads():
+    casc = I.default_cascade()
+    W = I.draw_weights(casc, 1)
+    ctx = _ctx(casc, W, 3840, 2160, 1000)
+    for c in I.CONFIGS[:4]:
+        ctx.set_params(c["min_face"], c["scale_step"])
+        lay = ctx.pyramid_layout(c["width"], c["height"])
+        ref = O.pyramid_layout(c["width"], c["height"], c["min_face"], c["scale_step"])
+        assert lay["lvl_w"] == ref.lvl_w and lay["lvl_h"] == ref.lvl_h and lay["scale"] == ref.scale
+        assert lay["score_off"] == ref.score_off
+    ctx.close()
+
+
+def test_runs_are_deterministic_and_contexts_reusable():
+    torch = _torch()
+    casc = I.default_cascade()
+    W = I.draw_weights(casc, 1508)
+    ctx = _ctx(casc, W, 640, 480)
+    f0 = I.make_frame(640, 480, 1)
+    f1 = I.make_frame(320, 200, 2)
+    thr = (0.5, -0.2, 0.0)
+    ctx.set_params(60, 1.25, thr)
+    a = run_gpu_steps(ctx, torch.from_numpy(f0).cuda(), thr)
+    b = run_gpu_steps(ctx, torch.from_numpy(f1).cuda(), thr)      # other size in between: buffers re-laid out
+    a2 = run_gpu_steps(ctx, torch.from_numpy(f0).cuda(), thr)
+    for k in ("pyramid", "score1", "idx1", "score2", "idx2", "score3", "idx3"):
+        assert np.array_equal(a[k], a2[k]), k
+    assert a["det"] == a2["det"] and len(b["score1"]) != len(a["score1"])
+    ctx.close()
+
+
+def test_async_contexts_on_streams_match_synchronous_results():
+    """Several frames in flight on separate streams (the paper's asynchronous mode maps to this):
+    every frame's detections equal those of a synchronous call."""
+    torch = _torch()
+    casc = I.default_cascade()
+    W = I.draw_weights(casc, I.config_seed(4))
+    frames = [I.make_frame(480, 270, I.config_seed(4), i, None) for i in range(6)]
+    thr = (0.6, -0.3, 0.0)
+    sync = _ctx(casc, W, 480, 270)
+    sync.set_params(60, 1.25, thr)
+    dev = [torch.from_numpy(f).cuda() for f in frames]
+    want = [[d.as_dict() for d in sync.detect(t, 8192)] for t in dev]
+    sync.close()
+    ctxs = [_ctx(casc, W, 480, 270) for _ in range(3)]
+    streams = [torch.cuda.Stream() for _ in range(3)]
+    for c in ctxs:
+        c.set_params(60, 1.25, thr)
+    torch.cuda.synchronize()
+    got = [None] * len(frames)
+    for base in range(0, len(frames), 3):
+        for j in range(3):
+            ctxs[j].detect_async(dev[base + j], streams[j])
+        for j in range(3):
+            got[base + j] = [d.as_dict() for d in ctxs[j].fetch_detections(8192)]
+    assert got == want
+    for c in ctxs:
+        c.close()
+
+
+def test_uhd_headline_workload_full_oracle():
+    """The 3840x2160, min-face-60 workload the throughput is quoted on, against the full oracle."""
+    c = I.CONFIGS[2]
+    casc = I.default_cascade()
+    W = I.draw_weights(casc, I.config_seed(2))
+    frame = I.make_frame(c["width"], c["height"], I.config_seed(2))
+    tr, g, _ = _full_case(frame, casc, W, c["min_face"], c["scale_step"], name="uhd")
+    assert tr.score1.size == 856540 and len(tr.idx1) == 17130 and len(tr.idx2) == 3426
+
+
+def test_uhd_small_faces_sampled():
+    """3840x2160 with 24-pixel faces (6.6 M windows): full score map and stage-1 survivors against the
+    dense oracle; later stages on a sample of the windows the GPU evaluated."""
+    torch = _torch()
+    c = I.CONFIGS[3]
+    casc = I.default_cascade()
+    W = I.draw_weights(casc, I.config_seed(3))
+    frame = I.make_frame(c["width"], c["height"], I.config_seed(3))
+    print("case uhd small faces", flush=True)
+    pyr = O.build_pyramid(frame, c["min_face"], c["scale_step"])
+    s1 = O.stage1_scores(pyr, casc[0], W[0])
+    assert s1.size == 6588676
+    t1 = O.threshold_from_quantile(s1, 0.02)
+    ctx = _ctx(casc, W, 3840, 2160, 200000)
+    ctx.set_params(c["min_face"], c["scale_step"], (t1, 0.0, 0.0))
+    ft = torch.from_numpy(frame).cuda()
+    ctx.build_pyramid(ft)
+    assert np.array_equal(ctx.get_pyramid(), np.concatenate([l.ravel() for l in pyr.levels]))
+    ctx.stage1_scoremap()
+    assert_scores(ctx.get_scoremap(), s1, "stage-1 score map")
+    ctx.compact_survivors(1, float(t1))
+    idx1, _ = ctx.get_survivors(1)
+    assert_survivors(idx1, s1, np.arange(s1.size), t1, "stage-1 survivors")
+    assert abs(len(idx1) - 131773) <= 3
+    ctx.eval_stage(2)
+    sc2 = ctx.get_stage_scores(2)
+    rng = np.random.default_rng(0)
+    pick = np.sort(rng.choice(len(idx1), 1500, replace=False))
+    assert_scores(sc2[pick], O.eval_stage(frame, pyr, idx1[pick], casc[1], W[1]), "stage-2 scores (sample)")
+    t2 = float(np.sort(sc2)[::-1][len(sc2) // 5])            # any threshold: survivors checked by property
+    ctx.compact_survivors(2, t2)
+    idx2, s2k = ctx.get_survivors(2)
+    assert np.array_equal(idx2, idx1[sc2 > np.float32(t2)]) and np.array_equal(s2k, sc2[sc2 > np.float32(t2)])
+    ctx.eval_stage(3)
+    sc3 = ctx.get_stage_scores(3)
+    pick = np.sort(rng.choice(len(idx2), 200, replace=False))
+    assert_scores(sc3[pick], O.eval_stage(frame, pyr, idx2[pick], casc[2], W[2]), "stage-3 scores (sample)")
+    ctx.compact_survivors(3, 0.0)
+    idx3, s3k = ctx.get_survivors(3)
+    assert np.array_equal(idx3, idx2[sc3 > 0]) and np.array_equal(s3k, sc3[sc3 > 0])
+    det = [d.as_dict() for d in ctx.merge_detections(32768)]
+    bx, by, bs, _ = boxes_of(pyr, idx3)
+    assert [(d["index"], d["neighbors"]) for d in det] == \
+        [(int(idx3[p]), n) for p, n in greedy_merge_check(bx, by, bs, s3k, idx3)]
+    ctx.close()

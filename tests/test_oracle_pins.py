@@ -479,3 +479,22 @@ def test_cascade_bookkeeping_small_frame():
     # the per-window form gives the same survivors on this frame
     tr2 = O.detect(f, casc, W, 60, 1.25, form="windows")
     assert np.array_equal(tr.idx1, tr2.idx1) and np.array_equal(tr.idx3, tr2.idx3)
+
+
+def test_numpy_merge_check_agrees_with_oracle_merge():
+    """The test-side greedy merge used as a validity check in the GPU tests is itself checked here."""
+    from parity import boxes_of, greedy_merge_check
+    rng = np.random.default_rng(23)
+    for n in (1, 40, 300):
+        bx, by = rng.integers(0, 300, n), rng.integers(0, 300, n)
+        bs, sc = rng.integers(20, 120, n), rng.standard_normal(n).astype(np.float32)
+        sc[n // 2:] = sc[:n - n // 2]                       # exact ties
+        order = rng.permutation(n)
+        for mn in (1, 2):
+            kept, nb = O.merge(bx, by, bs, sc, order, 0.3, mn)
+            assert [(int(p), int(k)) for p, k in zip(kept, nb)] == greedy_merge_check(bx, by, bs, sc, order, 0.3, mn)
+    p = O.pyramid_layout(640, 480, 60, 1.25)
+    idx = rng.integers(0, p.score_off[-1], 200)
+    a = O.window_boxes(p, idx)
+    b = boxes_of(p, idx)
+    assert all(np.array_equal(u, v) for u, v in zip(a, b[:3]))
