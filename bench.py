@@ -1,0 +1,174 @@
+#!/usr/bin/env python3
+"""Benchmark of the cascade hot path on one MI355X.
+
+A step is one whole pass (pyramid -> stage-1 score map -> compaction -> stage 2 -> compaction ->
+stage 3 -> compaction -> merge -> detections on the host) over one synthetic 3840x2160 frame that is
+already resident in device memory.  Prints ONE JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--inflight F] [--workload uhd|uhd_small_faces|fhd|vga]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+METRIC = "frames/sec at 3840x2160, min face 60 px (full cascade); stage-1 windows/sec"
+
+# Algorithmic work per unit ("Rooflines").
+S1_FLOP_PER_WINDOW = 2 * 396
+S2_FLOP_PER_CROP = 2 * 161952
+S3_FLOP_PER_CROP = 2 * 5473600
+PEAK_HBM = 8000.0          # GB/s
+PEAK_FP32_VECTOR = 157.3   # TFLOP/s, published vector fp32 figure
+PEAK_FP32_MFMA = 157.3     # TFLOP/s, published dense fp32 matrix figure
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=300)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--inflight", type=int, default=3, help="frames in flight on separate streams")
+    ap.add_argument("--workload", default="uhd")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    a = ap.parse_args()
+    if a.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus %d is not supported (no collectives, no sharding)" % a.gpus,
+              file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import cnnc_inputs as I
+    import paper_1508_01292_amd as P
+    from oracle import oracle as O
+
+    ci = [c["name"] for c in I.CONFIGS].index(a.workload)
+    cfg = I.CONFIGS[ci]
+    seed = I.config_seed(ci)
+    casc = I.default_cascade()
+    W = I.draw_weights(casc, seed)
+    frame = I.make_frame(cfg["width"], cfg["height"], seed)
+
+    # ---- CPU oracle: thresholds at the survival quantiles (the oracle's job) and the cpu_baseline leg
+    t0 = time.perf_counter()
+    tr = O.detect(frame, casc, W, cfg["min_face"], cfg["scale_step"], quantiles=(0.02, 0.2))
+    t_cpu = time.perf_counter() - t0
+    n_windows = int(tr.score1.size)
+    cpu = None
+    if not a.no_cpu_baseline:
+        cpu = {"value": 1.0 / t_cpu, "unit": "frames/s", "cores": O.num_threads(), "kind": "oracle",
+               "sample": "1 whole %dx%d frame through the oracle (dense stage-1 form, fp64, OpenMP): %.2f s; "
+                         "stage-1 windows/s on the CPU = %.3g" % (cfg["width"], cfg["height"], t_cpu, n_windows / t_cpu)}
+
+    # ---- GPU
+    torch.cuda.set_device(0)
+    dev_frame = torch.from_numpy(frame).cuda()
+    F = max(1, a.inflight)
+    ctxs = [P.Context(casc, W, cfg["width"], cfg["height"], 262144) for _ in range(F)]
+    streams = [torch.cuda.Stream() for _ in range(F)]
+    for c in ctxs:
+        c.set_params(cfg["min_face"], cfg["scale_step"], tr.thr)
+
+    def run(n_steps):
+        busy = [False] * F
+        n_det = 0
+        for i in range(n_steps):
+            j = i % F
+            if busy[j]:
+                n_det = len(ctxs[j].fetch_detections(8192))
+            ctxs[j].detect_async(dev_frame, streams[j])
+            busy[j] = True
+        for j in range(F):
+            if busy[j]:
+                n_det = len(ctxs[j].fetch_detections(8192))
+        return n_det
+
+    run(a.warmup)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    n_det = run(a.steps)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    fps = a.steps / elapsed
+
+    # one frame at a time (latency), same context
+    c0 = ctxs[0]
+    for _ in range(3):
+        c0.detect(dev_frame, 8192)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    n_lat = max(10, a.steps // 4)
+    for _ in range(n_lat):
+        c0.detect(dev_frame, 8192)
+    torch.cuda.synchronize()
+    latency_ms = (time.perf_counter() - t0) / n_lat * 1e3
+
+    # per-kernel times: HIP events recorded by the library on the stream the kernels run on
+    c0.set_timing(True)
+    c0.get_timings()
+    for _ in range(a.steps):
+        c0.detect_async(dev_frame, streams[0])
+        c0.fetch_detections(8192)
+    tm = c0.get_timings()
+    c0.set_timing(False)
+    ms = {k: (v[0] / v[1] if v[1] else 0.0) for k, v in tm.items()}
+    n1, n2, n3 = (c0.survivor_count(s) for s in (1, 2, 3))
+    lay = c0.pyramid_layout(cfg["width"], cfg["height"])
+    pyr_bytes = lay["pyr_off"][-1]
+
+    def tflops(flop, t_ms):
+        return flop / (t_ms * 1e-3) / 1e12 if t_ms > 0 else 0.0
+
+    def gbs(nbytes, t_ms):
+        return nbytes / (t_ms * 1e-3) / 1e9 if t_ms > 0 else 0.0
+
+    kernels = {
+        "pyramid": {"bound": "hbm", "ms": ms["pyramid"], "achieved": gbs(cfg["width"] * cfg["height"] + pyr_bytes, ms["pyramid"]),
+                    "peak": PEAK_HBM, "unit": "GB/s"},
+        "stage1": {"bound": "alu", "ms": ms["stage1"], "achieved": tflops(S1_FLOP_PER_WINDOW * n_windows, ms["stage1"]),
+                   "peak": PEAK_FP32_VECTOR, "unit": "TFLOP/s"},
+        "compact1": {"bound": "hbm", "ms": ms["compact1"], "achieved": gbs(4 * n_windows + 8 * n1, ms["compact1"]),
+                     "peak": PEAK_HBM, "unit": "GB/s"},
+        "stage2": {"bound": "alu", "ms": ms["stage2"], "achieved": tflops(S2_FLOP_PER_CROP * n1, ms["stage2"]),
+                   "peak": PEAK_FP32_VECTOR, "unit": "TFLOP/s"},
+        "stage3": {"bound": "alu", "ms": ms["stage3"], "achieved": tflops(S3_FLOP_PER_CROP * n2, ms["stage3"]),
+                   "peak": PEAK_FP32_VECTOR, "unit": "TFLOP/s"},
+        "compact2": {"ms": ms["compact2"]}, "compact3": {"ms": ms["compact3"]}, "merge": {"ms": ms["merge"]},
+    }
+    for k in kernels.values():
+        if "achieved" in k:
+            k["frac"] = k["achieved"] / k["peak"]
+    dom = max(("stage1", "stage2", "stage3", "pyramid", "compact1"), key=lambda k: ms[k])
+    roof = dict(kernels[dom])
+    roof.update({"kernel": dom, "traffic": None})
+    roof.pop("ms")
+    roof["avg_launch_ms"] = ms[dom]
+
+    out = {
+        "metric": METRIC, "value": fps, "unit": "frames/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+        "ms_per_step": elapsed / a.steps * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "%s: one %dx%d uint8 frame, min face %g px, scale step %g, 2%% / 20%% survival quantiles, T3 = 0"
+                               % (cfg["name"], cfg["width"], cfg["height"], cfg["min_face"], cfg["scale_step"]),
+                   "frames_in_flight": F, "windows": n_windows, "survivors": [n1, n2, n3], "detections": n_det},
+        "stage1_windows_per_s": n_windows / (ms["stage1"] * 1e-3) if ms["stage1"] > 0 else None,
+        "latency_ms_single_frame": latency_ms,
+        "sum_of_kernel_ms": sum(ms.values()),
+        "roofline": roof,
+        "kernels": kernels,
+        "cpu_baseline": cpu,
+    }
+    for c in ctxs:
+        c.close()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

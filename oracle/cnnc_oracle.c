@@ -28,6 +28,9 @@
 #include <stdint.h>
 #include <stdlib.h>
 #include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
 
 enum { ORC_CONV = 0, ORC_POOL = 1, ORC_FC = 2 };
 enum { ORC_ACT_NONE = 0, ORC_ACT_RATIONAL = 1, ORC_ACT_SCALED_TANH = 2, ORC_ACT_TANH = 3 };
@@ -38,6 +41,16 @@ typedef struct {
     int32_t k;   /* kernel side; FC: side of its input map */
     int32_t act; /* ORC_ACT_* applied to the output */
 } orc_layer;
+
+/* Threads the parallel loops below will use (for reporting timings).        */
+int orc_num_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
 
 /* ------------------------------------------------------------------------ */
 /* Activation.  Paper, Section 3.1, eq. (1): f(x) = 1.7159 tanh(2x/3) with   */

@@ -50,6 +50,10 @@ def _layers(stage):
     return arr
 
 
+def num_threads() -> int:
+    return int(lib().orc_num_threads())
+
+
 def rational_tanh(y: float) -> float:
     return lib().orc_rational_tanh(float(y))
 
