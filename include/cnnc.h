@@ -101,7 +101,7 @@ enum {
  *   stage 2: 24x24 | conv5 1->8, pool, conv3 8->16, pool, fc 16x4x4->32, fc 32->1
  *   stage 3: 48x48 | conv5 1->16, pool, conv5 16->32, pool, conv3 32->32, fc 32x7x7->64, fc 64->1
  *   hidden layers all use one activation kind (1, 2 or 3), output layers kind 0.
- * max_w, max_h: largest frame accepted.  max_survivors: capacity of every survivor list
+ * max_w, max_h: largest frame accepted.  max_survivors (<= 2^20): capacity of every survivor list
  * (stage 1, 2 and 3) and of the merge input.  Allocates device memory (hipMalloc). */
 int cnnc_create(cnnc_ctx **out, const cnnc_stage_desc stages[3], int max_w, int max_h, int max_survivors);
 int cnnc_destroy(cnnc_ctx *ctx);
@@ -173,6 +173,11 @@ int cnnc_survivor_count(cnnc_ctx *ctx, int stage, int *n, void *stream);
  * reset and the number of calls per step (host arrays of CNNC_T_COUNT entries), then resets. */
 int cnnc_set_timing(cnnc_ctx *ctx, int on);
 int cnnc_get_timings(cnnc_ctx *ctx, double *ms_sum, int32_t *calls);
+
+/* Which kernels cnnc_eval_stage uses: 1 (default) = implicit-GEMM kernels on the matrix cores (fp32 MFMA),
+ * 0 = direct convolution on the vector ALU.  Same results within rounding; kept so that the choice stays
+ * measurable (the paper's Section 3.4 argues for code specialised per network and processor). */
+int cnnc_set_eval_impl(cnnc_ctx *ctx, int impl);
 
 const char *cnnc_last_error(const cnnc_ctx *ctx);
 const char *cnnc_version(void);

@@ -18,7 +18,7 @@ EXPORTS = [
     "cnnc_stage1_scoremap", "cnnc_compact_survivors", "cnnc_eval_stage", "cnnc_merge_detections",
     "cnnc_detect", "cnnc_detect_async", "cnnc_fetch_detections", "cnnc_get_pyramid", "cnnc_get_scoremap",
     "cnnc_get_survivors", "cnnc_get_stage_scores", "cnnc_survivor_count", "cnnc_set_timing",
-    "cnnc_get_timings", "cnnc_last_error", "cnnc_version",
+    "cnnc_get_timings", "cnnc_set_eval_impl", "cnnc_last_error", "cnnc_version",
 ]
 STEP_NAMES = ["pyramid", "stage1", "compact1", "stage2", "compact2", "stage3", "compact3", "merge"]
 MAX_LEVELS = 64
@@ -229,6 +229,9 @@ class Context:
         p = C.c_void_p(0)
         self._check(lib().cnnc_get_stage_scores(self._h, C.c_int(k), C.byref(p)))
         return _d2h(p.value, n * 4, np.float32)
+
+    def set_eval_impl(self, impl: int):
+        self._check(lib().cnnc_set_eval_impl(self._h, C.c_int(impl)))
 
     def set_timing(self, on: bool):
         self._check(lib().cnnc_set_timing(self._h, C.c_int(1 if on else 0)))

@@ -229,7 +229,7 @@ int cnnc_create(cnnc_ctx **out, const cnnc_stage_desc stages[3], int max_w, int 
     if (!out) return CNNC_E_INVAL;
     *out = nullptr;
     if (!stages || max_w < kWin || max_h < kWin || max_w > 16384 || max_h > 16384 || max_survivors < 1 ||
-        max_survivors > (1 << 24))
+        max_survivors > (1 << 20))
         return CNNC_E_INVAL;
     const int a1 = check_stage(stages[0], kStage1, 4, 12);
     const int a2 = check_stage(stages[1], kStage2, 6, kS2In);
@@ -252,6 +252,15 @@ int cnnc_create(cnnc_ctx **out, const cnnc_stage_desc stages[3], int max_w, int 
         if (hipMalloc((void **)&c->d_wt[s], sizeof(float) * n_params[s]) != hipSuccess) return bail(CNNC_E_NOMEM);
         if (hipMemcpy(c->d_wt[s], stages[s].weights, sizeof(float) * n_params[s], hipMemcpyHostToDevice) != hipSuccess)
             return bail(CNNC_E_HIP);
+    }
+    {
+        std::vector<float> frag(eval3_frag_floats());
+        eval3_make_fragments(stages[2].weights, frag.data());
+        if (hipMalloc((void **)&c->d_frag[1], sizeof(float) * frag.size()) != hipSuccess) return bail(CNNC_E_NOMEM);
+        if (hipMemcpy(c->d_frag[1], frag.data(), sizeof(float) * frag.size(), hipMemcpyHostToDevice) != hipSuccess)
+            return bail(CNNC_E_HIP);
+        if (hipMalloc((void **)&c->d_feat[1], sizeof(float) * eval3_feat_floats() * (size_t)max_survivors) != hipSuccess)
+            return bail(CNNC_E_NOMEM);
     }
     for (int s = 0; s < 3; ++s) {
         if (hipMalloc((void **)&c->d_idx[s], sizeof(uint32_t) * (size_t)max_survivors) != hipSuccess) return bail(CNNC_E_NOMEM);
@@ -276,7 +285,7 @@ int cnnc_destroy(cnnc_ctx *c)
     if (!c) return CNNC_E_INVAL;
     (void)hipDeviceSynchronize();
     for (int s = 0; s < 3; ++s) { (void)hipFree(c->d_wt[s]); (void)hipFree(c->d_idx[s]); (void)hipFree(c->d_sc[s]); }
-    for (int s = 0; s < 2; ++s) (void)hipFree(c->d_eval[s]);
+    for (int s = 0; s < 2; ++s) { (void)hipFree(c->d_eval[s]); (void)hipFree(c->d_frag[s]); (void)hipFree(c->d_feat[s]); }
     (void)hipFree(c->d_levels); (void)hipFree(c->d_taps); (void)hipFree(c->d_tiles_pyr); (void)hipFree(c->d_tiles_s1);
     (void)hipFree(c->d_pyr); (void)hipFree(c->d_score1); (void)hipFree(c->d_blockcnt); (void)hipFree(c->d_cnt);
     (void)hipFree(c->d_merge_ws); (void)hipFree(c->d_det);
@@ -392,7 +401,8 @@ int cnnc_eval_stage(cnnc_ctx *c, int k, void *stream)
     c->last_stream = st;
     {
         Timed t(c, k == 2 ? CNNC_T_STAGE2 : CNNC_T_STAGE3, st);
-        HIP_TRY(c, k == 2 ? launch_eval2(c, st) : launch_eval3(c, st));
+        if (k == 2) HIP_TRY(c, launch_eval2(c, st));
+        else HIP_TRY(c, c->eval_impl ? launch_eval3_mfma(c, st) : launch_eval3(c, st));
     }
     const int keep = k == 2 ? (DONE_PYR | DONE_S1 | DONE_C1) : (DONE_PYR | DONE_S1 | DONE_C1 | DONE_E2 | DONE_C2);
     c->progress = (c->progress & keep) | (k == 2 ? DONE_E2 : DONE_E3);
@@ -496,6 +506,14 @@ int cnnc_survivor_count(cnnc_ctx *c, int stage, int *n, void *stream)
     HIP_TRY(c, hipStreamSynchronize(st));
     *n = c->h_cnt->n[stage - 1];
     return *n > c->max_surv ? fail(c, CNNC_E_OVERFLOW, "survivor list truncated") : CNNC_OK;
+}
+
+int cnnc_set_eval_impl(cnnc_ctx *c, int impl)
+{
+    if (!c) return CNNC_E_INVAL;
+    if (impl != 0 && impl != 1) return fail(c, CNNC_E_INVAL, "implementation must be 0 or 1");
+    c->eval_impl = impl;
+    return CNNC_OK;
 }
 
 int cnnc_set_timing(cnnc_ctx *c, int on)

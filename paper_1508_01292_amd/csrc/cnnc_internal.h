@@ -64,6 +64,11 @@ struct cnnc_ctx {
 
     // weights on the device: the caller's blobs
     float *d_wt[3] = {nullptr, nullptr, nullptr};
+    // stages 2 / 3 on the matrix cores: weights re-ordered into MFMA operand fragments, and the
+    // per-window activations handed from the convolution kernel to the fully connected kernel
+    float *d_frag[2] = {nullptr, nullptr};
+    float *d_feat[2] = {nullptr, nullptr};
+    int eval_impl = 1;                        // 1: MFMA kernels, 0: direct convolution on the vector ALU
 
     // geometry of the current frame size / parameters
     bool layout_valid = false;
@@ -119,6 +124,10 @@ hipError_t launch_compact(const cnnc_ctx *c, const float *vals, const uint32_t *
                           hipStream_t st);
 hipError_t launch_eval2(const cnnc_ctx *c, hipStream_t st);
 hipError_t launch_eval3(const cnnc_ctx *c, hipStream_t st);
+hipError_t launch_eval3_mfma(const cnnc_ctx *c, hipStream_t st);
+size_t eval3_frag_floats();
+size_t eval3_feat_floats();
+void eval3_make_fragments(const float *blob, float *frag);
 hipError_t launch_merge(const cnnc_ctx *c, hipStream_t st);
 size_t merge_workspace_bytes(int merge_cap);
 

@@ -1,0 +1,316 @@
+// Stages 2 and 3 on the matrix cores (paper, Section 3.3, selective unit; Section 3.4: code written
+// for each network shape).
+//
+// The convolutions of the later stages are dense contractions once a crop sits in LDS: stage-3 conv2
+// is M = 324 positions x N = 32 channels x K = 400 per crop.  They run as implicit GEMMs on
+// v_mfma_f32_16x16x4_f32 (fp32 in, fp32 accumulate):
+//   * A operand (16 positions x 4 k) is read straight from the LDS map: lane (i = lane % 16,
+//     g = lane / 16) reads the input value of position i for k-index g of the step.
+//   * B operand (4 k x 16 channels) comes from weights that the host re-orders once into the lane
+//     order of the instruction ("fragments"), so a wave loads them with one coalesced access.
+//   * The 16 positions of a tile are four 2x2 pooling blocks, so the four accumulator registers of a
+//     lane are exactly one pooling block of one channel: max-pool, bias and activation happen in
+//     registers and only the pooled map goes back to LDS.
+// The order of the k-indices is free as long as A and B agree; it is chosen so that the LDS address
+// of the A operand is (per-lane base) + (compile-time or wave-uniform offset).
+//
+// The fully connected layers are batched over crops in a second kernel (M = crops), so their
+// weights are read once per 16 crops instead of once per crop.
+#include "eval_common.h"
+
+namespace cnnc {
+
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+#define CNNC_MFMA(a, b, c) __builtin_amdgcn_mfma_f32_16x16x4f32((a), (b), (c), 0, 0, 0)
+
+namespace {
+using namespace evalc;
+
+__device__ __forceinline__ float max4(const floatx4 v) { return fmaxf(fmaxf(v[0], v[1]), fmaxf(v[2], v[3])); }
+
+// ---- stage 3 geometry ---------------------------------------------------------------------------
+constexpr int kCropW = 48;                 // crop row pitch in LDS
+constexpr int kP1Row = 24, kP1Ch = 22 * kP1Row;   // pooled conv1 map [16][22][24] (row padded: bank spread)
+constexpr int kP2Ch = 81;                  // pooled conv2 map [32][9*9]
+constexpr int kRegionA = 32 * kP2Ch;       // crop (2304) then pooled conv2 map (2592)
+constexpr int kRegionB = 16 * kP1Ch;       // pooled conv1 map (8448) then conv3 output (1568)
+
+// conv2 of stage 3 for the NT position tiles wslot, wslot + 4, ... of one crop.
+template <int NT, int ACT>
+__device__ __forceinline__ void s3_conv2(const float *sP1, float *sP2, const float *__restrict__ B2F, int wslot,
+                                         int lane, float bias_lo, float bias_hi)
+{
+    const int i = lane & 15, g = lane >> 4;
+    floatx4 acc[NT][2];
+    int abase[NT];
+#pragma unroll
+    for (int u = 0; u < NT; ++u) {
+        acc[u][0] = floatx4{0, 0, 0, 0};
+        acc[u][1] = floatx4{0, 0, 0, 0};
+        const int pb = min(4 * (wslot + 4 * u) + (i >> 2), 80);       // pooling block of this lane's position
+        const int y = 2 * (pb / 9) + ((i >> 1) & 1), x = 2 * (pb % 9) + (i & 1);
+        abase[u] = g * kP1Ch + y * kP1Row + x;
+    }
+    const float4 *bp = reinterpret_cast<const float4 *>(B2F) + lane;   // [tap][n-tile][lane] float4 (4 channel quads)
+    float4 bc0 = bp[0], bc1 = bp[64];
+#pragma unroll 1
+    for (int tap = 0; tap < 25; ++tap) {
+        const int tn = min(tap + 1, 24);
+        const float4 bn0 = bp[tn * 128], bn1 = bp[tn * 128 + 64];      // next tap's weights, in flight during the math
+        const int toff = (tap / 5) * kP1Row + tap % 5;
+        const float b0[4] = {bc0.x, bc0.y, bc0.z, bc0.w}, b1[4] = {bc1.x, bc1.y, bc1.z, bc1.w};
+#pragma unroll
+        for (int cq = 0; cq < 4; ++cq)
+#pragma unroll
+            for (int u = 0; u < NT; ++u) {
+                const float a = sP1[abase[u] + toff + cq * 4 * kP1Ch];
+                acc[u][0] = CNNC_MFMA(a, b0[cq], acc[u][0]);
+                acc[u][1] = CNNC_MFMA(a, b1[cq], acc[u][1]);
+            }
+        bc0 = bn0; bc1 = bn1;
+    }
+    const int j = lane & 15;
+#pragma unroll
+    for (int u = 0; u < NT; ++u) {
+        const int pb = 4 * (wslot + 4 * u) + g;
+        if (pb < 81) {
+            sP2[j * kP2Ch + pb] = act_f<ACT>(max4(acc[u][0]) + bias_lo);
+            sP2[(16 + j) * kP2Ch + pb] = act_f<ACT>(max4(acc[u][1]) + bias_hi);
+        }
+    }
+}
+}  // namespace
+
+// Fragment buffer of stage 3 (floats): conv1 [7][64], conv2 [25][2][64][4], conv3 [9][2][64][8], fc [98][4][64][4].
+constexpr int kS3F1 = 0, kS3F2 = kS3F1 + 7 * 64, kS3F3 = kS3F2 + 25 * 2 * 64 * 4, kS3F4 = kS3F3 + 9 * 2 * 64 * 8,
+              kS3FragFloats = kS3F4 + 98 * 4 * 64 * 4;
+constexpr int kS3Feat = 1568;
+
+// Crop -> conv1 -> pool -> conv2 -> pool -> conv3 for each surviving window; writes the 1568 conv3
+// activations of the window (order [channel][row][col]) to `feat`.
+template <int ACT>
+__global__ __launch_bounds__(kThreads)
+void eval3_conv_kernel(const uint8_t *__restrict__ frame, int fw, int fh, int pitch, const LevelDev *__restrict__ levels,
+                       int n_levels, const uint32_t *__restrict__ idx, const int32_t *__restrict__ d_n, int n_max,
+                       const float *__restrict__ wt, const float *__restrict__ frag, float *__restrict__ feat)
+{
+    __shared__ float sA[kRegionA];
+    __shared__ float sB[kRegionB];
+    __shared__ uint32_t sTab[2 * kS3In];
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, g = lane >> 4, j = lane & 15;
+
+    float b1f[7];
+#pragma unroll
+    for (int s = 0; s < 7; ++s) b1f[s] = frag[kS3F1 + s * 64 + lane];
+    const float bias1 = wt[s3::B1 + j];
+    const float bias2_lo = wt[s3::B2 + j], bias2_hi = wt[s3::B2 + 16 + j];
+    const float bias3_lo = wt[s3::B3 + j], bias3_hi = wt[s3::B3 + 16 + j];
+    // conv1 k-order: steps 0..4 = taps (a = step, b = g); step 5 = taps (a = g, b = 4);
+    // step 6 = tap (4, 4) in group 0, zero weights elsewhere (those lanes re-read their own pixel)
+    const int off5 = g * kCropW + 4, off6 = g == 0 ? 4 * kCropW + 4 : 0;
+
+    const int n = min(*d_n, n_max);
+    int rot = 0;
+    for (int crop = blockIdx.x; crop < n; crop += gridDim.x, ++rot) {
+        const Survivor sv = decode(idx[crop], levels, n_levels);
+        gather_crop<kS3In>(frame, fw, fh, pitch, sv.x, sv.y, levels[sv.level].scale_q16, sTab, sA);
+
+        // ---- conv1 5x5 1->16 + pool: 121 tiles of four pooling blocks, four tiles in flight per wave
+#pragma unroll 1
+        for (int q0 = 0; q0 < 32; q0 += 4) {
+            floatx4 acc[4];
+            int base[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                acc[u] = floatx4{0, 0, 0, 0};
+                const int t = min(wave + 4 * (q0 + u), 120);
+                const int pb = 4 * t + (j >> 2);
+                base[u] = (2 * (pb / 22) + ((j >> 1) & 1)) * kCropW + 2 * (pb % 22) + (j & 1);
+            }
+#pragma unroll
+            for (int s = 0; s < 5; ++s)
+#pragma unroll
+                for (int u = 0; u < 4; ++u) acc[u] = CNNC_MFMA(sA[base[u] + g + s * kCropW], b1f[s], acc[u]);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) acc[u] = CNNC_MFMA(sA[base[u] + off5], b1f[5], acc[u]);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) acc[u] = CNNC_MFMA(sA[base[u] + off6], b1f[6], acc[u]);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int t = wave + 4 * (q0 + u);
+                if (t < 121) {
+                    const int pb = 4 * t + g;
+                    sB[j * kP1Ch + (pb / 22) * kP1Row + pb % 22] = act_f<ACT>(max4(acc[u]) + bias1);
+                }
+            }
+        }
+        __syncthreads();
+
+        // ---- conv2 5x5 16->32 + pool: 21 tiles; the wave that takes six of them rotates per crop
+        const int wslot = (wave + rot) & 3;
+        if (wslot == 0) s3_conv2<6, ACT>(sB, sA, frag + kS3F2, wslot, lane, bias2_lo, bias2_hi);
+        else s3_conv2<5, ACT>(sB, sA, frag + kS3F2, wslot, lane, bias2_lo, bias2_hi);
+        __syncthreads();
+
+        // ---- conv3 3x3 32->32: 49 positions = 4 tiles, one per wave; two accumulator sets for ILP
+        {
+            const int pos = min(16 * wave + j, 48);
+            const int abase = g * kP2Ch + (pos / 7) * 9 + pos % 7;
+            floatx4 acc[2][2] = {{floatx4{0, 0, 0, 0}, floatx4{0, 0, 0, 0}}, {floatx4{0, 0, 0, 0}, floatx4{0, 0, 0, 0}}};
+            const float4 *bp = reinterpret_cast<const float4 *>(frag + kS3F3) + lane * 2;   // [tap][n-tile][lane][8]
+#pragma unroll 1
+            for (int tap = 0; tap < 9; ++tap) {
+                const float4 p0 = bp[(tap * 2) * 128], p1 = bp[(tap * 2) * 128 + 1];
+                const float4 q0 = bp[(tap * 2 + 1) * 128], q1 = bp[(tap * 2 + 1) * 128 + 1];
+                const float b0[8] = {p0.x, p0.y, p0.z, p0.w, p1.x, p1.y, p1.z, p1.w};
+                const float b1[8] = {q0.x, q0.y, q0.z, q0.w, q1.x, q1.y, q1.z, q1.w};
+                const int toff = (tap / 3) * 9 + tap % 3;
+#pragma unroll
+                for (int cq = 0; cq < 8; ++cq) {
+                    const float a = sA[abase + toff + cq * 4 * kP2Ch];
+                    acc[cq & 1][0] = CNNC_MFMA(a, b0[cq], acc[cq & 1][0]);
+                    acc[cq & 1][1] = CNNC_MFMA(a, b1[cq], acc[cq & 1][1]);
+                }
+            }
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int p = 16 * wave + 4 * g + r;
+                if (p < 49) {
+                    sB[j * 49 + p] = act_f<ACT>(acc[0][0][r] + acc[1][0][r] + bias3_lo);
+                    sB[(16 + j) * 49 + p] = act_f<ACT>(acc[0][1][r] + acc[1][1][r] + bias3_hi);
+                }
+            }
+        }
+        __syncthreads();
+
+        // ---- conv3 activations to global memory, coalesced
+        {
+            float4 *dst = reinterpret_cast<float4 *>(feat + (size_t)crop * kS3Feat);
+            const float4 *src = reinterpret_cast<const float4 *>(sB);
+            for (int e = tid; e < kS3Feat / 4; e += kThreads) dst[e] = src[e];
+        }
+        __syncthreads();
+    }
+}
+
+// fc 1568->64 + f, fc 64->1 for 16 windows per workgroup: the four waves split K, partial tiles meet in LDS.
+template <int ACT>
+__global__ __launch_bounds__(kThreads)
+void eval3_fc_kernel(const float *__restrict__ feat, const int32_t *__restrict__ d_n, int n_max,
+                     const float *__restrict__ wt, const float *__restrict__ frag, float *__restrict__ out)
+{
+    __shared__ float sPart[4][16][65];
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, g = lane >> 4, j = lane & 15;
+    const int n = min(*d_n, n_max);
+    const float4 *wf = reinterpret_cast<const float4 *>(frag + kS3F4) + lane;     // [chunk][n-tile][lane] float4
+    for (int tile = blockIdx.x; tile * 16 < n; tile += gridDim.x) {
+        const int row = min(tile * 16 + j, n - 1);
+        const float4 *ap = reinterpret_cast<const float4 *>(feat + (size_t)row * kS3Feat) + g;
+        floatx4 acc[4] = {floatx4{0, 0, 0, 0}, floatx4{0, 0, 0, 0}, floatx4{0, 0, 0, 0}, floatx4{0, 0, 0, 0}};
+#pragma unroll 2
+        for (int ch = wave; ch < 98; ch += 4) {
+            const float4 a4 = ap[ch * 4];
+            const float a[4] = {a4.x, a4.y, a4.z, a4.w};
+            float4 b4[4];
+#pragma unroll
+            for (int nt = 0; nt < 4; ++nt) b4[nt] = wf[(ch * 4 + nt) * 64];
+#pragma unroll
+            for (int s = 0; s < 4; ++s)
+#pragma unroll
+                for (int nt = 0; nt < 4; ++nt) {
+                    const float b = s == 0 ? b4[nt].x : s == 1 ? b4[nt].y : s == 2 ? b4[nt].z : b4[nt].w;
+                    acc[nt] = CNNC_MFMA(a[s], b, acc[nt]);
+                }
+        }
+#pragma unroll
+        for (int nt = 0; nt < 4; ++nt)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) sPart[wave][4 * g + r][nt * 16 + j] = acc[nt][r];
+        __syncthreads();
+        {
+            const int r = tid >> 4, c0 = tid & 15;
+            float part = 0.0f;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int c = c0 + 16 * q;
+                const float h = sPart[0][r][c] + sPart[1][r][c] + sPart[2][r][c] + sPart[3][r][c] + wt[s3::B4 + c];
+                part = fmaf(wt[s3::W5 + c], act_f<ACT>(h), part);
+            }
+#pragma unroll
+            for (int d = 8; d >= 1; d >>= 1) part += __shfl_xor(part, d, 64);
+            if (c0 == 0 && tile * 16 + r < n) out[tile * 16 + r] = part + wt[s3::B5];
+        }
+        __syncthreads();
+    }
+}
+
+// ---- host: weight fragments ---------------------------------------------------------------------
+size_t eval3_frag_floats() { return kS3FragFloats; }
+size_t eval3_feat_floats() { return kS3Feat; }
+
+// Re-order the stage-3 weights (blob layout: [cout][cin][k][k] per layer) into MFMA B fragments.
+void eval3_make_fragments(const float *w, float *f)
+{
+    for (int s = 0; s < 7; ++s)
+        for (int lane = 0; lane < 64; ++lane) {
+            const int g = lane >> 4, j = lane & 15;
+            int a = -1, b = -1;
+            if (s < 5) { a = s; b = g; }
+            else if (s == 5) { a = g; b = 4; }
+            else if (g == 0) { a = 4; b = 4; }
+            f[kS3F1 + s * 64 + lane] = a < 0 ? 0.0f : w[s3::W1 + (j * 5 + a) * 5 + b];
+        }
+    for (int tap = 0; tap < 25; ++tap)
+        for (int nt = 0; nt < 2; ++nt)
+            for (int lane = 0; lane < 64; ++lane)
+                for (int cq = 0; cq < 4; ++cq) {
+                    const int g = lane >> 4, j = lane & 15, oc = nt * 16 + j, c = 4 * cq + g;
+                    f[kS3F2 + ((tap * 2 + nt) * 64 + lane) * 4 + cq] = w[s3::W2 + (oc * 16 + c) * 25 + tap];
+                }
+    for (int tap = 0; tap < 9; ++tap)
+        for (int nt = 0; nt < 2; ++nt)
+            for (int lane = 0; lane < 64; ++lane)
+                for (int cq = 0; cq < 8; ++cq) {
+                    const int g = lane >> 4, j = lane & 15, oc = nt * 16 + j, c = 4 * cq + g;
+                    f[kS3F3 + ((tap * 2 + nt) * 64 + lane) * 8 + cq] = w[s3::W3 + (oc * 32 + c) * 9 + tap];
+                }
+    for (int ch = 0; ch < 98; ++ch)
+        for (int nt = 0; nt < 4; ++nt)
+            for (int lane = 0; lane < 64; ++lane)
+                for (int s = 0; s < 4; ++s) {
+                    const int g = lane >> 4, j = lane & 15;
+                    f[kS3F4 + ((ch * 4 + nt) * 64 + lane) * 4 + s] = w[s3::W4 + (nt * 16 + j) * 1568 + 16 * ch + 4 * g + s];
+                }
+}
+
+namespace {
+int conv_grid(const cnnc_ctx *c)
+{
+    const int g = 256 * 3;   // three workgroups fit a compute unit's LDS; each strides over the list
+    return c->max_surv < g ? c->max_surv : g;
+}
+int fc_grid(const cnnc_ctx *c)
+{
+    const int tiles = (c->max_surv + 15) / 16;
+    return tiles < 1024 ? tiles : 1024;
+}
+}  // namespace
+
+hipError_t launch_eval3_mfma(const cnnc_ctx *c, hipStream_t st)
+{
+#define CNNC_E3(ACT)                                                                                              \
+    hipLaunchKernelGGL(eval3_conv_kernel<ACT>, dim3(conv_grid(c)), dim3(kThreads), 0, st, c->d_frame, c->fw, c->fh, \
+                       c->fpitch, c->d_levels, c->n_levels, c->d_idx[1], &c->d_cnt->n[1], c->max_surv, c->d_wt[2], \
+                       c->d_frag[1], c->d_feat[1]);                                                                \
+    hipLaunchKernelGGL(eval3_fc_kernel<ACT>, dim3(fc_grid(c)), dim3(kThreads), 0, st, c->d_feat[1], &c->d_cnt->n[1], \
+                       c->max_surv, c->d_wt[2], c->d_frag[1], c->d_eval[1])
+    switch (c->act) {
+    case CNNC_ACT_RATIONAL: CNNC_E3(CNNC_ACT_RATIONAL); break;
+    case CNNC_ACT_SCALED_TANH: CNNC_E3(CNNC_ACT_SCALED_TANH); break;
+    default: CNNC_E3(CNNC_ACT_TANH); break;
+    }
+#undef CNNC_E3
+    return hipGetLastError();
+}
+
+}  // namespace cnnc

@@ -59,6 +59,22 @@ def test_fhd_workload():
     assert tr.score1.size == 199030 and len(tr.idx1) == 3980 and len(tr.idx2) == 796
 
 
+def test_vector_alu_variant_of_later_stages():
+    """cnnc_set_eval_impl(0): the direct-convolution kernels kept beside the matrix-core ones."""
+    torch = _torch()
+    c = I.CONFIGS[0]
+    casc = I.default_cascade()
+    W = I.draw_weights(casc, 5, bias_sd=0.1)
+    frame = I.make_frame(c["width"], c["height"], 55)
+    tr = O.detect(frame, casc, W, c["min_face"], c["scale_step"])
+    ctx = _ctx(casc, W, c["width"], c["height"])
+    ctx.set_params(c["min_face"], c["scale_step"], tr.thr)
+    ctx.set_eval_impl(0)
+    g = run_gpu_steps(ctx, torch.from_numpy(frame).cuda(), tr.thr)
+    compare_with_trace(g, tr, frame, casc, W)
+    ctx.close()
+
+
 def test_ragged_sizes_and_nonzero_biases():
     """Odd frame sizes: level sizes that leave ragged tile tails in every kernel, small scale steps,
     a pitch larger than the width."""
