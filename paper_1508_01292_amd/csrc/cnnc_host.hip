@@ -273,6 +273,7 @@ int cnnc_create(cnnc_ctx **out, const cnnc_stage_desc stages[3], int max_w, int 
     if (hipHostMalloc((void **)&c->h_cnt, sizeof(Counters), hipHostMallocDefault) != hipSuccess) return bail(CNNC_E_NOMEM);
     memset(c->h_cnt, 0, sizeof(Counters));
     if (hipMalloc(&c->d_merge_ws, merge_workspace_bytes(c->merge_cap)) != hipSuccess) return bail(CNNC_E_NOMEM);
+    if (merge_init_workspace(c) != hipSuccess) return bail(CNNC_E_HIP);
     if (hipMalloc((void **)&c->d_det, sizeof(cnnc_det) * (size_t)c->merge_cap) != hipSuccess) return bail(CNNC_E_NOMEM);
     if (hipHostMalloc((void **)&c->h_det, sizeof(cnnc_det) * (size_t)c->merge_cap, hipHostMallocDefault) != hipSuccess)
         return bail(CNNC_E_NOMEM);

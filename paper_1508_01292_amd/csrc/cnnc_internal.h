@@ -130,6 +130,7 @@ size_t eval3_feat_floats();
 void eval3_make_fragments(const float *blob, float *frag);
 hipError_t launch_merge(const cnnc_ctx *c, hipStream_t st);
 size_t merge_workspace_bytes(int merge_cap);
+hipError_t merge_init_workspace(const cnnc_ctx *c);
 
 constexpr int kCompactBlock = 256;
 constexpr int kCompactPerBlock = 2048;   // values handled by one workgroup

@@ -132,6 +132,12 @@ def test_every_window_survives_and_capacity_overflow():
     ctx.set_params(12, 1.5, thr)
     g = run_gpu_steps(ctx, torch.from_numpy(frame).cuda(), thr)
     compare_with_trace(g, tr, frame, casc, W)
+    # densely overlapping boxes give long chains in the merge; also with a neighbour requirement
+    for mn, iou in ((3, 0.3), (1, 0.6), (2, 0.05)):
+        trn = O.detect(frame, casc, W, 12, 1.5, thr=thr, min_neighbors=mn, iou=iou)
+        ctx.set_params(12, 1.5, thr, merge_iou=iou, min_neighbors=mn)
+        det = [d.as_dict() for d in ctx.detect(torch.from_numpy(frame).cuda(), 8192)]
+        assert [(d["index"], d["neighbors"]) for d in det] == [(d["index"], d["neighbors"]) for d in trn.det], (mn, iou)
     ctx.close()
     small = _ctx(casc, W, 48, 40, 100)
     small.set_params(12, 1.5, thr)
