@@ -254,6 +254,15 @@ int cnnc_create(cnnc_ctx **out, const cnnc_stage_desc stages[3], int max_w, int 
             return bail(CNNC_E_HIP);
     }
     {
+        std::vector<float> frag(eval2_frag_floats());
+        eval2_make_fragments(stages[1].weights, frag.data());
+        if (hipMalloc((void **)&c->d_frag[0], sizeof(float) * frag.size()) != hipSuccess) return bail(CNNC_E_NOMEM);
+        if (hipMemcpy(c->d_frag[0], frag.data(), sizeof(float) * frag.size(), hipMemcpyHostToDevice) != hipSuccess)
+            return bail(CNNC_E_HIP);
+        if (hipMalloc((void **)&c->d_feat[0], sizeof(float) * eval2_feat_floats() * (size_t)max_survivors) != hipSuccess)
+            return bail(CNNC_E_NOMEM);
+    }
+    {
         std::vector<float> frag(eval3_frag_floats());
         eval3_make_fragments(stages[2].weights, frag.data());
         if (hipMalloc((void **)&c->d_frag[1], sizeof(float) * frag.size()) != hipSuccess) return bail(CNNC_E_NOMEM);
@@ -402,7 +411,7 @@ int cnnc_eval_stage(cnnc_ctx *c, int k, void *stream)
     c->last_stream = st;
     {
         Timed t(c, k == 2 ? CNNC_T_STAGE2 : CNNC_T_STAGE3, st);
-        if (k == 2) HIP_TRY(c, launch_eval2(c, st));
+        if (k == 2) HIP_TRY(c, c->eval_impl ? launch_eval2_mfma(c, st) : launch_eval2(c, st));
         else HIP_TRY(c, c->eval_impl ? launch_eval3_mfma(c, st) : launch_eval3(c, st));
     }
     const int keep = k == 2 ? (DONE_PYR | DONE_S1 | DONE_C1) : (DONE_PYR | DONE_S1 | DONE_C1 | DONE_E2 | DONE_C2);

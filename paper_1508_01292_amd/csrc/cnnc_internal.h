@@ -125,6 +125,10 @@ hipError_t launch_compact(const cnnc_ctx *c, const float *vals, const uint32_t *
 hipError_t launch_eval2(const cnnc_ctx *c, hipStream_t st);
 hipError_t launch_eval3(const cnnc_ctx *c, hipStream_t st);
 hipError_t launch_eval3_mfma(const cnnc_ctx *c, hipStream_t st);
+hipError_t launch_eval2_mfma(const cnnc_ctx *c, hipStream_t st);
+size_t eval2_frag_floats();
+size_t eval2_feat_floats();
+void eval2_make_fragments(const float *blob, float *frag);
 size_t eval3_frag_floats();
 size_t eval3_feat_floats();
 void eval3_make_fragments(const float *blob, float *frag);

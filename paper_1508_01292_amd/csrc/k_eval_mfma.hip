@@ -283,6 +283,201 @@ void eval3_make_fragments(const float *w, float *f)
                 }
 }
 
+// =================================================================================================
+// Stage 2.  The network is small (162 k MAC per crop), so one WAVE owns a crop: no workgroup barriers,
+// four independent crops per workgroup, everything of a crop in that wave's slice of LDS.
+// =================================================================================================
+namespace {
+constexpr int kC2W = 24;                                   // crop row pitch
+constexpr int kQ1Row = 16, kQ1Ch = 10 * kQ1Row + 8;        // pooled conv1 map [8][10][16], channel pitch 168 (bank spread)
+constexpr int kS2Crop = 24 * 24, kS2Tab = 48, kS2P1 = 8 * kQ1Ch;
+constexpr int kS2WaveFloats = kS2Crop + kS2Tab + kS2P1;    // 1968 floats per wave
+static_assert(kS2WaveFloats % 4 == 0, "per-wave LDS slices must keep 16-byte alignment");
+
+// Orders this wave's LDS writes before its later LDS reads by other lanes.
+__device__ __forceinline__ void wave_sync()
+{
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
+    __builtin_amdgcn_wave_barrier();
+}
+}  // namespace
+
+// Fragment buffer of stage 2 (floats): conv1 [7][64], conv2 [9 taps][2 quads][64], fc [16][2][64][4].
+constexpr int kS2F1 = 0, kS2F2 = kS2F1 + 7 * 64, kS2F3 = kS2F2 + 18 * 64, kS2FragFloats = kS2F3 + 16 * 2 * 64 * 4;
+constexpr int kS2Feat = 256;
+
+template <int ACT>
+__global__ __launch_bounds__(kThreads)
+void eval2_conv_kernel(const uint8_t *__restrict__ frame, int fw, int fh, int pitch, const LevelDev *__restrict__ levels,
+                       int n_levels, const uint32_t *__restrict__ idx, const int32_t *__restrict__ d_n, int n_max,
+                       const float *__restrict__ wt, const float *__restrict__ frag, float *__restrict__ feat)
+{
+    __shared__ __attribute__((aligned(16))) float sMem[4][kS2WaveFloats];
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, g = lane >> 4, j = lane & 15;
+    float *sCrop = sMem[wave];
+    uint32_t *sTab = reinterpret_cast<uint32_t *>(sCrop + kS2Crop);
+    float *sP1 = sCrop + kS2Crop + kS2Tab;
+    float *sP2 = sCrop;                          // pooled conv2 output [16][16] re-uses the crop's space
+
+    float b1f[7], b2f[18];
+#pragma unroll
+    for (int s = 0; s < 7; ++s) b1f[s] = frag[kS2F1 + s * 64 + lane];
+#pragma unroll
+    for (int s = 0; s < 18; ++s) b2f[s] = frag[kS2F2 + s * 64 + lane];
+    const float bias1 = j < 8 ? wt[s2::B1 + j] : 0.0f, bias2 = wt[s2::B2 + j];
+    const int off5 = g * kC2W + 4, off6 = g == 0 ? 4 * kC2W + 4 : 0;     // conv1 k-order as in stage 3
+
+    const int n = min(*d_n, n_max);
+    for (int crop = blockIdx.x * 4 + wave; crop < n; crop += gridDim.x * 4) {
+        const Survivor sv = decode(idx[crop], levels, n_levels);
+        const int64_t S = levels[sv.level].scale_q16;
+        if (lane < 24) crop_axis<kS2In>(sv.x, S, fw, sTab, lane);
+        else if (lane < 48) crop_axis<kS2In>(sv.y, S, fh, sTab + 24, lane - 24);
+        wave_sync();
+#pragma unroll 3
+        for (int it = 0; it < 9; ++it) {
+            const int e = it * 64 + lane, r = e / 24, q = e % 24;
+            const uint32_t ex = sTab[q], ey = sTab[24 + r];
+            const int x0 = ex >> 9, y0 = ey >> 9;
+            const uint32_t wx = ex & 511u, wy = ey & 511u;
+            const int x1 = min(x0 + 1, fw - 1), y1 = min(y0 + 1, fh - 1);
+            const uint8_t *r0 = frame + (size_t)y0 * pitch, *r1 = frame + (size_t)y1 * pitch;
+            const uint32_t acc = r0[x0] * (256u - wx) * (256u - wy) + r0[x1] * wx * (256u - wy)
+                               + r1[x0] * (256u - wx) * wy + r1[x1] * wx * wy;
+            sCrop[e] = normalise((float)acc * (1.0f / 65536.0f));
+        }
+        wave_sync();
+
+        // ---- conv1 5x5 1->8 + pool: 25 tiles of four pooling blocks, five in flight
+#pragma unroll 1
+        for (int t0 = 0; t0 < 25; t0 += 5) {
+            floatx4 acc[5];
+            int base[5];
+#pragma unroll
+            for (int u = 0; u < 5; ++u) {
+                acc[u] = floatx4{0, 0, 0, 0};
+                const int pb = 4 * (t0 + u) + (j >> 2);
+                base[u] = (2 * (pb / 10) + ((j >> 1) & 1)) * kC2W + 2 * (pb % 10) + (j & 1);
+            }
+#pragma unroll
+            for (int s = 0; s < 5; ++s)
+#pragma unroll
+                for (int u = 0; u < 5; ++u) acc[u] = CNNC_MFMA(sCrop[base[u] + g + s * kC2W], b1f[s], acc[u]);
+#pragma unroll
+            for (int u = 0; u < 5; ++u) acc[u] = CNNC_MFMA(sCrop[base[u] + off5], b1f[5], acc[u]);
+#pragma unroll
+            for (int u = 0; u < 5; ++u) acc[u] = CNNC_MFMA(sCrop[base[u] + off6], b1f[6], acc[u]);
+            if (j < 8) {
+#pragma unroll
+                for (int u = 0; u < 5; ++u) {
+                    const int pb = 4 * (t0 + u) + g;
+                    sP1[j * kQ1Ch + (pb / 10) * kQ1Row + pb % 10] = act_f<ACT>(max4(acc[u]) + bias1);
+                }
+            }
+        }
+        wave_sync();
+
+        // ---- conv2 3x3 8->16 + pool: 16 pooling blocks = 4 tiles
+        {
+            floatx4 acc[4];
+            int abase[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                acc[u] = floatx4{0, 0, 0, 0};
+                const int pb = 4 * u + (j >> 2);
+                abase[u] = g * kQ1Ch + (2 * (pb / 4) + ((j >> 1) & 1)) * kQ1Row + 2 * (pb % 4) + (j & 1);
+            }
+#pragma unroll
+            for (int tap = 0; tap < 9; ++tap)
+#pragma unroll
+                for (int cq = 0; cq < 2; ++cq)
+#pragma unroll
+                    for (int u = 0; u < 4; ++u)
+                        acc[u] = CNNC_MFMA(sP1[abase[u] + (tap / 3) * kQ1Row + tap % 3 + cq * 4 * kQ1Ch], b2f[tap * 2 + cq], acc[u]);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) sP2[j * 16 + 4 * u + g] = act_f<ACT>(max4(acc[u]) + bias2);
+        }
+        wave_sync();
+        reinterpret_cast<float4 *>(feat + (size_t)crop * kS2Feat)[lane] = reinterpret_cast<const float4 *>(sP2)[lane];
+        wave_sync();
+    }
+}
+
+// fc 256->32 + f, fc 32->1 for 16 windows per workgroup; the four waves split K.
+template <int ACT>
+__global__ __launch_bounds__(kThreads)
+void eval2_fc_kernel(const float *__restrict__ feat, const int32_t *__restrict__ d_n, int n_max,
+                     const float *__restrict__ wt, const float *__restrict__ frag, float *__restrict__ out)
+{
+    __shared__ float sPart[4][16][33];
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, g = lane >> 4, j = lane & 15;
+    const int n = min(*d_n, n_max);
+    const float4 *wf = reinterpret_cast<const float4 *>(frag + kS2F3) + lane;     // [chunk][n-tile][lane] float4
+    for (int tile = blockIdx.x; tile * 16 < n; tile += gridDim.x) {
+        const int row = min(tile * 16 + j, n - 1);
+        const float4 *ap = reinterpret_cast<const float4 *>(feat + (size_t)row * kS2Feat) + g;
+        floatx4 acc[2] = {floatx4{0, 0, 0, 0}, floatx4{0, 0, 0, 0}};
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int ch = wave + 4 * q;
+            const float4 a4 = ap[ch * 4];
+            const float4 p = wf[(ch * 2) * 64], r = wf[(ch * 2 + 1) * 64];
+            acc[0] = CNNC_MFMA(a4.x, p.x, acc[0]); acc[1] = CNNC_MFMA(a4.x, r.x, acc[1]);
+            acc[0] = CNNC_MFMA(a4.y, p.y, acc[0]); acc[1] = CNNC_MFMA(a4.y, r.y, acc[1]);
+            acc[0] = CNNC_MFMA(a4.z, p.z, acc[0]); acc[1] = CNNC_MFMA(a4.z, r.z, acc[1]);
+            acc[0] = CNNC_MFMA(a4.w, p.w, acc[0]); acc[1] = CNNC_MFMA(a4.w, r.w, acc[1]);
+        }
+#pragma unroll
+        for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) sPart[wave][4 * g + r][nt * 16 + j] = acc[nt][r];
+        __syncthreads();
+        {
+            const int r = tid >> 4, c0 = tid & 15;
+            float part = 0.0f;
+#pragma unroll
+            for (int q = 0; q < 2; ++q) {
+                const int c = c0 + 16 * q;
+                const float h = sPart[0][r][c] + sPart[1][r][c] + sPart[2][r][c] + sPart[3][r][c] + wt[s2::B3 + c];
+                part = fmaf(wt[s2::W4 + c], act_f<ACT>(h), part);
+            }
+#pragma unroll
+            for (int d = 8; d >= 1; d >>= 1) part += __shfl_xor(part, d, 64);
+            if (c0 == 0 && tile * 16 + r < n) out[tile * 16 + r] = part + wt[s2::B4];
+        }
+        __syncthreads();
+    }
+}
+
+size_t eval2_frag_floats() { return kS2FragFloats; }
+size_t eval2_feat_floats() { return kS2Feat; }
+
+void eval2_make_fragments(const float *w, float *f)
+{
+    for (int s = 0; s < 7; ++s)
+        for (int lane = 0; lane < 64; ++lane) {
+            const int g = lane >> 4, j = lane & 15;
+            int a = -1, b = -1;
+            if (s < 5) { a = s; b = g; }
+            else if (s == 5) { a = g; b = 4; }
+            else if (g == 0) { a = 4; b = 4; }
+            f[kS2F1 + s * 64 + lane] = (a < 0 || j >= 8) ? 0.0f : w[s2::W1 + (j * 5 + a) * 5 + b];
+        }
+    for (int tap = 0; tap < 9; ++tap)
+        for (int cq = 0; cq < 2; ++cq)
+            for (int lane = 0; lane < 64; ++lane) {
+                const int g = lane >> 4, j = lane & 15, c = 4 * cq + g;
+                f[kS2F2 + (tap * 2 + cq) * 64 + lane] = w[s2::W2 + (j * 8 + c) * 9 + tap];
+            }
+    for (int ch = 0; ch < 16; ++ch)
+        for (int nt = 0; nt < 2; ++nt)
+            for (int lane = 0; lane < 64; ++lane)
+                for (int s = 0; s < 4; ++s) {
+                    const int g = lane >> 4, j = lane & 15;
+                    f[kS2F3 + ((ch * 2 + nt) * 64 + lane) * 4 + s] = w[s2::W3 + (nt * 16 + j) * 256 + 16 * ch + 4 * g + s];
+                }
+}
+
 namespace {
 int conv_grid(const cnnc_ctx *c)
 {
@@ -310,6 +505,25 @@ hipError_t launch_eval3_mfma(const cnnc_ctx *c, hipStream_t st)
     default: CNNC_E3(CNNC_ACT_TANH); break;
     }
 #undef CNNC_E3
+    return hipGetLastError();
+}
+
+hipError_t launch_eval2_mfma(const cnnc_ctx *c, hipStream_t st)
+{
+    const int waves = c->max_surv < 256 * 3 * 4 ? c->max_surv : 256 * 3 * 4;   // three workgroups of four crops per compute unit (register limit)
+    const int grid = (waves + 3) / 4;
+#define CNNC_E2(ACT)                                                                                              \
+    hipLaunchKernelGGL(eval2_conv_kernel<ACT>, dim3(grid), dim3(kThreads), 0, st, c->d_frame, c->fw, c->fh,         \
+                       c->fpitch, c->d_levels, c->n_levels, c->d_idx[0], &c->d_cnt->n[0], c->max_surv, c->d_wt[1], \
+                       c->d_frag[0], c->d_feat[0]);                                                                \
+    hipLaunchKernelGGL(eval2_fc_kernel<ACT>, dim3(fc_grid(c)), dim3(kThreads), 0, st, c->d_feat[0], &c->d_cnt->n[0], \
+                       c->max_surv, c->d_wt[1], c->d_frag[0], c->d_eval[0])
+    switch (c->act) {
+    case CNNC_ACT_RATIONAL: CNNC_E2(CNNC_ACT_RATIONAL); break;
+    case CNNC_ACT_SCALED_TANH: CNNC_E2(CNNC_ACT_SCALED_TANH); break;
+    default: CNNC_E2(CNNC_ACT_TANH); break;
+    }
+#undef CNNC_E2
     return hipGetLastError();
 }
 
