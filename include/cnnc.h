@@ -179,6 +179,11 @@ int cnnc_get_timings(cnnc_ctx *ctx, double *ms_sum, int32_t *calls);
  * measurable (the paper's Section 3.4 argues for code specialised per network and processor). */
 int cnnc_set_eval_impl(cnnc_ctx *ctx, int impl);
 
+/* Measurement aid for benchmarks: what this GPU sustains on three synthetic probes (dense fp32 MFMA loop,
+ * fp32 FMA loop on the vector ALU, 1 GiB device-to-device copy counted as read + write).  Runs on the
+ * current device's default stream, allocates and frees 2 GiB, synchronises.  Outputs are host pointers. */
+int cnnc_measure_peaks(double *mfma_f32_tflops, double *valu_f32_tflops, double *hbm_copy_gbs);
+
 const char *cnnc_last_error(const cnnc_ctx *ctx);
 const char *cnnc_version(void);
 

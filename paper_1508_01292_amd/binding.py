@@ -18,7 +18,7 @@ EXPORTS = [
     "cnnc_stage1_scoremap", "cnnc_compact_survivors", "cnnc_eval_stage", "cnnc_merge_detections",
     "cnnc_detect", "cnnc_detect_async", "cnnc_fetch_detections", "cnnc_get_pyramid", "cnnc_get_scoremap",
     "cnnc_get_survivors", "cnnc_get_stage_scores", "cnnc_survivor_count", "cnnc_set_timing",
-    "cnnc_get_timings", "cnnc_set_eval_impl", "cnnc_last_error", "cnnc_version",
+    "cnnc_get_timings", "cnnc_set_eval_impl", "cnnc_measure_peaks", "cnnc_last_error", "cnnc_version",
 ]
 STEP_NAMES = ["pyramid", "stage1", "compact1", "stage2", "compact2", "stage3", "compact3", "merge"]
 MAX_LEVELS = 64
@@ -241,6 +241,15 @@ class Context:
         calls = (C.c_int32 * len(STEP_NAMES))()
         self._check(lib().cnnc_get_timings(self._h, ms, calls))
         return {n: (ms[i], calls[i]) for i, n in enumerate(STEP_NAMES)}
+
+
+def cnnc_measure_peaks():
+    """(dense fp32 MFMA TFLOP/s, fp32 vector FMA TFLOP/s, HBM copy GB/s) sustained by synthetic probes."""
+    a, b, c = C.c_double(0), C.c_double(0), C.c_double(0)
+    rc = lib().cnnc_measure_peaks(C.byref(a), C.byref(b), C.byref(c))
+    if rc != 0:
+        raise CnncError(rc, "cnnc_measure_peaks failed")
+    return a.value, b.value, c.value
 
 
 # Same-named thin functions for callers that prefer the C spelling.

@@ -140,7 +140,7 @@ constexpr int kCompactBlock = 256;
 constexpr int kCompactPerBlock = 2048;   // values handled by one workgroup
 
 // Stage-1 tile (outputs per workgroup) and pyramid tile.
-constexpr int kS1TileW = 32, kS1TileH = 24;
+constexpr int kS1TileW = 32, kS1TileH = 16;
 constexpr int kPyrTileW = 64, kPyrTileH = 4;
 
 // tile table entry: level in the top 8 bits, tile row in the next 12, tile column in the low 12

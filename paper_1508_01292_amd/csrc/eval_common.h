@@ -25,16 +25,27 @@ __device__ void gather_crop(const uint8_t *__restrict__ frame, int fw, int fh, i
     if (tid < N) crop_axis<N>(x, S, fw, sTab, tid);
     else if (tid < 2 * N) crop_axis<N>(y, S, fh, sTab + N, tid - N);
     __syncthreads();
-    for (int e = tid; e < N * N; e += kThreads) {
+    // all pixel loads of a thread are issued before the first blend, so their latency is paid once
+    constexpr int kIt = (N * N + kThreads - 1) / kThreads;
+    uint32_t p00[kIt], p01[kIt], p10[kIt], p11[kIt], wxy[kIt];
+#pragma unroll
+    for (int it = 0; it < kIt; ++it) {
+        const int e = min(it * kThreads + tid, N * N - 1);
         const int i = e / N, j = e % N;
         const uint32_t ex = sTab[j], ey = sTab[N + i];
         const int x0 = ex >> 9, y0 = ey >> 9;
-        const uint32_t wx = ex & 511u, wy = ey & 511u;
         const int x1 = min(x0 + 1, fw - 1), y1 = min(y0 + 1, fh - 1);
         const uint8_t *r0 = frame + (size_t)y0 * pitch, *r1 = frame + (size_t)y1 * pitch;
-        const uint32_t acc = r0[x0] * (256u - wx) * (256u - wy) + r0[x1] * wx * (256u - wy)
-                           + r1[x0] * (256u - wx) * wy + r1[x1] * wx * wy;
-        sCrop[e] = normalise((float)acc * (1.0f / 65536.0f));
+        p00[it] = r0[x0]; p01[it] = r0[x1]; p10[it] = r1[x0]; p11[it] = r1[x1];
+        wxy[it] = ((ex & 511u) << 16) | (ey & 511u);
+    }
+#pragma unroll
+    for (int it = 0; it < kIt; ++it) {
+        const int e = it * kThreads + tid;
+        const uint32_t wx = wxy[it] >> 16, wy = wxy[it] & 0xFFFFu;
+        const uint32_t acc = p00[it] * (256u - wx) * (256u - wy) + p01[it] * wx * (256u - wy)
+                           + p10[it] * (256u - wx) * wy + p11[it] * wx * wy;
+        if (e < N * N) sCrop[e] = normalise((float)acc * (1.0f / 65536.0f));
     }
     __syncthreads();
 }

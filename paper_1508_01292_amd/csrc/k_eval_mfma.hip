@@ -33,7 +33,9 @@ constexpr int kCropW = 48;                 // crop row pitch in LDS
 constexpr int kP1Row = 24, kP1Ch = 22 * kP1Row;   // pooled conv1 map [16][22][24] (row padded: bank spread)
 constexpr int kP2Ch = 81;                  // pooled conv2 map [32][9*9]
 constexpr int kRegionA = 32 * kP2Ch;       // crop (2304) then pooled conv2 map (2592)
-constexpr int kRegionB = 16 * kP1Ch;       // pooled conv1 map (8448) then conv3 output (1568)
+constexpr int kRegionB = 16 * kP1Ch;       // pooled conv1 map (8448) then conv3 partial sums [4][32][66]
+constexpr int kP3Pitch = 66;
+static_assert(4 * 32 * kP3Pitch <= kRegionB, "conv3 partial sums must fit the conv1 region");
 
 // conv2 of stage 3 for the NT position tiles wslot, wslot + 4, ... of one crop.
 template <int NT, int ACT>
@@ -57,6 +59,7 @@ __device__ __forceinline__ void s3_conv2(const float *sP1, float *sP2, const flo
     for (int tap = 0; tap < 25; ++tap) {
         const int tn = min(tap + 1, 24);
         const float4 bn0 = bp[tn * 128], bn1 = bp[tn * 128 + 64];      // next tap's weights, in flight during the math
+        asm volatile("" ::: "memory");                                 // keeps the loads here: they must not sink to their use
         const int toff = (tap / 5) * kP1Row + tap % 5;
         const float b0[4] = {bc0.x, bc0.y, bc0.z, bc0.w}, b1[4] = {bc1.x, bc1.y, bc1.z, bc1.w};
 #pragma unroll
@@ -89,7 +92,7 @@ constexpr int kS3Feat = 1568;
 // Crop -> conv1 -> pool -> conv2 -> pool -> conv3 for each surviving window; writes the 1568 conv3
 // activations of the window (order [channel][row][col]) to `feat`.
 template <int ACT>
-__global__ __launch_bounds__(kThreads)
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(3, 3)))
 void eval3_conv_kernel(const uint8_t *__restrict__ frame, int fw, int fh, int pitch, const LevelDev *__restrict__ levels,
                        int n_levels, const uint32_t *__restrict__ idx, const int32_t *__restrict__ d_n, int n_max,
                        const float *__restrict__ wt, const float *__restrict__ frag, float *__restrict__ feat)
@@ -104,7 +107,6 @@ void eval3_conv_kernel(const uint8_t *__restrict__ frame, int fw, int fh, int pi
     for (int s = 0; s < 7; ++s) b1f[s] = frag[kS3F1 + s * 64 + lane];
     const float bias1 = wt[s3::B1 + j];
     const float bias2_lo = wt[s3::B2 + j], bias2_hi = wt[s3::B2 + 16 + j];
-    const float bias3_lo = wt[s3::B3 + j], bias3_hi = wt[s3::B3 + 16 + j];
     // conv1 k-order: steps 0..4 = taps (a = step, b = g); step 5 = taps (a = g, b = 4);
     // step 6 = tap (4, 4) in group 0, zero weights elsewhere (those lanes re-read their own pixel)
     const int off5 = g * kCropW + 4, off6 = g == 0 ? 4 * kCropW + 4 : 0;
@@ -147,49 +149,67 @@ void eval3_conv_kernel(const uint8_t *__restrict__ frame, int fw, int fh, int pi
         __syncthreads();
 
         // ---- conv2 5x5 16->32 + pool: 21 tiles; the wave that takes six of them rotates per crop
-        const int wslot = (wave + rot) & 3;
+        const int wslot = (wave + rot + blockIdx.x + (blockIdx.x >> 8)) & 3;
         if (wslot == 0) s3_conv2<6, ACT>(sB, sA, frag + kS3F2, wslot, lane, bias2_lo, bias2_hi);
         else s3_conv2<5, ACT>(sB, sA, frag + kS3F2, wslot, lane, bias2_lo, bias2_hi);
         __syncthreads();
 
-        // ---- conv3 3x3 32->32: 49 positions = 4 tiles, one per wave; two accumulator sets for ILP
+        // ---- conv3 3x3 32->32: 49 positions = 4 tiles.  The waves split K (wave w takes input channels
+        // 8w .. 8w+7 of every tap), so each needs only a quarter of the weights, all loaded up front; the
+        // partial tiles meet in LDS.
         {
-            const int pos = min(16 * wave + j, 48);
-            const int abase = g * kP2Ch + (pos / 7) * 9 + pos % 7;
-            floatx4 acc[2][2] = {{floatx4{0, 0, 0, 0}, floatx4{0, 0, 0, 0}}, {floatx4{0, 0, 0, 0}, floatx4{0, 0, 0, 0}}};
-            const float4 *bp = reinterpret_cast<const float4 *>(frag + kS3F3) + lane * 2;   // [tap][n-tile][lane][8]
-#pragma unroll 1
+            float2 b3[9][2];
+            const float2 *bp = reinterpret_cast<const float2 *>(frag + kS3F3) + lane * 4 + wave;   // [tap][n-tile][lane][8]
+#pragma unroll
             for (int tap = 0; tap < 9; ++tap) {
-                const float4 p0 = bp[(tap * 2) * 128], p1 = bp[(tap * 2) * 128 + 1];
-                const float4 q0 = bp[(tap * 2 + 1) * 128], q1 = bp[(tap * 2 + 1) * 128 + 1];
-                const float b0[8] = {p0.x, p0.y, p0.z, p0.w, p1.x, p1.y, p1.z, p1.w};
-                const float b1[8] = {q0.x, q0.y, q0.z, q0.w, q1.x, q1.y, q1.z, q1.w};
-                const int toff = (tap / 3) * 9 + tap % 3;
+                b3[tap][0] = bp[(tap * 2) * 256];
+                b3[tap][1] = bp[(tap * 2 + 1) * 256];
+            }
+            floatx4 acc[4][2];
+            int abase[4];
 #pragma unroll
-                for (int cq = 0; cq < 8; ++cq) {
-                    const float a = sA[abase + toff + cq * 4 * kP2Ch];
-                    acc[cq & 1][0] = CNNC_MFMA(a, b0[cq], acc[cq & 1][0]);
-                    acc[cq & 1][1] = CNNC_MFMA(a, b1[cq], acc[cq & 1][1]);
-                }
+            for (int u = 0; u < 4; ++u) {
+                acc[u][0] = floatx4{0, 0, 0, 0};
+                acc[u][1] = floatx4{0, 0, 0, 0};
+                const int pos = min(16 * u + j, 48);
+                abase[u] = (8 * wave + g) * kP2Ch + (pos / 7) * 9 + pos % 7;
             }
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const int p = 16 * wave + 4 * g + r;
-                if (p < 49) {
-                    sB[j * 49 + p] = act_f<ACT>(acc[0][0][r] + acc[1][0][r] + bias3_lo);
-                    sB[(16 + j) * 49 + p] = act_f<ACT>(acc[0][1][r] + acc[1][1][r] + bias3_hi);
+            for (int tap = 0; tap < 9; ++tap) {
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    const float w0 = h ? b3[tap][0].y : b3[tap][0].x, w1 = h ? b3[tap][1].y : b3[tap][1].x;
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        const float a = sA[abase[u] + (tap / 3) * 9 + tap % 3 + h * 4 * kP2Ch];
+                        acc[u][0] = CNNC_MFMA(a, w0, acc[u][0]);
+                        acc[u][1] = CNNC_MFMA(a, w1, acc[u][1]);
+                    }
                 }
             }
+            // partial sums: sB as [wave][channel 32][66] (position-contiguous)
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int p = 16 * u + 4 * g + r;
+                    sB[(wave * 32 + j) * kP3Pitch + p] = acc[u][0][r];
+                    sB[(wave * 32 + 16 + j) * kP3Pitch + p] = acc[u][1][r];
+                }
         }
         __syncthreads();
 
-        // ---- conv3 activations to global memory, coalesced
+        // ---- sum the four partial tiles, bias, activation, and out to global memory (order [channel][row][col])
         {
-            float4 *dst = reinterpret_cast<float4 *>(feat + (size_t)crop * kS3Feat);
-            const float4 *src = reinterpret_cast<const float4 *>(sB);
-            for (int e = tid; e < kS3Feat / 4; e += kThreads) dst[e] = src[e];
+            float *dst = feat + (size_t)crop * kS3Feat;
+            for (int e = tid; e < kS3Feat; e += kThreads) {
+                const int oc = e / 49, p = e % 49;
+                const float v = sB[oc * kP3Pitch + p] + sB[(32 + oc) * kP3Pitch + p] + sB[(64 + oc) * kP3Pitch + p] +
+                                sB[(96 + oc) * kP3Pitch + p];
+                dst[e] = act_f<ACT>(v + wt[s3::B3 + oc]);
+            }
         }
-        __syncthreads();
+        // no barrier here: the next crop's gather synchronises before anything overwrites sB
     }
 }
 

@@ -9,6 +9,12 @@
 //   M_c = max of A_c over (y..y+1, x..x+1)
 //   C_k = f(b2_k + sum w2_k[c][a][b] M_c(y+2a, x+2b))              conv 3x3, 4 -> 8, spacing 2
 //   score = b3 + sum w3[k][i][j] C_k(y+2i, x+2j)                    fc over 8x3x3, spacing 2
+//
+// Register blocking: a thread computes four neighbouring positions at a time, so every LDS value is
+// read once per four outputs and with 16-byte loads.  For the spacing-2 layers the maps M and C are
+// stored with even and odd columns apart ([channel][row][column parity][column / 2]); the four
+// positions of a thread are then four consecutive entries of one parity, and their taps are
+// consecutive too.  Weights are wave-uniform and come through scalar loads.
 #include "act.h"
 #include "cnnc_internal.h"
 
@@ -16,14 +22,23 @@ namespace cnnc {
 
 namespace {
 constexpr int TW = kS1TileW, TH = kS1TileH;
-constexpr int IN_W = TW + 11, IN_H = TH + 11;
-constexpr int A_W = TW + 9, A_H = TH + 9;
-constexpr int M_W = TW + 8, M_H = TH + 8;
-constexpr int C_W = TW + 4, C_H = TH + 4;
+static_assert(TW == 32 && TH == 16, "the unit decomposition below is written for 32 x 16 tiles");
 constexpr int kThreads = 256;
-constexpr int kRegionX = 8 * C_W * C_H;                 // C maps; earlier holds A maps + input
-constexpr int kRegionM = 4 * M_W * M_H;
-static_assert(4 * A_W * A_H + IN_W * IN_H <= kRegionX, "A maps and input must fit in the C region");
+constexpr int IN_H = TH + 11, IN_P = 44;          // input patch rows, row pitch (43 columns used)
+constexpr int A_H = TH + 9, A_P = 44;             // conv1 map: 41 columns used
+constexpr int M_H = TH + 8, M_P = 40;             // max map: 2 parities x 20 columns
+constexpr int C_H = TH + 4, C_P = 40;             // conv2 map: 2 parities x 20 columns (18 used)
+constexpr int kIn = IN_H * IN_P + 4, kA = 4 * A_H * A_P, kM = 4 * M_H * M_P, kC = 8 * C_H * C_P;
+constexpr int kRegionX = kC > kA + kIn ? kC : kA + kIn;   // A maps + input, later the C maps
+
+struct f6 { float v[6]; };
+// six consecutive floats starting at a 16-byte aligned LDS address
+__device__ __forceinline__ f6 load6(const float *p)
+{
+    const float4 a = *reinterpret_cast<const float4 *>(p);
+    const float2 b = *reinterpret_cast<const float2 *>(p + 4);
+    return {{a.x, a.y, a.z, a.w, b.x, b.y}};
+}
 }  // namespace
 
 template <int ACT>
@@ -32,11 +47,13 @@ void stage1_kernel(const uint8_t *__restrict__ pyr, const LevelDev *__restrict__
                    const uint32_t *__restrict__ tiles, const float *__restrict__ wt,
                    float *__restrict__ score)
 {
-    __shared__ float sX[kRegionX];
-    __shared__ float sM[kRegionM];
-    float *sA = sX;                         // [4][A_H][A_W]
-    float *sIn = sX + 4 * A_W * A_H;        // [IN_H][IN_W]
-    float *sC = sX;                         // [8][C_H][C_W], written after A and the input are dead
+    // 40 KiB: four workgroups share a compute unit's LDS.  sM sits first so that the two floats some lanes
+    // read past its end (feeding only discarded columns) fall inside the same array.
+    __shared__ __attribute__((aligned(16))) float sAll[kM + kRegionX];
+    float *sM = sAll, *sX = sAll + kM;
+    float *sA = sX;                 // [4][A_H][A_P]
+    float *sIn = sX + kA;           // [IN_H][IN_P]
+    float *sC = sX;                 // [8][C_H][2][20], written after A and the input are dead
 
     const uint32_t t = tiles[blockIdx.x];
     const int lvl = t >> 24, oy = ((t >> 12) & 0xFFF) * TH, ox = (t & 0xFFF) * TW;
@@ -44,77 +61,128 @@ void stage1_kernel(const uint8_t *__restrict__ pyr, const LevelDev *__restrict__
     const uint8_t *img = pyr + L.pyr_off;
     const int tid = threadIdx.x;
 
-    // input patch, normalised; positions past the level edge repeat the edge (they only feed
+    // ---- input patch, normalised; positions past the level edge repeat the edge (they only feed
     // outputs that are not written)
-    for (int e = tid; e < IN_W * IN_H; e += kThreads) {
-        const int r = e / IN_W, c = e % IN_W;
+    for (int e = tid; e < kIn; e += kThreads) {
+        const int r = min(e / IN_P, IN_H - 1), c = e % IN_P;
         const int y = min(oy + r, L.h - 1), x = min(ox + c, L.w - 1);
         sIn[e] = normalise((float)img[(size_t)y * L.w + x]);
     }
     __syncthreads();
 
-    // conv1 + f
-    for (int e = tid; e < A_W * A_H; e += kThreads) {
-        const int r = e / A_W, c = e % A_W;
-        float v[9];
+    // ---- conv1 + f: 25 rows x 10 groups of four columns, then the single column 40
+    if (tid < A_H * 10) {
+        const int r = tid / 10, x0 = 4 * (tid % 10);
+        float acc[4][4];
 #pragma unroll
-        for (int a = 0; a < 3; ++a)
+        for (int ch = 0; ch < 4; ++ch)
 #pragma unroll
-            for (int b = 0; b < 3; ++b) v[a * 3 + b] = sIn[(r + a) * IN_W + c + b];
+            for (int p = 0; p < 4; ++p) acc[ch][p] = wt[s1::B1 + ch];
 #pragma unroll
-        for (int ch = 0; ch < 4; ++ch) {
+        for (int a = 0; a < 3; ++a) {
+            const f6 in = load6(sIn + (r + a) * IN_P + x0);
+#pragma unroll
+            for (int b = 0; b < 3; ++b)
+#pragma unroll
+                for (int ch = 0; ch < 4; ++ch)
+#pragma unroll
+                    for (int p = 0; p < 4; ++p) acc[ch][p] = fmaf(wt[s1::W1 + ch * 9 + a * 3 + b], in.v[p + b], acc[ch][p]);
+        }
+#pragma unroll
+        for (int ch = 0; ch < 4; ++ch)
+            *reinterpret_cast<float4 *>(sA + (ch * A_H + r) * A_P + x0) =
+                make_float4(act_f<ACT>(acc[ch][0]), act_f<ACT>(acc[ch][1]), act_f<ACT>(acc[ch][2]), act_f<ACT>(acc[ch][3]));
+    } else if (tid - A_H * 10 < 4) {
+        // the last thread group does column 40: one channel each, 25 rows
+        const int ch = tid - A_H * 10;
+        for (int r = 0; r < A_H; ++r) {
             float acc = wt[s1::B1 + ch];
 #pragma unroll
-            for (int q = 0; q < 9; ++q) acc = fmaf(wt[s1::W1 + ch * 9 + q], v[q], acc);
-            sA[(ch * A_H + r) * A_W + c] = act_f<ACT>(acc);
+            for (int a = 0; a < 3; ++a)
+#pragma unroll
+                for (int b = 0; b < 3; ++b) acc = fmaf(wt[s1::W1 + ch * 9 + a * 3 + b], sIn[(r + a) * IN_P + 40 + b], acc);
+            sA[(ch * A_H + r) * A_P + 40] = act_f<ACT>(acc);
         }
     }
     __syncthreads();
 
-    // stride-1 2x2 max
-    for (int e = tid; e < 4 * M_W * M_H; e += kThreads) {
-        const int ch = e / (M_W * M_H), r = (e / M_W) % M_H, c = e % M_W;
-        const float *p = sA + (ch * A_H + r) * A_W + c;
-        sM[e] = fmaxf(fmaxf(p[0], p[1]), fmaxf(p[A_W], p[A_W + 1]));
+    // ---- stride-1 2x2 max, stored with even and odd columns apart: 24 rows x 10 groups of four columns
+    if (tid < M_H * 10) {
+        const int r = tid / 10, g = tid % 10, x0 = 4 * g;
+#pragma unroll
+        for (int ch = 0; ch < 4; ++ch) {
+            const float *p0 = sA + (ch * A_H + r) * A_P + x0, *p1 = p0 + A_P;
+            const float4 u = *reinterpret_cast<const float4 *>(p0), v = *reinterpret_cast<const float4 *>(p1);
+            const float u4 = p0[4], v4 = p1[4];
+            const float c0 = fmaxf(u.x, v.x), c1 = fmaxf(u.y, v.y), c2 = fmaxf(u.z, v.z), c3 = fmaxf(u.w, v.w),
+                        c4 = fmaxf(u4, v4);
+            float *m = sM + (ch * M_H + r) * M_P + 2 * g;
+            *reinterpret_cast<float2 *>(m) = make_float2(fmaxf(c0, c1), fmaxf(c2, c3));        // even columns x0, x0+2
+            *reinterpret_cast<float2 *>(m + 20) = make_float2(fmaxf(c1, c2), fmaxf(c3, c4));   // odd columns x0+1, x0+3
+        }
     }
     __syncthreads();
 
-    // conv2 (tap spacing 2) + f, all 8 output channels of a position in one thread
-    for (int e = tid; e < C_W * C_H; e += kThreads) {
-        const int r = e / C_W, c = e % C_W;
-        float acc[8];
-#pragma unroll
-        for (int k = 0; k < 8; ++k) acc[k] = wt[s1::B2 + k];
-#pragma unroll
-        for (int ch = 0; ch < 4; ++ch)
-#pragma unroll
-            for (int a = 0; a < 3; ++a)
-#pragma unroll
-                for (int b = 0; b < 3; ++b) {
-                    const float m = sM[(ch * M_H + r + 2 * a) * M_W + c + 2 * b];
-#pragma unroll
-                    for (int k = 0; k < 8; ++k)
-                        acc[k] = fmaf(wt[s1::W2 + ((k * 4 + ch) * 3 + a) * 3 + b], m, acc[k]);
-                }
-#pragma unroll
-        for (int k = 0; k < 8; ++k) sC[(k * C_H + r) * C_W + c] = act_f<ACT>(acc[k]);
-    }
-    __syncthreads();
-
-    // fc over the 8x3x3 block at tap spacing 2
-    for (int e = tid; e < TW * TH; e += kThreads) {
-        const int r = e / TW, c = e % TW;
-        const int y = oy + r, x = ox + c;
-        if (y >= L.oh || x >= L.ow) continue;
-        float acc = wt[s1::B3];
+    // ---- conv2 (tap spacing 2) + f: 20 rows x 2 parities x 5 groups of four same-parity columns, all 8 channels
+    if (tid < C_H * 10) {
+        const int r = tid / 10, px = (tid % 10) / 5, j0 = 4 * (tid % 5);
+        float acc[8][4];
 #pragma unroll
         for (int k = 0; k < 8; ++k)
 #pragma unroll
-            for (int i = 0; i < 3; ++i)
+            for (int p = 0; p < 4; ++p) acc[k][p] = wt[s1::B2 + k];
 #pragma unroll
-                for (int j = 0; j < 3; ++j)
-                    acc = fmaf(wt[s1::W3 + (k * 3 + i) * 3 + j], sC[(k * C_H + r + 2 * i) * C_W + c + 2 * j], acc);
-        score[(size_t)L.score_off + (size_t)y * L.ow + x] = acc;
+        for (int ch = 0; ch < 4; ++ch)
+#pragma unroll
+            for (int a = 0; a < 3; ++a) {
+                const f6 m = load6(sM + (ch * M_H + r + 2 * a) * M_P + px * 20 + j0);
+#pragma unroll
+                for (int b = 0; b < 3; ++b)
+#pragma unroll
+                    for (int k = 0; k < 8; ++k)
+#pragma unroll
+                        for (int p = 0; p < 4; ++p)
+                            acc[k][p] = fmaf(wt[s1::W2 + ((k * 4 + ch) * 3 + a) * 3 + b], m.v[p + b], acc[k][p]);
+            }
+#pragma unroll
+        for (int k = 0; k < 8; ++k)
+            *reinterpret_cast<float4 *>(sC + (k * C_H + r) * C_P + px * 20 + j0) =
+                make_float4(act_f<ACT>(acc[k][0]), act_f<ACT>(acc[k][1]), act_f<ACT>(acc[k][2]), act_f<ACT>(acc[k][3]));
+    }
+    __syncthreads();
+
+    // ---- fc over the 8x3x3 block at tap spacing 2: 16 rows x 2 parities x 4 groups of four columns, and
+    // two threads per unit that take four channels each and add their halves
+    {
+        const int half = tid & 1, u = tid >> 1;
+        const int r = u / 8, px = (u % 8) / 4, j0 = 4 * (u % 4);
+        float acc[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+            const int k = 4 * half + kk;
+#pragma unroll
+            for (int i = 0; i < 3; ++i) {
+                const f6 c = load6(sC + (k * C_H + r + 2 * i) * C_P + px * 20 + j0);
+#pragma unroll
+                for (int j = 0; j < 3; ++j) {
+                    const float w = half ? wt[s1::W3 + ((4 + kk) * 3 + i) * 3 + j] : wt[s1::W3 + (kk * 3 + i) * 3 + j];
+#pragma unroll
+                    for (int p = 0; p < 4; ++p) acc[p] = fmaf(w, c.v[p + j], acc[p]);
+                }
+            }
+        }
+#pragma unroll
+        for (int p = 0; p < 4; ++p) acc[p] += __shfl_xor(acc[p], 1, 64);
+        const int y = oy + r;
+        if (y < L.oh) {
+            float *row = score + (size_t)L.score_off + (size_t)y * L.ow;
+            const float b3 = wt[s1::B3];
+#pragma unroll
+            for (int q = 0; q < 2; ++q) {            // this thread writes two of the unit's four outputs
+                const int p = 2 * half + q, x = ox + 2 * (j0 + p) + px;
+                if (x < L.ow) row[x] = (half ? (q ? acc[3] : acc[2]) : (q ? acc[1] : acc[0])) + b3;
+            }
+        }
     }
 }
 
