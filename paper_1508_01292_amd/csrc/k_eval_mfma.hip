@@ -16,9 +16,26 @@
 //
 // The fully connected layers are batched over crops in a second kernel (M = crops), so their
 // weights are read once per 16 crops instead of once per crop.
+#include <stdlib.h>
+
 #include "eval_common.h"
 
 namespace cnnc {
+
+#ifdef CNNC_PHASE_PROBE
+__device__ unsigned long long g_probe[16];
+__device__ unsigned long long g_span[2 * 1024];
+#define CNNC_PROBE(k)                                                                     \
+    do {                                                                                  \
+        if (threadIdx.x == 0 && blockIdx.x == 0) {                                        \
+            const unsigned long long now_ = clock64();                                    \
+            g_probe[k] += now_ - probe_t_;                                                \
+            probe_t_ = now_;                                                              \
+        }                                                                                 \
+    } while (0)
+#else
+#define CNNC_PROBE(k) do {} while (0)
+#endif
 
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 #define CNNC_MFMA(a, b, c) __builtin_amdgcn_mfma_f32_16x16x4f32((a), (b), (c), 0, 0, 0)
@@ -113,9 +130,18 @@ void eval3_conv_kernel(const uint8_t *__restrict__ frame, int fw, int fh, int pi
 
     const int n = min(*d_n, n_max);
     int rot = 0;
+#ifdef CNNC_PHASE_PROBE
+    unsigned long long probe_t_ = clock64();
+    const unsigned long long probe_c0_ = probe_t_, probe_w0_ = wall_clock64();
+#endif
+    // Static striding over the list.  (Handing windows out through an atomic ticket counter was measured:
+    // it does not shorten the kernel, the device-scope atomics cost more than the balance gains.)
     for (int crop = blockIdx.x; crop < n; crop += gridDim.x, ++rot) {
+        CNNC_PROBE(0);
         const Survivor sv = decode(idx[crop], levels, n_levels);
+        CNNC_PROBE(1);
         gather_crop<kS3In>(frame, fw, fh, pitch, sv.x, sv.y, levels[sv.level].scale_q16, sTab, sA);
+        CNNC_PROBE(2);
 
         // ---- conv1 5x5 1->16 + pool: 121 tiles of four pooling blocks, four tiles in flight per wave
 #pragma unroll 1
@@ -146,13 +172,17 @@ void eval3_conv_kernel(const uint8_t *__restrict__ frame, int fw, int fh, int pi
                 }
             }
         }
+        CNNC_PROBE(3);
         __syncthreads();
+        CNNC_PROBE(4);
 
         // ---- conv2 5x5 16->32 + pool: 21 tiles; the wave that takes six of them rotates per crop
         const int wslot = (wave + rot + blockIdx.x + (blockIdx.x >> 8)) & 3;
         if (wslot == 0) s3_conv2<6, ACT>(sB, sA, frag + kS3F2, wslot, lane, bias2_lo, bias2_hi);
         else s3_conv2<5, ACT>(sB, sA, frag + kS3F2, wslot, lane, bias2_lo, bias2_hi);
+        CNNC_PROBE(5);
         __syncthreads();
+        CNNC_PROBE(6);
 
         // ---- conv3 3x3 32->32: 49 positions = 4 tiles.  The waves split K (wave w takes input channels
         // 8w .. 8w+7 of every tap), so each needs only a quarter of the weights, all loaded up front; the
@@ -197,7 +227,9 @@ void eval3_conv_kernel(const uint8_t *__restrict__ frame, int fw, int fh, int pi
                     sB[(wave * 32 + 16 + j) * kP3Pitch + p] = acc[u][1][r];
                 }
         }
+        CNNC_PROBE(7);
         __syncthreads();
+        CNNC_PROBE(8);
 
         // ---- sum the four partial tiles, bias, activation, and out to global memory (order [channel][row][col])
         {
@@ -209,8 +241,19 @@ void eval3_conv_kernel(const uint8_t *__restrict__ frame, int fw, int fh, int pi
                 dst[e] = act_f<ACT>(v + wt[s3::B3 + oc]);
             }
         }
+        CNNC_PROBE(9);
         // no barrier here: the next crop's gather synchronises before anything overwrites sB
     }
+#ifdef CNNC_PHASE_PROBE
+    if (threadIdx.x == 0 && blockIdx.x == 0) {
+        g_probe[10] += clock64() - probe_c0_;
+        g_probe[11] += wall_clock64() - probe_w0_;
+    }
+    if (threadIdx.x == 0 && blockIdx.x < 1024) {
+        g_span[2 * blockIdx.x] = probe_w0_;
+        g_span[2 * blockIdx.x + 1] = wall_clock64();
+    }
+#endif
 }
 
 // fc 1568->64 + f, fc 64->1 for 16 windows per workgroup: the four waves split K, partial tiles meet in LDS.
@@ -348,7 +391,7 @@ void eval2_conv_kernel(const uint8_t *__restrict__ frame, int fw, int fh, int pi
     const int off5 = g * kC2W + 4, off6 = g == 0 ? 4 * kC2W + 4 : 0;     // conv1 k-order as in stage 3
 
     const int n = min(*d_n, n_max);
-    for (int crop = blockIdx.x * 4 + wave; crop < n; crop += gridDim.x * 4) {
+    for (int crop = __builtin_amdgcn_readfirstlane(blockIdx.x * 4 + wave); crop < n; crop += gridDim.x * 4) {
         const Survivor sv = decode(idx[crop], levels, n_levels);
         const int64_t S = levels[sv.level].scale_q16;
         if (lane < 24) crop_axis<kS2In>(sv.x, S, fw, sTab, lane);
@@ -501,7 +544,8 @@ void eval2_make_fragments(const float *w, float *f)
 namespace {
 int conv_grid(const cnnc_ctx *c)
 {
-    const int g = 256 * 3;   // three workgroups fit a compute unit's LDS; each strides over the list
+    int g = 256 * 3;   // three workgroups fit a compute unit's LDS; each strides over the list
+    if (const char *e = getenv("CNNC_DBG_E3_GRID")) g = atoi(e);
     return c->max_surv < g ? c->max_surv : g;
 }
 int fc_grid(const cnnc_ctx *c)
@@ -510,6 +554,23 @@ int fc_grid(const cnnc_ctx *c)
     return tiles < 1024 ? tiles : 1024;
 }
 }  // namespace
+
+#ifdef CNNC_PHASE_PROBE
+extern "C" void cnnc_debug_read_probe(unsigned long long *out, int reset)
+{
+    (void)hipDeviceSynchronize();
+    (void)hipMemcpyFromSymbol(out, HIP_SYMBOL(g_probe), sizeof(unsigned long long) * 16);
+    if (reset) {
+        unsigned long long z[16] = {0};
+        (void)hipMemcpyToSymbol(HIP_SYMBOL(g_probe), z, sizeof(z));
+    }
+}
+extern "C" void cnnc_debug_read_span(unsigned long long *out)
+{
+    (void)hipDeviceSynchronize();
+    (void)hipMemcpyFromSymbol(out, HIP_SYMBOL(g_span), sizeof(unsigned long long) * 2048);
+}
+#endif
 
 hipError_t launch_eval3_mfma(const cnnc_ctx *c, hipStream_t st)
 {
