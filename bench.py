@@ -19,13 +19,18 @@ if ROOT not in sys.path:
 
 METRIC = "frames/sec at 3840x2160, min face 60 px (full cascade); stage-1 windows/sec"
 
-# Algorithmic work per unit ("Rooflines").
+# Algorithmic work per unit ("Kernels and rooflines").
 S1_FLOP_PER_WINDOW = 2 * 396
 S2_FLOP_PER_CROP = 2 * 161952
 S3_FLOP_PER_CROP = 2 * 5473600
+S2_CONV_FLOP_PER_CROP = 2 * (80000 + 73728)            # conv kernel of stage 2 (conv1 + conv2)
+S3_CONV_FLOP_PER_CROP = 2 * (774400 + 4147200 + 451584)  # conv kernel of stage 3 (conv1..conv3)
 PEAK_HBM = 8000.0          # GB/s
 PEAK_FP32_VECTOR = 157.3   # TFLOP/s, published vector fp32 figure
 PEAK_FP32_MFMA = 157.3     # TFLOP/s, published dense fp32 matrix figure
+# HBM bytes per launch of the dominant kernel from rocprofv3 FETCH_SIZE / WRITE_SIZE passes
+# (profiles/eval3_conv_uhd_pmc.txt), or None where not measured for that workload.
+MEASURED_TRAFFIC = {}
 
 
 def main():
@@ -136,20 +141,32 @@ def main():
                    "peak": PEAK_FP32_VECTOR, "unit": "TFLOP/s"},
         "compact1": {"bound": "hbm", "ms": ms["compact1"], "achieved": gbs(4 * n_windows + 8 * n1, ms["compact1"]),
                      "peak": PEAK_HBM, "unit": "GB/s"},
-        "stage2": {"bound": "alu", "ms": ms["stage2"], "achieved": tflops(S2_FLOP_PER_CROP * n1, ms["stage2"]),
-                   "peak": PEAK_FP32_VECTOR, "unit": "TFLOP/s"},
-        "stage3": {"bound": "alu", "ms": ms["stage3"], "achieved": tflops(S3_FLOP_PER_CROP * n2, ms["stage3"]),
-                   "peak": PEAK_FP32_VECTOR, "unit": "TFLOP/s"},
+        "stage2": {"bound": "mfma", "ms": ms["stage2"], "achieved": tflops(S2_FLOP_PER_CROP * n1, ms["stage2"]),
+                   "peak": PEAK_FP32_MFMA, "unit": "TFLOP/s"},
+        "stage2_conv": {"bound": "mfma", "ms": ms["stage2_conv"], "achieved": tflops(S2_CONV_FLOP_PER_CROP * n1, ms["stage2_conv"]),
+                        "peak": PEAK_FP32_MFMA, "unit": "TFLOP/s"},
+        "stage3": {"bound": "mfma", "ms": ms["stage3"], "achieved": tflops(S3_FLOP_PER_CROP * n2, ms["stage3"]),
+                   "peak": PEAK_FP32_MFMA, "unit": "TFLOP/s"},
+        "stage3_conv": {"bound": "mfma", "ms": ms["stage3_conv"], "achieved": tflops(S3_CONV_FLOP_PER_CROP * n2, ms["stage3_conv"]),
+                        "peak": PEAK_FP32_MFMA, "unit": "TFLOP/s"},
         "compact2": {"ms": ms["compact2"]}, "compact3": {"ms": ms["compact3"]}, "merge": {"ms": ms["merge"]},
     }
     for k in kernels.values():
         if "achieved" in k:
             k["frac"] = k["achieved"] / k["peak"]
-    dom = max(("stage1", "stage2", "stage3", "pyramid", "compact1"), key=lambda k: ms[k])
-    roof = dict(kernels[dom])
-    roof.update({"kernel": dom, "traffic": None})
-    roof.pop("ms")
-    roof["avg_launch_ms"] = ms[dom]
+    # the dominant single kernel: the convolution kernel of the slowest step, or the step's own kernel
+    dom = max(("stage1", "stage2_conv", "stage3_conv", "pyramid"), key=lambda k: ms[k])
+    kernel_names = {"stage1": "stage1_kernel", "stage2_conv": "eval2_conv_kernel", "stage3_conv": "eval3_conv_kernel",
+                    "pyramid": "pyramid_kernel"}
+    roof = {"bound": kernels[dom]["bound"], "achieved": kernels[dom]["achieved"], "peak": kernels[dom]["peak"],
+            "unit": kernels[dom]["unit"], "frac": kernels[dom]["frac"],
+            "traffic": MEASURED_TRAFFIC.get((dom, a.workload)), "kernel": kernel_names[dom],
+            "avg_launch_ms": ms[dom]}
+    try:
+        mf, vf, hb = P.cnnc_measure_peaks()
+        roof["sustained_on_this_gpu"] = {"mfma_f32_tflops": mf, "valu_f32_tflops": vf, "hbm_copy_gbs": hb}
+    except Exception as e:       # a probe failure must not lose the benchmark line
+        roof["sustained_on_this_gpu"] = {"error": str(e)}
 
     out = {
         "metric": METRIC, "value": fps, "unit": "frames/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
@@ -160,7 +177,7 @@ def main():
                    "frames_in_flight": F, "windows": n_windows, "survivors": [n1, n2, n3], "detections": n_det},
         "stage1_windows_per_s": n_windows / (ms["stage1"] * 1e-3) if ms["stage1"] > 0 else None,
         "latency_ms_single_frame": latency_ms,
-        "sum_of_kernel_ms": sum(ms.values()),
+        "sum_of_kernel_ms": sum(v for k, v in ms.items() if not k.endswith("_conv")),
         "roofline": roof,
         "kernels": kernels,
         "cpu_baseline": cpu,

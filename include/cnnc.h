@@ -92,7 +92,9 @@ typedef struct {
 /* Names of the timed steps for cnnc_get_timings. */
 enum {
     CNNC_T_PYRAMID = 0, CNNC_T_STAGE1, CNNC_T_COMPACT1, CNNC_T_STAGE2, CNNC_T_COMPACT2,
-    CNNC_T_STAGE3, CNNC_T_COMPACT3, CNNC_T_MERGE, CNNC_T_COUNT
+    CNNC_T_STAGE3, CNNC_T_COMPACT3, CNNC_T_MERGE,
+    /* the convolution kernel alone inside cnnc_eval_stage(2) / (3) (the step also runs a small fc kernel) */
+    CNNC_T_STAGE2_CONV, CNNC_T_STAGE3_CONV, CNNC_T_COUNT
 };
 
 /* Create a context on the current HIP device.

@@ -168,22 +168,7 @@ hipEvent_t take_event(StepTimer &t)
     return e;
 }
 
-struct Timed {
-    cnnc_ctx *c; int step; hipStream_t st; hipEvent_t b = nullptr;
-    Timed(cnnc_ctx *c_, int step_, hipStream_t st_) : c(c_), step(step_), st(st_)
-    {
-        if (c->timing && (b = take_event(c->timers[step]))) (void)hipEventRecord(b, st);
-    }
-    ~Timed()
-    {
-        if (!b) return;
-        StepTimer &t = c->timers[step];
-        hipEvent_t e = take_event(t);
-        if (!e) { t.pool.push_back(b); return; }
-        (void)hipEventRecord(e, st);
-        t.begin.push_back(b); t.end.push_back(e);
-    }
-};
+using Timed = cnnc::ScopedTimer;
 
 int fetch(cnnc_ctx *c, cnnc_det *out, int cap, int *n_out)
 {
@@ -216,6 +201,22 @@ int enqueue_readback(cnnc_ctx *c, hipStream_t st)
 }
 
 }  // namespace
+
+namespace cnnc {
+ScopedTimer::ScopedTimer(cnnc_ctx *c_, int step_, hipStream_t st_) : c(c_), step(step_), st(st_)
+{
+    if (c->timing && (b = take_event(c->timers[step]))) (void)hipEventRecord(b, st);
+}
+ScopedTimer::~ScopedTimer()
+{
+    if (!b) return;
+    StepTimer &t = c->timers[step];
+    hipEvent_t e = take_event(t);
+    if (!e) { t.pool.push_back(b); return; }
+    (void)hipEventRecord(e, st);
+    t.begin.push_back(b); t.end.push_back(e);
+}
+}  // namespace cnnc
 
 // ------------------------------------------------------------------------------------------------
 extern "C" {

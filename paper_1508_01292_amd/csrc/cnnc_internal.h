@@ -124,8 +124,19 @@ hipError_t launch_compact(const cnnc_ctx *c, const float *vals, const uint32_t *
                           hipStream_t st);
 hipError_t launch_eval2(const cnnc_ctx *c, hipStream_t st);
 hipError_t launch_eval3(const cnnc_ctx *c, hipStream_t st);
-hipError_t launch_eval3_mfma(const cnnc_ctx *c, hipStream_t st);
-hipError_t launch_eval2_mfma(const cnnc_ctx *c, hipStream_t st);
+hipError_t launch_eval3_mfma(cnnc_ctx *c, hipStream_t st);
+hipError_t launch_eval2_mfma(cnnc_ctx *c, hipStream_t st);
+
+// Brackets the launches made during its lifetime with a pair of events on the stream when the context's
+// timing is on; the pair is read back by cnnc_get_timings.
+struct ScopedTimer {
+    cnnc_ctx *c;
+    int step;
+    hipStream_t st;
+    hipEvent_t b = nullptr;
+    ScopedTimer(cnnc_ctx *c_, int step_, hipStream_t st_);
+    ~ScopedTimer();
+};
 size_t eval2_frag_floats();
 size_t eval2_feat_floats();
 void eval2_make_fragments(const float *blob, float *frag);

@@ -365,12 +365,12 @@ __device__ __forceinline__ void wave_sync()
 }
 }  // namespace
 
-// Fragment buffer of stage 2 (floats): conv1 [7][64], conv2 [9 taps][2 quads][64], fc [16][2][64][4].
-constexpr int kS2F1 = 0, kS2F2 = kS2F1 + 7 * 64, kS2F3 = kS2F2 + 18 * 64, kS2FragFloats = kS2F3 + 16 * 2 * 64 * 4;
+// Fragment buffer of stage 2 (floats): conv1 [8][64], conv2 [9 taps][2 quads][64], fc [16][2][64][4].
+constexpr int kS2F1 = 0, kS2F2 = kS2F1 + 8 * 64, kS2F3 = kS2F2 + 18 * 64, kS2FragFloats = kS2F3 + 16 * 2 * 64 * 4;
 constexpr int kS2Feat = 256;
 
 template <int ACT>
-__global__ __launch_bounds__(kThreads)
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(3, 3)))
 void eval2_conv_kernel(const uint8_t *__restrict__ frame, int fw, int fh, int pitch, const LevelDev *__restrict__ levels,
                        int n_levels, const uint32_t *__restrict__ idx, const int32_t *__restrict__ d_n, int n_max,
                        const float *__restrict__ wt, const float *__restrict__ frag, float *__restrict__ feat)
@@ -382,13 +382,17 @@ void eval2_conv_kernel(const uint8_t *__restrict__ frame, int fw, int fh, int pi
     float *sP1 = sCrop + kS2Crop + kS2Tab;
     float *sP2 = sCrop;                          // pooled conv2 output [16][16] re-uses the crop's space
 
-    float b1f[7], b2f[18];
+    float b1f[8], b2f[18];
 #pragma unroll
-    for (int s = 0; s < 7; ++s) b1f[s] = frag[kS2F1 + s * 64 + lane];
+    for (int s = 0; s < 8; ++s) b1f[s] = frag[kS2F1 + s * 64 + lane];
 #pragma unroll
     for (int s = 0; s < 18; ++s) b2f[s] = frag[kS2F2 + s * 64 + lane];
-    const float bias1 = j < 8 ? wt[s2::B1 + j] : 0.0f, bias2 = wt[s2::B2 + j];
-    const int off5 = g * kC2W + 4, off6 = g == 0 ? 4 * kC2W + 4 : 0;     // conv1 k-order as in stage 3
+    const float bias1 = wt[s2::B1 + (j >> 1)], bias2 = wt[s2::B2 + j];
+    // conv1 runs with N = 8 channels x 2 adjacent output columns (the two columns of a pooling block), so no
+    // half of the matrix tile is idle: K = 5 rows x 6 input columns = 30 -> 8 steps of 4.
+    // k-order: steps 0..4 = (row = step, column = g); step 5 = (row = g, column 4); step 6 = (row = g, column 5);
+    // step 7 = (4, 4) in group 0, (4, 5) in group 1, zero weights in groups 2 and 3.
+    const int off5 = g * kC2W + 4, off6 = g * kC2W + 5, off7 = g == 0 ? 4 * kC2W + 4 : (g == 1 ? 4 * kC2W + 5 : 0);
 
     const int n = min(*d_n, n_max);
     for (int crop = __builtin_amdgcn_readfirstlane(blockIdx.x * 4 + wave); crop < n; crop += gridDim.x * 4) {
@@ -397,45 +401,61 @@ void eval2_conv_kernel(const uint8_t *__restrict__ frame, int fw, int fh, int pi
         if (lane < 24) crop_axis<kS2In>(sv.x, S, fw, sTab, lane);
         else if (lane < 48) crop_axis<kS2In>(sv.y, S, fh, sTab + 24, lane - 24);
         wave_sync();
-#pragma unroll 3
-        for (int it = 0; it < 9; ++it) {
-            const int e = it * 64 + lane, r = e / 24, q = e % 24;
-            const uint32_t ex = sTab[q], ey = sTab[24 + r];
-            const int x0 = ex >> 9, y0 = ey >> 9;
-            const uint32_t wx = ex & 511u, wy = ey & 511u;
-            const int x1 = min(x0 + 1, fw - 1), y1 = min(y0 + 1, fh - 1);
-            const uint8_t *r0 = frame + (size_t)y0 * pitch, *r1 = frame + (size_t)y1 * pitch;
-            const uint32_t acc = r0[x0] * (256u - wx) * (256u - wy) + r0[x1] * wx * (256u - wy)
-                               + r1[x0] * (256u - wx) * wy + r1[x1] * wx * wy;
-            sCrop[e] = normalise((float)acc * (1.0f / 65536.0f));
+        {   // all 36 pixel loads of a lane are issued before the first blend
+            uint32_t p00[9], p01[9], p10[9], p11[9], wxy[9];
+#pragma unroll
+            for (int it = 0; it < 9; ++it) {
+                const int e = it * 64 + lane, r = e / 24, q = e % 24;
+                const uint32_t ex = sTab[q], ey = sTab[24 + r];
+                const int x0 = ex >> 9, y0 = ey >> 9;
+                const int x1 = min(x0 + 1, fw - 1), y1 = min(y0 + 1, fh - 1);
+                const uint32_t o0 = (uint32_t)(y0 * pitch), o1 = (uint32_t)(y1 * pitch);
+                p00[it] = frame[o0 + x0]; p01[it] = frame[o0 + x1]; p10[it] = frame[o1 + x0]; p11[it] = frame[o1 + x1];
+                wxy[it] = ((ex & 511u) << 16) | (ey & 511u);
+            }
+#pragma unroll
+            for (int it = 0; it < 9; ++it) {
+                const uint32_t wx = wxy[it] >> 16, wy = wxy[it] & 0xFFFFu;
+                const uint32_t acc = p00[it] * (256u - wx) * (256u - wy) + p01[it] * wx * (256u - wy)
+                                   + p10[it] * (256u - wx) * wy + p11[it] * wx * wy;
+                sCrop[it * 64 + lane] = normalise((float)acc * (1.0f / 65536.0f));
+            }
         }
         wave_sync();
 
-        // ---- conv1 5x5 1->8 + pool: 25 tiles of four pooling blocks, five in flight
+        // ---- conv1 5x5 1->8 + pool.  A tile is 16 base positions (even columns) = 8 pooling blocks:
+        // row i of the tile = pooling block 8 t + 2 (i / 4) + (i / 2) % 2, line i % 2 of the block.
+        // 100 blocks = 12.5 tiles, done as two rounds of seven (the 14th is a clamped duplicate).
 #pragma unroll 1
-        for (int t0 = 0; t0 < 25; t0 += 5) {
-            floatx4 acc[5];
-            int base[5];
+        for (int t0 = 0; t0 < 14; t0 += 7) {
+            floatx4 acc[7];
+            int base[7];
 #pragma unroll
-            for (int u = 0; u < 5; ++u) {
+            for (int u = 0; u < 7; ++u) {
                 acc[u] = floatx4{0, 0, 0, 0};
-                const int pb = 4 * (t0 + u) + (j >> 2);
-                base[u] = (2 * (pb / 10) + ((j >> 1) & 1)) * kC2W + 2 * (pb % 10) + (j & 1);
+                const int pb = min(8 * (t0 + u) + 2 * (j >> 2) + ((j >> 1) & 1), 99);
+                base[u] = (2 * (pb / 10) + (j & 1)) * kC2W + 2 * (pb % 10);
             }
 #pragma unroll
             for (int s = 0; s < 5; ++s)
 #pragma unroll
-                for (int u = 0; u < 5; ++u) acc[u] = CNNC_MFMA(sCrop[base[u] + g + s * kC2W], b1f[s], acc[u]);
+                for (int u = 0; u < 7; ++u) acc[u] = CNNC_MFMA(sCrop[base[u] + g + s * kC2W], b1f[s], acc[u]);
 #pragma unroll
-            for (int u = 0; u < 5; ++u) acc[u] = CNNC_MFMA(sCrop[base[u] + off5], b1f[5], acc[u]);
+            for (int u = 0; u < 7; ++u) acc[u] = CNNC_MFMA(sCrop[base[u] + off5], b1f[5], acc[u]);
 #pragma unroll
-            for (int u = 0; u < 5; ++u) acc[u] = CNNC_MFMA(sCrop[base[u] + off6], b1f[6], acc[u]);
-            if (j < 8) {
+            for (int u = 0; u < 7; ++u) acc[u] = CNNC_MFMA(sCrop[base[u] + off6], b1f[6], acc[u]);
 #pragma unroll
-                for (int u = 0; u < 5; ++u) {
-                    const int pb = 4 * (t0 + u) + g;
-                    sP1[j * kQ1Ch + (pb / 10) * kQ1Row + pb % 10] = act_f<ACT>(max4(acc[u]) + bias1);
-                }
+            for (int u = 0; u < 7; ++u) acc[u] = CNNC_MFMA(sCrop[base[u] + off7], b1f[7], acc[u]);
+            // lane (g, j = 2 channel + column): registers 0,1 = the two lines of block 8t + 2g, registers 2,3 of
+            // block 8t + 2g + 1; the other column of each block sits in lane j ^ 1
+#pragma unroll
+            for (int u = 0; u < 7; ++u) {
+                float lo = fmaxf(acc[u][0], acc[u][1]), hi = fmaxf(acc[u][2], acc[u][3]);
+                lo = fmaxf(lo, __shfl_xor(lo, 1, 64));
+                hi = fmaxf(hi, __shfl_xor(hi, 1, 64));
+                const int pb = 8 * (t0 + u) + 2 * g + (j & 1);        // even lanes finish the first block, odd the second
+                if (pb < 100)
+                    sP1[(j >> 1) * kQ1Ch + (pb / 10) * kQ1Row + pb % 10] = act_f<ACT>(((j & 1) ? hi : lo) + bias1);
             }
         }
         wave_sync();
@@ -517,14 +537,19 @@ size_t eval2_feat_floats() { return kS2Feat; }
 
 void eval2_make_fragments(const float *w, float *f)
 {
-    for (int s = 0; s < 7; ++s)
+    // conv1: column n of the tile = (channel n / 2, output column n % 2); k = (row a, input column b) with the
+    // input column counted from the even output column, so the weight is w[channel][a][b - n % 2]
+    for (int s = 0; s < 8; ++s)
         for (int lane = 0; lane < 64; ++lane) {
-            const int g = lane >> 4, j = lane & 15;
+            const int g = lane >> 4, j = lane & 15, ch = j >> 1, dx = j & 1;
             int a = -1, b = -1;
             if (s < 5) { a = s; b = g; }
             else if (s == 5) { a = g; b = 4; }
+            else if (s == 6) { a = g; b = 5; }
             else if (g == 0) { a = 4; b = 4; }
-            f[kS2F1 + s * 64 + lane] = (a < 0 || j >= 8) ? 0.0f : w[s2::W1 + (j * 5 + a) * 5 + b];
+            else if (g == 1) { a = 4; b = 5; }
+            const int tap = b - dx;
+            f[kS2F1 + s * 64 + lane] = (a < 0 || a > 4 || tap < 0 || tap > 4) ? 0.0f : w[s2::W1 + (ch * 5 + a) * 5 + tap];
         }
     for (int tap = 0; tap < 9; ++tap)
         for (int cq = 0; cq < 2; ++cq)
@@ -572,12 +597,15 @@ extern "C" void cnnc_debug_read_span(unsigned long long *out)
 }
 #endif
 
-hipError_t launch_eval3_mfma(const cnnc_ctx *c, hipStream_t st)
+hipError_t launch_eval3_mfma(cnnc_ctx *c, hipStream_t st)
 {
 #define CNNC_E3(ACT)                                                                                              \
-    hipLaunchKernelGGL(eval3_conv_kernel<ACT>, dim3(conv_grid(c)), dim3(kThreads), 0, st, c->d_frame, c->fw, c->fh, \
+    {                                                                                                             \
+        ScopedTimer timer_(c, CNNC_T_STAGE3_CONV, st);                                                            \
+        hipLaunchKernelGGL(eval3_conv_kernel<ACT>, dim3(conv_grid(c)), dim3(kThreads), 0, st, c->d_frame, c->fw, c->fh, \
                        c->fpitch, c->d_levels, c->n_levels, c->d_idx[1], &c->d_cnt->n[1], c->max_surv, c->d_wt[2], \
                        c->d_frag[1], c->d_feat[1]);                                                                \
+    }                                                                                                             \
     hipLaunchKernelGGL(eval3_fc_kernel<ACT>, dim3(fc_grid(c)), dim3(kThreads), 0, st, c->d_feat[1], &c->d_cnt->n[1], \
                        c->max_surv, c->d_wt[2], c->d_frag[1], c->d_eval[1])
     switch (c->act) {
@@ -589,14 +617,17 @@ hipError_t launch_eval3_mfma(const cnnc_ctx *c, hipStream_t st)
     return hipGetLastError();
 }
 
-hipError_t launch_eval2_mfma(const cnnc_ctx *c, hipStream_t st)
+hipError_t launch_eval2_mfma(cnnc_ctx *c, hipStream_t st)
 {
     const int waves = c->max_surv < 256 * 3 * 4 ? c->max_surv : 256 * 3 * 4;   // three workgroups of four crops per compute unit (register limit)
     const int grid = (waves + 3) / 4;
 #define CNNC_E2(ACT)                                                                                              \
-    hipLaunchKernelGGL(eval2_conv_kernel<ACT>, dim3(grid), dim3(kThreads), 0, st, c->d_frame, c->fw, c->fh,         \
+    {                                                                                                             \
+        ScopedTimer timer_(c, CNNC_T_STAGE2_CONV, st);                                                            \
+        hipLaunchKernelGGL(eval2_conv_kernel<ACT>, dim3(grid), dim3(kThreads), 0, st, c->d_frame, c->fw, c->fh,         \
                        c->fpitch, c->d_levels, c->n_levels, c->d_idx[0], &c->d_cnt->n[0], c->max_surv, c->d_wt[1], \
                        c->d_frag[0], c->d_feat[0]);                                                                \
+    }                                                                                                             \
     hipLaunchKernelGGL(eval2_fc_kernel<ACT>, dim3(fc_grid(c)), dim3(kThreads), 0, st, c->d_feat[0], &c->d_cnt->n[0], \
                        c->max_surv, c->d_wt[1], c->d_frag[0], c->d_eval[0])
     switch (c->act) {
