@@ -28,9 +28,11 @@ S3_CONV_FLOP_PER_CROP = 2 * (774400 + 4147200 + 451584)  # conv kernel of stage 
 PEAK_HBM = 8000.0          # GB/s
 PEAK_FP32_VECTOR = 157.3   # TFLOP/s, published vector fp32 figure
 PEAK_FP32_MFMA = 157.3     # TFLOP/s, published dense fp32 matrix figure
-# HBM bytes per launch of the dominant kernel from rocprofv3 FETCH_SIZE / WRITE_SIZE passes
-# (profiles/eval3_conv_uhd_pmc.txt), or None where not measured for that workload.
-MEASURED_TRAFFIC = {}
+# HBM bytes per launch from the rocprofv3 FETCH_SIZE / WRITE_SIZE passes summarised in
+# profiles/hbm_traffic_uhd_pmc.txt (read + written, scaled by the copy-kernel calibration); None where
+# that workload was not measured.
+MEASURED_TRAFFIC = {("stage3_conv", "uhd"): 43.34e6 + 33.28e6, ("stage2_conv", "uhd"): 69.73e6 + 17.54e6,
+                    ("stage1", "uhd"): 5.72e6 + 4.21e6, ("pyramid", "uhd"): 17.02e6 + 1.22e6}
 
 
 def main():
