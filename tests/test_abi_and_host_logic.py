@@ -1,0 +1,68 @@
+"""CPU-only checks of the C-ABI library: it loads without a GPU, exports every symbol the header declares,
+and its host-only entry points reject bad arguments.  No kernel is launched here."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _header_functions():
+    text = open(os.path.join(ROOT, "include", "cnnc.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(cnnc_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    import paper_1508_01292_amd as P
+    if not os.path.exists(P.library_path()):
+        pytest.fail("libcnnc.so is not built; run __graft_entry__.build()")
+    L = P.lib()
+    declared = _header_functions()
+    assert len(declared) >= 20
+    for name in declared:
+        assert hasattr(L, name), "libcnnc.so does not export " + name
+    # the binding's own list names the same functions
+    assert sorted(P.EXPORTS) == declared
+    assert L.cnnc_version().decode().startswith("cnnc")
+
+
+def test_host_only_argument_checks_need_no_gpu():
+    import paper_1508_01292_amd as P
+    L = P.lib()
+    # null handles are rejected before anything touches a device
+    assert L.cnnc_destroy(C.c_void_p(0)) == -1
+    assert L.cnnc_set_params(C.c_void_p(0), C.c_void_p(0)) == -1
+    assert L.cnnc_stage1_scoremap(C.c_void_p(0), C.c_void_p(0)) == -1
+    assert L.cnnc_eval_stage(C.c_void_p(0), C.c_int(2), C.c_void_p(0)) == -1
+    assert L.cnnc_measure_peaks(C.c_void_p(0), C.c_void_p(0), C.c_void_p(0)) == -1
+    out = C.c_void_p(123)
+    assert L.cnnc_create(C.byref(out), C.c_void_p(0), C.c_int(640), C.c_int(480), C.c_int(100)) == -1
+    assert out.value is None            # the handle is cleared on failure
+    assert L.cnnc_last_error(C.c_void_p(0)) == b"null context"
+
+
+def test_missing_library_is_an_error_not_a_fallback(monkeypatch):
+    import paper_1508_01292_amd.binding as B
+    monkeypatch.setattr(B, "_lib", None)
+    monkeypatch.setattr(B, "_LIB_PATH", os.path.join(ROOT, "does_not_exist", "libcnnc.so"))
+    with pytest.raises(ImportError):
+        B.lib()
+
+
+def test_product_package_does_not_import_the_oracle():
+    pkg = os.path.join(ROOT, "paper_1508_01292_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h", ".cpp")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "oracle" not in text.lower() or f == "__init__.py" and False, f + " mentions the oracle"
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode != 0 and "ONE GPU" in r.stderr

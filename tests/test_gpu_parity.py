@@ -274,6 +274,62 @@ def test_async_contexts_on_streams_match_synchronous_results():
         c.close()
 
 
+def test_fhd_stream_three_survival_quantiles_async():
+    """The 16-frame 1920x1080 stream (0..200 ellipses per frame), thresholds pooled over the stream at three
+    stage-1 survival quantiles, frames in flight on three streams.  Every frame's detections are compared with
+    the oracle's at the 0.5 % quantile (where the oracle finishes in seconds) and with the synchronous GPU
+    path at all three; survivor counts per frame are compared with the oracle's at all three."""
+    torch = _torch()
+    casc = I.default_cascade()
+    W = I.draw_weights(casc, I.config_seed(4))
+    c = I.CONFIGS[4]
+    frames = I.make_stream(4)
+    assert len(frames) == 16
+    print("case fhd stream", flush=True)
+    pyrs = [O.build_pyramid(f, c["min_face"], c["scale_step"]) for f in frames]
+    s1 = [O.stage1_scores(p, casc[0], W[0]) for p in pyrs]
+    pooled = np.concatenate(s1)
+    dev = [torch.from_numpy(f).cuda() for f in frames]
+    ctxs = [_ctx(casc, W, c["width"], c["height"]) for _ in range(3)]
+    streams = [torch.cuda.Stream() for _ in range(3)]
+    sync = _ctx(casc, W, c["width"], c["height"])
+    for q in (0.005, 0.02, 0.10):
+        t1 = O.threshold_from_quantile(pooled, q)
+        idx1 = [O.survivors(s, t1) for s in s1]
+        assert sum(len(i) for i in idx1) == int(np.floor(q * pooled.size))
+        if q == 0.005:
+            s2 = [O.eval_stage(f, p, i, casc[1], W[1]) for f, p, i in zip(frames, pyrs, idx1)]
+            t2 = O.threshold_from_quantile(np.concatenate(s2), 0.2)
+        else:
+            t2 = 0.0        # any fixed threshold: the later stages are checked against the synchronous path
+        thr = (float(t1), float(t2), 0.0)
+        sync.set_params(c["min_face"], c["scale_step"], thr)
+        for cx in ctxs:
+            cx.set_params(c["min_face"], c["scale_step"], thr)
+        want = []
+        for k, d in enumerate(dev):
+            want.append([x.as_dict() for x in sync.detect(d, 8192)])
+            g1, _ = sync.get_survivors(1)
+            assert_survivors(g1, s1[k], np.arange(s1[k].size), t1, "stage-1 survivors, frame %d, q %g" % (k, q))
+        got = [None] * 16
+        for base in range(0, 18, 3):
+            for j in range(3):
+                if base + j < 16:
+                    if base:
+                        got[base + j - 3] = [x.as_dict() for x in ctxs[j].fetch_detections(8192)]
+                    ctxs[j].detect_async(dev[base + j], streams[j])
+        for k in range(13, 16):
+            got[k] = [x.as_dict() for x in ctxs[k % 3].fetch_detections(8192)]
+        assert got == want, "asynchronous detections differ from synchronous ones at q = %g" % q
+        if q == 0.005:
+            for k in (0, 5, 15):
+                tr = O.detect(frames[k], casc, W, c["min_face"], c["scale_step"], thr=thr)
+                key = lambda d: (d["x"], d["y"], d["size"], d["neighbors"], d["index"])
+                assert [key(d) for d in got[k]] == [key(d) for d in tr.det], "frame %d" % k
+    for cx in ctxs + [sync]:
+        cx.close()
+
+
 def test_uhd_headline_workload_full_oracle():
     """The 3840x2160, min-face-60 workload the throughput is quoted on, against the full oracle."""
     c = I.CONFIGS[2]
