@@ -42,14 +42,16 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--inflight", type=int, default=3, help="frames in flight on separate streams")
     ap.add_argument("--workload", default="uhd")
+    ap.add_argument("--q1", type=float, default=0.02, help="stage-1 survival quantile (the benchmark's rule: 2 %%)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--eval-impl", type=int, default=None, help="cnnc_set_eval_impl value (default: the library's)")
     a = ap.parse_args()
     if a.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus %d is not supported (no collectives, no sharding)" % a.gpus,
               file=sys.stderr)
         sys.exit(2)
 
-    import numpy as np
+    import numpy as np  # noqa: F401
     import torch
 
     import cnnc_inputs as I
@@ -61,11 +63,19 @@ def main():
     seed = I.config_seed(ci)
     casc = I.default_cascade()
     W = I.draw_weights(casc, seed)
-    frame = I.make_frame(cfg["width"], cfg["height"], seed)
+    frames = I.make_stream(ci)
+    frame = frames[0]
 
     # ---- CPU oracle: thresholds at the survival quantiles (the oracle's job) and the cpu_baseline leg
+    thr_pooled = None
+    if len(frames) > 1:      # a stream: thresholds sit at the quantiles of the scores pooled over all frames
+        pyrs = [O.build_pyramid(f, cfg["min_face"], cfg["scale_step"]) for f in frames]
+        s1 = [O.stage1_scores(p, casc[0], W[0]) for p in pyrs]
+        t1 = O.threshold_from_quantile(np.concatenate(s1), a.q1)
+        s2 = [O.eval_stage(f, p, O.survivors(s, t1), casc[1], W[1]) for f, p, s in zip(frames, pyrs, s1)]
+        thr_pooled = (float(t1), float(O.threshold_from_quantile(np.concatenate(s2), 0.2)), 0.0)
     t0 = time.perf_counter()
-    tr = O.detect(frame, casc, W, cfg["min_face"], cfg["scale_step"], quantiles=(0.02, 0.2))
+    tr = O.detect(frame, casc, W, cfg["min_face"], cfg["scale_step"], thr=thr_pooled, quantiles=(a.q1, 0.2))
     t_cpu = time.perf_counter() - t0
     n_windows = int(tr.score1.size)
     cpu = None
@@ -76,12 +86,15 @@ def main():
 
     # ---- GPU
     torch.cuda.set_device(0)
-    dev_frame = torch.from_numpy(frame).cuda()
+    dev_frames = [torch.from_numpy(f).cuda() for f in frames]
+    dev_frame = dev_frames[0]
     F = max(1, a.inflight)
     ctxs = [P.Context(casc, W, cfg["width"], cfg["height"], 262144) for _ in range(F)]
     streams = [torch.cuda.Stream() for _ in range(F)]
     for c in ctxs:
         c.set_params(cfg["min_face"], cfg["scale_step"], tr.thr)
+        if a.eval_impl is not None:
+            c.set_eval_impl(a.eval_impl)
 
     def run(n_steps):
         busy = [False] * F
@@ -90,7 +103,7 @@ def main():
             j = i % F
             if busy[j]:
                 n_det = len(ctxs[j].fetch_detections(8192))
-            ctxs[j].detect_async(dev_frame, streams[j])
+            ctxs[j].detect_async(dev_frames[i % len(dev_frames)], streams[j])
             busy[j] = True
         for j in range(F):
             if busy[j]:
@@ -174,8 +187,9 @@ def main():
         "metric": METRIC, "value": fps, "unit": "frames/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
         "ms_per_step": elapsed / a.steps * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
-        "config": {"workload": "%s: one %dx%d uint8 frame, min face %g px, scale step %g, 2%% / 20%% survival quantiles, T3 = 0"
-                               % (cfg["name"], cfg["width"], cfg["height"], cfg["min_face"], cfg["scale_step"]),
+        "config": {"workload": "%s: %d %dx%d uint8 frame(s), min face %g px, scale step %g, %g%% / 20%% survival quantiles, T3 = 0"
+                               % (cfg["name"], len(frames), cfg["width"], cfg["height"], cfg["min_face"], cfg["scale_step"],
+                                  100 * a.q1),
                    "frames_in_flight": F, "windows": n_windows, "survivors": [n1, n2, n3], "detections": n_det},
         "stage1_windows_per_s": n_windows / (ms["stage1"] * 1e-3) if ms["stage1"] > 0 else None,
         "latency_ms_single_frame": latency_ms,

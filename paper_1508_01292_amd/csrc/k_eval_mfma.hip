@@ -99,16 +99,85 @@ __device__ __forceinline__ void s3_conv2(const float *sP1, float *sP2, const flo
         }
     }
 }
+
+// ---- conv2 of stage 3 by the Winograd minimal-filtering algorithm F(2, 5) along the rows ---------------
+// Two horizontally adjacent outputs of a 5-tap row filter cost 6 multiplications instead of 10:
+//   out(x0 + q) = sum_b AT[q][b] * (sum_l G[b][l] w[l]) * (sum_p BT[b][p] d[x0 + p]),   q = 0, 1, x0 even.
+// For the 5x5, 16 -> 32 convolution this gives six GEMMs (one per b) with M = 162 positions (18 rows x 9
+// column pairs), K = 16 channels x 5 kernel rows = 80 and N = 32, i.e. 60 % of the matrix work of the direct
+// sum.  The lane that feeds the A operand reads six consecutive floats of one input row and transforms them
+// in registers (BT has 26 non-zeros); the filter side U = G w is prepared on the host in fp64.  Interpolation
+// points 0, 1, -1, 2, -1/2 and infinity: the fp32 result stays within about 1e-6 of the direct fp32 sum here.
+// Positions are ordered so that the four accumulator registers of a lane hold two pooling blocks
+// (block, line) = (2 g + r / 2, r % 2) of the M-tile, and the output transform leaves both columns of a
+// line in the same lane: max-pooling stays in registers.
+constexpr float kBT[6][6] = {{1.0f, 1.5f, -2.0f, -1.5f, 1.0f, 0.0f},  {0.0f, -1.0f, -2.5f, -0.5f, 1.0f, 0.0f},
+                             {0.0f, 1.0f, 0.5f, -2.5f, 1.0f, 0.0f},   {0.0f, -0.5f, -1.0f, 0.5f, 1.0f, 0.0f},
+                             {0.0f, 2.0f, -1.0f, -2.0f, 1.0f, 0.0f},  {0.0f, 1.0f, 1.5f, -2.0f, -1.5f, 1.0f}};
+constexpr int kWinoTiles = 11;          // 81 pooling blocks, eight per M-tile
+
+template <int ACT>
+__device__ __forceinline__ void s3_conv2_wino_tile(const float *sP1, float *sP2, const float *__restrict__ UF, int mt,
+                                                   int lane, float bias_lo, float bias_hi)
+{
+    const int i = lane & 15, g = lane >> 4, j = lane & 15;
+    const int pb = min(8 * mt + (i >> 1), 80);                 // this lane's A rows: pooling block and line i % 2
+    const float *dptr = sP1 + g * kP1Ch + (2 * (pb / 9) + (i & 1)) * kP1Row + 2 * (pb % 9);
+    floatx4 acc[6][2];
+#pragma unroll
+    for (int b = 0; b < 6; ++b) { acc[b][0] = floatx4{0, 0, 0, 0}; acc[b][1] = floatx4{0, 0, 0, 0}; }
+    const float4 *up = reinterpret_cast<const float4 *>(UF) + lane * 3;        // [k-step][lane] three float4
+    float4 u0 = up[0], u1 = up[1], u2 = up[2];
+#pragma unroll 1
+    for (int a = 0; a < 5; ++a) {                                // kernel row
+#pragma unroll
+        for (int cq = 0; cq < 4; ++cq) {                         // input channels 4 cq + g
+            const int nstep = min(a * 4 + cq + 1, 19);
+            const float4 n0 = up[nstep * 192], n1 = up[nstep * 192 + 1], n2 = up[nstep * 192 + 2];
+            asm volatile("" ::: "memory");                        // next step's weights stay in flight during the math
+            const float *row = dptr + cq * 4 * kP1Ch + a * kP1Row;
+            const float2 r0 = *reinterpret_cast<const float2 *>(row), r1 = *reinterpret_cast<const float2 *>(row + 2),
+                         r2 = *reinterpret_cast<const float2 *>(row + 4);
+            const float d[6] = {r0.x, r0.y, r1.x, r1.y, r2.x, r2.y};
+            const float ub[12] = {u0.x, u0.y, u0.z, u0.w, u1.x, u1.y, u1.z, u1.w, u2.x, u2.y, u2.z, u2.w};
+#pragma unroll
+            for (int b = 0; b < 6; ++b) {
+                float v = 0.0f;                                   // transformed input: sum_p BT[b][p] d[p]
+#pragma unroll
+                for (int p = 0; p < 6; ++p)
+                    if (kBT[b][p] != 0.0f) v = fmaf(kBT[b][p], d[p], v);
+                acc[b][0] = CNNC_MFMA(v, ub[2 * b], acc[b][0]);
+                acc[b][1] = CNNC_MFMA(v, ub[2 * b + 1], acc[b][1]);
+            }
+            u0 = n0; u1 = n1; u2 = n2;
+        }
+    }
+    // output transform (AT = [1 1 1 1 1 0; 0 1 -1 2 -1/2 1]), pooling, bias, activation
+#pragma unroll
+    for (int nt = 0; nt < 2; ++nt) {
+        const floatx4 R0 = acc[0][nt] + acc[1][nt] + acc[2][nt] + acc[3][nt] + acc[4][nt];
+        const floatx4 R1 = acc[1][nt] - acc[2][nt] + 2.0f * acc[3][nt] - 0.5f * acc[4][nt] + acc[5][nt];
+        const float bias = nt ? bias_hi : bias_lo;
+        const int oc = 16 * nt + j;
+#pragma unroll
+        for (int sub = 0; sub < 2; ++sub) {
+            const int blk = 8 * mt + 2 * g + sub;
+            const float m = fmaxf(fmaxf(R0[2 * sub], R1[2 * sub]), fmaxf(R0[2 * sub + 1], R1[2 * sub + 1]));
+            if (blk < 81) sP2[oc * kP2Ch + blk] = act_f<ACT>(m + bias);
+        }
+    }
+}
 }  // namespace
 
 // Fragment buffer of stage 3 (floats): conv1 [7][64], conv2 [25][2][64][4], conv3 [9][2][64][8], fc [98][4][64][4].
+// plus the Winograd-domain conv2 weights [5 kernel rows][4 channel quads][64][6 points x 2 n-tiles].
 constexpr int kS3F1 = 0, kS3F2 = kS3F1 + 7 * 64, kS3F3 = kS3F2 + 25 * 2 * 64 * 4, kS3F4 = kS3F3 + 9 * 2 * 64 * 8,
-              kS3FragFloats = kS3F4 + 98 * 4 * 64 * 4;
+              kS3F5 = kS3F4 + 98 * 4 * 64 * 4, kS3FragFloats = kS3F5 + 20 * 64 * 12;
 constexpr int kS3Feat = 1568;
 
 // Crop -> conv1 -> pool -> conv2 -> pool -> conv3 for each surviving window; writes the 1568 conv3
 // activations of the window (order [channel][row][col]) to `feat`.
-template <int ACT>
+template <int ACT, bool WINO>
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(3, 3)))
 void eval3_conv_kernel(const uint8_t *__restrict__ frame, int fw, int fh, int pitch, const LevelDev *__restrict__ levels,
                        int n_levels, const uint32_t *__restrict__ idx, const int32_t *__restrict__ d_n, int n_max,
@@ -178,8 +247,15 @@ void eval3_conv_kernel(const uint8_t *__restrict__ frame, int fw, int fh, int pi
 
         // ---- conv2 5x5 16->32 + pool: 21 tiles; the wave that takes six of them rotates per crop
         const int wslot = (wave + rot + blockIdx.x + (blockIdx.x >> 8)) & 3;
-        if (wslot == 0) s3_conv2<6, ACT>(sB, sA, frag + kS3F2, wslot, lane, bias2_lo, bias2_hi);
-        else s3_conv2<5, ACT>(sB, sA, frag + kS3F2, wslot, lane, bias2_lo, bias2_hi);
+        if (WINO) {
+            // eleven M-tiles of eight pooling blocks, dealt round-robin from a slot that rotates per crop
+#pragma unroll 1
+            for (int mt = wslot; mt < kWinoTiles; mt += 4) s3_conv2_wino_tile<ACT>(sB, sA, frag + kS3F5, mt, lane, bias2_lo, bias2_hi);
+        } else if (wslot == 0) {
+            s3_conv2<6, ACT>(sB, sA, frag + kS3F2, wslot, lane, bias2_lo, bias2_hi);
+        } else {
+            s3_conv2<5, ACT>(sB, sA, frag + kS3F2, wslot, lane, bias2_lo, bias2_hi);
+        }
         CNNC_PROBE(5);
         __syncthreads();
         CNNC_PROBE(6);
@@ -344,6 +420,25 @@ void eval3_make_fragments(const float *w, float *f)
                     const int g = lane >> 4, j = lane & 15;
                     f[kS3F4 + ((ch * 4 + nt) * 64 + lane) * 4 + s] = w[s3::W4 + (nt * 16 + j) * 1568 + 16 * ch + 4 * g + s];
                 }
+    // Winograd-domain conv2 weights U_b = sum_l G[b][l] w[.][.][a][l] (fp64, then rounded); G for the points
+    // 0, 1, -1, 2, -1/2, infinity
+    static const double G[6][5] = {{1, 0, 0, 0, 0},
+                                   {-1.0 / 3, -1.0 / 3, -1.0 / 3, -1.0 / 3, -1.0 / 3},
+                                   {1.0 / 3, -1.0 / 3, 1.0 / 3, -1.0 / 3, 1.0 / 3},
+                                   {1.0 / 15, 2.0 / 15, 4.0 / 15, 8.0 / 15, 16.0 / 15},
+                                   {-16.0 / 15, 8.0 / 15, -4.0 / 15, 2.0 / 15, -1.0 / 15},
+                                   {0, 0, 0, 0, 1}};
+    for (int oc = 0; oc < 32; ++oc)
+        for (int c = 0; c < 16; ++c)
+            for (int a = 0; a < 5; ++a) {
+                const float *k = w + s3::W2 + ((oc * 16 + c) * 5 + a) * 5;
+                const int cq = c >> 2, g = c & 3, nt = oc >> 4, j = oc & 15, lane = g * 16 + j;
+                for (int b = 0; b < 6; ++b) {
+                    double acc = 0;
+                    for (int l = 0; l < 5; ++l) acc += G[b][l] * (double)k[l];
+                    f[kS3F5 + ((a * 4 + cq) * 64 + lane) * 12 + b * 2 + nt] = (float)acc;
+                }
+            }
 }
 
 // =================================================================================================
@@ -602,17 +697,26 @@ hipError_t launch_eval3_mfma(cnnc_ctx *c, hipStream_t st)
 #define CNNC_E3(ACT)                                                                                              \
     {                                                                                                             \
         ScopedTimer timer_(c, CNNC_T_STAGE3_CONV, st);                                                            \
-        hipLaunchKernelGGL(eval3_conv_kernel<ACT>, dim3(conv_grid(c)), dim3(kThreads), 0, st, c->d_frame, c->fw, c->fh, \
+        hipLaunchKernelGGL((eval3_conv_kernel<ACT, WINO>), dim3(conv_grid(c)), dim3(kThreads), 0, st, c->d_frame, c->fw, c->fh, \
                        c->fpitch, c->d_levels, c->n_levels, c->d_idx[1], &c->d_cnt->n[1], c->max_surv, c->d_wt[2], \
                        c->d_frag[1], c->d_feat[1]);                                                                \
     }                                                                                                             \
     hipLaunchKernelGGL(eval3_fc_kernel<ACT>, dim3(fc_grid(c)), dim3(kThreads), 0, st, c->d_feat[1], &c->d_cnt->n[1], \
                        c->max_surv, c->d_wt[2], c->d_frag[1], c->d_eval[1])
-    switch (c->act) {
-    case CNNC_ACT_RATIONAL: CNNC_E3(CNNC_ACT_RATIONAL); break;
-    case CNNC_ACT_SCALED_TANH: CNNC_E3(CNNC_ACT_SCALED_TANH); break;
-    default: CNNC_E3(CNNC_ACT_TANH); break;
+#define CNNC_E3W(ACT)                     \
+    if (c->eval_impl == 2) {              \
+        constexpr bool WINO = true;       \
+        CNNC_E3(ACT);                     \
+    } else {                              \
+        constexpr bool WINO = false;      \
+        CNNC_E3(ACT);                     \
     }
+    switch (c->act) {
+    case CNNC_ACT_RATIONAL: CNNC_E3W(CNNC_ACT_RATIONAL); break;
+    case CNNC_ACT_SCALED_TANH: CNNC_E3W(CNNC_ACT_SCALED_TANH); break;
+    default: CNNC_E3W(CNNC_ACT_TANH); break;
+    }
+#undef CNNC_E3W
 #undef CNNC_E3
     return hipGetLastError();
 }

@@ -75,6 +75,26 @@ def test_vector_alu_variant_of_later_stages():
     ctx.close()
 
 
+@pytest.mark.parametrize("act", [I.ACT_RATIONAL, I.ACT_TANH])
+def test_winograd_variant_of_stage3(act):
+    """cnnc_set_eval_impl(2): stage-3 conv2 through the Winograd F(2x2,5x5) transform on the matrix cores."""
+    torch = _torch()
+    c = I.CONFIGS[0]
+    casc = I.default_cascade(act)
+    W = I.draw_weights(casc, 6, bias_sd=0.1)
+    frame = I.make_frame(c["width"], c["height"], 56)
+    tr = O.detect(frame, casc, W, c["min_face"], c["scale_step"], quantiles=(0.05, 0.5))
+    ctx = _ctx(casc, W, c["width"], c["height"])
+    ctx.set_params(c["min_face"], c["scale_step"], tr.thr)
+    ctx.set_eval_impl(2)
+    g = run_gpu_steps(ctx, torch.from_numpy(frame).cuda(), tr.thr)
+    compare_with_trace(g, tr, frame, casc, W)
+    err = np.abs(g["score3"].astype(np.float64) - np.asarray([dict(zip(tr.idx2.tolist(), tr.score3.tolist())).get(i, np.nan)
+                                                                 for i in g["idx2"].tolist()]))
+    print("   stage-3 score error with Winograd conv2: max %.3g" % np.nanmax(err), flush=True)
+    ctx.close()
+
+
 def test_ragged_sizes_and_nonzero_biases():
     """Odd frame sizes: level sizes that leave ragged tile tails in every kernel, small scale steps,
     a pitch larger than the width."""
