@@ -176,9 +176,11 @@ int cnnc_survivor_count(cnnc_ctx *ctx, int stage, int *n, void *stream);
 int cnnc_set_timing(cnnc_ctx *ctx, int on);
 int cnnc_get_timings(cnnc_ctx *ctx, double *ms_sum, int32_t *calls);
 
-/* Which kernels cnnc_eval_stage uses: 1 (default) = implicit-GEMM kernels on the matrix cores (fp32 MFMA),
- * 0 = direct convolution on the vector ALU.  Same results within rounding; kept so that the choice stays
- * measurable (the paper's Section 3.4 argues for code specialised per network and processor). */
+/* Which kernels cnnc_eval_stage uses: 2 (default) = implicit-GEMM kernels on the matrix cores (fp32 MFMA) with
+ * the 5x5, 16 -> 32 convolution of stage 3 evaluated by the Winograd F(2,5) minimal-filtering algorithm along
+ * rows; 1 = the same kernels with direct sums only; 0 = direct convolution on the vector ALU.  Same results
+ * within fp32 rounding (about 1e-6 on a score); kept so that the choice stays measurable (the paper's
+ * Section 3.4 argues for code specialised per network and processor). */
 int cnnc_set_eval_impl(cnnc_ctx *ctx, int impl);
 
 /* Measurement aid for benchmarks: what this GPU sustains on three synthetic probes (dense fp32 MFMA loop,

@@ -16,8 +16,6 @@
 //
 // The fully connected layers are batched over crops in a second kernel (M = crops), so their
 // weights are read once per 16 crops instead of once per crop.
-#include <stdlib.h>
-
 #include "eval_common.h"
 
 namespace cnnc {
@@ -116,16 +114,22 @@ constexpr float kBT[6][6] = {{1.0f, 1.5f, -2.0f, -1.5f, 1.0f, 0.0f},  {0.0f, -1.
                              {0.0f, 2.0f, -1.0f, -2.0f, 1.0f, 0.0f},  {0.0f, 1.0f, 1.5f, -2.0f, -1.5f, 1.0f}};
 constexpr int kWinoTiles = 11;          // 81 pooling blocks, eight per M-tile
 
-template <int ACT>
-__device__ __forceinline__ void s3_conv2_wino_tile(const float *sP1, float *sP2, const float *__restrict__ UF, int mt,
-                                                   int lane, float bias_lo, float bias_hi)
+// NT M-tiles (mt0, mt0 + 4, ...) in one pass over the filter: every loaded filter fragment feeds NT tiles, which
+// divides the L2 -> register traffic of the filter by NT.
+template <int NT, int ACT>
+__device__ __forceinline__ void s3_conv2_wino_tiles(const float *sP1, float *sP2, const float *__restrict__ UF, int mt0,
+                                                    int lane, float bias_lo, float bias_hi)
 {
     const int i = lane & 15, g = lane >> 4, j = lane & 15;
-    const int pb = min(8 * mt + (i >> 1), 80);                 // this lane's A rows: pooling block and line i % 2
-    const float *dptr = sP1 + g * kP1Ch + (2 * (pb / 9) + (i & 1)) * kP1Row + 2 * (pb % 9);
-    floatx4 acc[6][2];
+    const float *dptr[NT];
+    floatx4 acc[NT][6][2];
 #pragma unroll
-    for (int b = 0; b < 6; ++b) { acc[b][0] = floatx4{0, 0, 0, 0}; acc[b][1] = floatx4{0, 0, 0, 0}; }
+    for (int t = 0; t < NT; ++t) {
+        const int pb = min(8 * (mt0 + 4 * t) + (i >> 1), 80);    // this lane's A rows: pooling block and line i % 2
+        dptr[t] = sP1 + g * kP1Ch + (2 * (pb / 9) + (i & 1)) * kP1Row + 2 * (pb % 9);
+#pragma unroll
+        for (int b = 0; b < 6; ++b) { acc[t][b][0] = floatx4{0, 0, 0, 0}; acc[t][b][1] = floatx4{0, 0, 0, 0}; }
+    }
     const float4 *up = reinterpret_cast<const float4 *>(UF) + lane * 3;        // [k-step][lane] three float4
     float4 u0 = up[0], u1 = up[1], u2 = up[2];
 #pragma unroll 1
@@ -135,37 +139,42 @@ __device__ __forceinline__ void s3_conv2_wino_tile(const float *sP1, float *sP2,
             const int nstep = min(a * 4 + cq + 1, 19);
             const float4 n0 = up[nstep * 192], n1 = up[nstep * 192 + 1], n2 = up[nstep * 192 + 2];
             asm volatile("" ::: "memory");                        // next step's weights stay in flight during the math
-            const float *row = dptr + cq * 4 * kP1Ch + a * kP1Row;
-            const float2 r0 = *reinterpret_cast<const float2 *>(row), r1 = *reinterpret_cast<const float2 *>(row + 2),
-                         r2 = *reinterpret_cast<const float2 *>(row + 4);
-            const float d[6] = {r0.x, r0.y, r1.x, r1.y, r2.x, r2.y};
             const float ub[12] = {u0.x, u0.y, u0.z, u0.w, u1.x, u1.y, u1.z, u1.w, u2.x, u2.y, u2.z, u2.w};
 #pragma unroll
-            for (int b = 0; b < 6; ++b) {
-                float v = 0.0f;                                   // transformed input: sum_p BT[b][p] d[p]
+            for (int t = 0; t < NT; ++t) {
+                const float *row = dptr[t] + cq * 4 * kP1Ch + a * kP1Row;
+                const float2 r0 = *reinterpret_cast<const float2 *>(row), r1 = *reinterpret_cast<const float2 *>(row + 2),
+                             r2 = *reinterpret_cast<const float2 *>(row + 4);
+                const float d[6] = {r0.x, r0.y, r1.x, r1.y, r2.x, r2.y};
 #pragma unroll
-                for (int p = 0; p < 6; ++p)
-                    if (kBT[b][p] != 0.0f) v = fmaf(kBT[b][p], d[p], v);
-                acc[b][0] = CNNC_MFMA(v, ub[2 * b], acc[b][0]);
-                acc[b][1] = CNNC_MFMA(v, ub[2 * b + 1], acc[b][1]);
+                for (int b = 0; b < 6; ++b) {
+                    float v = 0.0f;                               // transformed input: sum_p BT[b][p] d[p]
+#pragma unroll
+                    for (int p = 0; p < 6; ++p)
+                        if (kBT[b][p] != 0.0f) v = fmaf(kBT[b][p], d[p], v);
+                    acc[t][b][0] = CNNC_MFMA(v, ub[2 * b], acc[t][b][0]);
+                    acc[t][b][1] = CNNC_MFMA(v, ub[2 * b + 1], acc[t][b][1]);
+                }
             }
             u0 = n0; u1 = n1; u2 = n2;
         }
     }
     // output transform (AT = [1 1 1 1 1 0; 0 1 -1 2 -1/2 1]), pooling, bias, activation
 #pragma unroll
-    for (int nt = 0; nt < 2; ++nt) {
-        const floatx4 R0 = acc[0][nt] + acc[1][nt] + acc[2][nt] + acc[3][nt] + acc[4][nt];
-        const floatx4 R1 = acc[1][nt] - acc[2][nt] + 2.0f * acc[3][nt] - 0.5f * acc[4][nt] + acc[5][nt];
-        const float bias = nt ? bias_hi : bias_lo;
-        const int oc = 16 * nt + j;
+    for (int t = 0; t < NT; ++t)
 #pragma unroll
-        for (int sub = 0; sub < 2; ++sub) {
-            const int blk = 8 * mt + 2 * g + sub;
-            const float m = fmaxf(fmaxf(R0[2 * sub], R1[2 * sub]), fmaxf(R0[2 * sub + 1], R1[2 * sub + 1]));
-            if (blk < 81) sP2[oc * kP2Ch + blk] = act_f<ACT>(m + bias);
+        for (int nt = 0; nt < 2; ++nt) {
+            const floatx4 R0 = acc[t][0][nt] + acc[t][1][nt] + acc[t][2][nt] + acc[t][3][nt] + acc[t][4][nt];
+            const floatx4 R1 = acc[t][1][nt] - acc[t][2][nt] + 2.0f * acc[t][3][nt] - 0.5f * acc[t][4][nt] + acc[t][5][nt];
+            const float bias = nt ? bias_hi : bias_lo;
+            const int oc = 16 * nt + j;
+#pragma unroll
+            for (int sub = 0; sub < 2; ++sub) {
+                const int blk = 8 * (mt0 + 4 * t) + 2 * g + sub;
+                const float m = fmaxf(fmaxf(R0[2 * sub], R1[2 * sub]), fmaxf(R0[2 * sub + 1], R1[2 * sub + 1]));
+                if (blk < 81) sP2[oc * kP2Ch + blk] = act_f<ACT>(m + bias);
+            }
         }
-    }
 }
 }  // namespace
 
@@ -188,11 +197,6 @@ void eval3_conv_kernel(const uint8_t *__restrict__ frame, int fw, int fh, int pi
     __shared__ uint32_t sTab[2 * kS3In];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, g = lane >> 4, j = lane & 15;
 
-    float b1f[7];
-#pragma unroll
-    for (int s = 0; s < 7; ++s) b1f[s] = frag[kS3F1 + s * 64 + lane];
-    const float bias1 = wt[s3::B1 + j];
-    const float bias2_lo = wt[s3::B2 + j], bias2_hi = wt[s3::B2 + 16 + j];
     // conv1 k-order: steps 0..4 = taps (a = step, b = g); step 5 = taps (a = g, b = 4);
     // step 6 = tap (4, 4) in group 0, zero weights elsewhere (those lanes re-read their own pixel)
     const int off5 = g * kCropW + 4, off6 = g == 0 ? 4 * kCropW + 4 : 0;
@@ -213,6 +217,14 @@ void eval3_conv_kernel(const uint8_t *__restrict__ frame, int fw, int fh, int pi
         CNNC_PROBE(2);
 
         // ---- conv1 5x5 1->16 + pool: 121 tiles of four pooling blocks, four tiles in flight per wave
+        // (small per-layer constants are re-read per window instead of living in registers through the other layers)
+        float b1f[7];
+#pragma unroll
+        for (int s = 0; s < 7; ++s) b1f[s] = frag[kS3F1 + s * 64 + lane];
+        const float bias1 = wt[s3::B1 + j];
+        int wave_here = wave;
+        asm volatile("" : "+v"(wave_here));      // keeps the tile addresses below from being hoisted out of the
+                                                 // window loop into dozens of long-lived registers
 #pragma unroll 1
         for (int q0 = 0; q0 < 32; q0 += 4) {
             floatx4 acc[4];
@@ -220,7 +232,7 @@ void eval3_conv_kernel(const uint8_t *__restrict__ frame, int fw, int fh, int pi
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
                 acc[u] = floatx4{0, 0, 0, 0};
-                const int t = min(wave + 4 * (q0 + u), 120);
+                const int t = min(wave_here + 4 * (q0 + u), 120);
                 const int pb = 4 * t + (j >> 2);
                 base[u] = (2 * (pb / 22) + ((j >> 1) & 1)) * kCropW + 2 * (pb % 22) + (j & 1);
             }
@@ -247,10 +259,13 @@ void eval3_conv_kernel(const uint8_t *__restrict__ frame, int fw, int fh, int pi
 
         // ---- conv2 5x5 16->32 + pool: 21 tiles; the wave that takes six of them rotates per crop
         const int wslot = (wave + rot + blockIdx.x + (blockIdx.x >> 8)) & 3;
+        const float bias2_lo = wt[s3::B2 + j], bias2_hi = wt[s3::B2 + 16 + j];
         if (WINO) {
-            // eleven M-tiles of eight pooling blocks, dealt round-robin from a slot that rotates per crop
+            // eleven M-tiles of eight pooling blocks, dealt round-robin from a slot that rotates per window.
+            // (Two tiles per pass over the filter halve its L2 traffic but spill registers: measured slower.)
 #pragma unroll 1
-            for (int mt = wslot; mt < kWinoTiles; mt += 4) s3_conv2_wino_tile<ACT>(sB, sA, frag + kS3F5, mt, lane, bias2_lo, bias2_hi);
+            for (int mt = wslot; mt < kWinoTiles; mt += 4)
+                s3_conv2_wino_tiles<1, ACT>(sB, sA, frag + kS3F5, mt, lane, bias2_lo, bias2_hi);
         } else if (wslot == 0) {
             s3_conv2<6, ACT>(sB, sA, frag + kS3F2, wslot, lane, bias2_lo, bias2_hi);
         } else {
@@ -665,7 +680,6 @@ namespace {
 int conv_grid(const cnnc_ctx *c)
 {
     int g = 256 * 3;   // three workgroups fit a compute unit's LDS; each strides over the list
-    if (const char *e = getenv("CNNC_DBG_E3_GRID")) g = atoi(e);
     return c->max_surv < g ? c->max_surv : g;
 }
 int fc_grid(const cnnc_ctx *c)
