@@ -7,46 +7,78 @@ namespace cnnc {
 namespace evalc {
 constexpr int kThreads = 256;
 
-// Sample positions of one crop axis: tab[i] = (index of left pixel << 9) | weight of the right one.
+// Sample positions of one crop axis: tab[i] = (index of left pixel << 9) | weight of the right one (0..256).
+// The left index never is the last pixel of the axis: a position clamped onto it is stored as the pixel
+// before with weight 256, which blends to the same integer and lets every reader fetch index and index + 1.
 template <int N>
 __device__ __forceinline__ void crop_axis(int origin, int64_t S, int n_in, uint32_t *tab, int i)
 {
     int64_t P = (int64_t)origin * S + ((int64_t)(2 * i + 1) * kWin * S) / (2 * N) - 32768;
     const int64_t hi = (int64_t)(n_in - 1) << 16;
     P = P < 0 ? 0 : (P > hi ? hi : P);
-    tab[i] = ((uint32_t)(P >> 16) << 9) | (uint32_t)(((P & 0xFFFF) + 128) >> 8);
+    uint32_t idx = (uint32_t)(P >> 16), w = (uint32_t)(((P & 0xFFFF) + 128) >> 8);
+    if (idx == (uint32_t)(n_in - 1)) { idx -= 1; w = 256; }      // P == hi here, so w was 0
+    tab[i] = (idx << 9) | w;
+}
+
+// The gather of a crop in three parts, so that a kernel can put other work between the issue of the pixel
+// loads and their use: (1) tables of sample positions into LDS, (2) all pixel loads of a thread into
+// registers, (3) blend, normalise and store into the crop buffer.  The caller synchronises between the parts
+// and leaves the tables alone until part 3 is done.
+typedef uint16_t __attribute__((aligned(1))) pixel_pair;           // two neighbouring pixels of a row, any address
+
+template <int N>
+struct CropPixels {
+    static constexpr int kIt = (N * N + kThreads - 1) / kThreads;
+    uint32_t top[kIt], bot[kIt];                                   // pixel pairs of the upper and the lower row
+};
+
+template <int N>
+__device__ __forceinline__ void crop_tables(int x, int y, int64_t S, int fw, int fh, uint32_t *sTab)
+{
+    const int tid = threadIdx.x;
+    if (tid < N) crop_axis<N>(x, S, fw, sTab, tid);
+    else if (tid < 2 * N) crop_axis<N>(y, S, fh, sTab + N, tid - N);
+}
+
+template <int N>
+__device__ __forceinline__ void crop_issue(const uint8_t *__restrict__ frame, int pitch, const uint32_t *sTab, CropPixels<N> &px)
+{
+    const int tid = threadIdx.x;
+#pragma unroll
+    for (int it = 0; it < CropPixels<N>::kIt; ++it) {
+        const int e = min(it * kThreads + tid, N * N - 1);
+        const int i = e / N, j = e % N;
+        const uint32_t x0 = sTab[j] >> 9, y0 = sTab[N + i] >> 9;
+        const uint8_t *r0 = frame + (size_t)y0 * pitch + x0;
+        px.top[it] = *reinterpret_cast<const pixel_pair *>(r0);
+        px.bot[it] = *reinterpret_cast<const pixel_pair *>(r0 + pitch);
+    }
+}
+
+template <int N>
+__device__ __forceinline__ void crop_finish(const CropPixels<N> &px, const uint32_t *sTab, float *sCrop)
+{
+    const int tid = threadIdx.x;
+#pragma unroll
+    for (int it = 0; it < CropPixels<N>::kIt; ++it) {
+        const int e = it * kThreads + tid, ec = min(e, N * N - 1);
+        const uint32_t wx = sTab[ec % N] & 511u, wy = sTab[N + ec / N] & 511u;
+        const uint32_t acc = (px.top[it] & 255u) * (256u - wx) * (256u - wy) + (px.top[it] >> 8) * wx * (256u - wy)
+                           + (px.bot[it] & 255u) * (256u - wx) * wy + (px.bot[it] >> 8) * wx * wy;
+        if (e < N * N) sCrop[e] = normalise((float)acc * (1.0f / 65536.0f));
+    }
 }
 
 template <int N>
 __device__ void gather_crop(const uint8_t *__restrict__ frame, int fw, int fh, int pitch, int x, int y,
                             int64_t S, uint32_t *sTab, float *sCrop)
 {
-    const int tid = threadIdx.x;
-    if (tid < N) crop_axis<N>(x, S, fw, sTab, tid);
-    else if (tid < 2 * N) crop_axis<N>(y, S, fh, sTab + N, tid - N);
+    crop_tables<N>(x, y, S, fw, fh, sTab);
     __syncthreads();
-    // all pixel loads of a thread are issued before the first blend, so their latency is paid once
-    constexpr int kIt = (N * N + kThreads - 1) / kThreads;
-    uint32_t p00[kIt], p01[kIt], p10[kIt], p11[kIt], wxy[kIt];
-#pragma unroll
-    for (int it = 0; it < kIt; ++it) {
-        const int e = min(it * kThreads + tid, N * N - 1);
-        const int i = e / N, j = e % N;
-        const uint32_t ex = sTab[j], ey = sTab[N + i];
-        const int x0 = ex >> 9, y0 = ey >> 9;
-        const int x1 = min(x0 + 1, fw - 1), y1 = min(y0 + 1, fh - 1);
-        const uint8_t *r0 = frame + (size_t)y0 * pitch, *r1 = frame + (size_t)y1 * pitch;
-        p00[it] = r0[x0]; p01[it] = r0[x1]; p10[it] = r1[x0]; p11[it] = r1[x1];
-        wxy[it] = ((ex & 511u) << 16) | (ey & 511u);
-    }
-#pragma unroll
-    for (int it = 0; it < kIt; ++it) {
-        const int e = it * kThreads + tid;
-        const uint32_t wx = wxy[it] >> 16, wy = wxy[it] & 0xFFFFu;
-        const uint32_t acc = p00[it] * (256u - wx) * (256u - wy) + p01[it] * wx * (256u - wy)
-                           + p10[it] * (256u - wx) * wy + p11[it] * wx * wy;
-        if (e < N * N) sCrop[e] = normalise((float)acc * (1.0f / 65536.0f));
-    }
+    CropPixels<N> px;
+    crop_issue<N>(frame, pitch, sTab, px);
+    crop_finish<N>(px, sTab, sCrop);
     __syncthreads();
 }
 

@@ -46,8 +46,15 @@ __device__ __forceinline__ float max4(const floatx4 v) { return fmaxf(fmaxf(v[0]
 // ---- stage 3 geometry ---------------------------------------------------------------------------
 constexpr int kCropW = 48;                 // crop row pitch in LDS
 constexpr int kP1Row = 24, kP1Ch = 22 * kP1Row;   // pooled conv1 map [16][22][24] (row padded: bank spread)
-constexpr int kP2Ch = 81;                  // pooled conv2 map [32][9*9]
-constexpr int kRegionA = 32 * kP2Ch;       // crop (2304) then pooled conv2 map (2592)
+constexpr int kP2Ch = 81;                  // pooled conv2 map [32][9][9] of the direct-sum variant
+constexpr int kP2RowW = 10, kP2ChW = 9 * kP2RowW;   // Winograd variant: rows padded to 10 so that row reads are 8-byte aligned
+constexpr int kRegionA = 32 * kP2ChW;      // crop (2304) then pooled conv2 map (2592 or 2880)
+// position of pooling block `blk` (0..80) of channel `oc` in the pooled conv2 map
+template <bool WINO>
+__device__ __forceinline__ int p2_index(int oc, int blk)
+{
+    return WINO ? oc * kP2ChW + (blk / 9) * kP2RowW + blk % 9 : oc * kP2Ch + blk;
+}
 constexpr int kRegionB = 16 * kP1Ch;       // pooled conv1 map (8448) then conv3 partial sums [4][32][66]
 constexpr int kP3Pitch = 66;
 static_assert(4 * 32 * kP3Pitch <= kRegionB, "conv3 partial sums must fit the conv1 region");
@@ -92,8 +99,8 @@ __device__ __forceinline__ void s3_conv2(const float *sP1, float *sP2, const flo
     for (int u = 0; u < NT; ++u) {
         const int pb = 4 * (wslot + 4 * u) + g;
         if (pb < 81) {
-            sP2[j * kP2Ch + pb] = act_f<ACT>(max4(acc[u][0]) + bias_lo);
-            sP2[(16 + j) * kP2Ch + pb] = act_f<ACT>(max4(acc[u][1]) + bias_hi);
+            sP2[p2_index<false>(j, pb)] = act_f<ACT>(max4(acc[u][0]) + bias_lo);
+            sP2[p2_index<false>(16 + j, pb)] = act_f<ACT>(max4(acc[u][1]) + bias_hi);
         }
     }
 }
@@ -104,22 +111,25 @@ __device__ __forceinline__ void s3_conv2(const float *sP1, float *sP2, const flo
 // For the 5x5, 16 -> 32 convolution this gives six GEMMs (one per b) with M = 162 positions (18 rows x 9
 // column pairs), K = 16 channels x 5 kernel rows = 80 and N = 32, i.e. 60 % of the matrix work of the direct
 // sum.  The lane that feeds the A operand reads six consecutive floats of one input row and transforms them
-// in registers (BT has 26 non-zeros); the filter side U = G w is prepared on the host in fp64.  Interpolation
-// points 0, 1, -1, 2, -1/2 and infinity: the fp32 result stays within about 1e-6 of the direct fp32 sum here.
+// in registers; the filter side U = G w is prepared on the host in fp64.  Interpolation points 0, 1, -1, 2, -2 and
+// infinity: BT then pairs up into even and odd parts (twelve operations per six-vector),
+//   BT = [4 0 -5 0 1 0; 0 -4 -4 1 1 0; 0 4 -4 -1 1 0; 0 -2 -1 2 1 0; 0 2 -1 -2 1 0; 0 4 0 -5 0 1],
+//   AT = [1 1 1 1 1 0; 0 1 -1 2 -2 1],
+// and the fp32 result stays within about 2e-6 of the direct fp32 sum here.
 // Positions are ordered so that the four accumulator registers of a lane hold two pooling blocks
 // (block, line) = (2 g + r / 2, r % 2) of the M-tile, and the output transform leaves both columns of a
 // line in the same lane: max-pooling stays in registers.
-constexpr float kBT[6][6] = {{1.0f, 1.5f, -2.0f, -1.5f, 1.0f, 0.0f},  {0.0f, -1.0f, -2.5f, -0.5f, 1.0f, 0.0f},
-                             {0.0f, 1.0f, 0.5f, -2.5f, 1.0f, 0.0f},   {0.0f, -0.5f, -1.0f, 0.5f, 1.0f, 0.0f},
-                             {0.0f, 2.0f, -1.0f, -2.0f, 1.0f, 0.0f},  {0.0f, 1.0f, 1.5f, -2.0f, -1.5f, 1.0f}};
 constexpr int kWinoTiles = 11;          // 81 pooling blocks, eight per M-tile
 
-// NT M-tiles (mt0, mt0 + 4, ...) in one pass over the filter: every loaded filter fragment feeds NT tiles, which
-// divides the L2 -> register traffic of the filter by NT.
+// One M-tile per pass over the filter.  (Two tiles per pass would halve the filter's L2 -> register traffic,
+// but the 96 accumulator registers spill: measured slower.)  The loop is software-pipelined by hand: the filter
+// fragments are fetched two k-steps ahead and the input row one step ahead, and the compiler is kept from
+// sinking those loads to their uses.
 template <int NT, int ACT>
 __device__ __forceinline__ void s3_conv2_wino_tiles(const float *sP1, float *sP2, const float *__restrict__ UF, int mt0,
                                                     int lane, float bias_lo, float bias_hi)
 {
+    static_assert(NT == 1, "one M-tile per pass");
     const int i = lane & 15, g = lane >> 4, j = lane & 15;
     const float *dptr[NT];
     floatx4 acc[NT][6][2];
@@ -130,58 +140,174 @@ __device__ __forceinline__ void s3_conv2_wino_tiles(const float *sP1, float *sP2
 #pragma unroll
         for (int b = 0; b < 6; ++b) { acc[t][b][0] = floatx4{0, 0, 0, 0}; acc[t][b][1] = floatx4{0, 0, 0, 0}; }
     }
-    const float4 *up = reinterpret_cast<const float4 *>(UF) + lane * 3;        // [k-step][lane] three float4
-    float4 u0 = up[0], u1 = up[1], u2 = up[2];
+    // filter fragments [k-step][lane] three float4: uniform base + 32-bit lane offset, so the address math is scalar
+    const char *ubase = reinterpret_cast<const char *>(UF);
+    const uint32_t lane_off = lane * 48;
+    auto ldu = [&](int step, int k) {
+        return *reinterpret_cast<const float4 *>(ubase + (size_t)(step * 3072 + k * 16) + lane_off);
+    };
+    float4 u0 = ldu(0, 0), u1 = ldu(0, 1), u2 = ldu(0, 2);                     // step s
+    float4 v0 = ldu(1, 0), v1 = ldu(1, 1), v2 = ldu(1, 2);                     // step s + 1
+    float2 c0 = *reinterpret_cast<const float2 *>(dptr[0]), c1 = *reinterpret_cast<const float2 *>(dptr[0] + 2),
+           c2 = *reinterpret_cast<const float2 *>(dptr[0] + 4);
 #pragma unroll 1
     for (int a = 0; a < 5; ++a) {                                // kernel row
 #pragma unroll
         for (int cq = 0; cq < 4; ++cq) {                         // input channels 4 cq + g
-            const int nstep = min(a * 4 + cq + 1, 19);
-            const float4 n0 = up[nstep * 192], n1 = up[nstep * 192 + 1], n2 = up[nstep * 192 + 2];
-            asm volatile("" ::: "memory");                        // next step's weights stay in flight during the math
+            const int nstep = min(a * 4 + cq + 2, 19);
+            const float4 n0 = ldu(nstep, 0), n1 = ldu(nstep, 1), n2 = ldu(nstep, 2);
+            // input row of the next step (the last step reads its own row again)
+            const float *nrow = dptr[0] + (cq == 3 ? min(a + 1, 4) * kP1Row + (a == 4 ? 3 : 0) * 4 * kP1Ch
+                                                   : a * kP1Row + (cq + 1) * 4 * kP1Ch);
+            const float2 m0 = *reinterpret_cast<const float2 *>(nrow), m1 = *reinterpret_cast<const float2 *>(nrow + 2),
+                         m2 = *reinterpret_cast<const float2 *>(nrow + 4);
+            asm volatile("" ::: "memory");                        // the loads above stay in flight during the math below
             const float ub[12] = {u0.x, u0.y, u0.z, u0.w, u1.x, u1.y, u1.z, u1.w, u2.x, u2.y, u2.z, u2.w};
+            // transformed input BT d
+            const float e1 = fmaf(-4.0f, c1.x, c2.x), o1 = fmaf(-4.0f, c0.y, c1.y);
+            const float e2 = c2.x - c1.x, o2 = c1.y - c0.y;
+            const float v[6] = {fmaf(4.0f, c0.x, fmaf(-5.0f, c1.x, c2.x)), e1 + o1, e1 - o1, fmaf(2.0f, o2, e2), fmaf(-2.0f, o2, e2),
+                                fmaf(4.0f, c0.y, fmaf(-5.0f, c1.y, c2.y))};
 #pragma unroll
-            for (int t = 0; t < NT; ++t) {
-                const float *row = dptr[t] + cq * 4 * kP1Ch + a * kP1Row;
-                const float2 r0 = *reinterpret_cast<const float2 *>(row), r1 = *reinterpret_cast<const float2 *>(row + 2),
-                             r2 = *reinterpret_cast<const float2 *>(row + 4);
-                const float d[6] = {r0.x, r0.y, r1.x, r1.y, r2.x, r2.y};
-#pragma unroll
-                for (int b = 0; b < 6; ++b) {
-                    float v = 0.0f;                               // transformed input: sum_p BT[b][p] d[p]
-#pragma unroll
-                    for (int p = 0; p < 6; ++p)
-                        if (kBT[b][p] != 0.0f) v = fmaf(kBT[b][p], d[p], v);
-                    acc[t][b][0] = CNNC_MFMA(v, ub[2 * b], acc[t][b][0]);
-                    acc[t][b][1] = CNNC_MFMA(v, ub[2 * b + 1], acc[t][b][1]);
-                }
+            for (int b = 0; b < 6; ++b) {
+                acc[0][b][0] = CNNC_MFMA(v[b], ub[2 * b], acc[0][b][0]);
+                acc[0][b][1] = CNNC_MFMA(v[b], ub[2 * b + 1], acc[0][b][1]);
             }
-            u0 = n0; u1 = n1; u2 = n2;
+            u0 = v0; u1 = v1; u2 = v2;
+            v0 = n0; v1 = n1; v2 = n2;
+            c0 = m0; c1 = m1; c2 = m2;
         }
     }
-    // output transform (AT = [1 1 1 1 1 0; 0 1 -1 2 -1/2 1]), pooling, bias, activation
+    // output transform AT m, pooling, bias, activation
 #pragma unroll
     for (int t = 0; t < NT; ++t)
 #pragma unroll
         for (int nt = 0; nt < 2; ++nt) {
-            const floatx4 R0 = acc[t][0][nt] + acc[t][1][nt] + acc[t][2][nt] + acc[t][3][nt] + acc[t][4][nt];
-            const floatx4 R1 = acc[t][1][nt] - acc[t][2][nt] + 2.0f * acc[t][3][nt] - 0.5f * acc[t][4][nt] + acc[t][5][nt];
+            const floatx4 R0 = acc[t][0][nt] + (acc[t][1][nt] + acc[t][2][nt]) + (acc[t][3][nt] + acc[t][4][nt]);
+            const floatx4 R1 = (acc[t][1][nt] - acc[t][2][nt]) + 2.0f * (acc[t][3][nt] - acc[t][4][nt]) + acc[t][5][nt];
             const float bias = nt ? bias_hi : bias_lo;
             const int oc = 16 * nt + j;
 #pragma unroll
             for (int sub = 0; sub < 2; ++sub) {
                 const int blk = 8 * (mt0 + 4 * t) + 2 * g + sub;
                 const float m = fmaxf(fmaxf(R0[2 * sub], R1[2 * sub]), fmaxf(R0[2 * sub + 1], R1[2 * sub + 1]));
-                if (blk < 81) sP2[oc * kP2Ch + blk] = act_f<ACT>(m + bias);
+                if (blk < 81) sP2[p2_index<true>(oc, blk)] = act_f<ACT>(m + bias);
             }
         }
+}
+
+// ---- conv3 of stage 3, direct sums: 49 positions = 4 tiles.  The waves split K (wave w takes input channels
+// 8w .. 8w+7 of every tap), so each needs only a quarter of the weights, all loaded up front; the partial tiles
+// go to LDS as [wave][channel 32][kP3Pitch] and are summed by s3_conv3_direct_finish after a barrier.
+__device__ __forceinline__ void s3_conv3_direct(const float *sP2, float *sPart, const float *__restrict__ B3F, int wave, int lane)
+{
+    const int g = lane >> 4, j = lane & 15;
+    float2 b3[9][2];
+    const float2 *bp = reinterpret_cast<const float2 *>(B3F) + lane * 4 + wave;   // [tap][n-tile][lane][8]
+#pragma unroll
+    for (int tap = 0; tap < 9; ++tap) {
+        b3[tap][0] = bp[(tap * 2) * 256];
+        b3[tap][1] = bp[(tap * 2 + 1) * 256];
+    }
+    floatx4 acc[4][2];
+    int abase[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        acc[u][0] = floatx4{0, 0, 0, 0};
+        acc[u][1] = floatx4{0, 0, 0, 0};
+        const int pos = min(16 * u + j, 48);
+        abase[u] = (8 * wave + g) * kP2Ch + (pos / 7) * 9 + pos % 7;
+    }
+#pragma unroll
+    for (int tap = 0; tap < 9; ++tap) {
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const float w0 = h ? b3[tap][0].y : b3[tap][0].x, w1 = h ? b3[tap][1].y : b3[tap][1].x;
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const float a = sP2[abase[u] + (tap / 3) * 9 + tap % 3 + h * 4 * kP2Ch];
+                acc[u][0] = CNNC_MFMA(a, w0, acc[u][0]);
+                acc[u][1] = CNNC_MFMA(a, w1, acc[u][1]);
+            }
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int p = 16 * u + 4 * g + r;
+            sPart[(wave * 32 + j) * kP3Pitch + p] = acc[u][0][r];
+            sPart[(wave * 32 + 16 + j) * kP3Pitch + p] = acc[u][1][r];
+        }
+}
+
+template <int ACT>
+__device__ __forceinline__ void s3_conv3_direct_finish(const float *sPart, const float *__restrict__ wt, float *__restrict__ dst)
+{
+    for (int e = threadIdx.x; e < 1568; e += kThreads) {
+        const int oc = e / 49, p = e % 49;
+        const float v = sPart[oc * kP3Pitch + p] + sPart[(32 + oc) * kP3Pitch + p] + sPart[(64 + oc) * kP3Pitch + p] +
+                        sPart[(96 + oc) * kP3Pitch + p];
+        dst[e] = act_f<ACT>(v + wt[s3::B3 + oc]);
+    }
+}
+
+// ---- conv3 of stage 3 by Winograd F(2, 3) along the rows: two adjacent outputs of a 3-tap row filter cost four
+// multiplications instead of six (points 0, 1, -1, infinity):
+//   m0 = (d0 - d2) g0, m1 = (d1 + d2)(g0 + g1 + g2)/2, m2 = (d2 - d1)(g0 - g1 + g2)/2, m3 = (d1 - d3) g2,
+//   out(x0) = m0 + m1 + m2, out(x0 + 1) = m1 - m2 - m3.
+// Four GEMMs with M = 28 positions (7 rows x 4 column pairs; the 8th column is discarded), K = 32 channels x 3
+// kernel rows, N = 32: wave w takes M-tile w / 2 and output channels 16 (w % 2) .. +15, so nothing has to be
+// summed across waves and the activations go straight to global memory (order [channel][row][col]).
+template <int ACT>
+__device__ __forceinline__ void s3_conv3_wino(const float *sP2, const float *__restrict__ U3F, const float *__restrict__ wt,
+                                              float *__restrict__ dst, int wave, int lane)
+{
+    const int mtile = wave >> 1, nt = wave & 1;
+    const int i = lane & 15, g = lane >> 4, j = lane & 15;
+    const int p = min(16 * mtile + i, 27);
+    const float *dptr = sP2 + g * kP2ChW + (p >> 2) * kP2RowW + 2 * (p & 3);
+    floatx4 acc[4] = {floatx4{0, 0, 0, 0}, floatx4{0, 0, 0, 0}, floatx4{0, 0, 0, 0}, floatx4{0, 0, 0, 0}};
+    const float4 *up = reinterpret_cast<const float4 *>(U3F) + nt * 24 * 64 + lane;   // [n-tile][k-step][lane] four points
+    float4 ring[4] = {up[0], up[64], up[128], up[192]};
+    up += 256;
+#pragma unroll
+    for (int ks = 0; ks < 24; ++ks) {                            // k-step = kernel row a (3) x channel quad cq (8)
+        const int a = ks >> 3, cq = ks & 7;
+        const float4 u = ring[ks & 3];
+        if (ks + 4 < 24) {
+            ring[ks & 3] = *up;
+            up += 64;
+            asm volatile("" : "+v"(up));                          // one running address instead of twenty precomputed ones
+        }
+        asm volatile("" ::: "memory");                            // keeps the prefetch distance: loads stay where written
+        const float *row = dptr + cq * 4 * kP2ChW + a * kP2RowW;
+        const float2 r0 = *reinterpret_cast<const float2 *>(row), r1 = *reinterpret_cast<const float2 *>(row + 2);
+        acc[0] = CNNC_MFMA(r0.x - r1.x, u.x, acc[0]);
+        acc[1] = CNNC_MFMA(r0.y + r1.x, u.y, acc[1]);
+        acc[2] = CNNC_MFMA(r1.x - r0.y, u.z, acc[2]);
+        acc[3] = CNNC_MFMA(r0.y - r1.y, u.w, acc[3]);
+    }
+    const int oc = 16 * nt + j;
+    const float bias = wt[s3::B3 + oc];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int pp = 16 * mtile + 4 * g + r;                    // row pp / 4, column pair r
+        if (pp < 28) {
+            float *o = dst + oc * 49 + (pp >> 2) * 7 + 2 * r;
+            o[0] = act_f<ACT>(acc[0][r] + acc[1][r] + acc[2][r] + bias);
+            if (r < 3) o[1] = act_f<ACT>(acc[1][r] - acc[2][r] - acc[3][r] + bias);
+        }
+    }
 }
 }  // namespace
 
 // Fragment buffer of stage 3 (floats): conv1 [7][64], conv2 [25][2][64][4], conv3 [9][2][64][8], fc [98][4][64][4].
-// plus the Winograd-domain conv2 weights [5 kernel rows][4 channel quads][64][6 points x 2 n-tiles].
+// plus the Winograd-domain conv2 weights [5 kernel rows][4 channel quads][64][6 points x 2 n-tiles]
+// and conv3 weights [2 n-tiles][3 kernel rows x 8 channel quads][64][4 points].
 constexpr int kS3F1 = 0, kS3F2 = kS3F1 + 7 * 64, kS3F3 = kS3F2 + 25 * 2 * 64 * 4, kS3F4 = kS3F3 + 9 * 2 * 64 * 8,
-              kS3F5 = kS3F4 + 98 * 4 * 64 * 4, kS3FragFloats = kS3F5 + 20 * 64 * 12;
+              kS3F5 = kS3F4 + 98 * 4 * 64 * 4, kS3F6 = kS3F5 + 20 * 64 * 12, kS3FragFloats = kS3F6 + 2 * 24 * 64 * 4;
+static_assert(kS3F5 % 4 == 0 && kS3F6 % 4 == 0, "16-byte loads from the Winograd filter blocks");
 constexpr int kS3Feat = 1568;
 
 // Crop -> conv1 -> pool -> conv2 -> pool -> conv3 for each surviving window; writes the 1568 conv3
@@ -192,14 +318,19 @@ void eval3_conv_kernel(const uint8_t *__restrict__ frame, int fw, int fh, int pi
                        int n_levels, const uint32_t *__restrict__ idx, const int32_t *__restrict__ d_n, int n_max,
                        const float *__restrict__ wt, const float *__restrict__ frag, float *__restrict__ feat)
 {
-    __shared__ float sA[kRegionA];
-    __shared__ float sB[kRegionB];
+    __shared__ __attribute__((aligned(16))) float sA[kRegionA];
+    __shared__ __attribute__((aligned(16))) float sB[kRegionB];
     __shared__ uint32_t sTab[2 * kS3In];
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, g = lane >> 4, j = lane & 15;
+    __shared__ uint32_t sLut[484];          // per pooling block of conv1: crop offset of its corner | pooled-map offset << 16
+    const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, g = lane >> 4, j = lane & 15;
+    for (int pb = tid; pb < 484; pb += kThreads)
+        sLut[pb] = (uint32_t)(2 * (pb / 22) * kCropW + 2 * (pb % 22)) | (uint32_t)((pb / 22) * kP1Row + pb % 22) << 16;
+    const int in_lane = ((j >> 1) & 1) * kCropW + (j & 1) + g;     // A rows: line and column of the block, plus the tap column g
+    // (the first barrier of the gather below orders the table before its readers)
 
     // conv1 k-order: steps 0..4 = taps (a = step, b = g); step 5 = taps (a = g, b = 4);
     // step 6 = tap (4, 4) in group 0, zero weights elsewhere (those lanes re-read their own pixel)
-    const int off5 = g * kCropW + 4, off6 = g == 0 ? 4 * kCropW + 4 : 0;
+    const int off5 = g * kCropW + 4 - g, off6 = g == 0 ? 4 * kCropW + 4 : -g;     // relative to a base that includes + g
 
     const int n = min(*d_n, n_max);
     int rot = 0;
@@ -209,12 +340,16 @@ void eval3_conv_kernel(const uint8_t *__restrict__ frame, int fw, int fh, int pi
 #endif
     // Static striding over the list.  (Handing windows out through an atomic ticket counter was measured:
     // it does not shorten the kernel, the device-scope atomics cost more than the balance gains.)
-    for (int crop = blockIdx.x; crop < n; crop += gridDim.x, ++rot) {
-        CNNC_PROBE(0);
+    // The gather of a window is software-pipelined: its tables are computed during conv1 of the previous
+    // window, its pixel loads are in flight during conv3, and it lands in LDS once conv3 has released the buffer.
+    int crop = blockIdx.x;
+    if (crop < n) {
         const Survivor sv = decode(idx[crop], levels, n_levels);
-        CNNC_PROBE(1);
         gather_crop<kS3In>(frame, fw, fh, pitch, sv.x, sv.y, levels[sv.level].scale_q16, sTab, sA);
-        CNNC_PROBE(2);
+    }
+    for (; crop < n; crop += gridDim.x, ++rot) {
+        const int next = crop + gridDim.x;
+        CNNC_PROBE(0);
 
         // ---- conv1 5x5 1->16 + pool: 121 tiles of four pooling blocks, four tiles in flight per wave
         // (small per-layer constants are re-read per window instead of living in registers through the other layers)
@@ -222,9 +357,6 @@ void eval3_conv_kernel(const uint8_t *__restrict__ frame, int fw, int fh, int pi
 #pragma unroll
         for (int s = 0; s < 7; ++s) b1f[s] = frag[kS3F1 + s * 64 + lane];
         const float bias1 = wt[s3::B1 + j];
-        int wave_here = wave;
-        asm volatile("" : "+v"(wave_here));      // keeps the tile addresses below from being hoisted out of the
-                                                 // window loop into dozens of long-lived registers
 #pragma unroll 1
         for (int q0 = 0; q0 < 32; q0 += 4) {
             floatx4 acc[4];
@@ -232,14 +364,13 @@ void eval3_conv_kernel(const uint8_t *__restrict__ frame, int fw, int fh, int pi
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
                 acc[u] = floatx4{0, 0, 0, 0};
-                const int t = min(wave_here + 4 * (q0 + u), 120);
-                const int pb = 4 * t + (j >> 2);
-                base[u] = (2 * (pb / 22) + ((j >> 1) & 1)) * kCropW + 2 * (pb % 22) + (j & 1);
+                const int t = min(wave + 4 * (q0 + u), 120);
+                base[u] = (int)(sLut[4 * t + (j >> 2)] & 0xFFFFu) + in_lane;
             }
 #pragma unroll
             for (int s = 0; s < 5; ++s)
 #pragma unroll
-                for (int u = 0; u < 4; ++u) acc[u] = CNNC_MFMA(sA[base[u] + g + s * kCropW], b1f[s], acc[u]);
+                for (int u = 0; u < 4; ++u) acc[u] = CNNC_MFMA(sA[base[u] + s * kCropW], b1f[s], acc[u]);
 #pragma unroll
             for (int u = 0; u < 4; ++u) acc[u] = CNNC_MFMA(sA[base[u] + off5], b1f[5], acc[u]);
 #pragma unroll
@@ -247,17 +378,18 @@ void eval3_conv_kernel(const uint8_t *__restrict__ frame, int fw, int fh, int pi
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
                 const int t = wave + 4 * (q0 + u);
-                if (t < 121) {
-                    const int pb = 4 * t + g;
-                    sB[j * kP1Ch + (pb / 22) * kP1Row + pb % 22] = act_f<ACT>(max4(acc[u]) + bias1);
-                }
+                if (t < 121) sB[j * kP1Ch + (sLut[4 * t + g] >> 16)] = act_f<ACT>(max4(acc[u]) + bias1);
             }
+        }
+        if (next < n) {          // sample tables of the next window; the table buffer is idle until conv3
+            const Survivor sv = decode(idx[next], levels, n_levels);
+            crop_tables<kS3In>(sv.x, sv.y, levels[sv.level].scale_q16, fw, fh, sTab);
         }
         CNNC_PROBE(3);
         __syncthreads();
         CNNC_PROBE(4);
 
-        // ---- conv2 5x5 16->32 + pool: 21 tiles; the wave that takes six of them rotates per crop
+        // ---- conv2 5x5 16->32 + pool (overwrites the crop with the pooled map)
         const int wslot = (wave + rot + blockIdx.x + (blockIdx.x >> 8)) & 3;
         const float bias2_lo = wt[s3::B2 + j], bias2_hi = wt[s3::B2 + 16 + j];
         if (WINO) {
@@ -267,6 +399,7 @@ void eval3_conv_kernel(const uint8_t *__restrict__ frame, int fw, int fh, int pi
             for (int mt = wslot; mt < kWinoTiles; mt += 4)
                 s3_conv2_wino_tiles<1, ACT>(sB, sA, frag + kS3F5, mt, lane, bias2_lo, bias2_hi);
         } else if (wslot == 0) {
+            // 21 tiles of four pooling blocks; the wave that takes six of them rotates per window
             s3_conv2<6, ACT>(sB, sA, frag + kS3F2, wslot, lane, bias2_lo, bias2_hi);
         } else {
             s3_conv2<5, ACT>(sB, sA, frag + kS3F2, wslot, lane, bias2_lo, bias2_hi);
@@ -275,65 +408,21 @@ void eval3_conv_kernel(const uint8_t *__restrict__ frame, int fw, int fh, int pi
         __syncthreads();
         CNNC_PROBE(6);
 
-        // ---- conv3 3x3 32->32: 49 positions = 4 tiles.  The waves split K (wave w takes input channels
-        // 8w .. 8w+7 of every tap), so each needs only a quarter of the weights, all loaded up front; the
-        // partial tiles meet in LDS.
-        {
-            float2 b3[9][2];
-            const float2 *bp = reinterpret_cast<const float2 *>(frag + kS3F3) + lane * 4 + wave;   // [tap][n-tile][lane][8]
-#pragma unroll
-            for (int tap = 0; tap < 9; ++tap) {
-                b3[tap][0] = bp[(tap * 2) * 256];
-                b3[tap][1] = bp[(tap * 2 + 1) * 256];
-            }
-            floatx4 acc[4][2];
-            int abase[4];
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                acc[u][0] = floatx4{0, 0, 0, 0};
-                acc[u][1] = floatx4{0, 0, 0, 0};
-                const int pos = min(16 * u + j, 48);
-                abase[u] = (8 * wave + g) * kP2Ch + (pos / 7) * 9 + pos % 7;
-            }
-#pragma unroll
-            for (int tap = 0; tap < 9; ++tap) {
-#pragma unroll
-                for (int h = 0; h < 2; ++h) {
-                    const float w0 = h ? b3[tap][0].y : b3[tap][0].x, w1 = h ? b3[tap][1].y : b3[tap][1].x;
-#pragma unroll
-                    for (int u = 0; u < 4; ++u) {
-                        const float a = sA[abase[u] + (tap / 3) * 9 + tap % 3 + h * 4 * kP2Ch];
-                        acc[u][0] = CNNC_MFMA(a, w0, acc[u][0]);
-                        acc[u][1] = CNNC_MFMA(a, w1, acc[u][1]);
-                    }
-                }
-            }
-            // partial sums: sB as [wave][channel 32][66] (position-contiguous)
-#pragma unroll
-            for (int u = 0; u < 4; ++u)
-#pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const int p = 16 * u + 4 * g + r;
-                    sB[(wave * 32 + j) * kP3Pitch + p] = acc[u][0][r];
-                    sB[(wave * 32 + 16 + j) * kP3Pitch + p] = acc[u][1][r];
-                }
-        }
-        CNNC_PROBE(7);
-        __syncthreads();
-        CNNC_PROBE(8);
+        // ---- pixel loads of the next window go out now and stay in flight during conv3
+        CropPixels<kS3In> px;
+        if (next < n) crop_issue<kS3In>(frame, pitch, sTab, px);
 
-        // ---- sum the four partial tiles, bias, activation, and out to global memory (order [channel][row][col])
-        {
-            float *dst = feat + (size_t)crop * kS3Feat;
-            for (int e = tid; e < kS3Feat; e += kThreads) {
-                const int oc = e / 49, p = e % 49;
-                const float v = sB[oc * kP3Pitch + p] + sB[(32 + oc) * kP3Pitch + p] + sB[(64 + oc) * kP3Pitch + p] +
-                                sB[(96 + oc) * kP3Pitch + p];
-                dst[e] = act_f<ACT>(v + wt[s3::B3 + oc]);
-            }
-        }
+        // ---- conv3 3x3 32->32 and out to global memory
+        float *dst = feat + (size_t)crop * kS3Feat;
+        if (WINO) s3_conv3_wino<ACT>(sA, frag + kS3F6, wt, dst, wave, lane);
+        else s3_conv3_direct(sA, sB, frag + kS3F3, wave, lane);
+        CNNC_PROBE(7);
+        __syncthreads();                                   // conv3 has released the pooled map (and, direct form, written its partial sums)
+        CNNC_PROBE(8);
+        if (!WINO) s3_conv3_direct_finish<ACT>(sB, wt, dst);
+        if (next < n) crop_finish<kS3In>(px, sTab, sA);
         CNNC_PROBE(9);
-        // no barrier here: the next crop's gather synchronises before anything overwrites sB
+        __syncthreads();                                   // next crop in place; partial sums consumed before conv1 rewrites sB
     }
 #ifdef CNNC_PHASE_PROBE
     if (threadIdx.x == 0 && blockIdx.x == 0) {
@@ -436,12 +525,12 @@ void eval3_make_fragments(const float *w, float *f)
                     f[kS3F4 + ((ch * 4 + nt) * 64 + lane) * 4 + s] = w[s3::W4 + (nt * 16 + j) * 1568 + 16 * ch + 4 * g + s];
                 }
     // Winograd-domain conv2 weights U_b = sum_l G[b][l] w[.][.][a][l] (fp64, then rounded); G for the points
-    // 0, 1, -1, 2, -1/2, infinity
-    static const double G[6][5] = {{1, 0, 0, 0, 0},
-                                   {-1.0 / 3, -1.0 / 3, -1.0 / 3, -1.0 / 3, -1.0 / 3},
-                                   {1.0 / 3, -1.0 / 3, 1.0 / 3, -1.0 / 3, 1.0 / 3},
-                                   {1.0 / 15, 2.0 / 15, 4.0 / 15, 8.0 / 15, 16.0 / 15},
-                                   {-16.0 / 15, 8.0 / 15, -4.0 / 15, 2.0 / 15, -1.0 / 15},
+    // 0, 1, -1, 2, -2, infinity: row j = (a_j^l / prod_{i != j} (a_j - a_i)), last row picks the leading tap
+    static const double G[6][5] = {{1.0 / 4, 0, 0, 0, 0},
+                                   {-1.0 / 6, -1.0 / 6, -1.0 / 6, -1.0 / 6, -1.0 / 6},
+                                   {-1.0 / 6, 1.0 / 6, -1.0 / 6, 1.0 / 6, -1.0 / 6},
+                                   {1.0 / 24, 1.0 / 12, 1.0 / 6, 1.0 / 3, 2.0 / 3},
+                                   {1.0 / 24, -1.0 / 12, 1.0 / 6, -1.0 / 3, 2.0 / 3},
                                    {0, 0, 0, 0, 1}};
     for (int oc = 0; oc < 32; ++oc)
         for (int c = 0; c < 16; ++c)
@@ -453,6 +542,16 @@ void eval3_make_fragments(const float *w, float *f)
                     for (int l = 0; l < 5; ++l) acc += G[b][l] * (double)k[l];
                     f[kS3F5 + ((a * 4 + cq) * 64 + lane) * 12 + b * 2 + nt] = (float)acc;
                 }
+            }
+    // Winograd-domain conv3 weights along the kernel columns: g0, (g0 + g1 + g2) / 2, (g0 - g1 + g2) / 2, g2
+    for (int oc = 0; oc < 32; ++oc)
+        for (int c = 0; c < 32; ++c)
+            for (int a = 0; a < 3; ++a) {
+                const float *k = w + s3::W3 + ((oc * 32 + c) * 3 + a) * 3;
+                const double g0 = k[0], g1 = k[1], g2 = k[2];
+                const double u[4] = {g0, (g0 + g1 + g2) / 2, (g0 - g1 + g2) / 2, g2};
+                const int cq = c >> 2, g = c & 3, nt = oc >> 4, j = oc & 15, lane = g * 16 + j, ks = a * 8 + cq;
+                for (int b = 0; b < 4; ++b) f[kS3F6 + ((nt * 24 + ks) * 64 + lane) * 4 + b] = (float)u[b];
             }
 }
 
@@ -511,24 +610,22 @@ void eval2_conv_kernel(const uint8_t *__restrict__ frame, int fw, int fh, int pi
         if (lane < 24) crop_axis<kS2In>(sv.x, S, fw, sTab, lane);
         else if (lane < 48) crop_axis<kS2In>(sv.y, S, fh, sTab + 24, lane - 24);
         wave_sync();
-        {   // all 36 pixel loads of a lane are issued before the first blend
-            uint32_t p00[9], p01[9], p10[9], p11[9], wxy[9];
+        {   // all 18 pixel-pair loads of a lane are issued before the first blend
+            uint32_t top[9], bot[9];
 #pragma unroll
             for (int it = 0; it < 9; ++it) {
                 const int e = it * 64 + lane, r = e / 24, q = e % 24;
-                const uint32_t ex = sTab[q], ey = sTab[24 + r];
-                const int x0 = ex >> 9, y0 = ey >> 9;
-                const int x1 = min(x0 + 1, fw - 1), y1 = min(y0 + 1, fh - 1);
-                const uint32_t o0 = (uint32_t)(y0 * pitch), o1 = (uint32_t)(y1 * pitch);
-                p00[it] = frame[o0 + x0]; p01[it] = frame[o0 + x1]; p10[it] = frame[o1 + x0]; p11[it] = frame[o1 + x1];
-                wxy[it] = ((ex & 511u) << 16) | (ey & 511u);
+                const uint8_t *r0 = frame + (uint32_t)((sTab[24 + r] >> 9) * pitch) + (sTab[q] >> 9);
+                top[it] = *reinterpret_cast<const pixel_pair *>(r0);
+                bot[it] = *reinterpret_cast<const pixel_pair *>(r0 + pitch);
             }
 #pragma unroll
             for (int it = 0; it < 9; ++it) {
-                const uint32_t wx = wxy[it] >> 16, wy = wxy[it] & 0xFFFFu;
-                const uint32_t acc = p00[it] * (256u - wx) * (256u - wy) + p01[it] * wx * (256u - wy)
-                                   + p10[it] * (256u - wx) * wy + p11[it] * wx * wy;
-                sCrop[it * 64 + lane] = normalise((float)acc * (1.0f / 65536.0f));
+                const int e = it * 64 + lane, r = e / 24, q = e % 24;
+                const uint32_t wx = sTab[q] & 511u, wy = sTab[24 + r] & 511u;
+                const uint32_t acc = (top[it] & 255u) * (256u - wx) * (256u - wy) + (top[it] >> 8) * wx * (256u - wy)
+                                   + (bot[it] & 255u) * (256u - wx) * wy + (bot[it] >> 8) * wx * wy;
+                sCrop[e] = normalise((float)acc * (1.0f / 65536.0f));
             }
         }
         wave_sync();
