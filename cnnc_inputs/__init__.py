@@ -6,12 +6,12 @@ of the three network shapes.  It contains none of the detector's arithmetic
 the CPU oracle's tests and the HIP library's tests import.
 """
 from .cascade import (ACT_NONE, ACT_RATIONAL, ACT_SCALED_TANH, ACT_TANH, CONV,
-                      FC, POOL, Layer, Stage, default_cascade, draw_weights,
-                      uniform_weights)
+                      FC, POOL, Layer, RLayer, ScanNet, Stage, default_cascade,
+                      draw_scan_weights, draw_weights, paper_stage1, uniform_weights)
 from .frames import CONFIGS, config_seed, make_frame, make_stream
 
 __all__ = [
     "ACT_NONE", "ACT_RATIONAL", "ACT_SCALED_TANH", "ACT_TANH", "CONV", "FC",
     "POOL", "Layer", "Stage", "default_cascade", "draw_weights",
-    "uniform_weights", "CONFIGS", "config_seed", "make_frame", "make_stream",
+    "uniform_weights", "RLayer", "ScanNet", "paper_stage1", "draw_scan_weights", "CONFIGS", "config_seed", "make_frame", "make_stream",
 ]

@@ -130,3 +130,68 @@ def uniform_weights(cascade: Sequence[Stage], values: Sequence[Sequence[float]])
             j += 1
         blobs.append(np.concatenate(parts))
     return blobs
+
+
+# --------------------------------------------------------------------------
+# First stage in the paper's own geometry (Section 3.1: no fully connected layer, convolution stride 1,
+# pooling stride 2; Section 3.3: 27 x 31 window, 4 pixel step).  The shapes were printed only in the
+# paper's Figure 1.  Chosen here: square kernels that take a 27 x 31 window to one response,
+#   conv 4x4 1->4, pool 2, conv 3x3 4->11, pool 2, conv 5x6 (w x h) 11->1,
+# which has 806 parameters (the paper states 797; no list of square kernels with full connections
+# between maps gives exactly that).
+@dataclass(frozen=True)
+class RLayer:
+    kind: int   # CONV or POOL
+    cin: int
+    cout: int
+    kw: int     # kernel width (POOL: 2)
+    kh: int     # kernel height (POOL: 2)
+    act: int
+
+    @property
+    def n_weights(self) -> int:
+        return 0 if self.kind == POOL else self.cout * self.cin * self.kw * self.kh
+
+    @property
+    def n_params(self) -> int:
+        return 0 if self.kind == POOL else self.n_weights + self.cout
+
+    @property
+    def fan_in(self) -> int:
+        return self.cin * self.kw * self.kh
+
+
+@dataclass(frozen=True)
+class ScanNet:
+    win_w: int
+    win_h: int
+    step: int
+    layers: Sequence[RLayer]
+
+    @property
+    def n_params(self) -> int:
+        return sum(l.n_params for l in self.layers)
+
+
+SCAN_C2 = 11
+
+
+def paper_stage1(act: int = ACT_RATIONAL) -> ScanNet:
+    return ScanNet(27, 31, 4, (
+        RLayer(CONV, 1, 4, 4, 4, act), RLayer(POOL, 4, 4, 2, 2, ACT_NONE),
+        RLayer(CONV, 4, SCAN_C2, 3, 3, act), RLayer(POOL, SCAN_C2, SCAN_C2, 2, 2, ACT_NONE),
+        RLayer(CONV, SCAN_C2, 1, 5, 6, ACT_NONE)))
+
+
+def draw_scan_weights(net: ScanNet, seed: int, bias_sd: float = 0.0) -> np.ndarray:
+    """float32 blob: per conv layer weights [cout][cin][kh][kw] ~ N(0, 1/fan_in), then bias[cout]."""
+    rng = np.random.default_rng([seed, 0x5CA4])
+    brng = np.random.default_rng([seed, 0x5CA4, 0xB1A5])
+    parts = []
+    for l in net.layers:
+        if l.kind == POOL:
+            continue
+        w = rng.standard_normal(l.n_weights) * (l.fan_in ** -0.5)
+        b = brng.standard_normal(l.cout) * bias_sd if bias_sd > 0 else np.zeros(l.cout)
+        parts += [w.astype(np.float32), b.astype(np.float32)]
+    return np.concatenate(parts)

@@ -20,7 +20,10 @@
  * constant windows, hand-computed one-hot windows, library convolution,
  * per-window definition vs dense evaluation, translation equivariance,
  * threshold monotonicity, exact special cases of the resampling, merge
- * special cases.  The choice of the readings themselves (resampling
+ * special cases; for the first stage in the paper's own geometry (end of
+ * this file): library convolution on windows and whole levels, a
+ * hand-computed one-hot window, definition vs single pass, translation by
+ * one step.  The choice of the readings themselves (resampling
  * convention, crop rectangle, merge rule) cannot be pinned to the authors'
  * detector: parity unpinned for those choices.
  */
@@ -452,4 +455,174 @@ int32_t orc_merge(const int32_t *bx, const int32_t *by, const int32_t *bsize, co
     }
     free(key); free(dead);
     return kept;
+}
+
+/* ======================================================================== */
+/* First stage in the paper's own geometry (paper, Section 3.1: no fully     */
+/* connected layer, convolution stride 1, pooling stride 2; Section 3.3: the */
+/* output responses correspond to a 27 x 31 scanning window moved with a     */
+/* 4 pixel step).  The layer shapes were printed only in the paper's         */
+/* Figure 1; the shapes are therefore passed in, with rectangular kernels,   */
+/* and any list conv / pool / conv / pool / conv whose last kernel covers    */
+/* the remaining map of one window fits.                                      */
+/* ======================================================================== */
+typedef struct {
+    int32_t kind;    /* ORC_CONV or ORC_POOL */
+    int32_t cin, cout;
+    int32_t kw, kh;  /* kernel width and height (POOL: 2, 2) */
+    int32_t act;
+} orc_rlayer;
+
+static size_t rlayer_params(const orc_rlayer *l)
+{
+    return l->kind == ORC_POOL ? 0 : (size_t)l->cout * l->cin * l->kw * l->kh + (size_t)l->cout;
+}
+
+/* One window by the definition of the network: in is in_h rows of in_w       */
+/* doubles; weights per conv layer [cout][cin][kh][kw] then bias[cout].       */
+/* The last layer must leave a 1 x 1 map; out receives its cout values.       */
+int orc_rnet_forward(const orc_rlayer *layers, int n_layers, const float *weights, int in_w, int in_h,
+                     const double *in, double *out)
+{
+    int c = 1, w = in_w, h = in_h;
+    size_t cap = (size_t)in_w * in_h;
+    for (int i = 0, cc = 1, ww = in_w, hh = in_h; i < n_layers; ++i) {
+        const orc_rlayer *l = &layers[i];
+        if (l->kind == ORC_POOL) { ww /= 2; hh /= 2; } else { ww -= l->kw - 1; hh -= l->kh - 1; cc = l->cout; }
+        if (ww < 1 || hh < 1) return -1;
+        if ((size_t)cc * ww * hh > cap) cap = (size_t)cc * ww * hh;
+    }
+    double *cur = malloc(sizeof(double) * cap), *nxt = malloc(sizeof(double) * cap);
+    memcpy(cur, in, sizeof(double) * (size_t)in_w * in_h);
+    const float *wp = weights;
+    int rc = 0;
+    for (int i = 0; i < n_layers && rc == 0; ++i) {
+        const orc_rlayer *l = &layers[i];
+        if (l->cin != c) { rc = -1; break; }
+        if (l->kind == ORC_POOL) {
+            if (w % 2 || h % 2) { rc = -1; break; }
+            int ow = w / 2, oh = h / 2;
+            for (int ch = 0; ch < c; ++ch)
+                for (int y = 0; y < oh; ++y)
+                    for (int x = 0; x < ow; ++x) {
+                        const double *p = cur + ((size_t)ch * h + 2 * y) * w + 2 * x;
+                        double m = p[0];
+                        if (p[1] > m) m = p[1];
+                        if (p[w] > m) m = p[w];
+                        if (p[w + 1] > m) m = p[w + 1];
+                        nxt[((size_t)ch * oh + y) * ow + x] = m;
+                    }
+            w = ow; h = oh;
+        } else {
+            int ow = w - l->kw + 1, oh = h - l->kh + 1;
+            const float *bias = wp + (size_t)l->cout * c * l->kw * l->kh;
+            for (int oc = 0; oc < l->cout; ++oc)
+                for (int y = 0; y < oh; ++y)
+                    for (int x = 0; x < ow; ++x) {
+                        double acc = (double)bias[oc];
+                        for (int ic = 0; ic < c; ++ic)
+                            for (int a = 0; a < l->kh; ++a)
+                                for (int b = 0; b < l->kw; ++b)
+                                    acc += (double)wp[(((size_t)oc * c + ic) * l->kh + a) * l->kw + b]
+                                         * cur[((size_t)ic * h + y + a) * w + x + b];
+                        nxt[((size_t)oc * oh + y) * ow + x] = orc_activation(acc, l->act);
+                    }
+            wp += rlayer_params(l);
+            c = l->cout; w = ow; h = oh;
+        }
+        double *t = cur; cur = nxt; nxt = t;
+    }
+    if (rc == 0 && (w != 1 || h != 1)) rc = -1;
+    if (rc == 0) memcpy(out, cur, sizeof(double) * (size_t)c);
+    free(cur); free(nxt);
+    return rc;
+}
+
+/* The scan by its definition: the window of win_w x win_h pixels is cut at   */
+/* every position (step * i, step * j) that keeps it inside the level and     */
+/* run through the network on its own.                                        */
+/* scores: ((lh - win_h) / step + 1) rows of ((lw - win_w) / step + 1).       */
+int orc_scan_windows(const uint8_t *level, int lw, int lh, const orc_rlayer *layers, int n_layers,
+                     const float *weights, int win_w, int win_h, int step, double *scores)
+{
+    if (lw < win_w || lh < win_h || step < 1) return -1;
+    int ow = (lw - win_w) / step + 1, oh = (lh - win_h) / step + 1, rc = 0;
+#pragma omp parallel for schedule(dynamic)
+    for (int j = 0; j < oh; ++j) {
+        double *win = malloc(sizeof(double) * (size_t)win_w * win_h);
+        for (int i = 0; i < ow; ++i) {
+            for (int a = 0; a < win_h; ++a)
+                for (int b = 0; b < win_w; ++b)
+                    win[a * win_w + b] = normalise((double)level[(size_t)(step * j + a) * lw + step * i + b]);
+            double r = 0.0;
+            if (orc_rnet_forward(layers, n_layers, weights, win_w, win_h, win, &r) != 0) {
+#pragma omp atomic write
+                rc = -1;
+            }
+            scores[(size_t)j * ow + i] = r;
+        }
+        free(win);
+    }
+    return rc;
+}
+
+/* The same scan as one pass of the layers over the whole level (paper,       */
+/* Section 3.3: the network scans the image, its output layer holds the       */
+/* responses of all window positions): convolutions at stride 1, pools at     */
+/* stride 2 anchored at the level's corner (a trailing odd row or column is   */
+/* dropped).  The step between windows is 2^(number of pools).                */
+int orc_scan_fcn(const uint8_t *level, int lw, int lh, const orc_rlayer *layers, int n_layers,
+                 const float *weights, int win_w, int win_h, double *scores)
+{
+    int step = 1;
+    for (int i = 0; i < n_layers; ++i) if (layers[i].kind == ORC_POOL) step *= 2;
+    if (lw < win_w || lh < win_h) return -1;
+    int ow = (lw - win_w) / step + 1, oh = (lh - win_h) / step + 1;
+    int c = 1, W = lw, H = lh;
+    double *cur = malloc(sizeof(double) * (size_t)lw * lh);
+    for (size_t i = 0; i < (size_t)lw * lh; ++i) cur[i] = normalise((double)level[i]);
+    const float *wp = weights;
+    for (int i = 0; i < n_layers; ++i) {
+        const orc_rlayer *l = &layers[i];
+        int OW, OH, oc_n;
+        if (l->kind == ORC_POOL) { OW = W / 2; OH = H / 2; oc_n = c; }
+        else { OW = W - l->kw + 1; OH = H - l->kh + 1; oc_n = l->cout; }
+        if (OW < 1 || OH < 1) { free(cur); return -1; }
+        double *nxt = malloc(sizeof(double) * (size_t)oc_n * OW * OH);
+        if (l->kind == ORC_POOL) {
+#pragma omp parallel for collapse(2)
+            for (int ch = 0; ch < c; ++ch)
+                for (int y = 0; y < OH; ++y)
+                    for (int x = 0; x < OW; ++x) {
+                        const double *p = cur + ((size_t)ch * H + 2 * y) * W + 2 * x;
+                        double m = p[0];
+                        if (p[1] > m) m = p[1];
+                        if (p[W] > m) m = p[W];
+                        if (p[W + 1] > m) m = p[W + 1];
+                        nxt[((size_t)ch * OH + y) * OW + x] = m;
+                    }
+        } else {
+            const float *bias = wp + (size_t)l->cout * c * l->kw * l->kh;
+#pragma omp parallel for collapse(2)
+            for (int oc = 0; oc < l->cout; ++oc)
+                for (int y = 0; y < OH; ++y)
+                    for (int x = 0; x < OW; ++x) {
+                        double acc = (double)bias[oc];
+                        for (int ic = 0; ic < c; ++ic)
+                            for (int a = 0; a < l->kh; ++a)
+                                for (int b = 0; b < l->kw; ++b)
+                                    acc += (double)wp[(((size_t)oc * c + ic) * l->kh + a) * l->kw + b]
+                                         * cur[((size_t)ic * H + y + a) * W + x + b];
+                        nxt[((size_t)oc * OH + y) * OW + x] = orc_activation(acc, l->act);
+                    }
+            wp += rlayer_params(l);
+            c = l->cout;
+        }
+        free(cur); cur = nxt; W = OW; H = OH;
+    }
+    int rc = (c == 1 && W >= ow && H >= oh) ? 0 : -1;   /* equal when the window is the net's receptive field */
+    if (rc == 0)
+        for (int y = 0; y < oh; ++y) memcpy(scores + (size_t)y * ow, cur + (size_t)y * W, sizeof(double) * (size_t)ow);
+    free(cur);
+    return rc;
 }

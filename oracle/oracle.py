@@ -22,6 +22,11 @@ class _Layer(C.Structure):
                 ("k", C.c_int32), ("act", C.c_int32)]
 
 
+class _RLayer(C.Structure):
+    _fields_ = [("kind", C.c_int32), ("cin", C.c_int32), ("cout", C.c_int32),
+                ("kw", C.c_int32), ("kh", C.c_int32), ("act", C.c_int32)]
+
+
 _lib = None
 
 
@@ -154,6 +159,53 @@ def stage1_level(level: np.ndarray, stage, weights: np.ndarray, form: str = "den
     if rc != 0:
         raise ValueError("stage-1 evaluation failed")
     return out
+
+
+def _rlayers(net):
+    arr = (_RLayer * len(net.layers))()
+    for i, l in enumerate(net.layers):
+        arr[i] = _RLayer(l.kind, l.cin, l.cout, l.kw, l.kh, l.act)
+    return arr
+
+
+def scan_window(net, weights: np.ndarray, window: np.ndarray) -> float:
+    """The scanning network on one normalised window (win_h x win_w float64): its single response."""
+    window = np.ascontiguousarray(window, np.float64)
+    assert window.shape == (net.win_h, net.win_w)
+    weights = np.ascontiguousarray(weights, np.float32)
+    assert weights.size == net.n_params
+    out = np.zeros(1, np.float64)
+    rc = lib().orc_rnet_forward(_rlayers(net), C.c_int(len(net.layers)), _p(weights), C.c_int(net.win_w),
+                                C.c_int(net.win_h), _p(window), _p(out))
+    if rc != 0:
+        raise ValueError("layer list does not take the window to one response")
+    return float(out[0])
+
+
+def scan_level(level: np.ndarray, net, weights: np.ndarray, form: str = "fcn") -> np.ndarray:
+    """Responses of the scanning network on one level: ((H - win_h) // step + 1) x ((W - win_w) // step + 1)
+    float64; an empty array when the level is smaller than the window."""
+    level = np.ascontiguousarray(level, np.uint8)
+    weights = np.ascontiguousarray(weights, np.float32)
+    assert weights.size == net.n_params
+    lh, lw = level.shape
+    if lw < net.win_w or lh < net.win_h:
+        return np.zeros((0, 0), np.float64)
+    out = np.zeros(((lh - net.win_h) // net.step + 1, (lw - net.win_w) // net.step + 1), np.float64)
+    if form == "fcn":
+        rc = lib().orc_scan_fcn(_p(level), C.c_int(lw), C.c_int(lh), _rlayers(net), C.c_int(len(net.layers)),
+                                _p(weights), C.c_int(net.win_w), C.c_int(net.win_h), _p(out))
+    else:
+        rc = lib().orc_scan_windows(_p(level), C.c_int(lw), C.c_int(lh), _rlayers(net), C.c_int(len(net.layers)),
+                                    _p(weights), C.c_int(net.win_w), C.c_int(net.win_h), C.c_int(net.step), _p(out))
+    if rc != 0:
+        raise ValueError("scan failed")
+    return out
+
+
+def scan_scores(pyr: Pyramid, net, weights: np.ndarray, form: str = "fcn") -> np.ndarray:
+    """All responses of a frame's pyramid, flat in (level, row, column) order."""
+    return np.concatenate([scan_level(l, net, weights, form).ravel() for l in pyr.levels] + [np.zeros(0)])
 
 
 def stage1_scores(pyr: Pyramid, stage, weights: np.ndarray, form: str = "dense") -> np.ndarray:
