@@ -25,6 +25,7 @@ S2_FLOP_PER_CROP = 2 * 161952
 S3_FLOP_PER_CROP = 2 * 5473600
 S2_CONV_FLOP_PER_CROP = 2 * (80000 + 73728)            # conv kernel of stage 2 (conv1 + conv2)
 S3_CONV_FLOP_PER_CROP = 2 * (774400 + 4147200 + 451584)  # conv kernel of stage 3 (conv1..conv3)
+SCAN_FLOP_PER_POSITION = 2 * (1024 + 1584 + 330)       # 27x31 scan: conv1 + conv2 + conv3 MACs per window position at step 4
 PEAK_HBM = 8000.0          # GB/s
 PEAK_FP32_VECTOR = 157.3   # TFLOP/s, published vector fp32 figure
 PEAK_FP32_MFMA = 157.3     # TFLOP/s, published dense fp32 matrix figure
@@ -139,6 +140,20 @@ def main():
     tm = c0.get_timings()
     c0.set_timing(False)
     ms = {k: (v[0] / v[1] if v[1] else 0.0) for k, v in tm.items()}
+    # first stage in the paper's own geometry (27 x 31 window, 4 pixel step) on the same pyramid: reported beside the
+    # headline, in the paper's unit (window positions at step 4)
+    scan_net = I.paper_stage1()
+    c0.scan_set_weights(I.draw_scan_weights(scan_net, seed), 1)
+    c0.build_pyramid(dev_frame, streams[0])
+    c0.set_timing(True)
+    c0.get_timings()
+    for _ in range(a.steps):
+        c0.scan_scoremap(streams[0])
+    tm_scan = c0.get_timings()["scan"]
+    c0.set_timing(False)
+    ms_scan = tm_scan[0] / tm_scan[1] if tm_scan[1] else 0.0
+    n_scan = int(c0.scan_layout(cfg["width"], cfg["height"])["out_off"][-1])
+    c0.detect(dev_frame, 8192)           # leaves the context with the cascade's own survivor lists again
     n1, n2, n3 = (c0.survivor_count(s) for s in (1, 2, 3))
     lay = c0.pyramid_layout(cfg["width"], cfg["height"])
     pyr_bytes = lay["pyr_off"][-1]
@@ -193,7 +208,12 @@ def main():
                    "frames_in_flight": F, "windows": n_windows, "survivors": [n1, n2, n3], "detections": n_det},
         "stage1_windows_per_s": n_windows / (ms["stage1"] * 1e-3) if ms["stage1"] > 0 else None,
         "latency_ms_single_frame": latency_ms,
-        "sum_of_kernel_ms": sum(v for k, v in ms.items() if not k.endswith("_conv")),
+        "paper_geometry_stage1": {"window": "27x31", "step": 4, "positions": n_scan, "ms": ms_scan,
+                                  "positions_per_s": n_scan / (ms_scan * 1e-3) if ms_scan > 0 else None,
+                                  "bound": "alu", "achieved": tflops(SCAN_FLOP_PER_POSITION * n_scan, ms_scan),
+                                  "peak": PEAK_FP32_VECTOR, "unit": "TFLOP/s",
+                                  "frac": tflops(SCAN_FLOP_PER_POSITION * n_scan, ms_scan) / PEAK_FP32_VECTOR},
+        "sum_of_kernel_ms": sum(v for k, v in ms.items() if not k.endswith("_conv") and k != "scan"),
         "roofline": roof,
         "kernels": kernels,
         "cpu_baseline": cpu,

@@ -94,7 +94,9 @@ enum {
     CNNC_T_PYRAMID = 0, CNNC_T_STAGE1, CNNC_T_COMPACT1, CNNC_T_STAGE2, CNNC_T_COMPACT2,
     CNNC_T_STAGE3, CNNC_T_COMPACT3, CNNC_T_MERGE,
     /* the convolution kernel alone inside cnnc_eval_stage(2) / (3) (the step also runs a small fc kernel) */
-    CNNC_T_STAGE2_CONV, CNNC_T_STAGE3_CONV, CNNC_T_COUNT
+    CNNC_T_STAGE2_CONV, CNNC_T_STAGE3_CONV,
+    CNNC_T_SCAN,            /* cnnc_scan_scoremap */
+    CNNC_T_COUNT
 };
 
 /* Create a context on the current HIP device.
@@ -182,6 +184,28 @@ int cnnc_get_timings(cnnc_ctx *ctx, double *ms_sum, int32_t *calls);
  * within fp32 rounding (about 1e-6 on a score); kept so that the choice stays measurable (the paper's
  * Section 3.4 argues for code specialised per network and processor). */
 int cnnc_set_eval_impl(cnnc_ctx *ctx, int impl);
+
+/* ---- First stage in the paper's own geometry -------------------------------------------------
+ * Section 3.1: CNN_1 has no fully connected layer, convolution stride 1, pooling stride 2; Section 3.3: the
+ * responses of its output layer correspond to a 27 x 31 (width x height) window moved over each pyramid
+ * image with a 4 pixel step.  The layer shapes were printed only in the paper's Figure 1; built in here:
+ *   conv 4x4 1->4, f, pool 2 | conv 3x3 4->11, f, pool 2 | conv 5x6 (w x h) 11->1 (linear)   = 806 parameters
+ * (the paper states 797).  This scan is a second reader of the pyramid beside cnnc_stage1_scoremap; it does
+ * not feed the later stages.
+ *
+ * cnnc_scan_set_weights: weights = host pointer to n_floats = 806 float32, per conv layer w[cout][cin][kh][kw]
+ *   then bias[cout]; act = hidden activation kind (1, 2 or 3).  Copied to the device; synchronises.
+ * cnnc_scan_layout: host only.  For a w x h frame under the current parameters: out_w[l] x out_h[l] responses on
+ *   level l (0 x 0 when the level is smaller than the window), out_off[l] = first response of level l in the flat
+ *   map, out_off[n_levels] = their total.  Arrays: host, capacity CNNC_MAX_LEVELS (+ 1 for out_off), may be NULL.
+ * cnnc_scan_scoremap: needs cnnc_build_pyramid first (CNNC_E_STATE otherwise) and the weights.  Response (j, i)
+ *   of level l is the network on the window whose corner is pixel (4 i, 4 j) of that level, pixels entering as
+ *   (p - 128) / 128; fp32, flat order (level, row, column).  Enqueued on `stream`.
+ * cnnc_get_scan_scoremap: device view of that map and its length. */
+int cnnc_scan_set_weights(cnnc_ctx *ctx, const float *weights, int n_floats, int act);
+int cnnc_scan_layout(cnnc_ctx *ctx, int w, int h, int *n_levels, int32_t *out_w, int32_t *out_h, int64_t *out_off);
+int cnnc_scan_scoremap(cnnc_ctx *ctx, void *stream);
+int cnnc_get_scan_scoremap(cnnc_ctx *ctx, const float **d_scores, int64_t *n);
 
 /* Measurement aid for benchmarks: what this GPU sustains on three synthetic probes (dense fp32 MFMA loop,
  * fp32 FMA loop on the vector ALU, 1 GiB device-to-device copy counted as read + write).  Runs on the

@@ -19,9 +19,10 @@ EXPORTS = [
     "cnnc_detect", "cnnc_detect_async", "cnnc_fetch_detections", "cnnc_get_pyramid", "cnnc_get_scoremap",
     "cnnc_get_survivors", "cnnc_get_stage_scores", "cnnc_survivor_count", "cnnc_set_timing",
     "cnnc_get_timings", "cnnc_set_eval_impl", "cnnc_measure_peaks", "cnnc_last_error", "cnnc_version",
+    "cnnc_scan_set_weights", "cnnc_scan_layout", "cnnc_scan_scoremap", "cnnc_get_scan_scoremap",
 ]
 STEP_NAMES = ["pyramid", "stage1", "compact1", "stage2", "compact2", "stage3", "compact3", "merge",
-              "stage2_conv", "stage3_conv"]
+              "stage2_conv", "stage3_conv", "scan"]
 MAX_LEVELS = 64
 E_OVERFLOW = -3
 
@@ -231,6 +232,30 @@ class Context:
         self._check(lib().cnnc_get_stage_scores(self._h, C.c_int(k), C.byref(p)))
         return _d2h(p.value, n * 4, np.float32)
 
+    # ---- first stage in the paper's geometry (27 x 31 window, 4 pixel step)
+    def scan_set_weights(self, weights: np.ndarray, act: int = 1):
+        w = np.ascontiguousarray(weights, np.float32)
+        self._check(lib().cnnc_scan_set_weights(self._h, w.ctypes.data_as(C.c_void_p), C.c_int(w.size), C.c_int(act)))
+
+    def scan_layout(self, w: int, h: int):
+        n = C.c_int(0)
+        ow = np.zeros(MAX_LEVELS, np.int32)
+        oh = np.zeros(MAX_LEVELS, np.int32)
+        off = np.zeros(MAX_LEVELS + 1, np.int64)
+        self._check(lib().cnnc_scan_layout(self._h, C.c_int(w), C.c_int(h), C.byref(n), ow.ctypes.data_as(C.c_void_p),
+                                           oh.ctypes.data_as(C.c_void_p), off.ctypes.data_as(C.c_void_p)))
+        k = n.value
+        return {"n_levels": k, "out_w": ow[:k].copy(), "out_h": oh[:k].copy(), "out_off": off[:k + 1].copy()}
+
+    def scan_scoremap(self, stream=None):
+        self._check(lib().cnnc_scan_scoremap(self._h, _stream(stream)))
+
+    def get_scan_scoremap(self) -> np.ndarray:
+        _hiprt().hipDeviceSynchronize()
+        p, n = C.c_void_p(0), C.c_int64(0)
+        self._check(lib().cnnc_get_scan_scoremap(self._h, C.byref(p), C.byref(n)))
+        return _d2h(p.value, n.value * 4, np.float32)
+
     def set_eval_impl(self, impl: int):
         self._check(lib().cnnc_set_eval_impl(self._h, C.c_int(impl)))
 
@@ -251,6 +276,22 @@ def cnnc_measure_peaks():
     if rc != 0:
         raise CnncError(rc, "cnnc_measure_peaks failed")
     return a.value, b.value, c.value
+
+
+def cnnc_scan_set_weights(ctx, weights, act=1):
+    return ctx.scan_set_weights(weights, act)
+
+
+def cnnc_scan_layout(ctx, w, h):
+    return ctx.scan_layout(w, h)
+
+
+def cnnc_scan_scoremap(ctx, stream=None):
+    return ctx.scan_scoremap(stream)
+
+
+def cnnc_get_scan_scoremap(ctx):
+    return ctx.get_scan_scoremap()
 
 
 # Same-named thin functions for callers that prefer the C spelling.

@@ -9,12 +9,7 @@
 
 using namespace cnnc;
 
-namespace {
-
-enum { DONE_PYR = 1, DONE_S1 = 2, DONE_C1 = 4, DONE_E2 = 8, DONE_C2 = 16, DONE_E3 = 32, DONE_C3 = 64, DONE_MERGE = 128 };
-
-constexpr int kFastDets = 2048;   // detections copied to the host together with the counters
-
+namespace cnnc {
 int fail(cnnc_ctx *c, int code, const std::string &msg)
 {
     if (c) c->err = msg;
@@ -25,6 +20,11 @@ int hip_fail(cnnc_ctx *c, hipError_t e, const char *what)
 {
     return fail(c, e == hipErrorOutOfMemory ? CNNC_E_NOMEM : CNNC_E_HIP, std::string(what) + ": " + hipGetErrorString(e));
 }
+}  // namespace cnnc
+
+namespace {
+
+constexpr int kFastDets = 2048;   // detections copied to the host together with the counters
 
 #define HIP_TRY(c, expr)                                         \
     do {                                                         \
@@ -84,6 +84,9 @@ void axis_taps(int n_out, int n_in, double s, uint32_t *out)
     }
 }
 
+}  // namespace
+
+namespace cnnc {
 // Pyramid geometry for a frame size under the current parameters (host arithmetic only).
 int compute_levels(const cnnc_ctx *c, int w, int h, std::vector<LevelDev> &lv, int64_t &pyr_bytes, int64_t &n_windows)
 {
@@ -107,6 +110,10 @@ int compute_levels(const cnnc_ctx *c, int w, int h, std::vector<LevelDev> &lv, i
     pyr_bytes = poff; n_windows = soff;
     return lv.empty() ? CNNC_E_INVAL : CNNC_OK;
 }
+
+}  // namespace cnnc
+
+namespace {
 
 int prepare_layout(cnnc_ctx *c, int w, int h)
 {
@@ -156,6 +163,7 @@ int prepare_layout(cnnc_ctx *c, int w, int h)
     c->pyr_bytes = pyr_bytes; c->n_windows = n_windows;
     c->n_tiles_pyr = (int)tiles_pyr.size(); c->n_tiles_s1 = (int)tiles_s1.size();
     c->lay_w = w; c->lay_h = h; c->layout_valid = true;
+    ++c->layout_serial;
     return CNNC_OK;
 }
 
@@ -297,6 +305,7 @@ int cnnc_destroy(cnnc_ctx *c)
     (void)hipDeviceSynchronize();
     for (int s = 0; s < 3; ++s) { (void)hipFree(c->d_wt[s]); (void)hipFree(c->d_idx[s]); (void)hipFree(c->d_sc[s]); }
     for (int s = 0; s < 2; ++s) { (void)hipFree(c->d_eval[s]); (void)hipFree(c->d_frag[s]); (void)hipFree(c->d_feat[s]); }
+    scan_release(c);
     (void)hipFree(c->d_levels); (void)hipFree(c->d_taps); (void)hipFree(c->d_tiles_pyr); (void)hipFree(c->d_tiles_s1);
     (void)hipFree(c->d_pyr); (void)hipFree(c->d_score1); (void)hipFree(c->d_blockcnt); (void)hipFree(c->d_cnt);
     (void)hipFree(c->d_merge_ws); (void)hipFree(c->d_det);
@@ -356,6 +365,7 @@ int cnnc_build_pyramid(cnnc_ctx *c, const uint8_t *d_frame, int w, int h, int pi
     c->d_frame = d_frame; c->fw = w; c->fh = h; c->fpitch = pitch;
     c->last_stream = st;
     c->progress = 0;
+    c->scan_done = false;
     {
         Timed t(c, CNNC_T_PYRAMID, st);
         HIP_TRY(c, launch_pyramid(c, st));

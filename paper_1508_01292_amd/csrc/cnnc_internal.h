@@ -46,6 +46,17 @@ struct Counters {
     int32_t n[4];          // survivors of stage 1, 2, 3 and merged detections (untruncated counts)
 };
 
+// Completed steps of the current frame (cnnc_ctx::progress), for the call-order checks.
+enum { DONE_PYR = 1, DONE_S1 = 2, DONE_C1 = 4, DONE_E2 = 8, DONE_C2 = 16, DONE_E3 = 32, DONE_C3 = 64, DONE_MERGE = 128 };
+
+// One pyramid level as the scan of the paper-geometry first stage sees it.
+struct ScanLevel {
+    int32_t w, h;          // level size
+    int32_t ow, oh;        // responses per row / rows of responses (0 when the level is below 27 x 31)
+    int32_t pyr_off;       // first byte of the level in the pyramid buffer
+    int32_t out_off;       // first response of the level in the flat response map
+};
+
 struct StepTimer {
     std::vector<hipEvent_t> begin, end;   // recorded pairs not yet read
     std::vector<hipEvent_t> pool;         // events free for reuse
@@ -78,6 +89,17 @@ struct cnnc_ctx {
     std::vector<cnnc::LevelDev> levels;
     int64_t pyr_bytes = 0, n_windows = 0;
     int n_tiles_pyr = 0, n_tiles_s1 = 0;
+    int layout_serial = 0;                    // bumped whenever the geometry tables are rebuilt
+
+    // first stage in the paper's geometry (27 x 31 window, 4 pixel step): weights, tables and response map
+    float *d_scan_wt = nullptr;
+    int scan_act = 0;
+    cnnc::ScanLevel *d_scan_levels = nullptr;
+    uint32_t *d_scan_tiles = nullptr;
+    float *d_scan_map = nullptr;
+    int64_t cap_scan_tiles = 0, cap_scan_map = 0, n_scan = 0;
+    int n_scan_tiles = 0, scan_serial = -1;
+    bool scan_done = false;
 
     // device buffers that depend on the layout
     cnnc::LevelDev *d_levels = nullptr;
@@ -138,6 +160,11 @@ struct ScopedTimer {
     ScopedTimer(cnnc_ctx *c_, int step_, hipStream_t st_);
     ~ScopedTimer();
 };
+// Host helpers shared by the translation units that hold entry points.
+int fail(cnnc_ctx *c, int code, const std::string &msg);
+int hip_fail(cnnc_ctx *c, hipError_t e, const char *what);
+int compute_levels(const cnnc_ctx *c, int w, int h, std::vector<LevelDev> &lv, int64_t &pyr_bytes, int64_t &n_windows);
+void scan_release(cnnc_ctx *c);
 size_t eval2_frag_floats();
 size_t eval2_feat_floats();
 void eval2_make_fragments(const float *blob, float *frag);
