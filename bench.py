@@ -46,6 +46,7 @@ def main():
     ap.add_argument("--q1", type=float, default=0.02, help="stage-1 survival quantile (the benchmark's rule: 2 %%)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--eval-impl", type=int, default=None, help="cnnc_set_eval_impl value (default: the library's)")
+    ap.add_argument("--fused-stage1", type=int, default=None, help="cnnc_set_fused_stage1 value (default: the library's)")
     a = ap.parse_args()
     if a.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus %d is not supported (no collectives, no sharding)" % a.gpus,
@@ -96,6 +97,8 @@ def main():
         c.set_params(cfg["min_face"], cfg["scale_step"], tr.thr)
         if a.eval_impl is not None:
             c.set_eval_impl(a.eval_impl)
+        if a.fused_stage1 is not None:
+            c.set_fused_stage1(bool(a.fused_stage1))
 
     def run(n_steps):
         busy = [False] * F

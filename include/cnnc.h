@@ -133,6 +133,15 @@ int cnnc_build_pyramid(cnnc_ctx *ctx, const uint8_t *d_frame, int w, int h, int 
  * window order.  Pixels enter the network as (p - 128) / 128.  Needs cnnc_build_pyramid first. */
 int cnnc_stage1_scoremap(cnnc_ctx *ctx, void *stream);
 
+/* cnnc_stage1_scoremap and cnnc_compact_survivors(1, thr) in one step that never writes the score map (the
+ * paper's detector hands only the coordinates of windows above T_1 to the next unit, Section 3.3): the stage-1
+ * kernel keeps one bit per window and the scores of the passing windows, and the ordered list is built from
+ * those.  Leaves exactly the stage-1 survivor list of the two-call path (same order, same fp32 scores);
+ * afterwards cnnc_get_scoremap reports CNNC_E_STATE.  Needs cnnc_build_pyramid first.
+ * cnnc_set_fused_stage1(on): cnnc_detect / cnnc_detect_async take this step instead of the two calls. */
+int cnnc_stage1_survivors(cnnc_ctx *ctx, float thr, void *stream);
+int cnnc_set_fused_stage1(cnnc_ctx *ctx, int on);
+
 /* stage = 1, 2 or 3: list the windows with score_stage > thr, in ascending flat index.
  * Stage 1 reads the score map; stage k > 1 reads the scores cnnc_eval_stage(k) left for the
  * survivors of stage k - 1.  The count stays on the device; lists longer than max_survivors are

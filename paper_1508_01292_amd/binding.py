@@ -19,6 +19,7 @@ EXPORTS = [
     "cnnc_detect", "cnnc_detect_async", "cnnc_fetch_detections", "cnnc_get_pyramid", "cnnc_get_scoremap",
     "cnnc_get_survivors", "cnnc_get_stage_scores", "cnnc_survivor_count", "cnnc_set_timing",
     "cnnc_get_timings", "cnnc_set_eval_impl", "cnnc_measure_peaks", "cnnc_last_error", "cnnc_version",
+    "cnnc_stage1_survivors", "cnnc_set_fused_stage1",
     "cnnc_scan_set_weights", "cnnc_scan_layout", "cnnc_scan_scoremap", "cnnc_get_scan_scoremap",
 ]
 STEP_NAMES = ["pyramid", "stage1", "compact1", "stage2", "compact2", "stage3", "compact3", "merge",
@@ -173,6 +174,12 @@ class Context:
     def stage1_scoremap(self, stream=None):
         self._check(lib().cnnc_stage1_scoremap(self._h, _stream(stream)))
 
+    def stage1_survivors(self, thr: float, stream=None):
+        self._check(lib().cnnc_stage1_survivors(self._h, C.c_float(thr), _stream(stream)))
+
+    def set_fused_stage1(self, on: bool):
+        self._check(lib().cnnc_set_fused_stage1(self._h, C.c_int(1 if on else 0)))
+
     def compact_survivors(self, stage: int, thr: float, stream=None):
         self._check(lib().cnnc_compact_survivors(self._h, C.c_int(stage), C.c_float(thr), _stream(stream)))
 
@@ -276,6 +283,14 @@ def cnnc_measure_peaks():
     if rc != 0:
         raise CnncError(rc, "cnnc_measure_peaks failed")
     return a.value, b.value, c.value
+
+
+def cnnc_stage1_survivors(ctx, thr, stream=None):
+    return ctx.stage1_survivors(thr, stream)
+
+
+def cnnc_set_fused_stage1(ctx, on):
+    return ctx.set_fused_stage1(on)
 
 
 def cnnc_scan_set_weights(ctx, weights, act=1):

@@ -92,7 +92,7 @@ int compute_levels(const cnnc_ctx *c, int w, int h, std::vector<LevelDev> &lv, i
 {
     lv.clear();
     double s = c->params.min_face / (double)kWin;
-    int64_t poff = 0, soff = 0, toff = 0;
+    int64_t poff = 0, soff = 0, toff = 0, woff = 0;
     while ((int)lv.size() < CNNC_MAX_LEVELS) {
         const int lw = (int)floor((double)w / s + 1e-9), lh = (int)floor((double)h / s + 1e-9);
         if (lw < kWin || lh < kWin) break;
@@ -102,6 +102,8 @@ int compute_levels(const cnnc_ctx *c, int w, int h, std::vector<LevelDev> &lv, i
         L.xmap_off = (int32_t)toff; L.ymap_off = (int32_t)(toff + lw);
         L.scale_q16 = (int64_t)floor(s * 65536.0 + 0.5);
         L.scale = s;
+        L.word_off = (int32_t)woff; L.words_per_row = (L.ow + 31) / 32;
+        woff += (int64_t)L.words_per_row * L.oh;
         lv.push_back(L);
         poff += (int64_t)lw * lh; soff += (int64_t)L.ow * L.oh; toff += lw + lh;
         if (poff > INT32_MAX || soff > INT32_MAX) return CNNC_E_INVAL;
@@ -147,8 +149,11 @@ int prepare_layout(cnnc_ctx *c, int w, int h)
     if ((rc = ensure(c, c->d_tiles_s1, c->cap_tiles_s1, (int64_t)tiles_s1.size()))) return rc;
     if ((rc = ensure(c, c->d_pyr, c->cap_pyr, pyr_bytes))) return rc;
     if ((rc = ensure(c, c->d_score1, c->cap_score1, n_windows))) return rc;
-    const int64_t nblocks = std::max<int64_t>((n_windows + kCompactPerBlock - 1) / kCompactPerBlock,
-                                              (c->max_surv + kCompactPerBlock - 1) / kCompactPerBlock) + 1;
+    const int64_t n_words = (int64_t)lv.back().word_off + (int64_t)lv.back().words_per_row * lv.back().oh;
+    if ((rc = ensure(c, c->d_mask1, c->cap_mask1, n_words))) return rc;
+    const int64_t nblocks = std::max<int64_t>(std::max<int64_t>((n_windows + kCompactPerBlock - 1) / kCompactPerBlock,
+                                                                (c->max_surv + kCompactPerBlock - 1) / kCompactPerBlock),
+                                              (n_words + kCompactBlock - 1) / kCompactBlock) + 1;
     int64_t cap_blocks = c->cap_blocks;
     if ((rc = ensure(c, c->d_blockcnt, cap_blocks, nblocks))) return rc;
     c->cap_blocks = (int32_t)cap_blocks;
@@ -160,7 +165,7 @@ int prepare_layout(cnnc_ctx *c, int w, int h)
 
     c->levels = lv;
     c->n_levels = (int)lv.size();
-    c->pyr_bytes = pyr_bytes; c->n_windows = n_windows;
+    c->pyr_bytes = pyr_bytes; c->n_windows = n_windows; c->n_words = n_words;
     c->n_tiles_pyr = (int)tiles_pyr.size(); c->n_tiles_s1 = (int)tiles_s1.size();
     c->lay_w = w; c->lay_h = h; c->layout_valid = true;
     ++c->layout_serial;
@@ -307,7 +312,7 @@ int cnnc_destroy(cnnc_ctx *c)
     for (int s = 0; s < 2; ++s) { (void)hipFree(c->d_eval[s]); (void)hipFree(c->d_frag[s]); (void)hipFree(c->d_feat[s]); }
     scan_release(c);
     (void)hipFree(c->d_levels); (void)hipFree(c->d_taps); (void)hipFree(c->d_tiles_pyr); (void)hipFree(c->d_tiles_s1);
-    (void)hipFree(c->d_pyr); (void)hipFree(c->d_score1); (void)hipFree(c->d_blockcnt); (void)hipFree(c->d_cnt);
+    (void)hipFree(c->d_pyr); (void)hipFree(c->d_score1); (void)hipFree(c->d_mask1); (void)hipFree(c->d_blockcnt); (void)hipFree(c->d_cnt);
     (void)hipFree(c->d_merge_ws); (void)hipFree(c->d_det);
     if (c->h_cnt) (void)hipHostFree(c->h_cnt);
     if (c->h_det) (void)hipHostFree(c->h_det);
@@ -388,6 +393,32 @@ int cnnc_stage1_scoremap(cnnc_ctx *c, void *stream)
     return CNNC_OK;
 }
 
+int cnnc_stage1_survivors(cnnc_ctx *c, float thr, void *stream)
+{
+    if (!c) return CNNC_E_INVAL;
+    if (thr != thr) return fail(c, CNNC_E_INVAL, "threshold is NaN");
+    if (!(c->progress & DONE_PYR)) return fail(c, CNNC_E_STATE, "stage 1 needs a pyramid");
+    hipStream_t st = (hipStream_t)stream;
+    c->last_stream = st;
+    {
+        Timed t(c, CNNC_T_STAGE1, st);
+        HIP_TRY(c, launch_stage1_emit(c, thr, st));
+    }
+    {
+        Timed t(c, CNNC_T_COMPACT1, st);
+        HIP_TRY(c, launch_compact_mask(c, c->d_idx[0], c->d_sc[0], &c->d_cnt->n[0], st));
+    }
+    c->progress = DONE_PYR | DONE_C1;      // no score map: cnnc_get_scoremap reports CNNC_E_STATE
+    return CNNC_OK;
+}
+
+int cnnc_set_fused_stage1(cnnc_ctx *c, int on)
+{
+    if (!c) return CNNC_E_INVAL;
+    c->fused_stage1 = on != 0;
+    return CNNC_OK;
+}
+
 int cnnc_compact_survivors(cnnc_ctx *c, int stage, float thr, void *stream)
 {
     if (!c) return CNNC_E_INVAL;
@@ -455,8 +486,12 @@ int cnnc_detect_async(cnnc_ctx *c, const uint8_t *d_frame, int w, int h, int pit
 {
     int rc;
     if ((rc = cnnc_build_pyramid(c, d_frame, w, h, pitch, stream))) return rc;
-    if ((rc = cnnc_stage1_scoremap(c, stream))) return rc;
-    if ((rc = cnnc_compact_survivors(c, 1, c->params.thr[0], stream))) return rc;
+    if (c->fused_stage1) {
+        if ((rc = cnnc_stage1_survivors(c, c->params.thr[0], stream))) return rc;
+    } else {
+        if ((rc = cnnc_stage1_scoremap(c, stream))) return rc;
+        if ((rc = cnnc_compact_survivors(c, 1, c->params.thr[0], stream))) return rc;
+    }
     if ((rc = cnnc_eval_stage(c, 2, stream))) return rc;
     if ((rc = cnnc_compact_survivors(c, 2, c->params.thr[1], stream))) return rc;
     if ((rc = cnnc_eval_stage(c, 3, stream))) return rc;

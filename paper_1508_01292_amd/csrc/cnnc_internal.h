@@ -39,6 +39,8 @@ struct LevelDev {
     int32_t ymap_off;      // first entry of the level's row table
     int64_t scale_q16;     // round(scale * 65536)
     double scale;          // scale of the level (frame pixels per level pixel)
+    int32_t word_off;      // first word of the level in the survivor bit mask (rows padded to 32 windows)
+    int32_t words_per_row; // ceil(ow / 32)
 };
 
 // Small device-resident counters.
@@ -108,7 +110,10 @@ struct cnnc_ctx {
     uint32_t *d_tiles_s1 = nullptr;  // (level, tile) table of the stage-1 kernel
     uint8_t *d_pyr = nullptr;
     float *d_score1 = nullptr;
-    int64_t cap_pyr = 0, cap_score1 = 0, cap_taps = 0, cap_tiles_pyr = 0, cap_tiles_s1 = 0;
+    uint32_t *d_mask1 = nullptr;     // stage-1 survivor bits of the fused path, one word per 32 windows of a row
+    int64_t cap_pyr = 0, cap_score1 = 0, cap_taps = 0, cap_tiles_pyr = 0, cap_tiles_s1 = 0, cap_mask1 = 0;
+    int64_t n_words = 0;
+    bool fused_stage1 = false;       // cnnc_detect uses cnnc_stage1_survivors instead of score map + compaction
 
     // survivor lists (capacity max_surv each)
     uint32_t *d_idx[3] = {nullptr, nullptr, nullptr};
@@ -140,6 +145,11 @@ namespace cnnc {
 // Kernel launchers (one translation unit each).  All enqueue on `st` and return the launch status.
 hipError_t launch_pyramid(const cnnc_ctx *c, hipStream_t st);
 hipError_t launch_stage1(const cnnc_ctx *c, hipStream_t st);
+// Stage 1 that keeps only what passes `thr`: one bit per window in d_mask1 and the score of each passing window
+// at its place in d_score1 (all other entries of d_score1 are left as they were).
+hipError_t launch_stage1_emit(const cnnc_ctx *c, float thr, hipStream_t st);
+// Ordered survivor list from d_mask1 / d_score1.
+hipError_t launch_compact_mask(const cnnc_ctx *c, uint32_t *out_idx, float *out_sc, int32_t *d_count, hipStream_t st);
 // Compaction of `vals[0 .. n)`; n = *d_n clamped to n_max if d_n != nullptr, else n_literal.
 // src_idx == nullptr: the position itself is the index written.
 hipError_t launch_compact(const cnnc_ctx *c, const float *vals, const uint32_t *src_idx, const int32_t *d_n,

@@ -116,6 +116,69 @@ void compact_scatter_kernel(const float *__restrict__ vals, const uint32_t *__re
     }
 }
 
+// ---- the same list from the bit mask the fused stage-1 kernel leaves: one thread per mask word ------------
+__global__ __launch_bounds__(kCompactBlock)
+void mask_count_kernel(const uint32_t *__restrict__ mask, int n_words, int32_t *__restrict__ blockcnt)
+{
+    __shared__ int wsum[kWaves];
+    const int w = blockIdx.x * kCompactBlock + threadIdx.x;
+    int cnt = w < n_words ? __popc(mask[w]) : 0;
+    for (int d = 32; d >= 1; d >>= 1) cnt += __shfl_xor(cnt, d, 64);
+    if (threadIdx.x % 64 == 0) wsum[threadIdx.x / 64] = cnt;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int s = 0;
+        for (int k = 0; k < kWaves; ++k) s += wsum[k];
+        blockcnt[blockIdx.x] = s;
+    }
+}
+
+__global__ __launch_bounds__(kCompactBlock)
+void mask_scatter_kernel(const uint32_t *__restrict__ mask, int n_words, const float *__restrict__ score,
+                         const LevelDev *__restrict__ levels, int n_levels, const int32_t *__restrict__ blockoff,
+                         uint32_t *__restrict__ out_idx, float *__restrict__ out_sc, int cap)
+{
+    __shared__ int wsum[kWaves];
+    const int w = blockIdx.x * kCompactBlock + threadIdx.x, wave = threadIdx.x / 64, lane = threadIdx.x % 64;
+    uint32_t m = w < n_words ? mask[w] : 0u;
+    const int cnt = __popc(m);
+    int incl = cnt;
+    for (int d = 1; d < 64; d <<= 1) {
+        const int o = __shfl_up(incl, d, 64);
+        if (lane >= d) incl += o;
+    }
+    if (lane == 63) wsum[wave] = incl;
+    __syncthreads();
+    int pos = blockoff[blockIdx.x] + incl - cnt;
+    for (int k = 0; k < wave; ++k) pos += wsum[k];
+    if (m == 0u) return;
+    // word -> first window of its 32-window run: level, row, run within the row
+    int l = 0;
+    while (l + 1 < n_levels && w >= levels[l + 1].word_off) ++l;
+    const int rel = w - levels[l].word_off, wpr = levels[l].words_per_row;
+    const uint32_t g0 = (uint32_t)levels[l].score_off + (uint32_t)(rel / wpr) * (uint32_t)levels[l].ow + 32u * (uint32_t)(rel % wpr);
+    while (m) {
+        const int b = __ffs(m) - 1;
+        m &= m - 1;
+        if (pos < cap) {
+            out_idx[pos] = g0 + b;
+            out_sc[pos] = score[g0 + b];
+        }
+        ++pos;
+    }
+}
+
+hipError_t launch_compact_mask(const cnnc_ctx *c, uint32_t *out_idx, float *out_sc, int32_t *d_count, hipStream_t st)
+{
+    const int n_words = (int)c->n_words;
+    const int nblocks = (n_words + kCompactBlock - 1) / kCompactBlock;
+    hipLaunchKernelGGL(mask_count_kernel, dim3(nblocks), dim3(kCompactBlock), 0, st, c->d_mask1, n_words, c->d_blockcnt);
+    hipLaunchKernelGGL(compact_scan_kernel, dim3(1), dim3(1024), 0, st, c->d_blockcnt, nblocks, d_count);
+    hipLaunchKernelGGL(mask_scatter_kernel, dim3(nblocks), dim3(kCompactBlock), 0, st, c->d_mask1, n_words, c->d_score1,
+                       c->d_levels, c->n_levels, c->d_blockcnt, out_idx, out_sc, c->max_surv);
+    return hipGetLastError();
+}
+
 hipError_t launch_compact(const cnnc_ctx *c, const float *vals, const uint32_t *src_idx, const int32_t *d_n,
                           int64_t n_literal, float thr, uint32_t *out_idx, float *out_sc, int32_t *d_count,
                           hipStream_t st)

@@ -41,11 +41,14 @@ __device__ __forceinline__ f6 load6(const float *p)
 }
 }  // namespace
 
-template <int ACT>
+// EMIT = false: every score goes to the score map.  EMIT = true: only windows with score > thr leave the kernel,
+// as one bit per window (a word per 32-window row of the tile, so each word has one writer and needs no clearing)
+// plus the score at the window's place in the map.
+template <int ACT, bool EMIT>
 __global__ __launch_bounds__(kThreads)
 void stage1_kernel(const uint8_t *__restrict__ pyr, const LevelDev *__restrict__ levels,
                    const uint32_t *__restrict__ tiles, const float *__restrict__ wt,
-                   float *__restrict__ score)
+                   float *__restrict__ score, float thr, uint32_t *__restrict__ mask)
 {
     // 40 KiB: four workgroups share a compute unit's LDS.  sM sits first so that the two floats some lanes
     // read past its end (feeding only discarded columns) fall inside the same array.
@@ -174,31 +177,56 @@ void stage1_kernel(const uint8_t *__restrict__ pyr, const LevelDev *__restrict__
 #pragma unroll
         for (int p = 0; p < 4; ++p) acc[p] += __shfl_xor(acc[p], 1, 64);
         const int y = oy + r;
-        if (y < L.oh) {
-            float *row = score + (size_t)L.score_off + (size_t)y * L.ow;
-            const float b3 = wt[s1::B3];
+        float *row = score + (size_t)L.score_off + (size_t)y * L.ow;
+        const float b3 = wt[s1::B3];
+        uint32_t bits = 0;                       // EMIT: this thread's two windows of the row's 32-bit word
 #pragma unroll
-            for (int q = 0; q < 2; ++q) {            // this thread writes two of the unit's four outputs
-                const int p = 2 * half + q, x = ox + 2 * (j0 + p) + px;
-                if (x < L.ow) row[x] = (half ? (q ? acc[3] : acc[2]) : (q ? acc[1] : acc[0])) + b3;
+        for (int q = 0; q < 2; ++q) {            // this thread writes two of the unit's four outputs
+            const int p = 2 * half + q, x = ox + 2 * (j0 + p) + px;
+            const float sc = (half ? (q ? acc[3] : acc[2]) : (q ? acc[1] : acc[0])) + b3;
+            if (y < L.oh && x < L.ow) {
+                if (!EMIT) {
+                    row[x] = sc;
+                } else if (sc > thr) {
+                    row[x] = sc;
+                    bits |= 1u << (x - ox);
+                }
             }
+        }
+        if (EMIT) {
+            // a row of the tile belongs to sixteen consecutive lanes: OR their bits, one of them stores the word
+#pragma unroll
+            for (int d = 1; d < 16; d <<= 1) bits |= __shfl_xor(bits, d, 64);
+            if ((tid & 15) == 0 && y < L.oh) mask[L.word_off + y * L.words_per_row + ox / TW] = bits;
         }
     }
 }
 
+#define CNNC_S1(ACT, EMIT, THR, MASK)                                                                        \
+    hipLaunchKernelGGL((stage1_kernel<ACT, EMIT>), grid, block, 0, st, c->d_pyr, c->d_levels, c->d_tiles_s1, \
+                       c->d_wt[0], c->d_score1, THR, MASK)
+
 hipError_t launch_stage1(const cnnc_ctx *c, hipStream_t st)
 {
     dim3 grid(c->n_tiles_s1), block(kThreads);
-#define CNNC_S1(ACT)                                                                              \
-    hipLaunchKernelGGL(stage1_kernel<ACT>, grid, block, 0, st, c->d_pyr, c->d_levels, c->d_tiles_s1, \
-                       c->d_wt[0], c->d_score1)
     switch (c->act) {
-    case CNNC_ACT_RATIONAL: CNNC_S1(CNNC_ACT_RATIONAL); break;
-    case CNNC_ACT_SCALED_TANH: CNNC_S1(CNNC_ACT_SCALED_TANH); break;
-    default: CNNC_S1(CNNC_ACT_TANH); break;
+    case CNNC_ACT_RATIONAL: CNNC_S1(CNNC_ACT_RATIONAL, false, 0.0f, (uint32_t *)nullptr); break;
+    case CNNC_ACT_SCALED_TANH: CNNC_S1(CNNC_ACT_SCALED_TANH, false, 0.0f, (uint32_t *)nullptr); break;
+    default: CNNC_S1(CNNC_ACT_TANH, false, 0.0f, (uint32_t *)nullptr); break;
     }
-#undef CNNC_S1
     return hipGetLastError();
 }
+
+hipError_t launch_stage1_emit(const cnnc_ctx *c, float thr, hipStream_t st)
+{
+    dim3 grid(c->n_tiles_s1), block(kThreads);
+    switch (c->act) {
+    case CNNC_ACT_RATIONAL: CNNC_S1(CNNC_ACT_RATIONAL, true, thr, c->d_mask1); break;
+    case CNNC_ACT_SCALED_TANH: CNNC_S1(CNNC_ACT_SCALED_TANH, true, thr, c->d_mask1); break;
+    default: CNNC_S1(CNNC_ACT_TANH, true, thr, c->d_mask1); break;
+    }
+    return hipGetLastError();
+}
+#undef CNNC_S1
 
 }  // namespace cnnc
