@@ -201,6 +201,36 @@ def main():
     except Exception as e:       # a probe failure must not lose the benchmark line
         roof["sustained_on_this_gpu"] = {"error": str(e)}
 
+    # frames from pinned host memory through the ingest ring: copy in + path + results out, PCIe included
+    ingest = {}
+    D = F + 1                                    # one slot more than frames computing: its copy runs ahead
+    for use_graph in (False, True):
+        pipe = P.Pipe(casc, W, cfg["width"], cfg["height"], 262144, depth=D, use_graph=use_graph)
+        pipe.set_params(cfg["min_face"], cfg["scale_step"], tr.thr)
+        for j in range(D):                       # the producer's frames sit in the pinned buffers already
+            pipe.frame_buffer()[:] = frames[j % len(frames)]
+            pipe.fetch(pipe.submit(), 8192)
+
+        def run_pipe(n_steps):
+            q = []
+            for _ in range(n_steps):
+                if len(q) == D:
+                    pipe.fetch(q.pop(0), 8192)
+                q.append(pipe.submit())
+            n = 0
+            for t in q:
+                n = len(pipe.fetch(t, 8192))
+            return n
+
+        run_pipe(a.warmup)
+        t0 = time.perf_counter()
+        n_det_pipe = run_pipe(a.steps)
+        dt = time.perf_counter() - t0
+        ingest["graph" if use_graph else "eager"] = {"frames_per_s": a.steps / dt, "detections": n_det_pipe,
+                                                     "h2d_gb_per_s": a.steps / dt * cfg["width"] * cfg["height"] / 1e9}
+        pipe.close()
+    ingest["depth"] = D
+
     out = {
         "metric": METRIC, "value": fps, "unit": "frames/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
         "ms_per_step": elapsed / a.steps * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
@@ -216,6 +246,7 @@ def main():
                                   "bound": "alu", "achieved": tflops(SCAN_FLOP_PER_POSITION * n_scan, ms_scan),
                                   "peak": PEAK_FP32_VECTOR, "unit": "TFLOP/s",
                                   "frac": tflops(SCAN_FLOP_PER_POSITION * n_scan, ms_scan) / PEAK_FP32_VECTOR},
+        "ingest_from_pinned_host_memory": ingest,
         "sum_of_kernel_ms": sum(v for k, v in ms.items() if not k.endswith("_conv") and k != "scan"),
         "roofline": roof,
         "kernels": kernels,

@@ -216,6 +216,31 @@ int cnnc_scan_layout(cnnc_ctx *ctx, int w, int h, int *n_levels, int32_t *out_w,
 int cnnc_scan_scoremap(cnnc_ctx *ctx, void *stream);
 int cnnc_get_scan_scoremap(cnnc_ctx *ctx, const float **d_scores, int64_t *n);
 
+/* ---- Frame ingest from host memory ------------------------------------------------------------
+ * The paper's detector is fed video (Section 4.2) and overlaps its stages (Section 3.4, asynchronous mode).
+ * A pipe is a ring of `depth` slots (1..16); each slot owns a context, a HIP stream, a pinned host frame
+ * (w * h bytes, row pitch w) and a device frame, so the host-to-device copy of one frame overlaps the kernels of
+ * the others.  use_graph != 0: from a slot's second frame on, its copy + kernels + read-back run as one captured
+ * HIP graph launch.  All frames of a pipe have the size given at creation.  One thread per pipe.
+ *
+ * cnnc_pipe_frame_buffer: the pinned buffer the next submit will send, for producers that write frames in place
+ *   (CNNC_E_STATE while that slot's previous frame has not been fetched).
+ * cnnc_pipe_submit: h_frame = NULL or the pointer from cnnc_pipe_frame_buffer: send the buffer as it is; any other
+ *   host pointer: its w x h bytes (row pitch `pitch`) are copied into the buffer first.  Enqueues and returns a
+ *   ticket; CNNC_E_STATE when every slot is in flight.
+ * cnnc_pipe_fetch: waits for the frame with that ticket and returns its detections like cnnc_detect
+ *   (CNNC_E_OVERFLOW rules included); frees the slot.  Tickets may be fetched in any order.
+ * cnnc_pipe_set_params: for every slot; CNNC_E_STATE while frames are in flight. */
+typedef struct cnnc_pipe cnnc_pipe;
+int cnnc_pipe_create(cnnc_pipe **out, const cnnc_stage_desc stages[3], int w, int h, int max_survivors, int depth,
+                     int use_graph);
+int cnnc_pipe_destroy(cnnc_pipe *pipe);
+int cnnc_pipe_set_params(cnnc_pipe *pipe, const cnnc_params *p);
+int cnnc_pipe_frame_buffer(cnnc_pipe *pipe, uint8_t **h_frame);
+int cnnc_pipe_submit(cnnc_pipe *pipe, const uint8_t *h_frame, int pitch, int64_t *ticket);
+int cnnc_pipe_fetch(cnnc_pipe *pipe, int64_t ticket, cnnc_det *out, int cap, int *n_out);
+const char *cnnc_pipe_last_error(const cnnc_pipe *pipe);
+
 /* Measurement aid for benchmarks: what this GPU sustains on three synthetic probes (dense fp32 MFMA loop,
  * fp32 FMA loop on the vector ALU, 1 GiB device-to-device copy counted as read + write).  Runs on the
  * current device's default stream, allocates and frees 2 GiB, synchronises.  Outputs are host pointers. */

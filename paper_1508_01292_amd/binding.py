@@ -21,6 +21,8 @@ EXPORTS = [
     "cnnc_get_timings", "cnnc_set_eval_impl", "cnnc_measure_peaks", "cnnc_last_error", "cnnc_version",
     "cnnc_stage1_survivors", "cnnc_set_fused_stage1",
     "cnnc_scan_set_weights", "cnnc_scan_layout", "cnnc_scan_scoremap", "cnnc_get_scan_scoremap",
+    "cnnc_pipe_create", "cnnc_pipe_destroy", "cnnc_pipe_set_params", "cnnc_pipe_frame_buffer", "cnnc_pipe_submit",
+    "cnnc_pipe_fetch", "cnnc_pipe_last_error",
 ]
 STEP_NAMES = ["pyramid", "stage1", "compact1", "stage2", "compact2", "stage3", "compact3", "merge",
               "stage2_conv", "stage3_conv", "scan"]
@@ -76,6 +78,8 @@ def lib():
         L.cnnc_last_error.restype = C.c_char_p
         L.cnnc_last_error.argtypes = [C.c_void_p]
         L.cnnc_version.restype = C.c_char_p
+        L.cnnc_pipe_last_error.restype = C.c_char_p
+        L.cnnc_pipe_last_error.argtypes = [C.c_void_p]
         _lib = L
     return _lib
 
@@ -109,14 +113,7 @@ class Context:
                  max_survivors: int):
         self._h = C.c_void_p(0)
         self._keep = []
-        descs = (_StageDesc * 3)()
-        for s, (st, wt) in enumerate(zip(cascade, weights)):
-            layers = (_Layer * len(st.layers))(*[_Layer(l.kind, l.cin, l.cout, l.k, l.act) for l in st.layers])
-            w = np.ascontiguousarray(wt, np.float32)
-            if w.size != st.n_params:
-                raise ValueError("weight blob of stage %d has %d values, expected %d" % (s + 1, w.size, st.n_params))
-            self._keep += [layers, w]
-            descs[s] = _StageDesc(st.in_size, len(st.layers), layers, w.ctypes.data_as(C.POINTER(C.c_float)))
+        descs = _stage_descs(cascade, weights, self._keep)
         rc = lib().cnnc_create(C.byref(self._h), descs, C.c_int(max_w), C.c_int(max_h), C.c_int(max_survivors))
         if rc != 0:
             self._h = C.c_void_p(0)
@@ -274,6 +271,75 @@ class Context:
         calls = (C.c_int32 * len(STEP_NAMES))()
         self._check(lib().cnnc_get_timings(self._h, ms, calls))
         return {n: (ms[i], calls[i]) for i, n in enumerate(STEP_NAMES)}
+
+
+def _stage_descs(cascade, weights, keep):
+    descs = (_StageDesc * 3)()
+    for s, (st, wt) in enumerate(zip(cascade, weights)):
+        layers = (_Layer * len(st.layers))(*[_Layer(l.kind, l.cin, l.cout, l.k, l.act) for l in st.layers])
+        w = np.ascontiguousarray(wt, np.float32)
+        if w.size != st.n_params:
+            raise ValueError("weight blob of stage %d has %d values, expected %d" % (s + 1, w.size, st.n_params))
+        keep += [layers, w]
+        descs[s] = _StageDesc(st.in_size, len(st.layers), layers, w.ctypes.data_as(C.POINTER(C.c_float)))
+    return descs
+
+
+class Pipe:
+    """Frame ingest ring (cnnc_pipe): host frames in, detections out, copies and kernels of several frames overlapped."""
+
+    def __init__(self, cascade, weights, w: int, h: int, max_survivors: int, depth: int = 3, use_graph: bool = True):
+        self._h = C.c_void_p(0)
+        self._keep = []
+        self.w, self.h, self.depth = w, h, depth
+        rc = lib().cnnc_pipe_create(C.byref(self._h), _stage_descs(cascade, weights, self._keep), C.c_int(w), C.c_int(h),
+                                    C.c_int(max_survivors), C.c_int(depth), C.c_int(1 if use_graph else 0))
+        if rc != 0:
+            self._h = C.c_void_p(0)
+            raise CnncError(rc, "cnnc_pipe_create failed")
+
+    def _check(self, rc: int):
+        if rc != 0:
+            raise CnncError(rc, (lib().cnnc_pipe_last_error(self._h) or b"").decode())
+
+    def close(self):
+        if self._h:
+            lib().cnnc_pipe_destroy(self._h)
+            self._h = C.c_void_p(0)
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def set_params(self, min_face: float, scale_step: float, thr=(0.0, 0.0, 0.0), merge_iou: float = 0.3,
+                   min_neighbors: int = 1):
+        p = _Params(min_face, scale_step, (C.c_float * 3)(*[float(t) for t in thr]), merge_iou, min_neighbors)
+        self._check(lib().cnnc_pipe_set_params(self._h, C.byref(p)))
+
+    def frame_buffer(self) -> np.ndarray:
+        """The pinned h x w uint8 buffer that the next submit() sends (a view, valid until that frame is fetched)."""
+        p = C.c_void_p(0)
+        self._check(lib().cnnc_pipe_frame_buffer(self._h, C.byref(p)))
+        return np.ctypeslib.as_array(C.cast(p, C.POINTER(C.c_uint8)), shape=(self.h, self.w))
+
+    def submit(self, frame: Optional[np.ndarray] = None) -> int:
+        """frame = None: send the buffer last returned by frame_buffer(); else a host uint8 h x w array."""
+        t = C.c_int64(0)
+        if frame is None:
+            self._check(lib().cnnc_pipe_submit(self._h, C.c_void_p(0), C.c_int(self.w), C.byref(t)))
+        else:
+            if frame.dtype != np.uint8 or frame.ndim != 2 or frame.shape != (self.h, self.w) or frame.strides[1] != 1:
+                raise ValueError("frame must be a host uint8 array of the pipe's size with unit column stride")
+            self._check(lib().cnnc_pipe_submit(self._h, frame.ctypes.data_as(C.c_void_p), C.c_int(frame.strides[0]), C.byref(t)))
+        return t.value
+
+    def fetch(self, ticket: int, cap: int = 4096) -> List[Detection]:
+        out = (Detection * cap)()
+        n = C.c_int(0)
+        self._check(lib().cnnc_pipe_fetch(self._h, C.c_int64(ticket), out, C.c_int(cap), C.byref(n)))
+        return list(out[:n.value])
 
 
 def cnnc_measure_peaks():

@@ -1,0 +1,113 @@
+"""GPU tests of the frame ingest ring (cnnc_pipe): host frames in, detections out.  Every frame's detections are
+compared with the oracle's and with the library's own single-context path, with and without captured graphs; each
+slot's graph is replayed several times on different frames with eager work of other slots in between."""
+import numpy as np
+import pytest
+
+import cnnc_inputs as I
+from oracle import oracle as O
+
+pytestmark = pytest.mark.gpu
+
+
+def _stream_case():
+    ci = 4                                            # the 16-frame 1920x1080 stream
+    cfg = I.CONFIGS[ci]
+    frames = I.make_stream(ci)[:8]
+    casc = I.default_cascade()
+    W = I.draw_weights(casc, I.config_seed(ci))
+    # thresholds at the quantiles of the first frame; the other frames simply use them
+    tr0 = O.detect(frames[0], casc, W, cfg["min_face"], cfg["scale_step"])
+    return cfg, frames, casc, W, tr0
+
+
+@pytest.mark.parametrize("use_graph", [False, True])
+def test_pipe_matches_single_context_and_oracle(use_graph):
+    import torch
+    import paper_1508_01292_amd as P
+    cfg, frames, casc, W, tr0 = _stream_case()
+    w, h = cfg["width"], cfg["height"]
+    ctx = P.Context(casc, W, w, h, 100000)
+    ctx.set_params(cfg["min_face"], cfg["scale_step"], tr0.thr)
+    want = [[d.as_dict() for d in ctx.detect(torch.from_numpy(f).cuda(), 8192)] for f in frames]
+    assert [(d["index"], d["neighbors"]) for d in want[0]] == [(d["index"], d["neighbors"]) for d in tr0.det]
+    # one more frame straight against the oracle, at the same thresholds
+    tr5 = O.detect(frames[5], casc, W, cfg["min_face"], cfg["scale_step"], thr=tr0.thr)
+    assert [(d["index"], d["neighbors"]) for d in want[5]] == [(d["index"], d["neighbors"]) for d in tr5.det]
+
+    pipe = P.Pipe(casc, W, w, h, 100000, depth=3, use_graph=use_graph)
+    pipe.set_params(cfg["min_face"], cfg["scale_step"], tr0.thr)
+    print("pipe graph=%s: 3 slots, 3 passes over %d frames" % (use_graph, len(frames)), flush=True)
+    got = {}
+    tickets = []
+    order = list(range(len(frames))) + list(reversed(range(len(frames)))) + list(range(len(frames)))
+    for k, fi in enumerate(order):
+        if len(tickets) == 3:
+            t, f0 = tickets.pop(0)
+            got.setdefault(f0, []).append([d.as_dict() for d in pipe.fetch(t, 8192)])
+        if k % 2:
+            buf = pipe.frame_buffer()                 # producer writes in place
+            buf[:] = frames[fi]
+            tickets.append((pipe.submit(), fi))
+        else:
+            tickets.append((pipe.submit(frames[fi]), fi))
+        if k % 5 == 0:                                # eager work of another context between the replays
+            ctx.detect(torch.from_numpy(frames[(fi + 1) % len(frames)]).cuda(), 8192)
+            torch.cuda.synchronize()
+    for t, f0 in tickets:
+        got.setdefault(f0, []).append([d.as_dict() for d in pipe.fetch(t, 8192)])
+    for fi in range(len(frames)):
+        assert len(got[fi]) == 3
+        for rep in got[fi]:
+            assert rep == want[fi], "frame %d" % fi
+    pipe.close()
+    ctx.close()
+
+
+def test_pipe_errors_and_parameter_change():
+    import paper_1508_01292_amd as P
+    casc = I.default_cascade()
+    W = I.draw_weights(casc, 2)
+    frame = I.make_frame(320, 240, 2)
+    tr = O.detect(frame, casc, W, 24.0, 1.25)
+    with pytest.raises(P.CnncError):
+        P.Pipe(casc, W, 320, 240, 1000, depth=0)
+    with pytest.raises(P.CnncError):
+        P.Pipe(casc, W, 320, 240, 1000, depth=17)
+    pipe = P.Pipe(casc, W, 320, 240, 20000, depth=2, use_graph=True)
+    pipe.set_params(24.0, 1.25, tr.thr)
+    with pytest.raises(ValueError):
+        pipe.submit(frame[:-1])
+    t0 = pipe.submit(frame)
+    t1 = pipe.submit(frame)
+    with pytest.raises(P.CnncError) as e:             # ring full
+        pipe.submit(frame)
+    assert e.value.code == -5
+    with pytest.raises(P.CnncError) as e:
+        pipe.frame_buffer()
+    assert e.value.code == -5
+    with pytest.raises(P.CnncError) as e:             # parameters while frames are in flight
+        pipe.set_params(24.0, 1.25, tr.thr)
+    assert e.value.code == -5
+    with pytest.raises(P.CnncError) as e:             # unknown ticket
+        pipe.fetch(99)
+    assert e.value.code == -1
+    a = [d.as_dict() for d in pipe.fetch(t1)]         # any order
+    b = [d.as_dict() for d in pipe.fetch(t0)]
+    assert a == b and [(d["index"], d["neighbors"]) for d in a] == [(d["index"], d["neighbors"]) for d in tr.det]
+    with pytest.raises(P.CnncError):                  # already fetched
+        pipe.fetch(t0)
+    # graphs captured so far are dropped when the thresholds change; results follow the new parameters
+    for _ in range(4):
+        assert [d.as_dict() for d in pipe.fetch(pipe.submit(frame))] == a
+    tr2 = O.detect(frame, casc, W, 24.0, 1.25, quantiles=(0.05, 0.5))
+    pipe.set_params(24.0, 1.25, tr2.thr)
+    for _ in range(4):
+        got = [d.as_dict() for d in pipe.fetch(pipe.submit(frame))]
+        assert [(d["index"], d["neighbors"]) for d in got] == [(d["index"], d["neighbors"]) for d in tr2.det]
+    # a detection array that is too small reports the overflow and the slot is free again
+    with pytest.raises(P.CnncError) as e:
+        pipe.fetch(pipe.submit(frame), cap=1)
+    assert e.value.code == -3
+    assert len(pipe.fetch(pipe.submit(frame))) == len(tr2.det)
+    pipe.close()
