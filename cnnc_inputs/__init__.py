@@ -7,11 +7,12 @@ the CPU oracle's tests and the HIP library's tests import.
 """
 from .cascade import (ACT_NONE, ACT_RATIONAL, ACT_SCALED_TANH, ACT_TANH, CONV,
                       FC, POOL, Layer, RLayer, ScanNet, Stage, default_cascade,
-                      draw_scan_weights, draw_weights, paper_stage1, uniform_weights)
+                      draw_scan_weights, draw_weights, paper_stage1, paper_stage2, paper_stage3,
+                      uniform_weights, REGION_W, REGION_H, REGION_MARGIN)
 from .frames import CONFIGS, config_seed, make_frame, make_stream
 
 __all__ = [
     "ACT_NONE", "ACT_RATIONAL", "ACT_SCALED_TANH", "ACT_TANH", "CONV", "FC",
     "POOL", "Layer", "Stage", "default_cascade", "draw_weights",
-    "uniform_weights", "RLayer", "ScanNet", "paper_stage1", "draw_scan_weights", "CONFIGS", "config_seed", "make_frame", "make_stream",
+    "uniform_weights", "RLayer", "ScanNet", "paper_stage1", "paper_stage2", "paper_stage3", "REGION_W", "REGION_H", "REGION_MARGIN", "draw_scan_weights", "CONFIGS", "config_seed", "make_frame", "make_stream",
 ]

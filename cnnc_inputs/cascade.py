@@ -195,3 +195,26 @@ def draw_scan_weights(net: ScanNet, seed: int, bias_sd: float = 0.0) -> np.ndarr
         b = brng.standard_normal(l.cout) * bias_sd if bias_sd > 0 else np.zeros(l.cout)
         parts += [w.astype(np.float32), b.astype(np.float32)]
     return np.concatenate(parts)
+
+
+# The selective unit's networks in the paper's geometry (Section 3.3: the analysed region is scaled to 51 x 55
+# and each of CNN_2, CNN_3 gives a 5 x 5 response map).  Chosen: a 35 x 39 window scanned with the 4 pixel step
+# of two pools, (51 - 35) / 4 + 1 = 5, with the same layer pattern as the first network:
+#   conv 4x4 1->c1, pool 2, conv 3x3 c1->c2, pool 2, conv 7x8 (w x h) c2->1
+# CNN_2: c1, c2 = 4, 19 (1,836 parameters; the paper: 1,819).  CNN_3: 5, 28 (2,942; the paper: 2,923).
+REGION_W, REGION_H, REGION_MARGIN = 51, 55, 12
+
+
+def _region_net(c1: int, c2: int, act: int) -> ScanNet:
+    return ScanNet(35, 39, 4, (
+        RLayer(CONV, 1, c1, 4, 4, act), RLayer(POOL, c1, c1, 2, 2, ACT_NONE),
+        RLayer(CONV, c1, c2, 3, 3, act), RLayer(POOL, c2, c2, 2, 2, ACT_NONE),
+        RLayer(CONV, c2, 1, 7, 8, ACT_NONE)))
+
+
+def paper_stage2(act: int = ACT_RATIONAL) -> ScanNet:
+    return _region_net(4, 19, act)
+
+
+def paper_stage3(act: int = ACT_RATIONAL) -> ScanNet:
+    return _region_net(5, 28, act)

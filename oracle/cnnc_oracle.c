@@ -23,7 +23,10 @@
  * special cases; for the first stage in the paper's own geometry (end of
  * this file): library convolution on windows and whole levels, a
  * hand-computed one-hot window, definition vs single pass, translation by
- * one step.  The choice of the readings themselves (resampling
+ * one step; for the selective unit in that geometry: exact special cases and
+ * library bilinear for the region, closed forms of histogram equalisation,
+ * library convolution for the mirrored response maps, the truth table of
+ * eq. (2).  The choice of the readings themselves (resampling
  * convention, crop rectangle, merge rule) cannot be pinned to the authors'
  * detector: parity unpinned for those choices.
  */
@@ -624,5 +627,109 @@ int orc_scan_fcn(const uint8_t *level, int lw, int lh, const orc_rlayer *layers,
     if (rc == 0)
         for (int y = 0; y < oh; ++y) memcpy(scores + (size_t)y * ow, cur + (size_t)y * W, sizeof(double) * (size_t)ow);
     free(cur);
+    return rc;
+}
+
+/* ======================================================================== */
+/* The selective unit in the paper's geometry (paper, Section 3.3, second to */
+/* fourth paragraph, eq. (2)).                                                */
+/* ======================================================================== */
+
+/* Region of rw x rh level pixels whose corner is (x0, y0) in level           */
+/* coordinates (may lie outside the level: the frame edge is repeated), read  */
+/* from the original frame.  Paper: the analysed region is read from the      */
+/* original image together with a neighbourhood and scaled to 51 x 55.        */
+/* Reading: sample i sits at frame position (x0 + i + 0.5) s - 0.5 in 16.16   */
+/* fixed point with S = round(s * 65536), weights of 8 bits, and the pixel    */
+/* is rounded to uint8 (it feeds a histogram).                                */
+void orc_region(const uint8_t *frame, int w, int h, int pitch, int x0, int y0, double s, int rw, int rh,
+                uint8_t *out)
+{
+    const int64_t S = (int64_t)floor(s * 65536.0 + 0.5);
+    int32_t *xi = malloc(sizeof(int32_t) * 2 * (size_t)(rw + rh));
+    int32_t *xq = xi + rw, *yi = xq + rw, *yq = yi + rh;
+    for (int k = 0; k < rw + rh; ++k) {
+        const int is_y = k >= rw, i = is_y ? k - rw : k, n_in = is_y ? h : w;
+        int64_t P = (int64_t)(is_y ? y0 : x0) * S + ((int64_t)(2 * i + 1) * S) / 2 - 32768;
+        const int64_t hi = (int64_t)(n_in - 1) << 16;
+        if (P < 0) P = 0;
+        if (P > hi) P = hi;
+        (is_y ? yi : xi)[i] = (int32_t)(P >> 16);
+        (is_y ? yq : xq)[i] = (int32_t)(((P & 0xFFFF) + 128) >> 8);
+    }
+    for (int r = 0; r < rh; ++r)
+        for (int c = 0; c < rw; ++c) {
+            const int xa = xi[c], xb = xa + 1 < w ? xa + 1 : w - 1, ya = yi[r], yb = ya + 1 < h ? ya + 1 : h - 1;
+            const uint32_t qx = (uint32_t)xq[c], qy = (uint32_t)yq[r];
+            const uint32_t sum = frame[(size_t)ya * pitch + xa] * (256u - qx) * (256u - qy) + frame[(size_t)ya * pitch + xb] * qx * (256u - qy)
+                               + frame[(size_t)yb * pitch + xa] * (256u - qx) * qy + frame[(size_t)yb * pitch + xb] * qx * qy;
+            out[(size_t)r * rw + c] = (uint8_t)((sum + 32768u) >> 16);
+        }
+    free(xi);
+}
+
+/* Histogram equalisation of n uint8 values in place (paper, Section 3.3:     */
+/* the region's histogram is equalised).  The textbook rule: with cdf(v) =    */
+/* number of pixels <= v and c0 = cdf of the smallest value present,          */
+/* v -> round((cdf(v) - c0) * 255 / (n - c0)); a constant region (n == c0)    */
+/* is left as it is.  Integer arithmetic, ties of the rounding go up.         */
+void orc_histeq(uint8_t *img, int n)
+{
+    int64_t hist[256] = {0}, cdf = 0, c0 = -1;
+    uint8_t lut[256];
+    for (int i = 0; i < n; ++i) ++hist[img[i]];
+    for (int v = 0; v < 256; ++v) {
+        cdf += hist[v];
+        if (c0 < 0 && hist[v] > 0) c0 = cdf;
+        lut[v] = (uint8_t)v;
+        if (c0 >= 0 && n > c0) lut[v] = (uint8_t)((2 * (cdf - c0) * 255 + (n - c0)) / (2 * (n - c0)));
+    }
+    for (int i = 0; i < n; ++i) img[i] = lut[img[i]];
+}
+
+/* One region through the unit.  The equalised region and its mirror image    */
+/* (reflection about the vertical axis) go through CNN_2; response (v, u) of  */
+/* the region and response (v, nw - 1 - u) of the mirror belong to the same   */
+/* window.  Reading (the paper does not say how the two are combined): their  */
+/* mean.  K2 = number of combined responses > t2 (fp32, strict).  If K2 = 0   */
+/* the analysis stops (paper: "further analysis of the region stops"), else   */
+/* CNN_3 gives K3 the same way with t3, and eq. (2) decides:                  */
+/*   face = (K2 >= t_nn and K3 > 0) or (K2 > 0 and K3 >= t_nn).               */
+/* r2, r3: the combined response maps (nh x nw doubles each; r3 is zero when  */
+/* CNN_3 was not run).  Returns 0, -1 if a network does not fit the region.   */
+int orc_select_region(const uint8_t *region, int rw, int rh,
+                      const orc_rlayer *l2, int n2, const float *w2, const orc_rlayer *l3, int n3, const float *w3,
+                      int win_w, int win_h, float t2, float t3, int t_nn,
+                      int32_t *k2, int32_t *k3, int32_t *face, double *r2, double *r3)
+{
+    int step = 1;
+    for (int i = 0; i < n2; ++i) if (l2[i].kind == ORC_POOL) step *= 2;
+    const int nw = (rw - win_w) / step + 1, nh = (rh - win_h) / step + 1;
+    uint8_t *mir = malloc((size_t)rw * rh);
+    double *a = malloc(sizeof(double) * 2 * (size_t)nw * nh), *b = a + (size_t)nw * nh;
+    for (int y = 0; y < rh; ++y)
+        for (int x = 0; x < rw; ++x) mir[(size_t)y * rw + x] = region[(size_t)y * rw + (rw - 1 - x)];
+    int rc = 0;
+    *k2 = *k3 = *face = 0;
+    for (int i = 0; i < nw * nh; ++i) r2[i] = r3[i] = 0.0;
+    if (orc_scan_fcn(region, rw, rh, l2, n2, w2, win_w, win_h, a) || orc_scan_fcn(mir, rw, rh, l2, n2, w2, win_w, win_h, b)) rc = -1;
+    if (rc == 0) {
+        for (int v = 0; v < nh; ++v)
+            for (int u = 0; u < nw; ++u) {
+                r2[v * nw + u] = 0.5 * (a[v * nw + u] + b[v * nw + (nw - 1 - u)]);
+                if ((float)r2[v * nw + u] > t2) ++*k2;
+            }
+        if (*k2 > 0) {
+            if (orc_scan_fcn(region, rw, rh, l3, n3, w3, win_w, win_h, a) || orc_scan_fcn(mir, rw, rh, l3, n3, w3, win_w, win_h, b)) rc = -1;
+            if (rc == 0)
+                for (int v = 0; v < nh; ++v)
+                    for (int u = 0; u < nw; ++u) {
+                        r3[v * nw + u] = 0.5 * (a[v * nw + u] + b[v * nw + (nw - 1 - u)]);
+                        if ((float)r3[v * nw + u] > t3) ++*k3;
+                    }
+        }
+        *face = (*k2 >= t_nn && *k3 > 0) || (*k2 > 0 && *k3 >= t_nn);
+    }
+    free(mir); free(a);
     return rc;
 }

@@ -208,6 +208,59 @@ def scan_scores(pyr: Pyramid, net, weights: np.ndarray, form: str = "fcn") -> np
     return np.concatenate([scan_level(l, net, weights, form).ravel() for l in pyr.levels] + [np.zeros(0)])
 
 
+def region(frame: np.ndarray, x0: int, y0: int, scale: float, rw: int, rh: int) -> np.ndarray:
+    """rh x rw uint8 region whose corner is (x0, y0) in level coordinates, resampled from the frame."""
+    frame = np.ascontiguousarray(frame, np.uint8)
+    out = np.zeros((rh, rw), np.uint8)
+    lib().orc_region(_p(frame), C.c_int(frame.shape[1]), C.c_int(frame.shape[0]), C.c_int(frame.strides[0]), C.c_int(int(x0)),
+                     C.c_int(int(y0)), C.c_double(float(scale)), C.c_int(rw), C.c_int(rh), _p(out))
+    return out
+
+
+def histeq(img: np.ndarray) -> np.ndarray:
+    out = np.ascontiguousarray(img, np.uint8).copy()
+    lib().orc_histeq(_p(out), C.c_int(out.size))
+    return out
+
+
+def select_region(reg: np.ndarray, net2, w2: np.ndarray, net3, w3: np.ndarray, t2: float, t3: float, t_nn: int):
+    """One equalised region through CNN_2 / CNN_3 and the decision rule: (K2, K3, face, r2, r3)."""
+    reg = np.ascontiguousarray(reg, np.uint8)
+    w2 = np.ascontiguousarray(w2, np.float32)
+    w3 = np.ascontiguousarray(w3, np.float32)
+    assert w2.size == net2.n_params and w3.size == net3.n_params
+    rh, rw = reg.shape
+    nh, nw = (rh - net2.win_h) // net2.step + 1, (rw - net2.win_w) // net2.step + 1
+    k2, k3, face = C.c_int32(0), C.c_int32(0), C.c_int32(0)
+    r2 = np.zeros((nh, nw), np.float64)
+    r3 = np.zeros((nh, nw), np.float64)
+    rc = lib().orc_select_region(_p(reg), C.c_int(rw), C.c_int(rh), _rlayers(net2), C.c_int(len(net2.layers)), _p(w2),
+                                 _rlayers(net3), C.c_int(len(net3.layers)), _p(w3), C.c_int(net2.win_w), C.c_int(net2.win_h),
+                                 C.c_float(t2), C.c_float(t3), C.c_int(t_nn), C.byref(k2), C.byref(k3), C.byref(face),
+                                 _p(r2), _p(r3))
+    if rc != 0:
+        raise ValueError("a network does not fit the region")
+    return k2.value, k3.value, bool(face.value), r2, r3
+
+
+def select_unit(frame: np.ndarray, pyr: Pyramid, scan_idx: np.ndarray, net1, net2, w2, net3, w3, t2: float, t3: float,
+                t_nn: int, rw: int = 51, rh: int = 55, margin: int = 12):
+    """The selective unit for the scan responses with flat indices scan_idx: list of dicts (index, level, i, j, k2, k3,
+    face, r2, r3) in that order.  The region of window (i, j) of a level is the window plus `margin` level pixels."""
+    sizes = [((l.shape[0] - net1.win_h) // net1.step + 1, (l.shape[1] - net1.win_w) // net1.step + 1)
+             if l.shape[0] >= net1.win_h and l.shape[1] >= net1.win_w else (0, 0) for l in pyr.levels]
+    off = np.concatenate([[0], np.cumsum([a * b for a, b in sizes])])
+    out = []
+    for g in np.asarray(scan_idx, np.int64):
+        lvl = int(np.searchsorted(off, g, side="right") - 1)
+        rel = int(g - off[lvl])
+        j, i = divmod(rel, sizes[lvl][1])
+        reg = histeq(region(frame, net1.step * i - margin, net1.step * j - margin, pyr.scale[lvl], rw, rh))
+        k2, k3, face, r2, r3 = select_region(reg, net2, w2, net3, w3, t2, t3, t_nn)
+        out.append(dict(index=int(g), level=lvl, i=i, j=j, k2=k2, k3=k3, face=face, r2=r2, r3=r3))
+    return out
+
+
 def stage1_scores(pyr: Pyramid, stage, weights: np.ndarray, form: str = "dense") -> np.ndarray:
     """All stage-1 scores of a frame, flat in (level, y, x) order."""
     return np.concatenate([stage1_level(l, stage, weights, form).ravel() for l in pyr.levels])
