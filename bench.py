@@ -25,6 +25,8 @@ S2_FLOP_PER_CROP = 2 * 161952
 S3_FLOP_PER_CROP = 2 * 5473600
 S2_CONV_FLOP_PER_CROP = 2 * (80000 + 73728)            # conv kernel of stage 2 (conv1 + conv2)
 S3_CONV_FLOP_PER_CROP = 2 * (774400 + 4147200 + 451584)  # conv kernel of stage 3 (conv1..conv3)
+SEL_MAC_CNN2 = 48 * 52 * 4 * 16 + 22 * 24 * 19 * 36 + 25 * 19 * 56      # one pass of CNN_2 over a 51x55 region
+SEL_MAC_CNN3 = 48 * 52 * 5 * 16 + 22 * 24 * 28 * 45 + 25 * 28 * 56      # one pass of CNN_3
 SCAN_FLOP_PER_POSITION = 2 * (1024 + 1584 + 330)       # 27x31 scan: conv1 + conv2 + conv3 MACs per window position at step 4
 PEAK_HBM = 8000.0          # GB/s
 PEAK_FP32_VECTOR = 157.3   # TFLOP/s, published vector fp32 figure
@@ -53,7 +55,7 @@ def main():
               file=sys.stderr)
         sys.exit(2)
 
-    import numpy as np  # noqa: F401
+    import numpy as np
     import torch
 
     import cnnc_inputs as I
@@ -156,6 +158,27 @@ def main():
     c0.set_timing(False)
     ms_scan = tm_scan[0] / tm_scan[1] if tm_scan[1] else 0.0
     n_scan = int(c0.scan_layout(cfg["width"], cfg["height"])["out_off"][-1])
+    # the selective unit in that geometry on the positions above the 2 % quantile of the scan; thresholds of the two
+    # response maps at their medians over a sample of regions (oracle), T_nn = 5
+    n2_net, n3_net = I.paper_stage2(), I.paper_stage3()
+    w2_sel, w3_sel = I.draw_scan_weights(n2_net, seed + 1), I.draw_scan_weights(n3_net, seed + 2)
+    c0.select_set_weights(w2_sel, w3_sel, 1)
+    pyr_o = O.build_pyramid(frame, cfg["min_face"], cfg["scale_step"])
+    scan_o = O.scan_scores(pyr_o, scan_net, I.draw_scan_weights(scan_net, seed))
+    t1_scan = float(O.threshold_from_quantile(scan_o, 0.02))
+    sample = np.nonzero(scan_o.astype(np.float32) > np.float32(t1_scan))[0][::24]
+    ref_sel = O.select_unit(frame, pyr_o, sample, scan_net, n2_net, w2_sel, n3_net, w3_sel, -1e30, -1e30, 1)
+    t2_sel = float(np.median(np.concatenate([r["r2"].ravel() for r in ref_sel])))
+    t3_sel = float(np.median(np.concatenate([r["r3"].ravel() for r in ref_sel])))
+    c0.set_timing(True)
+    c0.get_timings()
+    for _ in range(max(10, a.steps // 4)):
+        c0.select_run(t1_scan, t2_sel, t3_sel, 5, streams[0])
+    tm_sel = c0.get_timings()["select"]
+    c0.set_timing(False)
+    ms_sel = tm_sel[0] / tm_sel[1] if tm_sel[1] else 0.0
+    sel = c0.select_fetch(65536)
+    sel_flop = 2.0 * sum(2 * SEL_MAC_CNN2 + (2 * SEL_MAC_CNN3 if r.k2 > 0 else 0) for r in sel)
     c0.detect(dev_frame, 8192)           # leaves the context with the cascade's own survivor lists again
     n1, n2, n3 = (c0.survivor_count(s) for s in (1, 2, 3))
     lay = c0.pyramid_layout(cfg["width"], cfg["height"])
@@ -247,7 +270,11 @@ def main():
                                   "peak": PEAK_FP32_VECTOR, "unit": "TFLOP/s",
                                   "frac": tflops(SCAN_FLOP_PER_POSITION * n_scan, ms_scan) / PEAK_FP32_VECTOR},
         "ingest_from_pinned_host_memory": ingest,
-        "sum_of_kernel_ms": sum(v for k, v in ms.items() if not k.endswith("_conv") and k != "scan"),
+        "paper_selective_unit": {"regions": len(sel), "faces": sum(r.face for r in sel), "ms": ms_sel,
+                                 "regions_per_s": len(sel) / (ms_sel * 1e-3) if ms_sel > 0 else None, "bound": "alu",
+                                 "achieved": tflops(sel_flop, ms_sel), "peak": PEAK_FP32_VECTOR, "unit": "TFLOP/s",
+                                 "frac": tflops(sel_flop, ms_sel) / PEAK_FP32_VECTOR},
+        "sum_of_kernel_ms": sum(v for k, v in ms.items() if not k.endswith("_conv") and k not in ("scan", "select")),
         "roofline": roof,
         "kernels": kernels,
         "cpu_baseline": cpu,

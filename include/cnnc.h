@@ -96,6 +96,7 @@ enum {
     /* the convolution kernel alone inside cnnc_eval_stage(2) / (3) (the step also runs a small fc kernel) */
     CNNC_T_STAGE2_CONV, CNNC_T_STAGE3_CONV,
     CNNC_T_SCAN,            /* cnnc_scan_scoremap */
+    CNNC_T_SELECT,          /* cnnc_select_run */
     CNNC_T_COUNT
 };
 
@@ -215,6 +216,38 @@ int cnnc_scan_set_weights(cnnc_ctx *ctx, const float *weights, int n_floats, int
 int cnnc_scan_layout(cnnc_ctx *ctx, int w, int h, int *n_levels, int32_t *out_w, int32_t *out_h, int64_t *out_off);
 int cnnc_scan_scoremap(cnnc_ctx *ctx, void *stream);
 int cnnc_get_scan_scoremap(cnnc_ctx *ctx, const float **d_scores, int64_t *n);
+
+/* ---- The selective unit in the paper's geometry -----------------------------------------------
+ * Section 3.3: a window position whose first-stage response exceeded T_1 is read from the original image together
+ * with a neighbourhood and scaled to 51 x 55 pixels; its histogram is equalised; the region and its mirror image
+ * (reflection about the vertical axis) go through CNN_2 and CNN_3, each giving a 5 x 5 response map; with K2, K3 the
+ * numbers of responses above the threshold, rule (2) decides: face = (K2 >= T_nn and K3 > 0) or (K2 > 0 and
+ * K3 >= T_nn); a region with K2 = 0 is not shown to CNN_3.
+ * What the paper leaves open is fixed as follows: neighbourhood = 12 level pixels on every side of the 27 x 31 window;
+ * region samples in 16.16 fixed point with 8-bit weights, rounded to uint8; equalisation v -> round((cdf(v) - c0) * 255
+ * / (n - c0)) with c0 the cdf of the smallest value present (a constant region is left alone); networks
+ * conv 4x4 1->c1, f, pool 2 | conv 3x3 c1->c2, f, pool 2 | conv 7x8 (w x h) c2->1 on a 35 x 39 window at step 4, with
+ * (c1, c2) = (4, 19) for CNN_2 (1836 parameters; the paper: 1819) and (5, 28) for CNN_3 (2942; the paper: 2923); a
+ * window's response is the mean of response (v, u) of the region and response (v, 4 - u) of the mirror image.
+ *
+ * cnnc_select_set_weights: host blobs (per conv layer w[cout][cin][kh][kw] then bias[cout]), n2 = 1836, n3 = 2942,
+ *   act = hidden activation kind; copied; synchronises; allocates the unit's buffers on first use.
+ * cnnc_select_run: needs cnnc_scan_scoremap of the current frame (CNNC_E_STATE otherwise), whose frame must still be
+ *   alive.  Lists the positions with response > t1 in ascending flat order and runs the unit on each; K2 counts
+ *   responses > t2, K3 responses > t3 (fp32, strict).  Enqueued on `stream`.
+ * cnnc_select_fetch: waits, then returns one record per listed position, in that order (out: host, capacity cap;
+ *   *n_out = their number, CNNC_E_OVERFLOW rules as for detections).  maps2 / maps3: optional host arrays of
+ *   cap x 25 floats receiving the combined response maps (row-major 5 x 5; maps3 is zero where CNN_3 was not run). */
+typedef struct {
+    int32_t index;          /* flat index of the position in the response map of cnnc_scan_scoremap */
+    int32_t level, i, j;    /* pyramid level, column and row of the position (window corner = pixel (4 i, 4 j)) */
+    int32_t k2, k3;         /* responses above the threshold in the 5 x 5 maps of CNN_2 and CNN_3 */
+    int32_t face;           /* decision rule (2) */
+    float response;         /* first-stage response of the position */
+} cnnc_region;
+int cnnc_select_set_weights(cnnc_ctx *ctx, const float *w2, int n2, const float *w3, int n3, int act);
+int cnnc_select_run(cnnc_ctx *ctx, float t1, float t2, float t3, int t_nn, void *stream);
+int cnnc_select_fetch(cnnc_ctx *ctx, cnnc_region *out, int cap, int *n_out, float *maps2, float *maps3);
 
 /* ---- Frame ingest from host memory ------------------------------------------------------------
  * The paper's detector is fed video (Section 4.2) and overlaps its stages (Section 3.4, asynchronous mode).

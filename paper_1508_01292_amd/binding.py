@@ -21,11 +21,12 @@ EXPORTS = [
     "cnnc_get_timings", "cnnc_set_eval_impl", "cnnc_measure_peaks", "cnnc_last_error", "cnnc_version",
     "cnnc_stage1_survivors", "cnnc_set_fused_stage1",
     "cnnc_scan_set_weights", "cnnc_scan_layout", "cnnc_scan_scoremap", "cnnc_get_scan_scoremap",
+    "cnnc_select_set_weights", "cnnc_select_run", "cnnc_select_fetch",
     "cnnc_pipe_create", "cnnc_pipe_destroy", "cnnc_pipe_set_params", "cnnc_pipe_frame_buffer", "cnnc_pipe_submit",
     "cnnc_pipe_fetch", "cnnc_pipe_last_error",
 ]
 STEP_NAMES = ["pyramid", "stage1", "compact1", "stage2", "compact2", "stage3", "compact3", "merge",
-              "stage2_conv", "stage3_conv", "scan"]
+              "stage2_conv", "stage3_conv", "scan", "select"]
 MAX_LEVELS = 64
 E_OVERFLOW = -3
 
@@ -48,6 +49,15 @@ class _StageDesc(C.Structure):
 class _Params(C.Structure):
     _fields_ = [("min_face", C.c_double), ("scale_step", C.c_double), ("thr", C.c_float * 3),
                 ("merge_iou", C.c_float), ("min_neighbors", C.c_int32)]
+
+
+class Region(C.Structure):
+    _fields_ = [("index", C.c_int32), ("level", C.c_int32), ("i", C.c_int32), ("j", C.c_int32), ("k2", C.c_int32),
+                ("k3", C.c_int32), ("face", C.c_int32), ("response", C.c_float)]
+
+    def as_dict(self):
+        return dict(index=self.index, level=self.level, i=self.i, j=self.j, k2=self.k2, k3=self.k3, face=bool(self.face),
+                    response=self.response)
 
 
 class Detection(C.Structure):
@@ -260,6 +270,27 @@ class Context:
         self._check(lib().cnnc_get_scan_scoremap(self._h, C.byref(p), C.byref(n)))
         return _d2h(p.value, n.value * 4, np.float32)
 
+    # ---- the selective unit in the paper's geometry
+    def select_set_weights(self, w2: np.ndarray, w3: np.ndarray, act: int = 1):
+        a, b = np.ascontiguousarray(w2, np.float32), np.ascontiguousarray(w3, np.float32)
+        self._check(lib().cnnc_select_set_weights(self._h, a.ctypes.data_as(C.c_void_p), C.c_int(a.size),
+                                                  b.ctypes.data_as(C.c_void_p), C.c_int(b.size), C.c_int(act)))
+
+    def select_run(self, t1: float, t2: float, t3: float, t_nn: int, stream=None):
+        self._check(lib().cnnc_select_run(self._h, C.c_float(t1), C.c_float(t2), C.c_float(t3), C.c_int(t_nn), _stream(stream)))
+
+    def select_fetch(self, cap: int = 65536, maps: bool = False):
+        """Records of the positions that passed T_1 (list of Region); with maps=True also the two (n, 5, 5) response maps."""
+        out = (Region * cap)()
+        n = C.c_int(0)
+        m2 = np.zeros((cap, 5, 5), np.float32) if maps else None
+        m3 = np.zeros((cap, 5, 5), np.float32) if maps else None
+        self._check(lib().cnnc_select_fetch(self._h, out, C.c_int(cap), C.byref(n),
+                                            m2.ctypes.data_as(C.c_void_p) if maps else C.c_void_p(0),
+                                            m3.ctypes.data_as(C.c_void_p) if maps else C.c_void_p(0)))
+        recs = list(out[:n.value])
+        return (recs, m2[:n.value], m3[:n.value]) if maps else recs
+
     def set_eval_impl(self, impl: int):
         self._check(lib().cnnc_set_eval_impl(self._h, C.c_int(impl)))
 
@@ -357,6 +388,18 @@ def cnnc_stage1_survivors(ctx, thr, stream=None):
 
 def cnnc_set_fused_stage1(ctx, on):
     return ctx.set_fused_stage1(on)
+
+
+def cnnc_select_set_weights(ctx, w2, w3, act=1):
+    return ctx.select_set_weights(w2, w3, act)
+
+
+def cnnc_select_run(ctx, t1, t2, t3, t_nn, stream=None):
+    return ctx.select_run(t1, t2, t3, t_nn, stream)
+
+
+def cnnc_select_fetch(ctx, cap=65536, maps=False):
+    return ctx.select_fetch(cap, maps)
 
 
 def cnnc_scan_set_weights(ctx, weights, act=1):

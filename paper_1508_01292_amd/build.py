@@ -9,7 +9,7 @@ INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 LIB = os.path.join(HERE, "libcnnc.so")
 OBJ = os.path.join(HERE, "_build")
 
-SOURCES = ["cnnc_host.hip", "k_pyramid.hip", "k_stage1.hip", "k_compact.hip", "k_eval.hip", "k_eval_mfma.hip", "k_merge.hip", "k_peaks.hip", "k_scan.hip", "cnnc_pipe.hip"]
+SOURCES = ["cnnc_host.hip", "k_pyramid.hip", "k_stage1.hip", "k_compact.hip", "k_eval.hip", "k_eval_mfma.hip", "k_merge.hip", "k_peaks.hip", "k_scan.hip", "k_select.hip", "cnnc_pipe.hip"]
 
 # -packed-fp32-ops is switched off on purpose: the compiler must not form packed fp32 instructions.
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",

@@ -311,6 +311,7 @@ int cnnc_destroy(cnnc_ctx *c)
     for (int s = 0; s < 3; ++s) { (void)hipFree(c->d_wt[s]); (void)hipFree(c->d_idx[s]); (void)hipFree(c->d_sc[s]); }
     for (int s = 0; s < 2; ++s) { (void)hipFree(c->d_eval[s]); (void)hipFree(c->d_frag[s]); (void)hipFree(c->d_feat[s]); }
     scan_release(c);
+    select_release(c);
     (void)hipFree(c->d_levels); (void)hipFree(c->d_taps); (void)hipFree(c->d_tiles_pyr); (void)hipFree(c->d_tiles_s1);
     (void)hipFree(c->d_pyr); (void)hipFree(c->d_score1); (void)hipFree(c->d_mask1); (void)hipFree(c->d_blockcnt); (void)hipFree(c->d_cnt);
     (void)hipFree(c->d_merge_ws); (void)hipFree(c->d_det);
@@ -371,6 +372,7 @@ int cnnc_build_pyramid(cnnc_ctx *c, const uint8_t *d_frame, int w, int h, int pi
     c->last_stream = st;
     c->progress = 0;
     c->scan_done = false;
+    c->sel_done = false;
     {
         Timed t(c, CNNC_T_PYRAMID, st);
         HIP_TRY(c, launch_pyramid(c, st));

@@ -5,6 +5,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <algorithm>
 #include <string>
 #include <vector>
 
@@ -103,6 +104,16 @@ struct cnnc_ctx {
     int n_scan_tiles = 0, scan_serial = -1;
     bool scan_done = false;
 
+    // the selective unit in that geometry: networks, list of positions above T_1, per-region records and response maps
+    float *d_sel_w2 = nullptr, *d_sel_w3 = nullptr;
+    int sel_act = 0;
+    uint32_t *d_sel_idx = nullptr;
+    float *d_sel_sc = nullptr;
+    cnnc_region *d_sel_rec = nullptr;
+    float *d_sel_maps = nullptr;             // [2][max_surv][25]
+    int32_t *d_sel_cnt = nullptr, *h_sel_cnt = nullptr;
+    bool sel_done = false;
+
     // device buffers that depend on the layout
     cnnc::LevelDev *d_levels = nullptr;
     uint32_t *d_taps = nullptr;      // column / row tap tables of all levels
@@ -175,6 +186,7 @@ int fail(cnnc_ctx *c, int code, const std::string &msg);
 int hip_fail(cnnc_ctx *c, hipError_t e, const char *what);
 int compute_levels(const cnnc_ctx *c, int w, int h, std::vector<LevelDev> &lv, int64_t &pyr_bytes, int64_t &n_windows);
 void scan_release(cnnc_ctx *c);
+void select_release(cnnc_ctx *c);
 size_t eval2_frag_floats();
 size_t eval2_feat_floats();
 void eval2_make_fragments(const float *blob, float *frag);

@@ -199,6 +199,7 @@ int cnnc_scan_set_weights(cnnc_ctx *c, const float *weights, int n_floats, int a
     HIP_TRY(c, hipMemcpy(c->d_scan_wt, weights, sizeof(float) * kScanParams, hipMemcpyHostToDevice));
     c->scan_act = act;
     c->scan_done = false;
+    c->sel_done = false;
     return CNNC_OK;
 }
 
@@ -266,6 +267,7 @@ int cnnc_scan_scoremap(cnnc_ctx *c, void *stream)
         HIP_TRY(c, hipGetLastError());
     }
     c->scan_done = true;
+    c->sel_done = false;
     return CNNC_OK;
 }
 

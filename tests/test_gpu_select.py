@@ -1,0 +1,137 @@
+"""GPU parity of the selective unit in the paper's geometry: positions listed, response maps, counts K2 / K3 and the
+decision of rule (2), against the oracle, region by region."""
+import numpy as np
+import pytest
+
+import cnnc_inputs as I
+from oracle import oracle as O
+
+from parity import ATOL, BAND, RTOL
+
+pytestmark = pytest.mark.gpu
+
+
+def _select_case(frame, min_face, step, act, seed, q1, q2, t_nn, bias_sd=0.0, name=""):
+    import torch
+    import paper_1508_01292_amd as P
+    print("select case", name, frame.shape, "act", act, "q1", q1, flush=True)
+    n1, n2, n3 = I.paper_stage1(act), I.paper_stage2(act), I.paper_stage3(act)
+    w1, w2, w3 = (I.draw_scan_weights(n, seed + k, bias_sd=bias_sd) for k, n in enumerate((n1, n2, n3)))
+    pyr = O.build_pyramid(frame, min_face, step)
+    s1 = O.scan_scores(pyr, n1, w1)
+    t1 = float(O.threshold_from_quantile(s1, q1))
+    want_idx = np.nonzero(s1.astype(np.float32) > np.float32(t1))[0]
+    # thresholds of the response maps: a quantile of CNN_2's responses over all listed regions
+    ref = O.select_unit(frame, pyr, want_idx, n1, n2, w2, n3, w3, -1e30, -1e30, 1)
+    t2 = float(np.float32(np.quantile(np.concatenate([r["r2"].ravel() for r in ref]), 1 - q2)))
+    t3 = float(np.float32(np.quantile(np.concatenate([r["r3"].ravel() for r in ref]), 1 - q2)))
+    ref = O.select_unit(frame, pyr, want_idx, n1, n2, w2, n3, w3, t2, t3, t_nn)
+
+    casc = I.default_cascade()
+    ctx = P.Context(casc, I.draw_weights(casc, seed), frame.shape[1], frame.shape[0], 50000)
+    ctx.set_params(min_face, step, (0.0, 0.0, 0.0))
+    ctx.scan_set_weights(w1, act)
+    ctx.select_set_weights(w2, w3, act)
+    ctx.build_pyramid(torch.from_numpy(frame).cuda())
+    ctx.scan_scoremap()
+    ctx.select_run(t1, t2, t3, t_nn)
+    recs, m2, m3 = ctx.select_fetch(50000, maps=True)
+    # positions: equal outside the band around t1
+    got_idx = np.array([r.index for r in recs], np.int64)
+    band1 = set(np.nonzero(np.abs(s1 - t1) <= BAND)[0].tolist())
+    assert not ((set(got_idx.tolist()) ^ set(want_idx.tolist())) - band1)
+    assert np.all(np.diff(got_idx) > 0)
+    by_idx = {r["index"]: r for r in ref}
+    n_cmp = n_face = n_banded = 0
+    for r, a2, a3 in zip(recs, m2, m3):
+        if r.index not in by_idx:
+            continue
+        w = by_idx[r.index]
+        assert (r.level, r.i, r.j) == (w["level"], w["i"], w["j"])
+        assert abs(r.response - s1[r.index]) <= ATOL + RTOL * abs(s1[r.index])
+        assert np.all(np.abs(a2 - w["r2"]) <= ATOL + RTOL * np.abs(w["r2"])), "CNN_2 map of %d: %g" % (r.index, np.abs(a2 - w["r2"]).max())
+        near2 = int((np.abs(w["r2"] - t2) <= BAND).sum())
+        assert abs(r.k2 - w["k2"]) <= near2
+        if near2 == 0 and w["k2"] > 0:
+            assert np.all(np.abs(a3 - w["r3"]) <= ATOL + RTOL * np.abs(w["r3"])), "CNN_3 map of %d" % r.index
+            near3 = int((np.abs(w["r3"] - t3) <= BAND).sum())
+            assert abs(r.k3 - w["k3"]) <= near3
+            if near3 == 0:
+                assert bool(r.face) == w["face"]
+                n_face += int(w["face"])
+            else:
+                n_banded += 1
+        elif near2 == 0:
+            assert r.k3 == 0 and not r.face and np.all(a3 == 0)       # CNN_3 not run
+        else:
+            n_banded += 1
+        # the record's own consistency with rule (2)
+        assert bool(r.face) == ((r.k2 >= t_nn and r.k3 > 0) or (r.k2 > 0 and r.k3 >= t_nn))
+        n_cmp += 1
+    ctx.close()
+    print("   %d positions listed, %d compared, %d faces, %d with a response inside the band" % (len(recs), n_cmp, n_face, n_banded),
+          flush=True)
+    assert n_cmp >= len(want_idx) - len(band1)
+    return recs, ref
+
+
+@pytest.mark.parametrize("act", [I.ACT_RATIONAL, I.ACT_TANH])
+def test_select_vga(act):
+    c = I.CONFIGS[0]
+    frame = I.make_frame(c["width"], c["height"], I.config_seed(0))
+    recs, ref = _select_case(frame, c["min_face"], c["scale_step"], act, 40, 0.1, 0.3, 5,
+                             bias_sd=0.0 if act == I.ACT_RATIONAL else 0.1, name="vga")
+    assert len(ref) == 85
+    assert any(r["face"] for r in ref) and not all(r["face"] for r in ref)
+
+
+def test_select_ragged_frame_regions_cut_by_the_border():
+    # small levels: most regions reach over the level edge, where the frame edge is repeated
+    frame = I.make_frame(333, 251, 5)
+    recs, ref = _select_case(frame, 12.0, 1.3, I.ACT_RATIONAL, 50, 0.03, 0.2, 3, bias_sd=0.1, name="333x251")
+    assert any(r["i"] == 0 or r["j"] == 0 for r in ref)
+
+
+def test_select_uhd_headline_frame():
+    c = I.CONFIGS[2]
+    frame = I.make_frame(c["width"], c["height"], I.config_seed(2))
+    recs, ref = _select_case(frame, c["min_face"], c["scale_step"], I.ACT_RATIONAL, 60, 0.02, 0.25, 6, name="uhd")
+    assert len(ref) == 965
+
+
+def test_select_errors_and_degenerate_cases():
+    import torch
+    import paper_1508_01292_amd as P
+    casc = I.default_cascade()
+    n1, n2, n3 = I.paper_stage1(), I.paper_stage2(), I.paper_stage3()
+    w1, w2, w3 = I.draw_scan_weights(n1, 1), I.draw_scan_weights(n2, 2), I.draw_scan_weights(n3, 3)
+    frame = I.make_frame(160, 120, 8)
+    ctx = P.Context(casc, I.draw_weights(casc, 1), 160, 120, 16)
+    ctx.set_params(12.0, 1.25, (0.0, 0.0, 0.0))
+    with pytest.raises(P.CnncError):
+        ctx.select_run(0.0, 0.0, 0.0, 1)              # no weights
+    with pytest.raises(P.CnncError):
+        ctx.select_set_weights(w2[:-1], w3, 1)
+    with pytest.raises(P.CnncError):
+        ctx.select_set_weights(w2, w3, 4)
+    ctx.select_set_weights(w2, w3, 1)
+    with pytest.raises(P.CnncError):
+        ctx.select_run(0.0, 0.0, 0.0, 1)              # no scan of this frame
+    ctx.scan_set_weights(w1, 1)
+    ctx.build_pyramid(torch.from_numpy(frame).cuda())
+    with pytest.raises(P.CnncError):
+        ctx.select_fetch(16)                          # nothing run
+    ctx.scan_scoremap()
+    with pytest.raises(P.CnncError):
+        ctx.select_run(float("nan"), 0.0, 0.0, 1)
+    ctx.select_run(1e30, 0.0, 0.0, 1)                 # nothing passes T_1
+    assert ctx.select_fetch(16) == []
+    ctx.select_run(-1e30, 0.0, 0.0, 1)                # everything passes: more than the capacity of 16
+    with pytest.raises(P.CnncError) as e:
+        ctx.select_fetch(16)
+    assert e.value.code == -3
+    # a new pyramid invalidates the unit's results
+    ctx.build_pyramid(torch.from_numpy(frame).cuda())
+    with pytest.raises(P.CnncError):
+        ctx.select_fetch(16)
+    ctx.close()
