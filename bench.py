@@ -19,7 +19,7 @@ if ROOT not in sys.path:
 
 METRIC = "frames/sec at 3840x2160, min face 60 px (full cascade); stage-1 windows/sec"
 
-# Algorithmic work per unit ("Kernels and rooflines").
+# Algorithmic work per unit: 2 x the multiply-accumulates of the layer definitions, whatever the kernels execute.
 S1_FLOP_PER_WINDOW = 2 * 396
 S2_FLOP_PER_CROP = 2 * 161952
 S3_FLOP_PER_CROP = 2 * 5473600
