@@ -585,7 +585,14 @@ void eval2_conv_kernel(const uint8_t *__restrict__ frame, int fw, int fh, int pi
                        const float *__restrict__ wt, const float *__restrict__ frag, float *__restrict__ feat)
 {
     __shared__ __attribute__((aligned(16))) float sMem[4][kS2WaveFloats];
+    // per pooling block of conv1 (clamped to the last one): crop offset of its corner | pooled-map offset << 16
+    __shared__ uint32_t sLut[112];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, g = lane >> 4, j = lane & 15;
+    if (tid < 112) {
+        const int pb = min(tid, 99);
+        sLut[tid] = (uint32_t)(2 * (pb / 10) * kC2W + 2 * (pb % 10)) | (uint32_t)((pb / 10) * kQ1Row + pb % 10) << 16;
+    }
+    __syncthreads();
     float *sCrop = sMem[wave];
     uint32_t *sTab = reinterpret_cast<uint32_t *>(sCrop + kS2Crop);
     float *sP1 = sCrop + kS2Crop + kS2Tab;
@@ -601,7 +608,9 @@ void eval2_conv_kernel(const uint8_t *__restrict__ frame, int fw, int fh, int pi
     // half of the matrix tile is idle: K = 5 rows x 6 input columns = 30 -> 8 steps of 4.
     // k-order: steps 0..4 = (row = step, column = g); step 5 = (row = g, column 4); step 6 = (row = g, column 5);
     // step 7 = (4, 4) in group 0, (4, 5) in group 1, zero weights in groups 2 and 3.
-    const int off5 = g * kC2W + 4, off6 = g * kC2W + 5, off7 = g == 0 ? 4 * kC2W + 4 : (g == 1 ? 4 * kC2W + 5 : 0);
+    // (offsets relative to a lane base that already includes the tap column g)
+    const int off5 = g * kC2W + 4 - g, off6 = g * kC2W + 5 - g, off7 = g == 0 ? 4 * kC2W + 4 : (g == 1 ? 4 * kC2W + 5 - g : -g);
+    const int in_lane = (j & 1) * kC2W + g, in_blk = 2 * (j >> 2) + ((j >> 1) & 1), out_blk = 2 * g + (j & 1);
 
     const int n = min(*d_n, n_max);
     for (int crop = __builtin_amdgcn_readfirstlane(blockIdx.x * 4 + wave); crop < n; crop += gridDim.x * 4) {
@@ -640,13 +649,12 @@ void eval2_conv_kernel(const uint8_t *__restrict__ frame, int fw, int fh, int pi
 #pragma unroll
             for (int u = 0; u < 7; ++u) {
                 acc[u] = floatx4{0, 0, 0, 0};
-                const int pb = min(8 * (t0 + u) + 2 * (j >> 2) + ((j >> 1) & 1), 99);
-                base[u] = (2 * (pb / 10) + (j & 1)) * kC2W + 2 * (pb % 10);
+                base[u] = (int)(sLut[8 * (t0 + u) + in_blk] & 0xFFFFu) + in_lane;
             }
 #pragma unroll
             for (int s = 0; s < 5; ++s)
 #pragma unroll
-                for (int u = 0; u < 7; ++u) acc[u] = CNNC_MFMA(sCrop[base[u] + g + s * kC2W], b1f[s], acc[u]);
+                for (int u = 0; u < 7; ++u) acc[u] = CNNC_MFMA(sCrop[base[u] + s * kC2W], b1f[s], acc[u]);
 #pragma unroll
             for (int u = 0; u < 7; ++u) acc[u] = CNNC_MFMA(sCrop[base[u] + off5], b1f[5], acc[u]);
 #pragma unroll
@@ -660,9 +668,8 @@ void eval2_conv_kernel(const uint8_t *__restrict__ frame, int fw, int fh, int pi
                 float lo = fmaxf(acc[u][0], acc[u][1]), hi = fmaxf(acc[u][2], acc[u][3]);
                 lo = fmaxf(lo, __shfl_xor(lo, 1, 64));
                 hi = fmaxf(hi, __shfl_xor(hi, 1, 64));
-                const int pb = 8 * (t0 + u) + 2 * g + (j & 1);        // even lanes finish the first block, odd the second
-                if (pb < 100)
-                    sP1[(j >> 1) * kQ1Ch + (pb / 10) * kQ1Row + pb % 10] = act_f<ACT>(((j & 1) ? hi : lo) + bias1);
+                const int pb = 8 * (t0 + u) + out_blk;                // even lanes finish the first block, odd the second
+                if (pb < 100) sP1[(j >> 1) * kQ1Ch + (sLut[pb] >> 16)] = act_f<ACT>(((j & 1) ? hi : lo) + bias1);
             }
         }
         wave_sync();
