@@ -569,7 +569,7 @@ int cnnc_survivor_count(cnnc_ctx *c, int stage, int *n, void *stream)
 int cnnc_set_eval_impl(cnnc_ctx *c, int impl)
 {
     if (!c) return CNNC_E_INVAL;
-    if (impl < 0 || impl > 2) return fail(c, CNNC_E_INVAL, "implementation must be 0, 1 or 2");
+    if (impl < 0 || impl > 3) return fail(c, CNNC_E_INVAL, "implementation must be 0, 1, 2 or 3");
     c->eval_impl = impl;
     return CNNC_OK;
 }

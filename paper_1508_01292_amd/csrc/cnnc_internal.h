@@ -82,8 +82,9 @@ struct cnnc_ctx {
     // per-window activations handed from the convolution kernel to the fully connected kernel
     float *d_frag[2] = {nullptr, nullptr};
     float *d_feat[2] = {nullptr, nullptr};
-    int eval_impl = 2;                        // 2: MFMA kernels with Winograd conv2 in stage 3, 1: MFMA kernels with
-                                              // direct sums only, 0: direct convolution on the vector ALU
+    int eval_impl = 3;                        // stage 2 / 3 kernels: 3: matrix cores, stage-3 conv2 by Winograd F(4,5);
+                                              // 2: the same with F(2,5); 1: matrix cores, direct sums only;
+                                              // 0: direct convolution on the vector ALU
 
     // geometry of the current frame size / parameters
     bool layout_valid = false;

@@ -50,7 +50,7 @@ constexpr int kP2Ch = 81;                  // pooled conv2 map [32][9][9] of the
 constexpr int kP2RowW = 10, kP2ChW = 9 * kP2RowW;   // Winograd variant: rows padded to 10 so that row reads are 8-byte aligned
 constexpr int kRegionA = 32 * kP2ChW;      // crop (2304) then pooled conv2 map (2592 or 2880)
 // position of pooling block `blk` (0..80) of channel `oc` in the pooled conv2 map
-template <bool WINO>
+template <int WINO>
 __device__ __forceinline__ int p2_index(int oc, int blk)
 {
     return WINO ? oc * kP2ChW + (blk / 9) * kP2RowW + blk % 9 : oc * kP2Ch + blk;
@@ -99,8 +99,8 @@ __device__ __forceinline__ void s3_conv2(const float *sP1, float *sP2, const flo
     for (int u = 0; u < NT; ++u) {
         const int pb = 4 * (wslot + 4 * u) + g;
         if (pb < 81) {
-            sP2[p2_index<false>(j, pb)] = act_f<ACT>(max4(acc[u][0]) + bias_lo);
-            sP2[p2_index<false>(16 + j, pb)] = act_f<ACT>(max4(acc[u][1]) + bias_hi);
+            sP2[p2_index<0>(j, pb)] = act_f<ACT>(max4(acc[u][0]) + bias_lo);
+            sP2[p2_index<0>(16 + j, pb)] = act_f<ACT>(max4(acc[u][1]) + bias_hi);
         }
     }
 }
@@ -191,9 +191,103 @@ __device__ __forceinline__ void s3_conv2_wino_tiles(const float *sP1, float *sP2
             for (int sub = 0; sub < 2; ++sub) {
                 const int blk = 8 * (mt0 + 4 * t) + 2 * g + sub;
                 const float m = fmaxf(fmaxf(R0[2 * sub], R1[2 * sub]), fmaxf(R0[2 * sub + 1], R1[2 * sub + 1]));
-                if (blk < 81) sP2[p2_index<true>(oc, blk)] = act_f<ACT>(m + bias);
+                if (blk < 81) sP2[p2_index<1>(oc, blk)] = act_f<ACT>(m + bias);
             }
         }
+}
+
+// ---- conv2 of stage 3 by Winograd F(4, 5) along the rows: four adjacent outputs of a 5-tap row filter cost 8
+// multiplications instead of 20 (F(2, 5) above: 12), points 0, 1, -1, 2, -2, 1/2, -1/2 and infinity:
+//   BT = [-1 0 21/4 0 -21/4 0 1 0; 0 1 1 -17/4 -17/4 1 1 0; 0 -1 1 17/4 -17/4 -1 1 0; 0 1/2 1/4 -5/2 -5/4 2 1 0;
+//         0 -1/2 1/4 5/2 -5/4 -2 1 0; 0 2 4 -5/2 -5 1/2 1 0; 0 -2 4 5/2 -5 -1/2 1 0; 0 -1 0 21/4 0 -21/4 0 1],
+//   AT = [1 1 1 1 1 1 1 0; 0 1 -1 2 -2 1/2 -1/2 0; 0 1 1 4 4 1/4 1/4 0; 0 1 -1 8 -8 1/8 -1/8 1],
+// both in even / odd pairs (26 operations per eight-vector); the fp32 result stays within about 2e-6 of the direct
+// fp32 sum here, as for F(2, 5).  Eight GEMMs with M = 90 rows (18 output rows x 5 groups of four columns, the last
+// group half empty), K = 80, N = 32: 1920 matrix instructions against 2640.
+// A unit is one pooling-block row pair Y and one column group xg: 45 units, eight per M-tile, two A rows each (the two
+// output rows of the pair).  A lane's four accumulator registers hold two units x two rows, and the output transform
+// leaves four columns = two pooling blocks per row in the lane, so max-pooling stays in registers.
+// Reads columns 22, 23 of the pooled conv1 map for its half-empty group: the kernel clears them once.
+
+// NTN = 2: the tile for all 32 output channels.  NTN = 1: for the sixteen channels of n-tile nt0 only (half the
+// matrix work with the same input transform).  The six tiles are dealt as one whole tile per wave (tiles 0..3) plus
+// one half of tile 4 or 5 per wave, so the four waves carry equal loads.
+template <int ACT, int NTN>
+__device__ __forceinline__ void s3_conv2_wino4_tile(const float *sP1, float *sP2, const float *__restrict__ UF, int mt, int nt0,
+                                                    int lane, const float *__restrict__ bias2)
+{
+    const int i = lane & 15, g = lane >> 4, j = lane & 15;
+    const int unit = min(8 * mt + (i >> 1), 44);
+    const float *dptr = sP1 + g * kP1Ch + (2 * (unit / 5) + (i & 1)) * kP1Row + 4 * (unit % 5);
+    floatx4 acc[8][NTN];
+#pragma unroll
+    for (int b = 0; b < 8; ++b)
+#pragma unroll
+        for (int t = 0; t < NTN; ++t) acc[b][t] = floatx4{0, 0, 0, 0};
+    // filter fragments [k-step][lane][n-tile][8 points]: uniform base + 32-bit lane offset
+    const char *ubase = reinterpret_cast<const char *>(UF);
+    const uint32_t lane_off = lane * 64 + (NTN == 1 ? nt0 * 32 : 0);
+    auto ldu = [&](int step, int k) {
+        return *reinterpret_cast<const float4 *>(ubase + (size_t)(step * 4096 + k * 16) + lane_off);
+    };
+    float4 u[2 * NTN], n[2 * NTN];
+#pragma unroll
+    for (int k = 0; k < 2 * NTN; ++k) u[k] = ldu(0, k);
+    float4 c0 = *reinterpret_cast<const float4 *>(dptr), c1 = *reinterpret_cast<const float4 *>(dptr + 4);
+#pragma unroll 1
+    for (int a = 0; a < 5; ++a) {                                // kernel row
+#pragma unroll
+        for (int cq = 0; cq < 4; ++cq) {                         // input channels 4 cq + g
+            const int nstep = min(a * 4 + cq + 1, 19);
+#pragma unroll
+            for (int k = 0; k < 2 * NTN; ++k) n[k] = ldu(nstep, k);
+            const float *nrow = dptr + (cq == 3 ? min(a + 1, 4) * kP1Row + (a == 4 ? 3 : 0) * 4 * kP1Ch
+                                                : a * kP1Row + (cq + 1) * 4 * kP1Ch);
+            const float4 m0 = *reinterpret_cast<const float4 *>(nrow), m1 = *reinterpret_cast<const float4 *>(nrow + 4);
+            asm volatile("" ::: "memory");                        // the loads above stay in flight during the math below
+            // transformed input BT d, d = (c0.x .. c1.w)
+            const float e1 = fmaf(-4.25f, c1.x, c0.z) + c1.z, o1 = fmaf(-4.25f, c0.w, c0.y) + c1.y;
+            const float e2 = fmaf(-1.25f, c1.x, fmaf(0.25f, c0.z, c1.z)), o2 = fmaf(2.0f, c1.y, fmaf(-2.5f, c0.w, 0.5f * c0.y));
+            const float e3 = fmaf(-5.0f, c1.x, fmaf(4.0f, c0.z, c1.z)), o3 = fmaf(0.5f, c1.y, fmaf(-2.5f, c0.w, 2.0f * c0.y));
+            const float v[8] = {fmaf(5.25f, c0.z - c1.x, c1.z - c0.x), e1 + o1, e1 - o1, e2 + o2, e2 - o2, e3 + o3, e3 - o3,
+                                fmaf(5.25f, c0.w - c1.y, c1.w - c0.y)};
+#pragma unroll
+            for (int t = 0; t < NTN; ++t) {
+                const float ub[8] = {u[2 * t].x, u[2 * t].y, u[2 * t].z, u[2 * t].w, u[2 * t + 1].x, u[2 * t + 1].y, u[2 * t + 1].z, u[2 * t + 1].w};
+#pragma unroll
+                for (int b = 0; b < 8; ++b) acc[b][t] = CNNC_MFMA(v[b], ub[b], acc[b][t]);
+            }
+#pragma unroll
+            for (int k = 0; k < 2 * NTN; ++k) u[k] = n[k];
+            c0 = m0; c1 = m1;
+        }
+    }
+    // output transform AT m (four columns per row), pooling over the two rows and the two column pairs, bias, activation
+#pragma unroll
+    for (int t = 0; t < NTN; ++t) {
+        const floatx4 s1 = acc[1][t] + acc[2][t], d1 = acc[1][t] - acc[2][t];
+        const floatx4 s2 = acc[3][t] + acc[4][t], d2 = acc[3][t] - acc[4][t];
+        const floatx4 s3 = acc[5][t] + acc[6][t], d3 = acc[5][t] - acc[6][t];
+        const floatx4 Y0 = acc[0][t] + s1 + (s2 + s3);
+        const floatx4 Y1 = d1 + 2.0f * d2 + 0.5f * d3;
+        const floatx4 Y2 = s1 + 4.0f * s2 + 0.25f * s3;
+        const floatx4 Y3 = d1 + 8.0f * d2 + 0.125f * d3 + acc[7][t];
+        const int oc = 16 * (NTN == 1 ? nt0 : t) + j;
+        const float bias = bias2[oc];
+#pragma unroll
+        for (int sub = 0; sub < 2; ++sub) {                      // registers 2 sub, 2 sub + 1 = the two rows of unit 2 g + sub
+            const int q = 8 * mt + 2 * g + sub;
+            if (q < 45) {
+                const int Y = q / 5, xg = q % 5;
+                const float left = fmaxf(fmaxf(Y0[2 * sub], Y1[2 * sub]), fmaxf(Y0[2 * sub + 1], Y1[2 * sub + 1]));
+                sP2[p2_index<1>(oc, Y * 9 + 2 * xg)] = act_f<ACT>(left + bias);
+                if (xg < 4) {
+                    const float right = fmaxf(fmaxf(Y2[2 * sub], Y3[2 * sub]), fmaxf(Y2[2 * sub + 1], Y3[2 * sub + 1]));
+                    sP2[p2_index<1>(oc, Y * 9 + 2 * xg + 1)] = act_f<ACT>(right + bias);
+                }
+            }
+        }
+    }
 }
 
 // ---- conv3 of stage 3, direct sums: 49 positions = 4 tiles.  The waves split K (wave w takes input channels
@@ -304,15 +398,16 @@ __device__ __forceinline__ void s3_conv3_wino(const float *sP2, const float *__r
 
 // Fragment buffer of stage 3 (floats): conv1 [7][64], conv2 [25][2][64][4], conv3 [9][2][64][8], fc [98][4][64][4].
 // plus the Winograd-domain conv2 weights [5 kernel rows][4 channel quads][64][6 points x 2 n-tiles]
-// and conv3 weights [2 n-tiles][3 kernel rows x 8 channel quads][64][4 points].
+// and conv3 weights [2 n-tiles][3 kernel rows x 8 channel quads][64][4 points], and the F(4,5) conv2 weights
+// [5 kernel rows][4 channel quads][64][2 n-tiles][8 points].
 constexpr int kS3F1 = 0, kS3F2 = kS3F1 + 7 * 64, kS3F3 = kS3F2 + 25 * 2 * 64 * 4, kS3F4 = kS3F3 + 9 * 2 * 64 * 8,
-              kS3F5 = kS3F4 + 98 * 4 * 64 * 4, kS3F6 = kS3F5 + 20 * 64 * 12, kS3FragFloats = kS3F6 + 2 * 24 * 64 * 4;
-static_assert(kS3F5 % 4 == 0 && kS3F6 % 4 == 0, "16-byte loads from the Winograd filter blocks");
+              kS3F5 = kS3F4 + 98 * 4 * 64 * 4, kS3F6 = kS3F5 + 20 * 64 * 12, kS3F7 = kS3F6 + 2 * 24 * 64 * 4, kS3FragFloats = kS3F7 + 20 * 64 * 16;
+static_assert(kS3F5 % 4 == 0 && kS3F6 % 4 == 0 && kS3F7 % 4 == 0, "16-byte loads from the Winograd filter blocks");
 constexpr int kS3Feat = 1568;
 
 // Crop -> conv1 -> pool -> conv2 -> pool -> conv3 for each surviving window; writes the 1568 conv3
 // activations of the window (order [channel][row][col]) to `feat`.
-template <int ACT, bool WINO>
+template <int ACT, int WINO>
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(3, 3)))
 void eval3_conv_kernel(const uint8_t *__restrict__ frame, int fw, int fh, int pitch, const LevelDev *__restrict__ levels,
                        int n_levels, const uint32_t *__restrict__ idx, const int32_t *__restrict__ d_n, int n_max,
@@ -325,6 +420,8 @@ void eval3_conv_kernel(const uint8_t *__restrict__ frame, int fw, int fh, int pi
     const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, g = lane >> 4, j = lane & 15;
     for (int pb = tid; pb < 484; pb += kThreads)
         sLut[pb] = (uint32_t)(2 * (pb / 22) * kCropW + 2 * (pb % 22)) | (uint32_t)((pb / 22) * kP1Row + pb % 22) << 16;
+    if (WINO == 2)                                                   // columns 22, 23 of the pooled conv1 map: read, never written
+        for (int e = tid; e < 16 * 22 * 2; e += kThreads) sB[(e >> 1) * kP1Row + 22 + (e & 1)] = 0.0f;
     const int in_lane = ((j >> 1) & 1) * kCropW + (j & 1) + g;     // A rows: line and column of the block, plus the tap column g
     // (the first barrier of the gather below orders the table before its readers)
 
@@ -392,7 +489,11 @@ void eval3_conv_kernel(const uint8_t *__restrict__ frame, int fw, int fh, int pi
         // ---- conv2 5x5 16->32 + pool (overwrites the crop with the pooled map)
         const int wslot = (wave + rot + blockIdx.x + (blockIdx.x >> 8)) & 3;
         const float bias2_lo = wt[s3::B2 + j], bias2_hi = wt[s3::B2 + 16 + j];
-        if (WINO) {
+        if (WINO == 2) {
+            // six M-tiles of eight units: a whole tile per wave, then half (one n-tile) of tile 4 or 5 per wave
+            s3_conv2_wino4_tile<ACT, 2>(sB, sA, frag + kS3F7, wslot, 0, lane, wt + s3::B2);
+            s3_conv2_wino4_tile<ACT, 1>(sB, sA, frag + kS3F7, 4 + (wslot >> 1), wslot & 1, lane, wt + s3::B2);
+        } else if (WINO == 1) {
             // eleven M-tiles of eight pooling blocks, dealt round-robin from a slot that rotates per window.
             // (Two tiles per pass over the filter halve its L2 traffic but spill registers: measured slower.)
 #pragma unroll 1
@@ -553,6 +654,30 @@ void eval3_make_fragments(const float *w, float *f)
                 const int cq = c >> 2, g = c & 3, nt = oc >> 4, j = oc & 15, lane = g * 16 + j, ks = a * 8 + cq;
                 for (int b = 0; b < 4; ++b) f[kS3F6 + ((nt * 24 + ks) * 64 + lane) * 4 + b] = (float)u[b];
             }
+    // F(4,5) conv2 weights: G[j][l] = a_j^l / prod_{i != j} (a_j - a_i) for the finite points, last row picks the leading tap
+    {
+        const double pts[7] = {0, 1, -1, 2, -2, 0.5, -0.5};
+        double G4[8][5];
+        for (int jj = 0; jj < 7; ++jj) {
+            double den = 1;
+            for (int ii = 0; ii < 7; ++ii)
+                if (ii != jj) den *= pts[jj] - pts[ii];
+            double pw = 1;
+            for (int l = 0; l < 5; ++l) { G4[jj][l] = pw / den; pw *= pts[jj]; }
+        }
+        for (int l = 0; l < 5; ++l) G4[7][l] = l == 4 ? 1.0 : 0.0;
+        for (int oc = 0; oc < 32; ++oc)
+            for (int c = 0; c < 16; ++c)
+                for (int a = 0; a < 5; ++a) {
+                    const float *k = w + s3::W2 + ((oc * 16 + c) * 5 + a) * 5;
+                    const int cq = c >> 2, g = c & 3, nt = oc >> 4, j = oc & 15, lane = g * 16 + j;
+                    for (int b = 0; b < 8; ++b) {
+                        double acc = 0;
+                        for (int l = 0; l < 5; ++l) acc += G4[b][l] * (double)k[l];
+                        f[kS3F7 + ((a * 4 + cq) * 64 + lane) * 16 + nt * 8 + b] = (float)acc;
+                    }
+                }
+    }
 }
 
 // =================================================================================================
@@ -822,11 +947,14 @@ hipError_t launch_eval3_mfma(cnnc_ctx *c, hipStream_t st)
     hipLaunchKernelGGL(eval3_fc_kernel<ACT>, dim3(fc_grid(c)), dim3(kThreads), 0, st, c->d_feat[1], &c->d_cnt->n[1], \
                        c->max_surv, c->d_wt[2], c->d_frag[1], c->d_eval[1])
 #define CNNC_E3W(ACT)                     \
-    if (c->eval_impl == 2) {              \
-        constexpr bool WINO = true;       \
+    if (c->eval_impl == 3) {              \
+        constexpr int WINO = 2;           \
+        CNNC_E3(ACT);                     \
+    } else if (c->eval_impl == 2) {       \
+        constexpr int WINO = 1;           \
         CNNC_E3(ACT);                     \
     } else {                              \
-        constexpr bool WINO = false;      \
+        constexpr int WINO = 0;           \
         CNNC_E3(ACT);                     \
     }
     switch (c->act) {

@@ -77,8 +77,8 @@ def test_vector_alu_variant_of_later_stages():
 
 @pytest.mark.parametrize("act", [I.ACT_RATIONAL, I.ACT_TANH])
 def test_direct_sum_variant_of_stage3(act):
-    """cnnc_set_eval_impl(1): the matrix-core kernels with stage-3 conv2 as a direct sum (the default, 2, uses the
-    Winograd F(2,5) form for it); also reports how far the default's scores are from the oracle's."""
+    """cnnc_set_eval_impl(1): the matrix-core kernels with stage-3 conv2 as a direct sum; 2 and 3 use the Winograd
+    F(2,5) and F(4,5) forms for it.  Also reports how far each one's scores are from the oracle's."""
     torch = _torch()
     c = I.CONFIGS[0]
     casc = I.default_cascade(act)
@@ -88,7 +88,7 @@ def test_direct_sum_variant_of_stage3(act):
     ctx = _ctx(casc, W, c["width"], c["height"])
     ctx.set_params(c["min_face"], c["scale_step"], tr.thr)
     ref3 = dict(zip(tr.idx2.tolist(), tr.score3.tolist()))
-    for impl in (1, 2):
+    for impl in (1, 2, 3):
         ctx.set_eval_impl(impl)
         g = run_gpu_steps(ctx, torch.from_numpy(frame).cuda(), tr.thr)
         compare_with_trace(g, tr, frame, casc, W)
