@@ -47,6 +47,8 @@ def main():
     ap.add_argument("--workload", default="uhd")
     ap.add_argument("--q1", type=float, default=0.02, help="stage-1 survival quantile (the benchmark's rule: 2 %%)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-ingest", action="store_true", help="skip the host-memory ingest leg (its frames overlap on several "
+                    "streams, which stretches per-kernel durations in a profiler trace)")
     ap.add_argument("--eval-impl", type=int, default=None, help="cnnc_set_eval_impl value (default: the library's)")
     ap.add_argument("--fused-stage1", type=int, default=None, help="cnnc_set_fused_stage1 value (default: the library's)")
     a = ap.parse_args()
@@ -227,7 +229,7 @@ def main():
     # frames from pinned host memory through the ingest ring: copy in + path + results out, PCIe included
     ingest = {}
     D = F + 1                                    # one slot more than frames computing: its copy runs ahead
-    for use_graph in (False, True):
+    for use_graph in (() if a.no_ingest else (False, True)):
         pipe = P.Pipe(casc, W, cfg["width"], cfg["height"], 262144, depth=D, use_graph=use_graph)
         pipe.set_params(cfg["min_face"], cfg["scale_step"], tr.thr)
         for j in range(D):                       # the producer's frames sit in the pinned buffers already

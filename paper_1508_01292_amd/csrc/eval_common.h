@@ -7,6 +7,15 @@ namespace cnnc {
 namespace evalc {
 constexpr int kThreads = 256;
 
+// The value itself, in a form the compiler must treat as new at every call: index arithmetic that depends on it is
+// then recomputed where it is used instead of being hoisted out of the per-window loop, kept in registers across all
+// layers and spilled to scratch memory.
+__device__ __forceinline__ int fresh(int x)
+{
+    asm volatile("" : "+v"(x));
+    return x;
+}
+
 // Sample positions of one crop axis: tab[i] = (index of left pixel << 9) | weight of the right one (0..256).
 // The left index never is the last pixel of the axis: a position clamped onto it is stored as the pixel
 // before with weight 256, which blends to the same integer and lets every reader fetch index and index + 1.
@@ -59,7 +68,7 @@ __device__ __forceinline__ void crop_issue(const uint8_t *__restrict__ frame, in
 template <int N>
 __device__ __forceinline__ void crop_finish(const CropPixels<N> &px, const uint32_t *sTab, float *sCrop)
 {
-    const int tid = threadIdx.x;
+    const int tid = fresh(threadIdx.x);
 #pragma unroll
     for (int it = 0; it < CropPixels<N>::kIt; ++it) {
         const int e = it * kThreads + tid, ec = min(e, N * N - 1);

@@ -515,7 +515,7 @@ void eval3_conv_kernel(const uint8_t *__restrict__ frame, int fw, int fh, int pi
 
         // ---- conv3 3x3 32->32 and out to global memory
         float *dst = feat + (size_t)crop * kS3Feat;
-        if (WINO) s3_conv3_wino<ACT>(sA, frag + kS3F6, wt, dst, wave, lane);
+        if (WINO) s3_conv3_wino<ACT>(sA, frag + kS3F6, wt, dst, wave, fresh(lane));
         else s3_conv3_direct(sA, sB, frag + kS3F3, wave, lane);
         CNNC_PROBE(7);
         __syncthreads();                                   // conv3 has released the pooled map (and, direct form, written its partial sums)
