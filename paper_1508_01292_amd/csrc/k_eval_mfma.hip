@@ -537,13 +537,15 @@ void eval3_conv_kernel(const uint8_t *__restrict__ frame, int fw, int fh, int pi
 #endif
 }
 
-// fc 1568->64 + f, fc 64->1 for 16 windows per workgroup: the four waves split K, partial tiles meet in LDS.
+// fc 1568->64 + f, fc 64->1 for 16 windows per workgroup: eight waves split K (the loop is bound by the latency of its
+// loads, so more waves with their own loads in flight shorten it), partial tiles meet in LDS.
+constexpr int kFcThreads = 512, kFcWaves = kFcThreads / 64;
 template <int ACT>
-__global__ __launch_bounds__(kThreads)
+__global__ __launch_bounds__(kFcThreads)
 void eval3_fc_kernel(const float *__restrict__ feat, const int32_t *__restrict__ d_n, int n_max,
                      const float *__restrict__ wt, const float *__restrict__ frag, float *__restrict__ out)
 {
-    __shared__ float sPart[4][16][65];
+    __shared__ float sPart[kFcWaves][16][65];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, g = lane >> 4, j = lane & 15;
     const int n = min(*d_n, n_max);
     const float4 *wf = reinterpret_cast<const float4 *>(frag + kS3F4) + lane;     // [chunk][n-tile][lane] float4
@@ -552,7 +554,7 @@ void eval3_fc_kernel(const float *__restrict__ feat, const int32_t *__restrict__
         const float4 *ap = reinterpret_cast<const float4 *>(feat + (size_t)row * kS3Feat) + g;
         floatx4 acc[4] = {floatx4{0, 0, 0, 0}, floatx4{0, 0, 0, 0}, floatx4{0, 0, 0, 0}, floatx4{0, 0, 0, 0}};
 #pragma unroll 2
-        for (int ch = wave; ch < 98; ch += 4) {
+        for (int ch = wave; ch < 98; ch += kFcWaves) {
             const float4 a4 = ap[ch * 4];
             const float a[4] = {a4.x, a4.y, a4.z, a4.w};
             float4 b4[4];
@@ -571,13 +573,15 @@ void eval3_fc_kernel(const float *__restrict__ feat, const int32_t *__restrict__
 #pragma unroll
             for (int r = 0; r < 4; ++r) sPart[wave][4 * g + r][nt * 16 + j] = acc[nt][r];
         __syncthreads();
-        {
+        if (tid < 256) {
             const int r = tid >> 4, c0 = tid & 15;
             float part = 0.0f;
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
                 const int c = c0 + 16 * q;
-                const float h = sPart[0][r][c] + sPart[1][r][c] + sPart[2][r][c] + sPart[3][r][c] + wt[s3::B4 + c];
+                float h = wt[s3::B4 + c];
+#pragma unroll
+                for (int w = 0; w < kFcWaves; ++w) h += sPart[w][r][c];
                 part = fmaf(wt[s3::W5 + c], act_f<ACT>(h), part);
             }
 #pragma unroll
@@ -944,7 +948,7 @@ hipError_t launch_eval3_mfma(cnnc_ctx *c, hipStream_t st)
                        c->fpitch, c->d_levels, c->n_levels, c->d_idx[1], &c->d_cnt->n[1], c->max_surv, c->d_wt[2], \
                        c->d_frag[1], c->d_feat[1]);                                                                \
     }                                                                                                             \
-    hipLaunchKernelGGL(eval3_fc_kernel<ACT>, dim3(fc_grid(c)), dim3(kThreads), 0, st, c->d_feat[1], &c->d_cnt->n[1], \
+    hipLaunchKernelGGL(eval3_fc_kernel<ACT>, dim3(fc_grid(c)), dim3(kFcThreads), 0, st, c->d_feat[1], &c->d_cnt->n[1], \
                        c->max_surv, c->d_wt[2], c->d_frag[1], c->d_eval[1])
 #define CNNC_E3W(ACT)                     \
     if (c->eval_impl == 3) {              \

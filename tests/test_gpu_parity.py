@@ -6,7 +6,7 @@ import pytest
 import cnnc_inputs as I
 from oracle import oracle as O
 
-from parity import (assert_scores, assert_survivors, boxes_of, compare_with_trace, greedy_merge_check,
+from parity import (ATOL, RTOL, assert_scores, assert_survivors, boxes_of, compare_with_trace, greedy_merge_check,
                     run_gpu_steps)
 
 pytestmark = pytest.mark.gpu
@@ -160,7 +160,17 @@ def test_every_window_survives_and_capacity_overflow():
         trn = O.detect(frame, casc, W, 12, 1.5, thr=thr, min_neighbors=mn, iou=iou)
         ctx.set_params(12, 1.5, thr, merge_iou=iou, min_neighbors=mn)
         det = [d.as_dict() for d in ctx.detect(torch.from_numpy(frame).cuda(), 8192)]
-        assert [(d["index"], d["neighbors"]) for d in det] == [(d["index"], d["neighbors"]) for d in trn.det], (mn, iou)
+        got = [(d["index"], d["neighbors"]) for d in det]
+        if got != [(d["index"], d["neighbors"]) for d in trn.det]:
+            # with every window accepted many scores lie closer together than the score tolerance, so the greedy
+            # order may legitimately differ from the oracle's: then the result must be the greedy merge of the
+            # library's own accepted windows and fp32 scores (numpy restatement of the rule in parity.py)
+            s3 = np.sort(np.asarray(trn.score3_kept, np.float64))
+            assert np.min(np.diff(s3)) <= 2 * (ATOL + RTOL * np.abs(s3).max()), (mn, iou)
+            idx3, sc3 = ctx.get_survivors(3)
+            bx, by, bs, _ = boxes_of(O.build_pyramid(frame, 12, 1.5), idx3)
+            valid = [(int(idx3[p]), int(n)) for p, n in greedy_merge_check(bx, by, bs, sc3, idx3, iou=iou, min_neighbors=mn)]
+            assert got == valid, (mn, iou)
     ctx.close()
     small = _ctx(casc, W, 48, 40, 100)
     small.set_params(12, 1.5, thr)
