@@ -363,24 +363,27 @@ __device__ __forceinline__ void s3_conv3_wino(const float *sP2, const float *__r
     const float *dptr = sP2 + g * kP2ChW + (p >> 2) * kP2RowW + 2 * (p & 3);
     floatx4 acc[4] = {floatx4{0, 0, 0, 0}, floatx4{0, 0, 0, 0}, floatx4{0, 0, 0, 0}, floatx4{0, 0, 0, 0}};
     const float4 *up = reinterpret_cast<const float4 *>(U3F) + nt * 24 * 64 + lane;   // [n-tile][k-step][lane] four points
-    float4 ring[4] = {up[0], up[64], up[128], up[192]};
-    up += 256;
+    // filter fragments run eight k-steps ahead: a step is only four matrix instructions long, and the loads come from L2
+    float4 ring[8] = {up[0], up[64], up[128], up[192], up[256], up[320], up[384], up[448]};
+    up += 512;
+    float2 r0 = *reinterpret_cast<const float2 *>(dptr), r1 = *reinterpret_cast<const float2 *>(dptr + 2);
 #pragma unroll
     for (int ks = 0; ks < 24; ++ks) {                            // k-step = kernel row a (3) x channel quad cq (8)
-        const int a = ks >> 3, cq = ks & 7;
-        const float4 u = ring[ks & 3];
-        if (ks + 4 < 24) {
-            ring[ks & 3] = *up;
+        const float4 u = ring[ks & 7];
+        if (ks + 8 < 24) {
+            ring[ks & 7] = *up;
             up += 64;
             asm volatile("" : "+v"(up));                          // one running address instead of twenty precomputed ones
         }
+        const int kn = ks + 1 < 24 ? ks + 1 : ks;                 // input row of the next step, fetched one step ahead
+        const float *nrow = dptr + (kn & 7) * 4 * kP2ChW + (kn >> 3) * kP2RowW;
+        const float2 n0 = *reinterpret_cast<const float2 *>(nrow), n1 = *reinterpret_cast<const float2 *>(nrow + 2);
         asm volatile("" ::: "memory");                            // keeps the prefetch distance: loads stay where written
-        const float *row = dptr + cq * 4 * kP2ChW + a * kP2RowW;
-        const float2 r0 = *reinterpret_cast<const float2 *>(row), r1 = *reinterpret_cast<const float2 *>(row + 2);
         acc[0] = CNNC_MFMA(r0.x - r1.x, u.x, acc[0]);
         acc[1] = CNNC_MFMA(r0.y + r1.x, u.y, acc[1]);
         acc[2] = CNNC_MFMA(r1.x - r0.y, u.z, acc[2]);
         acc[3] = CNNC_MFMA(r0.y - r1.y, u.w, acc[3]);
+        r0 = n0; r1 = n1;
     }
     const int oc = 16 * nt + j;
     const float bias = wt[s3::B3 + oc];
