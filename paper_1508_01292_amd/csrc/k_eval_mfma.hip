@@ -556,7 +556,6 @@ void eval3_fc_kernel(const float *__restrict__ feat, const int32_t *__restrict__
         const int row = min(tile * 16 + j, n - 1);
         const float4 *ap = reinterpret_cast<const float4 *>(feat + (size_t)row * kS3Feat) + g;
         floatx4 acc[4] = {floatx4{0, 0, 0, 0}, floatx4{0, 0, 0, 0}, floatx4{0, 0, 0, 0}, floatx4{0, 0, 0, 0}};
-#pragma unroll 2
         for (int ch = wave; ch < 98; ch += kFcWaves) {
             const float4 a4 = ap[ch * 4];
             const float a[4] = {a4.x, a4.y, a4.z, a4.w};
