@@ -190,7 +190,8 @@ int cnnc_get_timings(cnnc_ctx *ctx, double *ms_sum, int32_t *calls);
 
 /* Which kernels cnnc_eval_stage uses.  3 (default): implicit-GEMM kernels on the matrix cores (fp32 MFMA) with the
  * 5x5, 16 -> 32 convolution of stage 3 evaluated by the Winograd minimal-filtering algorithm F(4,5) along rows and its
- * 3x3, 32 -> 32 convolution by F(2,3); 2: the same with F(2,5) for the 5x5 convolution; 1: the matrix-core kernels with
+ * 3x3, 32 -> 32 convolution by F(2,3), and the 3x3, 8 -> 16 convolution of stage 2 by F(4,3); 2: F(2,5) for the 5x5
+ * convolution of stage 3, F(2,3) for its 3x3 one, direct sums in stage 2; 1: the matrix-core kernels with
  * direct sums only; 0: direct convolution on the vector ALU.  Same results within fp32 rounding (about 1e-6 on a
  * score); kept so that the choice stays measurable (the paper's Section 3.4 argues for code specialised per network
  * and processor). */

@@ -705,11 +705,13 @@ __device__ __forceinline__ void wave_sync()
 }
 }  // namespace
 
-// Fragment buffer of stage 2 (floats): conv1 [8][64], conv2 [9 taps][2 quads][64], fc [16][2][64][4].
-constexpr int kS2F1 = 0, kS2F2 = kS2F1 + 8 * 64, kS2F3 = kS2F2 + 18 * 64, kS2FragFloats = kS2F3 + 16 * 2 * 64 * 4;
+// Fragment buffer of stage 2 (floats): conv1 [8][64], conv2 [9 taps][2 quads][64], fc [16][2][64][4], and the
+// Winograd F(4,3) form of conv2 [3 kernel rows][2 quads][6 points][64].
+constexpr int kS2F1 = 0, kS2F2 = kS2F1 + 8 * 64, kS2F3 = kS2F2 + 18 * 64, kS2F4 = kS2F3 + 16 * 2 * 64 * 4,
+              kS2FragFloats = kS2F4 + 36 * 64;
 constexpr int kS2Feat = 256;
 
-template <int ACT>
+template <int ACT, bool WINO>
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(3, 3)))
 void eval2_conv_kernel(const uint8_t *__restrict__ frame, int fw, int fh, int pitch, const LevelDev *__restrict__ levels,
                        int n_levels, const uint32_t *__restrict__ idx, const int32_t *__restrict__ d_n, int n_max,
@@ -729,11 +731,11 @@ void eval2_conv_kernel(const uint8_t *__restrict__ frame, int fw, int fh, int pi
     float *sP1 = sCrop + kS2Crop + kS2Tab;
     float *sP2 = sCrop;                          // pooled conv2 output [16][16] re-uses the crop's space
 
-    float b1f[8], b2f[18];
+    float b1f[8], b2f[WINO ? 36 : 18];
 #pragma unroll
     for (int s = 0; s < 8; ++s) b1f[s] = frag[kS2F1 + s * 64 + lane];
 #pragma unroll
-    for (int s = 0; s < 18; ++s) b2f[s] = frag[kS2F2 + s * 64 + lane];
+    for (int s = 0; s < (WINO ? 36 : 18); ++s) b2f[s] = frag[(WINO ? kS2F4 : kS2F2) + s * 64 + lane];
     const float bias1 = wt[s2::B1 + (j >> 1)], bias2 = wt[s2::B2 + j];
     // conv1 runs with N = 8 channels x 2 adjacent output columns (the two columns of a pooling block), so no
     // half of the matrix tile is idle: K = 5 rows x 6 input columns = 30 -> 8 steps of 4.
@@ -805,8 +807,45 @@ void eval2_conv_kernel(const uint8_t *__restrict__ frame, int fw, int fh, int pi
         }
         wave_sync();
 
-        // ---- conv2 3x3 8->16 + pool: 16 pooling blocks = 4 tiles
-        {
+        // ---- conv2 3x3 8->16 + pool
+        if (WINO) {
+            // Winograd F(4, 3) along the rows (points 0, 1, -1, 2, -2, infinity; BT and the pairing of rows as in the
+            // F(2, 5) form of stage 3, AT = [1 1 1 1 1 0; 0 1 -1 2 -2 0; 0 1 1 4 4 0; 0 1 -1 8 -8 1]): the 8 x 8 output
+            // map is 16 rows of the GEMM (8 output rows x 2 groups of four columns) = one tile, K = 8 channels x 3 kernel
+            // rows = 6 steps, six GEMMs: 36 matrix instructions instead of 72.  Row i of the tile = output row
+            // 2 (i / 4) + i % 2, column group (i / 2) % 2, so a lane's registers hold both rows of two pooling-block
+            // pairs and the four columns of each: pooling stays in registers.
+            const int i = lane & 15, unit = i >> 1, Y = unit >> 1, xg = unit & 1;
+            const float *dptr = sP1 + g * kQ1Ch + (2 * Y + (i & 1)) * kQ1Row + 4 * xg;
+            floatx4 acc[6];
+#pragma unroll
+            for (int b = 0; b < 6; ++b) acc[b] = floatx4{0, 0, 0, 0};
+#pragma unroll
+            for (int a = 0; a < 3; ++a)
+#pragma unroll
+                for (int cq = 0; cq < 2; ++cq) {
+                    const float *row = dptr + cq * 4 * kQ1Ch + a * kQ1Row;
+                    const float4 c0 = *reinterpret_cast<const float4 *>(row);
+                    const float2 c1 = *reinterpret_cast<const float2 *>(row + 4);
+                    const float e1 = fmaf(-4.0f, c0.z, c1.x), o1 = fmaf(-4.0f, c0.y, c0.w);
+                    const float e2 = c1.x - c0.z, o2 = c0.w - c0.y;
+                    const float v[6] = {fmaf(4.0f, c0.x, fmaf(-5.0f, c0.z, c1.x)), e1 + o1, e1 - o1, fmaf(2.0f, o2, e2),
+                                        fmaf(-2.0f, o2, e2), fmaf(4.0f, c0.y, fmaf(-5.0f, c0.w, c1.y))};
+#pragma unroll
+                    for (int b = 0; b < 6; ++b) acc[b] = CNNC_MFMA(v[b], b2f[(a * 2 + cq) * 6 + b], acc[b]);
+                }
+            const floatx4 s1 = acc[1] + acc[2], d1 = acc[1] - acc[2], s2 = acc[3] + acc[4], d2 = acc[3] - acc[4];
+            const floatx4 Y0 = acc[0] + s1 + s2, Y1 = d1 + 2.0f * d2, Y2 = s1 + 4.0f * s2, Y3 = d1 + 8.0f * d2 + acc[5];
+#pragma unroll
+            for (int sub = 0; sub < 2; ++sub) {                  // registers 2 sub, 2 sub + 1: the two rows of unit 2 g + sub
+                const int u = 2 * g + sub, py = u >> 1, px = 2 * (u & 1);
+                const float left = fmaxf(fmaxf(Y0[2 * sub], Y1[2 * sub]), fmaxf(Y0[2 * sub + 1], Y1[2 * sub + 1]));
+                const float right = fmaxf(fmaxf(Y2[2 * sub], Y3[2 * sub]), fmaxf(Y2[2 * sub + 1], Y3[2 * sub + 1]));
+                sP2[j * 16 + 4 * py + px] = act_f<ACT>(left + bias2);
+                sP2[j * 16 + 4 * py + px + 1] = act_f<ACT>(right + bias2);
+            }
+        } else {
+            // direct sums: 16 pooling blocks = 4 tiles
             floatx4 acc[4];
             int abase[4];
 #pragma unroll
@@ -909,6 +948,17 @@ void eval2_make_fragments(const float *w, float *f)
                     const int g = lane >> 4, j = lane & 15;
                     f[kS2F3 + ((ch * 2 + nt) * 64 + lane) * 4 + s] = w[s2::W3 + (nt * 16 + j) * 256 + 16 * ch + 4 * g + s];
                 }
+    // conv2 in the Winograd F(4,3) domain along the kernel columns, points 0, 1, -1, 2, -2, infinity (fp64, then rounded)
+    static const double G[6][3] = {{1.0 / 4, 0, 0}, {-1.0 / 6, -1.0 / 6, -1.0 / 6}, {-1.0 / 6, 1.0 / 6, -1.0 / 6},
+                                   {1.0 / 24, 1.0 / 12, 1.0 / 6}, {1.0 / 24, -1.0 / 12, 1.0 / 6}, {0, 0, 1}};
+    for (int a = 0; a < 3; ++a)
+        for (int cq = 0; cq < 2; ++cq)
+            for (int b = 0; b < 6; ++b)
+                for (int lane = 0; lane < 64; ++lane) {
+                    const int g = lane >> 4, j = lane & 15, c = 4 * cq + g;
+                    const float *k = w + s2::W2 + ((j * 8 + c) * 3 + a) * 3;
+                    f[kS2F4 + ((a * 2 + cq) * 6 + b) * 64 + lane] = (float)(G[b][0] * k[0] + G[b][1] * k[1] + G[b][2] * k[2]);
+                }
 }
 
 namespace {
@@ -980,17 +1030,26 @@ hipError_t launch_eval2_mfma(cnnc_ctx *c, hipStream_t st)
 #define CNNC_E2(ACT)                                                                                              \
     {                                                                                                             \
         ScopedTimer timer_(c, CNNC_T_STAGE2_CONV, st);                                                            \
-        hipLaunchKernelGGL(eval2_conv_kernel<ACT>, dim3(grid), dim3(kThreads), 0, st, c->d_frame, c->fw, c->fh,         \
+        hipLaunchKernelGGL((eval2_conv_kernel<ACT, WINO>), dim3(grid), dim3(kThreads), 0, st, c->d_frame, c->fw, c->fh, \
                        c->fpitch, c->d_levels, c->n_levels, c->d_idx[0], &c->d_cnt->n[0], c->max_surv, c->d_wt[1], \
                        c->d_frag[0], c->d_feat[0]);                                                                \
     }                                                                                                             \
     hipLaunchKernelGGL(eval2_fc_kernel<ACT>, dim3(fc_grid(c)), dim3(kThreads), 0, st, c->d_feat[0], &c->d_cnt->n[0], \
                        c->max_surv, c->d_wt[1], c->d_frag[0], c->d_eval[0])
-    switch (c->act) {
-    case CNNC_ACT_RATIONAL: CNNC_E2(CNNC_ACT_RATIONAL); break;
-    case CNNC_ACT_SCALED_TANH: CNNC_E2(CNNC_ACT_SCALED_TANH); break;
-    default: CNNC_E2(CNNC_ACT_TANH); break;
+#define CNNC_E2W(ACT)                     \
+    if (c->eval_impl == 3) {              \
+        constexpr bool WINO = true;       \
+        CNNC_E2(ACT);                     \
+    } else {                              \
+        constexpr bool WINO = false;      \
+        CNNC_E2(ACT);                     \
     }
+    switch (c->act) {
+    case CNNC_ACT_RATIONAL: CNNC_E2W(CNNC_ACT_RATIONAL); break;
+    case CNNC_ACT_SCALED_TANH: CNNC_E2W(CNNC_ACT_SCALED_TANH); break;
+    default: CNNC_E2W(CNNC_ACT_TANH); break;
+    }
+#undef CNNC_E2W
 #undef CNNC_E2
     return hipGetLastError();
 }
