@@ -34,7 +34,7 @@ PEAK_FP32_MFMA = 157.3     # TFLOP/s, published dense fp32 matrix figure
 # HBM bytes per launch from the rocprofv3 FETCH_SIZE / WRITE_SIZE passes summarised in
 # profiles/hbm_traffic_uhd_pmc.txt (read + written, scaled by the copy-kernel calibration); None where
 # that workload was not measured.
-MEASURED_TRAFFIC = {("stage3_conv", "uhd"): 37.79e6 + 30.14e6, ("stage2_conv", "uhd"): 70.43e6 + 17.54e6,
+MEASURED_TRAFFIC = {("stage3_conv", "uhd"): 38.41e6 + 30.14e6, ("stage2_conv", "uhd"): 70.46e6 + 17.54e6,
                     ("stage1", "uhd"): 5.72e6 + 4.21e6, ("pyramid", "uhd"): 17.02e6 + 1.22e6}
 
 
