@@ -193,6 +193,32 @@ def test_every_window_survives_and_capacity_overflow():
     small.close()
 
 
+def test_merge_of_a_long_dense_list():
+    """Every window of a small frame accepted: about thirteen thousand heavily overlapping boxes, which takes the
+    merge through its long-list form; the result must be the greedy merge of exactly those boxes."""
+    torch = _torch()
+    casc = I.default_cascade()
+    W = I.draw_weights(casc, 8)
+    frame = I.make_frame(100, 80, 21)
+    thr = (-1e30, -1e30, -1e30)
+    n = O.pyramid_layout(100, 80, 12.0, 1.25).score_off[-1]
+    assert n > 8192
+    ctx = _ctx(casc, W, 100, 80, 20000)
+    for iou, mn in ((0.3, 1), (0.7, 2)):
+        ctx.set_params(12.0, 1.25, thr, merge_iou=iou, min_neighbors=mn)
+        det = [d.as_dict() for d in ctx.detect(torch.from_numpy(frame).cuda(), 20000)]
+        idx3, sc3 = ctx.get_survivors(3)
+        assert len(idx3) == n
+        bx, by, bs, _ = boxes_of(O.build_pyramid(frame, 12.0, 1.25), idx3)
+        valid = [(int(idx3[p]), int(k)) for p, k in greedy_merge_check(bx, by, bs, sc3, idx3, iou=iou, min_neighbors=mn)]
+        assert [(d["index"], d["neighbors"]) for d in det] == valid, (iou, mn)
+        # and against the oracle's own merge of the same boxes and fp32 scores
+        kept, nbs = O.merge(bx, by, bs, sc3, idx3.astype(np.int64), iou=iou, min_neighbors=mn)
+        assert [(int(idx3[p]), int(k)) for p, k in zip(kept, nbs)] == valid
+        print("   %d boxes -> %d detections at iou %.1f, min_neighbors %d" % (n, len(det), iou, mn), flush=True)
+    ctx.close()
+
+
 def test_detection_array_too_small_reports_overflow():
     import paper_1508_01292_amd as P
     torch = _torch()
