@@ -41,8 +41,8 @@ MEASURED_TRAFFIC = {("stage3_conv", "uhd"): 38.41e6 + 30.14e6, ("stage2_conv", "
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=300)
-    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--steps", type=int, default=2000)
+    ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--inflight", type=int, default=3, help="frames in flight on separate streams")
     ap.add_argument("--workload", default="uhd")
     ap.add_argument("--q1", type=float, default=0.02, help="stage-1 survival quantile (the benchmark's rule: 2 %%)")
