@@ -281,6 +281,10 @@ const char *cnnc_pipe_last_error(const cnnc_pipe *pipe);
  * current device's default stream, allocates and frees 2 GiB, synchronises.  Outputs are host pointers. */
 int cnnc_measure_peaks(double *mfma_f32_tflops, double *valu_f32_tflops, double *hbm_copy_gbs);
 
+/* For bindings: sizes in bytes of cnnc_layer, cnnc_stage_desc, cnnc_params, cnnc_det, cnnc_region, and the value of
+ * CNNC_T_COUNT, in that order, into out[0 .. n) (host; at most six are written).  Returns how many exist (6). */
+int cnnc_abi_sizes(int32_t *out, int n);
+
 const char *cnnc_last_error(const cnnc_ctx *ctx);
 const char *cnnc_version(void);
 

@@ -21,7 +21,7 @@ EXPORTS = [
     "cnnc_get_timings", "cnnc_set_eval_impl", "cnnc_measure_peaks", "cnnc_last_error", "cnnc_version",
     "cnnc_stage1_survivors", "cnnc_set_fused_stage1",
     "cnnc_scan_set_weights", "cnnc_scan_layout", "cnnc_scan_scoremap", "cnnc_get_scan_scoremap",
-    "cnnc_select_set_weights", "cnnc_select_run", "cnnc_select_fetch",
+    "cnnc_select_set_weights", "cnnc_select_run", "cnnc_select_fetch", "cnnc_abi_sizes",
     "cnnc_pipe_create", "cnnc_pipe_destroy", "cnnc_pipe_set_params", "cnnc_pipe_frame_buffer", "cnnc_pipe_submit",
     "cnnc_pipe_fetch", "cnnc_pipe_last_error",
 ]
@@ -371,6 +371,13 @@ class Pipe:
         n = C.c_int(0)
         self._check(lib().cnnc_pipe_fetch(self._h, C.c_int64(ticket), out, C.c_int(cap), C.byref(n)))
         return list(out[:n.value])
+
+
+def cnnc_abi_sizes():
+    """(sizeof cnnc_layer, cnnc_stage_desc, cnnc_params, cnnc_det, cnnc_region, CNNC_T_COUNT) as the library was built."""
+    out = (C.c_int32 * 6)()
+    n = lib().cnnc_abi_sizes(out, C.c_int(6))
+    return tuple(out[:n])
 
 
 def cnnc_measure_peaks():

@@ -66,3 +66,13 @@ def test_bench_refuses_more_than_one_gpu():
     import sys
     r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
     assert r.returncode != 0 and "ONE GPU" in r.stderr
+
+
+def test_struct_sizes_and_step_names_match_the_library():
+    """The ctypes mirrors of the C structs and the list of timed steps must be what the library was compiled with
+    (cnnc_get_timings writes CNNC_T_COUNT entries into arrays sized by the binding)."""
+    import ctypes as C
+    from paper_1508_01292_amd import binding as B
+    sizes = B.cnnc_abi_sizes()
+    assert sizes == (C.sizeof(B._Layer), C.sizeof(B._StageDesc), C.sizeof(B._Params), C.sizeof(B.Detection),
+                     C.sizeof(B.Region), len(B.STEP_NAMES))
