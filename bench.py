@@ -137,6 +137,19 @@ def main():
         c0.detect(dev_frame, 8192)
     torch.cuda.synchronize()
     latency_ms = (time.perf_counter() - t0) / n_lat * 1e3
+    # a stream: every frame on its own, to show how much the time depends on the content of the frame
+    per_frame = None
+    if len(dev_frames) > 1:
+        lat = []
+        for f in dev_frames:
+            c0.detect(f, 8192)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(5):
+                c0.detect(f, 8192)
+            torch.cuda.synchronize()
+            lat.append((time.perf_counter() - t0) / 5 * 1e3)
+        per_frame = {"min": min(lat), "mean": sum(lat) / len(lat), "max": max(lat)}
 
     # per-kernel times: HIP events recorded by the library on the stream the kernels run on
     c0.set_timing(True)
@@ -266,6 +279,7 @@ def main():
                    "frames_in_flight": F, "windows": n_windows, "survivors": [n1, n2, n3], "detections": n_det},
         "stage1_windows_per_s": n_windows / (ms["stage1"] * 1e-3) if ms["stage1"] > 0 else None,
         "latency_ms_single_frame": latency_ms,
+        "latency_ms_per_frame_of_stream": per_frame,
         "paper_geometry_stage1": {"window": "27x31", "step": 4, "positions": n_scan, "ms": ms_scan,
                                   "positions_per_s": n_scan / (ms_scan * 1e-3) if ms_scan > 0 else None,
                                   "bound": "alu", "achieved": tflops(SCAN_FLOP_PER_POSITION * n_scan, ms_scan),
