@@ -27,7 +27,9 @@
  * library bilinear for the region, closed forms of histogram equalisation,
  * library convolution for the mirrored response maps, the truth table of
  * eq. (2).  The choice of the readings themselves (resampling
- * convention, crop rectangle, merge rule) cannot be pinned to the authors'
+ * convention, crop rectangle, merge rule; in the paper's geometry the layer
+ * shapes, the width of the neighbourhood, the equalisation rule and how the
+ * mirror image's responses are combined) cannot be pinned to the authors'
  * detector: parity unpinned for those choices.
  */
 #include <math.h>
