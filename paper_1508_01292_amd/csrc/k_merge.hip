@@ -3,17 +3,25 @@
 // Greedy rule: in order of descending score (ties: ascending flat window index) a box not yet
 // absorbed is kept and absorbs every later box whose intersection exceeds merge_iou * union.
 //
-// The greedy rule is sequential as stated; here it is evaluated in parallel rounds that give the
-// same result.  With O the symmetric "overlaps more than the threshold" relation of the sorted
-// boxes, a box is KEPT once all earlier boxes overlapping it are known to be absorbed, and ABSORBED
-// once one earlier overlapping box is known to be kept.  The earliest undecided box is decided in
-// every round, so the rounds end; typical depth is a handful.  The neighbour count of a kept box
-// is the number of absorbed boxes whose FIRST kept overlapping predecessor it is, which is what the
-// sequential pass counts.
+// The greedy rule is sequential as stated; here it is evaluated in parallel in a way that gives the same
+// result.  With O the symmetric "overlaps more than the threshold" relation of the sorted boxes, a box is
+// KEPT once all earlier boxes overlapping it are known to be absorbed, and ABSORBED once one earlier
+// overlapping box is known to be kept.  The sorted list is taken in chunks of 1024 boxes, one per thread of a
+// single workgroup.  When a chunk starts every earlier chunk is final, so the chunk first looks for kept boxes
+// among the overlapping predecessors that lie in earlier chunks: the overlap kernel leaves them as one flat
+// array of (row, predecessor) pairs per chunk, which the threads share out evenly whatever the spread of pairs
+// over the rows (the bit rows themselves when a chunk has more pairs than the array holds).  What is left
+// depends on boxes of the same chunk only: the 16 words
+// of the chunk's diagonal block of the bit matrix sit in registers, the chunk's kept / absorbed bits in LDS,
+// and rounds repeat until no box of the chunk is undecided (the earliest undecided one is decided in every
+// round).  The neighbour count of a kept box is the number of absorbed boxes whose FIRST kept overlapping
+// predecessor it is, which is what the sequential pass counts.
 //
-// Launches: rank (counting sort position of every box, n^2 comparisons spread over the chip),
-// scatter into sorted order as frame-pixel boxes, overlap bit matrix, and the rounds + ordered
-// output in one workgroup.
+// Launches: rank (counting sort position of every box, n^2 comparisons spread over the chip), scatter into
+// sorted order as frame-pixel boxes, overlap bits (lower triangle) + predecessor lists, and the chunks +
+// ordered output in one workgroup.
+#include <climits>
+
 #include "cnnc_internal.h"
 
 namespace cnnc {
@@ -22,6 +30,10 @@ namespace {
 constexpr int kMergeCapMax = 32768;
 constexpr int kResolveThreads = 1024;
 constexpr int kRankSplit = 8;
+constexpr int kChunk = kResolveThreads;          // boxes decided together
+constexpr int kChunkWords = kChunk / 64;
+constexpr int kMaxChunks = kMergeCapMax / kChunk;
+constexpr int kPairCap = 128 * 1024;             // (row, predecessor in an earlier chunk) pairs held per chunk
 
 struct SortedBox {
     int32_t x, y, size;
@@ -33,8 +45,9 @@ struct MergeWs {
     SortedBox *sorted;
     int32_t *rank;     // zero between calls
     int32_t *nb;
-    unsigned long long *overlap;   // [cap][words]
-    int words;                      // 64-bit words per row
+    int32_t *npair;                 // [kMaxChunks] pairs of each chunk (may exceed kPairCap); zero between calls
+    uint32_t *pairs;                // [chunks of cap][kPairCap] row inside the chunk << 16 | predecessor, in no order
+    unsigned long long *overlap;   // [words][cap]: word w of row j at w * cap + j, for the words up to the row's own
 };
 
 __host__ __device__ inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
@@ -46,26 +59,31 @@ inline MergeWs carve(void *base, int cap)
     w.sorted = reinterpret_cast<SortedBox *>(p); p += align256(sizeof(SortedBox) * (size_t)cap);
     w.rank = reinterpret_cast<int32_t *>(p); p += align256(sizeof(int32_t) * (size_t)cap);
     w.nb = reinterpret_cast<int32_t *>(p); p += align256(sizeof(int32_t) * (size_t)cap);
+    w.npair = reinterpret_cast<int32_t *>(p); p += align256(sizeof(int32_t) * kMaxChunks);
+    w.pairs = reinterpret_cast<uint32_t *>(p); p += align256(sizeof(uint32_t) * (size_t)((cap + kChunk - 1) / kChunk) * kPairCap);
     w.overlap = reinterpret_cast<unsigned long long *>(p);
-    w.words = (cap + 63) / 64;
     return w;
 }
 
 __device__ __forceinline__ int32_t round_half_up(double v) { return (int32_t)floor(__dadd_rn(v, 0.5)); }
 
-__device__ __forceinline__ bool overlaps(const SortedBox &a, const SortedBox &b, double thr)
+// Frames are at most 16384 pixels a side, so a box area stays below 2^29 and a union below 2^30.
+struct Rect { int32_t x0, y0, x1, y1; };
+
+__device__ __forceinline__ bool overlaps(const Rect &a, const Rect &b, double thr)
 {
-    const int64_t iw = min((int64_t)a.x + a.size, (int64_t)b.x + b.size) - max((int64_t)a.x, (int64_t)b.x);
-    const int64_t ih = min((int64_t)a.y + a.size, (int64_t)b.y + b.size) - max((int64_t)a.y, (int64_t)b.y);
+    const int32_t iw = min(a.x1, b.x1) - max(a.x0, b.x0), ih = min(a.y1, b.y1) - max(a.y0, b.y0);
     if (iw <= 0 || ih <= 0) return false;
-    const int64_t inter = iw * ih, uni = (int64_t)a.size * a.size + (int64_t)b.size * b.size - inter;
-    return (double)inter > __dmul_rn(thr, (double)uni);   // exact: 24-bit threshold times an integer below 2^29
+    const int32_t sa = a.x1 - a.x0, sb = b.x1 - b.x0;
+    const int32_t inter = iw * ih, uni = sa * sa + sb * sb - inter;
+    return (double)inter > __dmul_rn(thr, (double)uni);   // exact: 24-bit threshold times an integer below 2^30
 }
 }  // namespace
 
 size_t merge_workspace_bytes(int cap)
 {
     return align256(sizeof(SortedBox) * (size_t)cap) + 2 * align256(sizeof(int32_t) * (size_t)cap) +
+           align256(sizeof(int32_t) * kMaxChunks) + align256(sizeof(uint32_t) * (size_t)((cap + kChunk - 1) / kChunk) * kPairCap) +
            sizeof(unsigned long long) * (size_t)cap * ((cap + 63) / 64);
 }
 
@@ -73,7 +91,7 @@ size_t merge_workspace_bytes(int cap)
 __global__ __launch_bounds__(256)
 void merge_rank_kernel(const float *__restrict__ sc, const int32_t *__restrict__ d_n, int n_max, int32_t *__restrict__ rank)
 {
-    __shared__ float sS[256];
+    __shared__ __attribute__((aligned(16))) float sS[256];
     const int n = min(*d_n, n_max);
     if ((int)blockIdx.x * 256 >= n) return;
     const int i = blockIdx.x * 256 + threadIdx.x;
@@ -83,12 +101,16 @@ void merge_rank_kernel(const float *__restrict__ sc, const int32_t *__restrict__
     int r = 0;
     for (int jb = j0; jb < j1; jb += 256) {
         __syncthreads();
-        sS[threadIdx.x] = jb + (int)threadIdx.x < n ? sc[jb + threadIdx.x] : -INFINITY;
+        sS[threadIdx.x] = jb + (int)threadIdx.x < n ? sc[jb + threadIdx.x] : -INFINITY;   // the padding sorts after all
         __syncthreads();
-        const int m = min(256, j1 - jb);
-        for (int q = 0; q < m; ++q) {
-            const float t = sS[q];
-            r += (t > s || (t == s && jb + q < i)) ? 1 : 0;
+        const int ties = i - jb;                                  // entries q < ties of this tile win a tie with box i
+#pragma unroll 4
+        for (int q = 0; q < 256; q += 4) {
+            const float4 t = *reinterpret_cast<const float4 *>(&sS[q]);
+            r += (t.x > s || (t.x == s && q + 0 < ties)) ? 1 : 0;
+            r += (t.y > s || (t.y == s && q + 1 < ties)) ? 1 : 0;
+            r += (t.z > s || (t.z == s && q + 2 < ties)) ? 1 : 0;
+            r += (t.w > s || (t.w == s && q + 3 < ties)) ? 1 : 0;
         }
     }
     if (i < n && r) atomicAdd(&rank[i], r);
@@ -99,10 +121,11 @@ __global__ __launch_bounds__(256)
 void merge_scatter_kernel(const uint32_t *__restrict__ idx, const float *__restrict__ sc,
                           const int32_t *__restrict__ d_n, int n_max, const LevelDev *__restrict__ levels,
                           int n_levels, int32_t *__restrict__ rank, int32_t *__restrict__ nb,
-                          SortedBox *__restrict__ sorted)
+                          int32_t *__restrict__ npair, SortedBox *__restrict__ sorted)
 {
     const int n = min(*d_n, n_max);
     const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i < kMaxChunks) npair[i] = 0;
     if (i >= n) return;
     const int r = rank[i];
     rank[i] = 0;
@@ -123,87 +146,206 @@ void merge_scatter_kernel(const uint32_t *__restrict__ idx, const float *__restr
     sorted[r] = b;
 }
 
-// overlap[j][w] bit b = box j overlaps box 64 w + b beyond the threshold (j itself excluded).
-// Workgroups stride over the (64-row block, word) pairs that exist for the current n.
+// Word w of row j (at overlap[w * n_max + j]), bit b: box j overlaps box 64 w + b beyond the threshold (j itself
+// excluded), for the words up to the one that holds j.  Overlapping boxes of earlier chunks are also appended to
+// the pair array of the row's chunk.
+// A work item is a block of 64 rows times a group of G consecutive words, G = 1, 4 or 16 (a whole chunk of
+// columns) growing with n: its pairs take one reservation in the chunk's array, so that long lists do not queue
+// on the chunk's counter, while short lists still spread over the chip.  Workgroups (one wave each) stride
+// over the items.
 __global__ __launch_bounds__(64)
 void merge_overlap_kernel(const SortedBox *__restrict__ sorted, const int32_t *__restrict__ d_n, int n_max, float iou,
-                          unsigned long long *__restrict__ overlap, int words)
+                          unsigned long long *__restrict__ overlap, int32_t *__restrict__ npair,
+                          uint32_t *__restrict__ pairs)
 {
-    __shared__ SortedBox sCol[64];
+    __shared__ Rect sCol[64];
     const int n = min(*d_n, n_max);
     const int nb64 = (n + 63) / 64;
+    const int G = n <= 2048 ? 1 : (n <= 8192 ? 4 : kChunkWords);
+    const int lane = threadIdx.x;
     const double thr = (double)iou;
-    for (int p = blockIdx.x; p < nb64 * nb64; p += gridDim.x) {
-        const int j = (p / nb64) * 64 + threadIdx.x, w = p % nb64;
-        const int c = w * 64 + threadIdx.x;
-        __syncthreads();
-        if (c < n) sCol[threadIdx.x] = sorted[c];
-        __syncthreads();
+    // Row block rb has rb / G + 1 groups.  The items are numbered row block by row block: the G row blocks
+    // q G .. q G + G - 1 have q + 1 groups each and start at item G q (q + 1) / 2.
+    const int qn = (nb64 + G - 1) / G;                            // number of such sets of row blocks, the last may be short
+    const int n_items = G * (qn - 1) * qn / 2 + (nb64 - (qn - 1) * G) * qn;
+    for (int p = blockIdx.x; p < n_items; p += gridDim.x) {
+        int q = (int)((sqrtf(8.0f * (float)p / (float)G + 1.0f) - 1.0f) * 0.5f);
+        while (G * q * (q + 1) / 2 > p) --q;
+        while (G * (q + 1) * (q + 2) / 2 <= p) ++q;
+        const int r = p - G * q * (q + 1) / 2;
+        const int rb = q * G + r / (q + 1), g0 = (r % (q + 1)) * G;
+        const int j = rb * 64 + lane;
+        Rect a = {0, 0, 0, 0};
         if (j < n) {
-            const SortedBox a = sorted[j];
-            const int m = min(64, n - w * 64);
-            unsigned long long bits = 0;
-            for (int b = 0; b < m; ++b)
-                if (w * 64 + b != j && overlaps(a, sCol[b], thr)) bits |= 1ull << b;
-            overlap[(size_t)j * words + w] = bits;
+            const SortedBox bj = sorted[j];
+            a = {bj.x, bj.y, bj.x + bj.size, bj.y + bj.size};
+        }
+        // column box of this lane in word w; beyond the list an empty box, which overlaps nothing
+        auto column = [&](int w) -> Rect {
+            const int c = w * 64 + lane;
+            if (c >= n) return {0, 0, 0, 0};
+            const SortedBox b = sorted[c];
+            return {b.x, b.y, b.x + b.size, b.y + b.size};
+        };
+        unsigned long long bits[kChunkWords];
+        int cnt = 0;
+        Rect next = column(g0);
+#pragma unroll
+        for (int g = 0; g < kChunkWords; ++g) {
+            bits[g] = 0;
+            const int w = g0 + g;
+            if (g >= G || w > rb) continue;                       // uniform
+            const Rect col = next;
+            if (g + 1 < G && w + 1 <= rb) next = column(w + 1);   // in flight during this word's comparisons
+            __syncthreads();
+            sCol[lane] = col;
+            __syncthreads();
+            if (j < n) {
+                unsigned long long v = 0;
+                for (int b = 0; b < 64; b += 8) {                // eight column boxes read together, then compared
+                    Rect r[8];
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) r[u] = sCol[b + u];
+#pragma unroll
+                    for (int u = 0; u < 8; ++u)
+                        if (overlaps(a, r[u], thr)) v |= 1ull << (b + u);
+                }
+                if (w == rb) v &= ~(1ull << lane);
+                overlap[(size_t)w * n_max + j] = v;
+                bits[g] = v;
+                cnt += __popcll(v);
+            }
+        }
+        const int chunk = rb / kChunkWords;
+        if (g0 / kChunkWords < chunk && __ballot(cnt != 0)) {
+            int incl = cnt;                                       // inclusive prefix sum over the wave
+#pragma unroll
+            for (int o = 1; o < 64; o <<= 1) {
+                const int t = __shfl_up(incl, o);
+                if (lane >= o) incl += t;
+            }
+            int base = 0;
+            if (lane == 63) base = atomicAdd(&npair[chunk], incl);
+            base = __shfl(base, 63);
+            uint32_t *out = pairs + (size_t)chunk * kPairCap;
+            const uint32_t row = (uint32_t)(j & (kChunk - 1)) << 16;
+            int pos = base + incl - cnt;
+#pragma unroll
+            for (int g = 0; g < kChunkWords; ++g)
+                for (unsigned long long v = bits[g]; v && pos < kPairCap; v &= v - 1ull, ++pos)
+                    out[pos] = row | (uint32_t)((g0 + g) * 64 + __ffsll((long long)v) - 1);
         }
     }
 }
 
 __global__ __launch_bounds__(kResolveThreads)
 void merge_resolve_kernel(const SortedBox *__restrict__ sorted, const unsigned long long *__restrict__ overlap,
-                          int words, const int32_t *__restrict__ d_n, int n_max, int min_neighbors,
+                          const int32_t *__restrict__ npair, const uint32_t *__restrict__ pairs,
+                          const int32_t *__restrict__ d_n, int n_max, int min_neighbors,
                           int32_t *__restrict__ nb, cnnc_det *__restrict__ det, int det_cap,
                           int32_t *__restrict__ d_ndet)
 {
-    __shared__ unsigned long long keptS[kMergeCapMax / 64], remS[kMergeCapMax / 64];
-    __shared__ int s_flag, s_wsum[kResolveThreads / 64], s_base;
+    __shared__ unsigned long long keptS[kMergeCapMax / 64], remC[kChunkWords];
+    __shared__ int firstS[kChunk], s_npair[kMaxChunks];
+    __shared__ int s_wsum[kResolveThreads / 64], s_base;
     const int tid = threadIdx.x;
     const int n = min(*d_n, n_max);
-    const int W = (n + 63) / 64;
-    for (int w = tid; w < W; w += kResolveThreads) { keptS[w] = 0; remS[w] = 0; }
-    uint32_t und = 0;                                   // bit q: box tid + 1024 q is still undecided
-    for (int q = 0; q < kMergeCapMax / kResolveThreads; ++q)
-        if (tid + kResolveThreads * q < n) und |= 1u << q;
-    if (tid == 0) s_flag = 0;
-    __syncthreads();
+    for (int w = tid; w < kMergeCapMax / 64; w += kResolveThreads) keptS[w] = 0;
+    if (tid < kMaxChunks) s_npair[tid] = npair[tid];
+    const int tw = tid >> 6;                                      // word of this thread's box inside its chunk
+    const unsigned long long tbit = 1ull << (tid & 63);
 
-    for (;;) {
-        uint32_t todo = und;
-        while (todo) {
-            const int q = __ffs(todo) - 1;
-            todo &= todo - 1;
-            const int j = tid + kResolveThreads * q, wj = j >> 6;
-            const unsigned long long *row = overlap + (size_t)j * words;
-            bool any_kept = false, all_removed = true;
-            for (int w = 0; w <= wj; ++w) {
-                unsigned long long p = row[w];
-                if (w == wj) p &= (1ull << (j & 63)) - 1ull;
-                if (p & keptS[w]) { any_kept = true; break; }
-                if (p & ~remS[w]) all_removed = false;
-            }
-            if (any_kept) { atomicOr(&remS[wj], 1ull << (j & 63)); und &= ~(1u << q); }
-            else if (all_removed) { atomicOr(&keptS[wj], 1ull << (j & 63)); und &= ~(1u << q); }
+    for (int c0 = 0; c0 < n; c0 += kChunk) {
+        const int j = c0 + tid, w0 = c0 >> 6;
+        const bool live = j < n;
+        __syncthreads();                                          // keptS of the earlier chunks is final (or cleared)
+        if (tid < kChunkWords) remC[tid] = 0;
+        firstS[tid] = INT_MAX;
+
+        // this box's words of the chunk's diagonal block, bits of earlier boxes only
+        unsigned long long d[kChunkWords];
+#pragma unroll
+        for (int k = 0; k < kChunkWords; ++k) d[k] = 0;
+        if (live) {
+#pragma unroll
+            for (int k = 0; k < kChunkWords; ++k)
+                if (k <= tw) d[k] = overlap[(size_t)(w0 + k) * n_max + j];
+#pragma unroll
+            for (int k = 0; k < kChunkWords; ++k)
+                if (k == tw) d[k] &= tbit - 1ull;
         }
-        if (und) s_flag = 1;
         __syncthreads();
-        const int more = s_flag;
-        __syncthreads();
-        if (tid == 0) s_flag = 0;
-        if (!more) break;
-        __syncthreads();
-    }
-    __syncthreads();
 
-    // neighbours: an absorbed box counts for its first kept overlapping predecessor
-    for (int j = tid; j < n; j += kResolveThreads) {
-        const int wj = j >> 6;
-        if (!((remS[wj] >> (j & 63)) & 1ull)) continue;
-        const unsigned long long *row = overlap + (size_t)j * words;
-        for (int w = 0; w <= wj; ++w) {
-            unsigned long long p = row[w] & keptS[w];
-            if (w == wj) p &= (1ull << (j & 63)) - 1ull;
-            if (p) { atomicAdd(&nb[w * 64 + __ffsll((long long)p) - 1], 1); break; }
+        // kept predecessors in earlier chunks: the lowest one of every row, or none
+        const int np = c0 ? s_npair[c0 / kChunk] : 0;
+        int first = INT_MAX;
+        if (np <= kPairCap) {
+            const uint32_t *pp = pairs + (size_t)(c0 / kChunk) * kPairCap;
+            for (int t0 = tid; t0 < np; t0 += 8 * kResolveThreads) {       // eight loads of a thread in flight together
+                uint32_t pr[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const int t = t0 + u * kResolveThreads;
+                    pr[u] = t < np ? pp[t] : 0xFFFFFFFFu;
+                }
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const int e = (int)(pr[u] & 0xFFFFu), r = (int)(pr[u] >> 16);
+                    if (pr[u] != 0xFFFFFFFFu && ((keptS[e >> 6] >> (e & 63)) & 1ull)) atomicMin(&firstS[r], e);
+                }
+            }
+        } else {
+            // more pairs than the array holds: every wave reads the bit rows of its boxes, 64 words of a row a step
+            for (int src = 0; src < 64 && c0 + (tid & ~63) + src < n; ++src) {
+                const unsigned long long *row = overlap + (c0 + (tid & ~63) + src);
+                int lowest = INT_MAX;
+                for (int w = w0 - 1 - (tid & 63); w >= 0; w -= 64) {
+                    const unsigned long long p = row[(size_t)w * n_max] & keptS[w];
+                    if (p) lowest = w * 64 + __ffsll((long long)p) - 1;
+                }
+#pragma unroll
+                for (int o = 32; o; o >>= 1) lowest = min(lowest, __shfl_xor(lowest, o));
+                if ((tid & 63) == src) first = lowest;
+            }
+        }
+        __syncthreads();
+        first = min(first, firstS[tid]);
+        bool und = live && first == INT_MAX;
+        if (live && !und) atomicOr(&remC[tw], tbit);
+
+        // Rounds inside the chunk.  A wave repeats its step while one of its boxes gets decided: what its own
+        // lanes wrote to LDS is visible to its next read, so chains inside a 64-box word need no barrier; the
+        // barrier rounds only carry decisions from one wave to another.
+        for (;;) {
+            __syncthreads();
+            bool progress;
+            do {
+                asm volatile("" ::: "memory");                    // read the LDS words again
+                progress = false;
+                if (und) {
+                    bool any_kept = false, all_removed = true;
+#pragma unroll
+                    for (int k = 0; k < kChunkWords; ++k) {
+                        if (d[k] & keptS[w0 + k]) any_kept = true;
+                        if (d[k] & ~remC[k]) all_removed = false;
+                    }
+                    if (any_kept) { atomicOr(&remC[tw], tbit); und = false; progress = true; }
+                    else if (all_removed) { atomicOr(&keptS[w0 + tw], tbit); und = false; progress = true; }
+                }
+            } while (__ballot(progress));
+            if (!__syncthreads_or(und)) break;
+        }
+
+        // an absorbed box counts for its first kept overlapping predecessor
+        if (live && !((keptS[w0 + tw] >> (tid & 63)) & 1ull)) {
+            if (first == INT_MAX) {
+#pragma unroll
+                for (int k = kChunkWords - 1; k >= 0; --k) {
+                    const unsigned long long p = d[k] & keptS[w0 + k];
+                    if (p) first = (w0 + k) * 64 + __ffsll((long long)p) - 1;
+                }
+            }
+            atomicAdd(&nb[first], 1);
         }
     }
     __threadfence();
@@ -247,7 +389,9 @@ void merge_resolve_kernel(const SortedBox *__restrict__ sorted, const unsigned l
 hipError_t merge_init_workspace(const cnnc_ctx *c)
 {
     const MergeWs w = carve(c->d_merge_ws, c->merge_cap);
-    return hipMemset(w.rank, 0, sizeof(int32_t) * (size_t)c->merge_cap);
+    hipError_t e = hipMemset(w.rank, 0, sizeof(int32_t) * (size_t)c->merge_cap);
+    if (e == hipSuccess) e = hipMemset(w.npair, 0, sizeof(int32_t) * kMaxChunks);
+    return e;
 }
 
 hipError_t launch_merge(const cnnc_ctx *c, hipStream_t st)
@@ -257,11 +401,11 @@ hipError_t launch_merge(const cnnc_ctx *c, hipStream_t st)
     const int32_t *d_n = &c->d_cnt->n[2];
     hipLaunchKernelGGL(merge_rank_kernel, dim3((cap + 255) / 256, kRankSplit), dim3(256), 0, st, c->d_sc[2], d_n, cap, w.rank);
     hipLaunchKernelGGL(merge_scatter_kernel, dim3((cap + 255) / 256), dim3(256), 0, st, c->d_idx[2], c->d_sc[2], d_n, cap,
-                       c->d_levels, c->n_levels, w.rank, w.nb, w.sorted);
-    const int pairs = ((cap + 63) / 64) * ((cap + 63) / 64);
-    hipLaunchKernelGGL(merge_overlap_kernel, dim3(pairs < 4096 ? pairs : 4096), dim3(64), 0, st, w.sorted, d_n, cap,
-                       c->params.merge_iou, w.overlap, w.words);
-    hipLaunchKernelGGL(merge_resolve_kernel, dim3(1), dim3(kResolveThreads), 0, st, w.sorted, w.overlap, w.words, d_n, cap,
+                       c->d_levels, c->n_levels, w.rank, w.nb, w.npair, w.sorted);
+    const int tiles = ((cap + 63) / 64) * ((cap + 63) / 64);
+    hipLaunchKernelGGL(merge_overlap_kernel, dim3(tiles < 4096 ? tiles : 4096), dim3(64), 0, st, w.sorted, d_n, cap,
+                       c->params.merge_iou, w.overlap, w.npair, w.pairs);
+    hipLaunchKernelGGL(merge_resolve_kernel, dim3(1), dim3(kResolveThreads), 0, st, w.sorted, w.overlap, w.npair, w.pairs, d_n, cap,
                        c->params.min_neighbors, w.nb, c->d_det, cap, &c->d_cnt->n[3]);
     return hipGetLastError();
 }
