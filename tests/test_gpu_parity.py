@@ -193,17 +193,21 @@ def test_every_window_survives_and_capacity_overflow():
     small.close()
 
 
-def test_merge_of_a_long_dense_list():
-    """Every window of a small frame accepted: about thirteen thousand heavily overlapping boxes, which takes the
-    merge through its long-list form; the result must be the greedy merge of exactly those boxes."""
+@pytest.mark.parametrize("size", [(64, 56), (100, 80)])
+def test_merge_of_a_long_dense_list(size):
+    """Every window of a small frame accepted: five thousand and fourteen thousand heavily overlapping boxes, which
+    take the merge through several chunks of its sorted list, through both sizes of its overlap work items above the
+    smallest and through the form for chunks with more overlapping predecessors than its pair arrays hold; the
+    result must be the greedy merge of exactly those boxes."""
     torch = _torch()
     casc = I.default_cascade()
     W = I.draw_weights(casc, 8)
-    frame = I.make_frame(100, 80, 21)
+    fw, fh = size
+    frame = I.make_frame(fw, fh, 21)
     thr = (-1e30, -1e30, -1e30)
-    n = O.pyramid_layout(100, 80, 12.0, 1.25).score_off[-1]
-    assert n > 8192
-    ctx = _ctx(casc, W, 100, 80, 20000)
+    n = O.pyramid_layout(fw, fh, 12.0, 1.25).score_off[-1]
+    assert (2048 < n <= 8192) if fw == 64 else n > 8192
+    ctx = _ctx(casc, W, fw, fh, 20000)
     for iou, mn in ((0.3, 1), (0.7, 2)):
         ctx.set_params(12.0, 1.25, thr, merge_iou=iou, min_neighbors=mn)
         det = [d.as_dict() for d in ctx.detect(torch.from_numpy(frame).cuda(), 20000)]
