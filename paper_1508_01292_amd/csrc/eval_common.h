@@ -73,8 +73,9 @@ __device__ __forceinline__ void crop_finish(const CropPixels<N> &px, const uint3
     for (int it = 0; it < CropPixels<N>::kIt; ++it) {
         const int e = it * kThreads + tid, ec = min(e, N * N - 1);
         const uint32_t wx = sTab[ec % N] & 511u, wy = sTab[N + ec / N] & 511u;
-        const uint32_t acc = (px.top[it] & 255u) * (256u - wx) * (256u - wy) + (px.top[it] >> 8) * wx * (256u - wy)
-                           + (px.bot[it] & 255u) * (256u - wx) * wy + (px.bot[it] >> 8) * wx * wy;
+        const uint32_t top = (px.top[it] & 255u) * (256u - wx) + (px.top[it] >> 8) * wx;     // the same integer as the
+        const uint32_t bot = (px.bot[it] & 255u) * (256u - wx) + (px.bot[it] >> 8) * wx;     // four-term sum, below 2^24
+        const uint32_t acc = top * (256u - wy) + bot * wy;
         if (e < N * N) sCrop[e] = normalise((float)acc * (1.0f / 65536.0f));
     }
 }

@@ -765,8 +765,9 @@ void eval2_conv_kernel(const uint8_t *__restrict__ frame, int fw, int fh, int pi
             for (int it = 0; it < 9; ++it) {
                 const int e = it * 64 + lane, r = e / 24, q = e % 24;
                 const uint32_t wx = sTab[q] & 511u, wy = sTab[24 + r] & 511u;
-                const uint32_t acc = (top[it] & 255u) * (256u - wx) * (256u - wy) + (top[it] >> 8) * wx * (256u - wy)
-                                   + (bot[it] & 255u) * (256u - wx) * wy + (bot[it] >> 8) * wx * wy;
+                const uint32_t tb = (top[it] & 255u) * (256u - wx) + (top[it] >> 8) * wx;
+                const uint32_t bb = (bot[it] & 255u) * (256u - wx) + (bot[it] >> 8) * wx;
+                const uint32_t acc = tb * (256u - wy) + bb * wy;
                 sCrop[e] = normalise((float)acc * (1.0f / 65536.0f));
             }
         }
