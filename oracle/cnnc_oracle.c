@@ -26,11 +26,13 @@
  * one step; for the selective unit in that geometry: exact special cases and
  * library bilinear for the region, closed forms of histogram equalisation,
  * library convolution for the mirrored response maps, the truth table of
- * eq. (2).  The choice of the readings themselves (resampling
- * convention, crop rectangle, merge rule; in the paper's geometry the layer
- * shapes, the width of the neighbourhood, the equalisation rule and how the
- * mirror image's responses are combined) cannot be pinned to the authors'
- * detector: parity unpinned for those choices.
+ * eq. (2), and the merge of the accepted rectangles against the square merge
+ * and a brute force in exact fractions.  The choice of the readings
+ * themselves (resampling convention, crop rectangle, merge rule; in the
+ * paper's geometry the layer shapes, the width of the neighbourhood, the
+ * equalisation rule, how the mirror image's responses are combined, and the
+ * box and the score an accepted region enters the merge with) cannot be
+ * pinned to the authors' detector: parity unpinned for those choices.
  */
 #include <math.h>
 #include <stdint.h>
@@ -734,4 +736,55 @@ int orc_select_region(const uint8_t *region, int rw, int rh,
     }
     free(mir); free(a);
     return rc;
+}
+
+/* ------------------------------------------------------------------------ */
+/* Merging of the regions the selective unit accepted (paper, Section 3.3:    */
+/* non-maximum suppression aggregates the found regions; Section 4.2:         */
+/* minNeighbors).  The greedy rule of orc_merge for rectangles bw x bh: order */
+/* by score (fp32) descending, ties by ascending `order`; the best rectangle  */
+/* not yet suppressed is kept and suppresses every later one with             */
+/* inter > iou * union (integer areas, exact in double, strict).              */
+/* Reading (the paper gives neither): an accepted region enters as its 27x31  */
+/* window in frame pixels (orc_region_box) with the largest combined CNN_3    */
+/* response of its map as score.                                              */
+/* ------------------------------------------------------------------------ */
+void orc_region_box(int i, int j, double s, int step, int win_w, int win_h,
+                    int32_t *bx, int32_t *by, int32_t *bw, int32_t *bh)
+{
+    *bx = (int32_t)floor((double)(step * i) * s + 0.5);
+    *by = (int32_t)floor((double)(step * j) * s + 0.5);
+    *bw = (int32_t)floor((double)win_w * s + 0.5);
+    *bh = (int32_t)floor((double)win_h * s + 0.5);
+}
+
+int32_t orc_merge_rect(const int32_t *bx, const int32_t *by, const int32_t *bw, const int32_t *bh, const float *score,
+                       const int64_t *order, int32_t n, float iou, int32_t min_neighbors,
+                       int32_t *out_index, int32_t *out_neighbors)
+{
+    merge_key *key = malloc(sizeof(merge_key) * (size_t)(n > 0 ? n : 1));
+    uint8_t *dead = calloc((size_t)(n > 0 ? n : 1), 1);
+    for (int32_t i = 0; i < n; ++i) { key[i].score = score[i]; key[i].order = order[i]; key[i].pos = i; }
+    qsort(key, (size_t)n, sizeof(merge_key), merge_cmp);
+    int32_t kept = 0;
+    for (int32_t i = 0; i < n; ++i) {
+        if (dead[i]) continue;
+        const int32_t p = key[i].pos;
+        int32_t nb = 0;
+        for (int32_t j = i + 1; j < n; ++j) {
+            if (dead[j]) continue;
+            const int32_t r = key[j].pos;
+            const int64_t right = (int64_t)bx[p] + bw[p] < (int64_t)bx[r] + bw[r] ? (int64_t)bx[p] + bw[p] : (int64_t)bx[r] + bw[r];
+            const int64_t left = bx[p] > bx[r] ? bx[p] : bx[r];
+            const int64_t bottom = (int64_t)by[p] + bh[p] < (int64_t)by[r] + bh[r] ? (int64_t)by[p] + bh[p] : (int64_t)by[r] + bh[r];
+            const int64_t top = by[p] > by[r] ? by[p] : by[r];
+            if (right <= left || bottom <= top) continue;
+            const int64_t inter = (right - left) * (bottom - top);
+            const int64_t uni = (int64_t)bw[p] * bh[p] + (int64_t)bw[r] * bh[r] - inter;
+            if ((double)inter > (double)iou * (double)uni) { dead[j] = 1; ++nb; }
+        }
+        if (nb + 1 >= min_neighbors) { out_index[kept] = p; out_neighbors[kept] = nb; ++kept; }
+    }
+    free(key); free(dead);
+    return kept;
 }

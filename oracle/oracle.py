@@ -40,6 +40,7 @@ def lib():
         L.orc_activation.argtypes = [C.c_double, C.c_int]
         L.orc_survivors.restype = C.c_int64
         L.orc_merge.restype = C.c_int32
+        L.orc_merge_rect.restype = C.c_int32
         _lib = L
     return _lib
 
@@ -338,6 +339,39 @@ def merge(bx, by, bs, score, order, iou: float = 0.3, min_neighbors: int = 1):
     k = lib().orc_merge(_p(bx), _p(by), _p(bs), _p(score), _p(order), C.c_int32(n), C.c_float(iou),
                         C.c_int32(min_neighbors), _p(oi), _p(on))
     return oi[:k].copy(), on[:k].copy()
+
+
+def merge_rect(bx, by, bw, bh, score, order, iou: float = 0.3, min_neighbors: int = 1):
+    """Greedy merge of rectangles; returns (positions of kept boxes in kept order, neighbour counts)."""
+    n = len(bx)
+    bx, by, bw, bh = (np.ascontiguousarray(a, np.int32) for a in (bx, by, bw, bh))
+    score = np.ascontiguousarray(score, np.float32)
+    order = np.ascontiguousarray(order, np.int64)
+    oi = np.zeros(max(n, 1), np.int32)
+    on = np.zeros(max(n, 1), np.int32)
+    k = lib().orc_merge_rect(_p(bx), _p(by), _p(bw), _p(bh), _p(score), _p(order), C.c_int32(n), C.c_float(iou),
+                             C.c_int32(min_neighbors), _p(oi), _p(on))
+    return oi[:k].copy(), on[:k].copy()
+
+
+def region_box(i: int, j: int, scale: float, net1):
+    """Frame-pixel rectangle (x, y, w, h) of the scan window (i, j) of a level with the given scale."""
+    v = [C.c_int32() for _ in range(4)]
+    lib().orc_region_box(C.c_int(int(i)), C.c_int(int(j)), C.c_double(float(scale)), C.c_int(net1.step),
+                         C.c_int(net1.win_w), C.c_int(net1.win_h), *[C.byref(a) for a in v])
+    return tuple(a.value for a in v)
+
+
+def select_merge(pyr: Pyramid, records, net1, iou: float = 0.3, min_neighbors: int = 1):
+    """Merge of the regions a selective-unit pass accepted (records from select_unit): list of dicts
+    (index, x, y, w, h, score, level, neighbors) in kept order."""
+    faces = [r for r in records if r["face"]]
+    box = [region_box(r["i"], r["j"], pyr.scale[r["level"]], net1) for r in faces]
+    sc = np.array([np.float32(r["r3"].max()) for r in faces], np.float32)
+    kept, nb = merge_rect([b[0] for b in box], [b[1] for b in box], [b[2] for b in box], [b[3] for b in box], sc,
+                          [r["index"] for r in faces], iou, min_neighbors)
+    return [dict(index=faces[p]["index"], x=box[p][0], y=box[p][1], w=box[p][2], h=box[p][3], score=float(sc[p]),
+                 level=faces[p]["level"], neighbors=int(k)) for p, k in zip(kept, nb)]
 
 
 # --------------------------------------------------------------------------

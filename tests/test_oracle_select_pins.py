@@ -128,3 +128,85 @@ def test_unit_geometry_window_sits_in_the_middle_of_its_region():
     rec1 = O.select_unit(frame, pyr, [off1 + 1], n1, n2, _constant_net(n2, 1.0), n3, _constant_net(n3, 1.0), 0.0, 0.0, 1)[0]
     assert (rec1["level"], rec1["i"], rec1["j"]) == (1, 1, 0)
     assert s.size > off1
+
+
+def test_rectangle_merge_special_cases_and_square_case():
+    """The merge of accepted regions: with equal sides it is the square merge (itself pinned by brute force), and a
+    few rectangles decided by hand."""
+    rng = np.random.default_rng(41)
+    for n in (1, 50, 400):
+        bx, by = rng.integers(0, 400, n), rng.integers(0, 300, n)
+        bs, sc = rng.integers(20, 120, n), rng.standard_normal(n).astype(np.float32)
+        sc[n // 2:] = sc[:n - n // 2]                 # exact ties, resolved by the order key
+        order = rng.permutation(n)
+        for iou, mn in ((0.3, 1), (0.5, 2)):
+            a = O.merge(bx, by, bs, sc, order, iou, mn)
+            b = O.merge_rect(bx, by, bs, bs, sc, order, iou, mn)
+            assert a[0].tolist() == b[0].tolist() and a[1].tolist() == b[1].tolist()
+    # 20 x 10 rectangles shifted along x by dx: inter = 10 (20 - dx), union = 400 - inter
+    # dx = 10: 100 / 300 = 0.333 > 0.3 absorbed; dx = 11: 90 / 310 = 0.290 kept
+    assert O.merge_rect([0, 10], [0, 0], [20, 20], [10, 10], [0.9, 0.8], [0, 1])[0].tolist() == [0]
+    assert O.merge_rect([0, 11], [0, 0], [20, 20], [10, 10], [0.9, 0.8], [0, 1])[0].tolist() == [0, 1]
+    # shifted along y by 5: inter = 20 * 5 = 100 again; by 6: 80 / 320 = 0.25, equal to a threshold of 0.25 -> kept (strict)
+    assert O.merge_rect([0, 0], [0, 5], [20, 20], [10, 10], [0.9, 0.8], [0, 1])[0].tolist() == [0]
+    assert O.merge_rect([0, 0], [0, 6], [20, 20], [10, 10], [0.9, 0.8], [0, 1], iou=0.25)[0].tolist() == [0, 1]
+    # a 10 x 40 and a 40 x 10 rectangle inside a 40 x 40 one: 400 / 1600 = 0.25 each -> kept at 0.3, absorbed at 0.2
+    # (the two small ones share a 10 x 10 patch only, 100 / 700)
+    kept, nb = O.merge_rect([0, 15, 0], [0, 0, 15], [40, 10, 40], [40, 40, 10], [0.9, 0.8, 0.7], [0, 1, 2], iou=0.3)
+    assert kept.tolist() == [0, 1, 2] and nb.tolist() == [0, 0, 0]
+    kept, nb = O.merge_rect([0, 15, 0], [0, 0, 15], [40, 10, 40], [40, 40, 10], [0.9, 0.8, 0.7], [0, 1, 2], iou=0.2)
+    assert kept.tolist() == [0] and nb.tolist() == [2]
+    # touching rectangles do not overlap; an empty list stays empty
+    assert O.merge_rect([0, 20], [0, 0], [20, 20], [10, 10], [0.5, 0.6], [0, 1], iou=0.0)[0].tolist() == [1, 0]
+    assert O.merge_rect([], [], [], [], [], [])[0].tolist() == []
+
+
+def test_rectangle_merge_against_exact_fractions():
+    from fractions import Fraction
+    rng = np.random.default_rng(43)
+    n = 80
+    bx, by = rng.integers(0, 150, n), rng.integers(0, 150, n)
+    bw, bh = rng.integers(10, 90, n), rng.integers(10, 90, n)
+    sc = rng.standard_normal(n).astype(np.float32)
+    order = rng.permutation(n)
+    for iou, mn in ((0.3, 1), (0.1, 3)):
+        kept, nb = O.merge_rect(bx, by, bw, bh, sc, order, iou, mn)
+        thr = Fraction(float(np.float32(iou)))
+        seq = sorted(range(n), key=lambda i: (-float(sc[i]), int(order[i])))
+        dead, want = set(), []
+        for pos, a in enumerate(seq):
+            if a in dead:
+                continue
+            cnt = 0
+            for b in seq[pos + 1:]:
+                if b in dead:
+                    continue
+                iw = min(int(bx[a] + bw[a]), int(bx[b] + bw[b])) - max(int(bx[a]), int(bx[b]))
+                ih = min(int(by[a] + bh[a]), int(by[b] + bh[b])) - max(int(by[a]), int(by[b]))
+                if iw <= 0 or ih <= 0:
+                    continue
+                inter = iw * ih
+                uni = int(bw[a]) * int(bh[a]) + int(bw[b]) * int(bh[b]) - inter
+                if Fraction(inter) > thr * uni:
+                    dead.add(b)
+                    cnt += 1
+            if cnt + 1 >= mn:
+                want.append((a, cnt))
+        assert [(int(p), int(k)) for p, k in zip(kept, nb)] == want
+
+
+def test_region_box_and_merge_of_a_unit_pass():
+    """Box rule: the 27 x 31 window in frame pixels, rounded half up; score: the largest combined CNN_3 response."""
+    n1 = I.paper_stage1()
+    assert O.region_box(9, 7, 1.0, n1) == (36, 28, 27, 31)
+    assert O.region_box(3, 2, 2.5, n1) == (30, 20, 68, 78)          # 67.5 and 77.5 round up
+    assert O.region_box(1, 1, 1.5625, n1) == (6, 6, 42, 48)         # 6.25, 42.19, 48.44
+    pyr = O.build_pyramid(I.make_frame(200, 160, 4), 12.0, 1.25)
+    r3a, r3b = np.full((5, 5), -1.0), np.full((5, 5), -1.0)
+    r3a[2, 3], r3b[0, 0] = 0.25, 0.75
+    recs = [dict(index=10, level=0, i=9, j=7, face=True, r3=r3a), dict(index=11, level=0, i=10, j=7, face=True, r3=r3b),
+            dict(index=12, level=0, i=11, j=7, face=False, r3=r3b), dict(index=40, level=0, i=30, j=20, face=True, r3=r3a)]
+    det = O.select_merge(pyr, recs, n1, 0.3, 1)
+    # windows (9, 7) and (10, 7) are 4 px apart: 23 x 31 of 27 x 31 in common -> merged, the one with 0.75 kept
+    assert [(d["index"], d["neighbors"], d["score"]) for d in det] == [(11, 1, 0.75), (40, 0, 0.25)]
+    assert (det[0]["x"], det[0]["y"], det[0]["w"], det[0]["h"]) == (40, 28, 27, 31)
