@@ -193,6 +193,12 @@ def main():
     c0.set_timing(False)
     ms_sel = tm_sel[0] / tm_sel[1] if tm_sel[1] else 0.0
     sel = c0.select_fetch(65536)
+    # merge of the accepted regions: the call waits for its result, so this is wall-clock time per call
+    sel_det = c0.select_merge(0.3, 1, 32768, streams[0])
+    t0 = time.perf_counter()
+    for _ in range(20):
+        c0.select_merge(0.3, 1, 32768, streams[0])
+    ms_sel_merge = (time.perf_counter() - t0) / 20 * 1e3
     sel_flop = 2.0 * sum(2 * SEL_MAC_CNN2 + (2 * SEL_MAC_CNN3 if r.k2 > 0 else 0) for r in sel)
     c0.detect(dev_frame, 8192)           # leaves the context with the cascade's own survivor lists again
     n1, n2, n3 = (c0.survivor_count(s) for s in (1, 2, 3))
@@ -289,7 +295,8 @@ def main():
         "paper_selective_unit": {"regions": len(sel), "faces": sum(r.face for r in sel), "ms": ms_sel,
                                  "regions_per_s": len(sel) / (ms_sel * 1e-3) if ms_sel > 0 else None, "bound": "alu",
                                  "achieved": tflops(sel_flop, ms_sel), "peak": PEAK_FP32_VECTOR, "unit": "TFLOP/s",
-                                 "frac": tflops(sel_flop, ms_sel) / PEAK_FP32_VECTOR},
+                                 "frac": tflops(sel_flop, ms_sel) / PEAK_FP32_VECTOR,
+                                 "merge": {"detections": len(sel_det), "ms_per_call_with_wait_and_readback": ms_sel_merge}},
         "sum_of_kernel_ms": sum(v for k, v in ms.items() if not k.endswith("_conv") and k not in ("scan", "select")),
         "roofline": roof,
         "kernels": kernels,

@@ -251,6 +251,25 @@ int cnnc_select_set_weights(cnnc_ctx *ctx, const float *w2, int n2, const float 
 int cnnc_select_run(cnnc_ctx *ctx, float t1, float t2, float t3, int t_nn, void *stream);
 int cnnc_select_fetch(cnnc_ctx *ctx, cnnc_region *out, int cap, int *n_out, float *maps2, float *maps3);
 
+/* Merging of the regions the unit accepted (Section 3.3: non-maximum suppression aggregates the found regions;
+ * Section 4.2: minNeighbors), by the greedy rule of cnnc_merge_detections on rectangles.  What the paper leaves open:
+ * an accepted region (face != 0) enters as its 27 x 31 window in frame pixels, x = round(4 i s), y = round(4 j s),
+ * w = round(27 s), h = round(31 s) with s the scale of its level, and with the largest of its 25 combined CNN_3
+ * responses as score (ties: ascending flat position).  A kept rectangle absorbs every later one whose intersection
+ * exceeds iou * union; kept rectangles with neighbors + 1 < min_neighbors are dropped.
+ * Needs cnnc_select_run of the current frame (CNNC_E_STATE otherwise).  Enqueued on `stream`, then waits.
+ * out: host array of capacity cap, kept order; *n_out = number of detections.  CNNC_E_OVERFLOW when the accepted
+ * regions exceed the merge capacity (min(max_survivors, 32768)) or the detections exceed cap (first cap are valid).
+ * Uses the merge workspace of the context: do not overlap with cnnc_merge_detections / cnnc_detect of the same context. */
+typedef struct {
+    int32_t x, y, w, h;     /* frame pixels */
+    float score;            /* largest combined CNN_3 response of the region */
+    int32_t level;          /* pyramid level of the region */
+    int32_t neighbors;      /* regions it absorbed */
+    int32_t index;          /* flat index of its position in the response map of cnnc_scan_scoremap */
+} cnnc_rdet;
+int cnnc_select_merge(cnnc_ctx *ctx, float iou, int min_neighbors, cnnc_rdet *out, int cap, int *n_out, void *stream);
+
 /* ---- Frame ingest from host memory ------------------------------------------------------------
  * The paper's detector is fed video (Section 4.2) and overlaps its stages (Section 3.4, asynchronous mode).
  * A pipe is a ring of `depth` slots (1..16); each slot owns a context, a HIP stream, a pinned host frame
@@ -281,8 +300,9 @@ const char *cnnc_pipe_last_error(const cnnc_pipe *pipe);
  * current device's default stream, allocates and frees 2 GiB, synchronises.  Outputs are host pointers. */
 int cnnc_measure_peaks(double *mfma_f32_tflops, double *valu_f32_tflops, double *hbm_copy_gbs);
 
-/* For bindings: sizes in bytes of cnnc_layer, cnnc_stage_desc, cnnc_params, cnnc_det, cnnc_region, and the value of
- * CNNC_T_COUNT, in that order, into out[0 .. n) (host; at most six are written).  Returns how many exist (6). */
+/* For bindings: sizes in bytes of cnnc_layer, cnnc_stage_desc, cnnc_params, cnnc_det, cnnc_region, the value of
+ * CNNC_T_COUNT, and the size of cnnc_rdet, in that order, into out[0 .. n) (host; at most seven are written).
+ * Returns how many exist (7). */
 int cnnc_abi_sizes(int32_t *out, int n);
 
 const char *cnnc_last_error(const cnnc_ctx *ctx);

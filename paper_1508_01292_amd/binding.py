@@ -21,7 +21,7 @@ EXPORTS = [
     "cnnc_get_timings", "cnnc_set_eval_impl", "cnnc_measure_peaks", "cnnc_last_error", "cnnc_version",
     "cnnc_stage1_survivors", "cnnc_set_fused_stage1",
     "cnnc_scan_set_weights", "cnnc_scan_layout", "cnnc_scan_scoremap", "cnnc_get_scan_scoremap",
-    "cnnc_select_set_weights", "cnnc_select_run", "cnnc_select_fetch", "cnnc_abi_sizes",
+    "cnnc_select_set_weights", "cnnc_select_run", "cnnc_select_fetch", "cnnc_select_merge", "cnnc_abi_sizes",
     "cnnc_pipe_create", "cnnc_pipe_destroy", "cnnc_pipe_set_params", "cnnc_pipe_frame_buffer", "cnnc_pipe_submit",
     "cnnc_pipe_fetch", "cnnc_pipe_last_error",
 ]
@@ -58,6 +58,15 @@ class Region(C.Structure):
     def as_dict(self):
         return dict(index=self.index, level=self.level, i=self.i, j=self.j, k2=self.k2, k3=self.k3, face=bool(self.face),
                     response=self.response)
+
+
+class RegionDetection(C.Structure):
+    _fields_ = [("x", C.c_int32), ("y", C.c_int32), ("w", C.c_int32), ("h", C.c_int32), ("score", C.c_float),
+                ("level", C.c_int32), ("neighbors", C.c_int32), ("index", C.c_int32)]
+
+    def as_dict(self):
+        return dict(x=self.x, y=self.y, w=self.w, h=self.h, score=self.score, level=self.level,
+                    neighbors=self.neighbors, index=self.index)
 
 
 class Detection(C.Structure):
@@ -291,6 +300,14 @@ class Context:
         recs = list(out[:n.value])
         return (recs, m2[:n.value], m3[:n.value]) if maps else recs
 
+    def select_merge(self, iou: float = 0.3, min_neighbors: int = 1, cap: int = 4096, stream=None):
+        """Greedy merge of the regions the last select_run accepted (list of RegionDetection, kept order)."""
+        out = (RegionDetection * cap)()
+        n = C.c_int(0)
+        self._check(lib().cnnc_select_merge(self._h, C.c_float(iou), C.c_int(min_neighbors), out, C.c_int(cap),
+                                            C.byref(n), _stream(stream)))
+        return list(out[:n.value])
+
     def set_eval_impl(self, impl: int):
         self._check(lib().cnnc_set_eval_impl(self._h, C.c_int(impl)))
 
@@ -374,9 +391,10 @@ class Pipe:
 
 
 def cnnc_abi_sizes():
-    """(sizeof cnnc_layer, cnnc_stage_desc, cnnc_params, cnnc_det, cnnc_region, CNNC_T_COUNT) as the library was built."""
-    out = (C.c_int32 * 6)()
-    n = lib().cnnc_abi_sizes(out, C.c_int(6))
+    """(sizeof cnnc_layer, cnnc_stage_desc, cnnc_params, cnnc_det, cnnc_region, CNNC_T_COUNT, sizeof cnnc_rdet) as the
+    library was built."""
+    out = (C.c_int32 * 7)()
+    n = lib().cnnc_abi_sizes(out, C.c_int(7))
     return tuple(out[:n])
 
 
@@ -403,6 +421,10 @@ def cnnc_select_set_weights(ctx, w2, w3, act=1):
 
 def cnnc_select_run(ctx, t1, t2, t3, t_nn, stream=None):
     return ctx.select_run(t1, t2, t3, t_nn, stream)
+
+
+def cnnc_select_merge(ctx, iou=0.3, min_neighbors=1, cap=4096, stream=None):
+    return ctx.select_merge(iou, min_neighbors, cap, stream)
 
 
 def cnnc_select_fetch(ctx, cap=65536, maps=False):

@@ -238,10 +238,11 @@ const char *cnnc_version(void) { return "cnnc 0.1 (gfx950)"; }
 
 int cnnc_abi_sizes(int32_t *out, int n)
 {
-    const int32_t v[6] = {(int32_t)sizeof(cnnc_layer), (int32_t)sizeof(cnnc_stage_desc), (int32_t)sizeof(cnnc_params),
-                          (int32_t)sizeof(cnnc_det), (int32_t)sizeof(cnnc_region), (int32_t)CNNC_T_COUNT};
-    for (int i = 0; out && i < n && i < 6; ++i) out[i] = v[i];
-    return 6;
+    const int32_t v[7] = {(int32_t)sizeof(cnnc_layer), (int32_t)sizeof(cnnc_stage_desc), (int32_t)sizeof(cnnc_params),
+                          (int32_t)sizeof(cnnc_det), (int32_t)sizeof(cnnc_region), (int32_t)CNNC_T_COUNT,
+                          (int32_t)sizeof(cnnc_rdet)};
+    for (int i = 0; out && i < n && i < 7; ++i) out[i] = v[i];
+    return 7;
 }
 
 const char *cnnc_last_error(const cnnc_ctx *ctx) { return ctx ? ctx->err.c_str() : "null context"; }

@@ -53,6 +53,9 @@ struct Counters {
 enum { DONE_PYR = 1, DONE_S1 = 2, DONE_C1 = 4, DONE_E2 = 8, DONE_C2 = 16, DONE_E3 = 32, DONE_C3 = 64, DONE_MERGE = 128 };
 
 // One pyramid level as the scan of the paper-geometry first stage sees it.
+// the scanning window of the paper's own geometry and its step, in level pixels (paper, Section 3.3)
+constexpr int kScanWinW = 27, kScanWinH = 31, kScanStep = 4;
+
 struct ScanLevel {
     int32_t w, h;          // level size
     int32_t ow, oh;        // responses per row / rows of responses (0 when the level is below 27 x 31)
@@ -112,7 +115,10 @@ struct cnnc_ctx {
     float *d_sel_sc = nullptr;
     cnnc_region *d_sel_rec = nullptr;
     float *d_sel_maps = nullptr;             // [2][max_surv][25]
-    int32_t *d_sel_cnt = nullptr, *h_sel_cnt = nullptr;
+    int32_t *d_sel_cnt = nullptr, *h_sel_cnt = nullptr;   // [0] positions listed, [1] regions accepted, [2] merged detections
+    float *d_sel_fsc = nullptr;              // [merge_cap] score of each accepted region
+    uint32_t *d_sel_pick = nullptr;          // [merge_cap] its number in the list of regions
+    cnnc_rdet *d_sel_det = nullptr;          // [merge_cap] merged detections of the unit
     bool sel_done = false;
 
     // device buffers that depend on the layout
@@ -197,6 +203,7 @@ void eval3_make_fragments(const float *blob, float *frag);
 hipError_t launch_merge(const cnnc_ctx *c, hipStream_t st);
 size_t merge_workspace_bytes(int merge_cap);
 hipError_t merge_init_workspace(const cnnc_ctx *c);
+hipError_t launch_merge_regions(const cnnc_ctx *c, float iou, int min_neighbors, hipStream_t st);
 
 constexpr int kCompactBlock = 256;
 constexpr int kCompactPerBlock = 2048;   // values handled by one workgroup

@@ -36,9 +36,9 @@ constexpr int kMaxChunks = kMergeCapMax / kChunk;
 constexpr int kPairCap = 128 * 1024;             // (row, predecessor in an earlier chunk) pairs held per chunk
 
 struct SortedBox {
-    int32_t x, y, size;
+    int32_t x, y, w, h;
     float score;
-    int32_t level, index;
+    int32_t level, index, pad;
 };
 
 struct MergeWs {
@@ -70,12 +70,13 @@ __device__ __forceinline__ int32_t round_half_up(double v) { return (int32_t)flo
 // Frames are at most 16384 pixels a side, so a box area stays below 2^29 and a union below 2^30.
 struct Rect { int32_t x0, y0, x1, y1; };
 
+__device__ __forceinline__ Rect rect_of(const SortedBox &b) { return {b.x, b.y, b.x + b.w, b.y + b.h}; }
+
 __device__ __forceinline__ bool overlaps(const Rect &a, const Rect &b, double thr)
 {
     const int32_t iw = min(a.x1, b.x1) - max(a.x0, b.x0), ih = min(a.y1, b.y1) - max(a.y0, b.y0);
     if (iw <= 0 || ih <= 0) return false;
-    const int32_t sa = a.x1 - a.x0, sb = b.x1 - b.x0;
-    const int32_t inter = iw * ih, uni = sa * sa + sb * sb - inter;
+    const int32_t inter = iw * ih, uni = (a.x1 - a.x0) * (a.y1 - a.y0) + (b.x1 - b.x0) * (b.y1 - b.y0) - inter;
     return (double)inter > __dmul_rn(thr, (double)uni);   // exact: 24-bit threshold times an integer below 2^30
 }
 }  // namespace
@@ -139,10 +140,79 @@ void merge_scatter_kernel(const uint32_t *__restrict__ idx, const float *__restr
     SortedBox b;
     b.x = round_half_up(__dmul_rn((double)(rem % ow), scale));
     b.y = round_half_up(__dmul_rn((double)(rem / ow), scale));
-    b.size = round_half_up(__dmul_rn((double)kWin, scale));
+    b.w = b.h = round_half_up(__dmul_rn((double)kWin, scale));
     b.score = sc[i];
     b.level = l;
     b.index = (int32_t)g;
+    b.pad = 0;
+    sorted[r] = b;
+}
+
+// ---- the regions the selective unit accepted (paper, Section 3.3: non-maximum suppression aggregates the found
+// regions).  A region enters as its 27 x 31 window in frame pixels with the largest combined CNN_3 response as score.
+// One workgroup lists them in ascending position order.
+__global__ __launch_bounds__(kResolveThreads)
+void merge_pick_faces_kernel(const cnnc_region *__restrict__ rec, const float *__restrict__ maps3,
+                             const int32_t *__restrict__ d_nreg, int reg_max, int cap, float *__restrict__ sc,
+                             uint32_t *__restrict__ pick, int32_t *__restrict__ d_nface)
+{
+    __shared__ int s_wsum[kResolveThreads / 64], s_base;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int n = min(*d_nreg, reg_max);
+    if (tid == 0) s_base = 0;
+    __syncthreads();
+    for (int i0 = 0; i0 < n; i0 += kResolveThreads) {
+        const int i = i0 + tid;
+        const bool f = i < n && rec[i].face != 0;
+        const unsigned long long ball = __ballot(f);
+        if (lane == 0) s_wsum[wave] = __popcll(ball);
+        __syncthreads();
+        int pos = s_base;
+        for (int w = 0; w < wave; ++w) pos += s_wsum[w];
+        pos += __popcll(ball & ((1ull << lane) - 1ull));
+        if (f && pos < cap) {
+            const float *m = maps3 + (size_t)i * 25;
+            float best = m[0];
+            for (int k = 1; k < 25; ++k) best = fmaxf(best, m[k]);
+            sc[pos] = best;
+            pick[pos] = (uint32_t)i;
+        }
+        __syncthreads();
+        if (tid == 0) {
+            int tot = 0;
+            for (int w = 0; w < kResolveThreads / 64; ++w) tot += s_wsum[w];
+            s_base += tot;
+        }
+        __syncthreads();
+    }
+    if (tid == 0) *d_nface = s_base;
+}
+
+// sorted[rank[i]] = frame-pixel rectangle of accepted region i; clears rank and the counters for the next call
+__global__ __launch_bounds__(256)
+void merge_scatter_rect_kernel(const cnnc_region *__restrict__ rec, const uint32_t *__restrict__ pick,
+                               const float *__restrict__ sc, const int32_t *__restrict__ d_n, int n_max,
+                               const LevelDev *__restrict__ levels, int32_t *__restrict__ rank, int32_t *__restrict__ nb,
+                               int32_t *__restrict__ npair, SortedBox *__restrict__ sorted)
+{
+    const int n = min(*d_n, n_max);
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i < kMaxChunks) npair[i] = 0;
+    if (i >= n) return;
+    const int r = rank[i];
+    rank[i] = 0;
+    nb[i] = 0;
+    const cnnc_region g = rec[pick[i]];
+    const double scale = levels[g.level].scale;
+    SortedBox b;
+    b.x = round_half_up(__dmul_rn((double)(kScanStep * g.i), scale));
+    b.y = round_half_up(__dmul_rn((double)(kScanStep * g.j), scale));
+    b.w = round_half_up(__dmul_rn((double)kScanWinW, scale));
+    b.h = round_half_up(__dmul_rn((double)kScanWinH, scale));
+    b.score = sc[i];
+    b.level = g.level;
+    b.index = g.index;
+    b.pad = 0;
     sorted[r] = b;
 }
 
@@ -177,15 +247,13 @@ void merge_overlap_kernel(const SortedBox *__restrict__ sorted, const int32_t *_
         const int j = rb * 64 + lane;
         Rect a = {0, 0, 0, 0};
         if (j < n) {
-            const SortedBox bj = sorted[j];
-            a = {bj.x, bj.y, bj.x + bj.size, bj.y + bj.size};
+            a = rect_of(sorted[j]);
         }
         // column box of this lane in word w; beyond the list an empty box, which overlaps nothing
         auto column = [&](int w) -> Rect {
             const int c = w * 64 + lane;
             if (c >= n) return {0, 0, 0, 0};
-            const SortedBox b = sorted[c];
-            return {b.x, b.y, b.x + b.size, b.y + b.size};
+            return rect_of(sorted[c]);
         };
         unsigned long long bits[kChunkWords];
         int cnt = 0;
@@ -238,11 +306,29 @@ void merge_overlap_kernel(const SortedBox *__restrict__ sorted, const int32_t *_
     }
 }
 
+template <typename DET> __device__ __forceinline__ DET make_det(const SortedBox &b, int neighbors);
+template <> __device__ __forceinline__ cnnc_det make_det<cnnc_det>(const SortedBox &b, int neighbors)
+{
+    cnnc_det d;
+    d.x = b.x; d.y = b.y; d.size = b.w; d.score = b.score;
+    d.level = b.level; d.neighbors = neighbors; d.index = b.index; d.reserved = 0;
+    return d;
+}
+template <> __device__ __forceinline__ cnnc_rdet make_det<cnnc_rdet>(const SortedBox &b, int neighbors)
+{
+    cnnc_rdet d;
+    d.x = b.x; d.y = b.y; d.w = b.w; d.h = b.h; d.score = b.score;
+    d.level = b.level; d.neighbors = neighbors; d.index = b.index;
+    return d;
+}
+
+// DET = cnnc_det (square windows of the cascade) or cnnc_rdet (rectangles of the selective unit)
+template <typename DET>
 __global__ __launch_bounds__(kResolveThreads)
 void merge_resolve_kernel(const SortedBox *__restrict__ sorted, const unsigned long long *__restrict__ overlap,
                           const int32_t *__restrict__ npair, const uint32_t *__restrict__ pairs,
                           const int32_t *__restrict__ d_n, int n_max, int min_neighbors,
-                          int32_t *__restrict__ nb, cnnc_det *__restrict__ det, int det_cap,
+                          int32_t *__restrict__ nb, DET *__restrict__ det, int det_cap,
                           int32_t *__restrict__ d_ndet)
 {
     __shared__ unsigned long long keptS[kMergeCapMax / 64], remC[kChunkWords];
@@ -369,11 +455,7 @@ void merge_resolve_kernel(const SortedBox *__restrict__ sorted, const unsigned l
         for (int w = 0; w < wave; ++w) pos += s_wsum[w];
         pos += __popcll(ball & ((1ull << lane) - 1ull));
         if (out && pos < det_cap) {
-            const SortedBox b = sorted[j];
-            cnnc_det d;
-            d.x = b.x; d.y = b.y; d.size = b.size; d.score = b.score;
-            d.level = b.level; d.neighbors = cnt; d.index = b.index; d.reserved = 0;
-            det[pos] = d;
+            det[pos] = make_det<DET>(sorted[j], cnt);
         }
         __syncthreads();
         if (tid == 0) {
@@ -394,6 +476,20 @@ hipError_t merge_init_workspace(const cnnc_ctx *c)
     return e;
 }
 
+namespace {
+template <typename DET>
+void launch_overlap_resolve(const cnnc_ctx *c, const MergeWs &w, const int32_t *d_n, float iou, int min_neighbors,
+                            DET *det, int32_t *d_ndet, hipStream_t st)
+{
+    const int cap = c->merge_cap;
+    const int tiles = ((cap + 63) / 64) * ((cap + 63) / 64);
+    hipLaunchKernelGGL(merge_overlap_kernel, dim3(tiles < 4096 ? tiles : 4096), dim3(64), 0, st, w.sorted, d_n, cap,
+                       iou, w.overlap, w.npair, w.pairs);
+    hipLaunchKernelGGL(merge_resolve_kernel<DET>, dim3(1), dim3(kResolveThreads), 0, st, w.sorted, w.overlap, w.npair, w.pairs,
+                       d_n, cap, min_neighbors, w.nb, det, cap, d_ndet);
+}
+}  // namespace
+
 hipError_t launch_merge(const cnnc_ctx *c, hipStream_t st)
 {
     const MergeWs w = carve(c->d_merge_ws, c->merge_cap);
@@ -402,11 +498,23 @@ hipError_t launch_merge(const cnnc_ctx *c, hipStream_t st)
     hipLaunchKernelGGL(merge_rank_kernel, dim3((cap + 255) / 256, kRankSplit), dim3(256), 0, st, c->d_sc[2], d_n, cap, w.rank);
     hipLaunchKernelGGL(merge_scatter_kernel, dim3((cap + 255) / 256), dim3(256), 0, st, c->d_idx[2], c->d_sc[2], d_n, cap,
                        c->d_levels, c->n_levels, w.rank, w.nb, w.npair, w.sorted);
-    const int tiles = ((cap + 63) / 64) * ((cap + 63) / 64);
-    hipLaunchKernelGGL(merge_overlap_kernel, dim3(tiles < 4096 ? tiles : 4096), dim3(64), 0, st, w.sorted, d_n, cap,
-                       c->params.merge_iou, w.overlap, w.npair, w.pairs);
-    hipLaunchKernelGGL(merge_resolve_kernel, dim3(1), dim3(kResolveThreads), 0, st, w.sorted, w.overlap, w.npair, w.pairs, d_n, cap,
-                       c->params.min_neighbors, w.nb, c->d_det, cap, &c->d_cnt->n[3]);
+    launch_overlap_resolve<cnnc_det>(c, w, d_n, c->params.merge_iou, c->params.min_neighbors, c->d_det, &c->d_cnt->n[3], st);
+    return hipGetLastError();
+}
+
+// Accepted regions of the last selective-unit pass -> d_sel_det, counts in d_sel_cnt[1] (accepted) and [2] (merged).
+hipError_t launch_merge_regions(const cnnc_ctx *c, float iou, int min_neighbors, hipStream_t st)
+{
+    const MergeWs w = carve(c->d_merge_ws, c->merge_cap);
+    const int cap = c->merge_cap;
+    const int32_t *d_n = &c->d_sel_cnt[1];
+    hipLaunchKernelGGL(merge_pick_faces_kernel, dim3(1), dim3(kResolveThreads), 0, st, c->d_sel_rec,
+                       c->d_sel_maps + (size_t)25 * c->max_surv, &c->d_sel_cnt[0], c->max_surv, cap, c->d_sel_fsc,
+                       c->d_sel_pick, &c->d_sel_cnt[1]);
+    hipLaunchKernelGGL(merge_rank_kernel, dim3((cap + 255) / 256, kRankSplit), dim3(256), 0, st, c->d_sel_fsc, d_n, cap, w.rank);
+    hipLaunchKernelGGL(merge_scatter_rect_kernel, dim3((cap + 255) / 256), dim3(256), 0, st, c->d_sel_rec, c->d_sel_pick,
+                       c->d_sel_fsc, d_n, cap, c->d_levels, w.rank, w.nb, w.npair, w.sorted);
+    launch_overlap_resolve<cnnc_rdet>(c, w, d_n, iou, min_neighbors, c->d_sel_det, &c->d_sel_cnt[2], st);
     return hipGetLastError();
 }
 

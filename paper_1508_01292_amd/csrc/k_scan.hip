@@ -17,7 +17,7 @@
 namespace cnnc {
 
 namespace {
-constexpr int kWinW = 27, kWinH = 31, kStep = 4;
+constexpr int kWinW = kScanWinW, kWinH = kScanWinH, kStep = kScanStep;
 constexpr int kC1 = 4, kC2 = 11;
 constexpr int kScanParams = 806;
 // offsets (floats) inside the weight blob: per layer w[cout][cin][kh][kw] then bias[cout]

@@ -20,7 +20,7 @@ namespace cnnc {
 
 namespace {
 constexpr int kThreads = 256;
-constexpr int kRegW = 51, kRegH = 55, kRegP = 52, kMargin = 12, kScanStep = 4;
+constexpr int kRegW = 51, kRegH = 55, kRegP = 52, kMargin = 12;
 constexpr int kWinW = 35, kWinH = 39;
 constexpr int kP1W = (kRegW - 3) / 2, kP1H = (kRegH - 3) / 2;         // 24 x 26
 constexpr int kP2W = (kP1W - 2) / 2, kP2H = (kP1H - 2) / 2, kP2P = 12; // 11 x 12
@@ -236,6 +236,8 @@ void select_release(cnnc_ctx *c)
 {
     (void)hipFree(c->d_sel_w2); (void)hipFree(c->d_sel_w3); (void)hipFree(c->d_sel_idx); (void)hipFree(c->d_sel_sc);
     (void)hipFree(c->d_sel_rec); (void)hipFree(c->d_sel_maps); (void)hipFree(c->d_sel_cnt);
+    (void)hipFree(c->d_sel_fsc); (void)hipFree(c->d_sel_pick); (void)hipFree(c->d_sel_det);
+    c->d_sel_fsc = nullptr; c->d_sel_pick = nullptr; c->d_sel_det = nullptr;
     if (c->h_sel_cnt) (void)hipHostFree(c->h_sel_cnt);
     c->d_sel_w2 = c->d_sel_w3 = nullptr; c->d_sel_idx = nullptr; c->d_sel_sc = nullptr; c->d_sel_rec = nullptr;
     c->d_sel_maps = nullptr; c->d_sel_cnt = nullptr; c->h_sel_cnt = nullptr;
@@ -268,8 +270,11 @@ int cnnc_select_set_weights(cnnc_ctx *c, const float *w2, int n2, const float *w
         HIP_TRY(c, hipMalloc((void **)&c->d_sel_sc, sizeof(float) * cap));
         HIP_TRY(c, hipMalloc((void **)&c->d_sel_rec, sizeof(cnnc_region) * cap));
         HIP_TRY(c, hipMalloc((void **)&c->d_sel_maps, sizeof(float) * 2 * kMap * cap));
-        HIP_TRY(c, hipMalloc((void **)&c->d_sel_cnt, sizeof(int32_t)));
-        HIP_TRY(c, hipHostMalloc((void **)&c->h_sel_cnt, sizeof(int32_t), hipHostMallocDefault));
+        HIP_TRY(c, hipMalloc((void **)&c->d_sel_cnt, sizeof(int32_t) * 4));
+        HIP_TRY(c, hipHostMalloc((void **)&c->h_sel_cnt, sizeof(int32_t) * 4, hipHostMallocDefault));
+        HIP_TRY(c, hipMalloc((void **)&c->d_sel_fsc, sizeof(float) * (size_t)c->merge_cap));
+        HIP_TRY(c, hipMalloc((void **)&c->d_sel_pick, sizeof(uint32_t) * (size_t)c->merge_cap));
+        HIP_TRY(c, hipMalloc((void **)&c->d_sel_det, sizeof(cnnc_rdet) * (size_t)c->merge_cap));
     }
     HIP_TRY(c, hipMemcpy(c->d_sel_w2, w2, sizeof(float) * kNet2Params, hipMemcpyHostToDevice));
     HIP_TRY(c, hipMemcpy(c->d_sel_w3, w3, sizeof(float) * kNet3Params, hipMemcpyHostToDevice));
@@ -324,6 +329,27 @@ int cnnc_select_fetch(cnnc_ctx *c, cnnc_region *out, int cap, int *n_out, float 
             HIP_TRY(c, hipMemcpy(maps3, c->d_sel_maps + (size_t)kMap * c->max_surv, sizeof(float) * kMap * (size_t)m, hipMemcpyDeviceToHost));
     }
     if (total > c->max_surv) return fail(c, CNNC_E_OVERFLOW, "more positions passed T_1 than the context's survivor capacity");
+    if (total > cap) return fail(c, CNNC_E_OVERFLOW, "output array too small");
+    return CNNC_OK;
+}
+
+int cnnc_select_merge(cnnc_ctx *c, float iou, int min_neighbors, cnnc_rdet *out, int cap, int *n_out, void *stream)
+{
+    if (!c) return CNNC_E_INVAL;
+    if (!n_out || cap < 0 || (!out && cap > 0)) return fail(c, CNNC_E_INVAL, "null output");
+    if (!(iou >= 0.0f && iou <= 1.0f) || min_neighbors < 1) return fail(c, CNNC_E_INVAL, "iou outside [0, 1] or min_neighbors < 1");
+    if (!c->sel_done) return fail(c, CNNC_E_STATE, "cnnc_select_run has not been called for this frame");
+    hipStream_t st = (hipStream_t)stream;
+    c->last_stream = st;
+    HIP_TRY(c, launch_merge_regions(c, iou, min_neighbors, st));
+    HIP_TRY(c, hipMemcpyAsync(c->h_sel_cnt, c->d_sel_cnt, sizeof(int32_t) * 3, hipMemcpyDeviceToHost, st));
+    HIP_TRY(c, hipStreamSynchronize(st));
+    *n_out = 0;
+    if (c->h_sel_cnt[0] > c->max_surv) return fail(c, CNNC_E_OVERFLOW, "more positions passed T_1 than the context's survivor capacity");
+    if (c->h_sel_cnt[1] > c->merge_cap) return fail(c, CNNC_E_OVERFLOW, "more regions accepted than the merge can take");
+    const int total = c->h_sel_cnt[2], m = std::min(total, cap);
+    *n_out = total;
+    if (m > 0) HIP_TRY(c, hipMemcpy(out, c->d_sel_det, sizeof(cnnc_rdet) * (size_t)m, hipMemcpyDeviceToHost));
     if (total > cap) return fail(c, CNNC_E_OVERFLOW, "output array too small");
     return CNNC_OK;
 }

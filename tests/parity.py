@@ -77,6 +77,29 @@ def greedy_merge_check(bx, by, bs, score, order, iou=0.3, min_neighbors=1):
     return out
 
 
+def greedy_merge_rect_check(bx, by, bw, bh, score, order, iou=0.3, min_neighbors=1):
+    """The same test-side check for rectangles (the regions the selective unit accepts)."""
+    n = len(bx)
+    seq = sorted(range(n), key=lambda i: (-float(np.float32(score[i])), int(order[i])))
+    bx, by, bw, bh = (np.asarray(a, np.int64)[seq] for a in (bx, by, bw, bh))
+    dead = np.zeros(n, bool)
+    thr = float(np.float32(iou))
+    out = []
+    for i in range(n):
+        if dead[i]:
+            continue
+        j = np.arange(i + 1, n)
+        iw = np.minimum(bx[i] + bw[i], bx[j] + bw[j]) - np.maximum(bx[i], bx[j])
+        ih = np.minimum(by[i] + bh[i], by[j] + bh[j]) - np.maximum(by[i], by[j])
+        inter = np.where((iw > 0) & (ih > 0), iw * ih, 0)
+        uni = bw[i] * bh[i] + bw[j] * bh[j] - inter
+        hit = (inter.astype(np.float64) > thr * uni.astype(np.float64)) & ~dead[j] & (inter > 0)
+        dead[j[hit]] = True
+        if hit.sum() + 1 >= min_neighbors:
+            out.append((seq[i], int(hit.sum())))
+    return out
+
+
 def run_gpu_steps(ctx, frame_t, thr, stream=None):
     """Run the path call by call and fetch every intermediate."""
     out = {}

@@ -75,4 +75,4 @@ def test_struct_sizes_and_step_names_match_the_library():
     from paper_1508_01292_amd import binding as B
     sizes = B.cnnc_abi_sizes()
     assert sizes == (C.sizeof(B._Layer), C.sizeof(B._StageDesc), C.sizeof(B._Params), C.sizeof(B.Detection),
-                     C.sizeof(B.Region), len(B.STEP_NAMES))
+                     C.sizeof(B.Region), len(B.STEP_NAMES), C.sizeof(B.RegionDetection))

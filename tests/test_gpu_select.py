@@ -6,7 +6,7 @@ import pytest
 import cnnc_inputs as I
 from oracle import oracle as O
 
-from parity import ATOL, BAND, RTOL
+from parity import ATOL, BAND, RTOL, greedy_merge_rect_check
 
 pytestmark = pytest.mark.gpu
 
@@ -68,6 +68,30 @@ def _select_case(frame, min_face, step, act, seed, q1, q2, t_nn, bias_sd=0.0, na
         # the record's own consistency with rule (2)
         assert bool(r.face) == ((r.k2 >= t_nn and r.k3 > 0) or (r.k2 > 0 and r.k3 >= t_nn))
         n_cmp += 1
+    # ---- merge of the accepted regions
+    faces = [k for k, r in enumerate(recs) if r.face]
+    box = np.array([O.region_box(recs[k].i, recs[k].j, pyr.scale[recs[k].level], n1) for k in faces], np.int64).reshape(-1, 4)
+    sc = m3[faces].reshape(len(faces), 25).max(axis=1) if faces else np.zeros(0, np.float32)
+    order = [recs[k].index for k in faces]
+    ref_faces = [r for r in ref if r["face"]]
+    ref_seq = sorted(ref_faces, key=lambda r: (-float(np.float32(r["r3"].max())), r["index"]))
+    gpu_seq = sorted(range(len(faces)), key=lambda p: (-float(sc[p]), order[p]))
+    same_input = [r["index"] for r in ref_seq] == [order[p] for p in gpu_seq]       # same regions in the same order
+    for iou, mn in ((0.3, 1), (0.5, 2)):
+        det = [d.as_dict() for d in ctx.select_merge(iou, mn, cap=50000)]
+        valid = greedy_merge_rect_check(box[:, 0], box[:, 1], box[:, 2], box[:, 3], sc, order, iou, mn)
+        assert [(d["index"], d["neighbors"]) for d in det] == [(order[p], k) for p, k in valid], (iou, mn)
+        for d, (p, _) in zip(det, valid):
+            assert (d["x"], d["y"], d["w"], d["h"]) == tuple(int(v) for v in box[p]) and d["level"] == recs[faces[p]].level
+            assert d["score"] == sc[p]
+        if same_input:
+            want = O.select_merge(pyr, ref, n1, iou, mn)
+            assert [(d["index"], d["neighbors"], d["x"], d["y"], d["w"], d["h"], d["level"]) for d in det] == \
+                [(w["index"], w["neighbors"], w["x"], w["y"], w["w"], w["h"], w["level"]) for w in want], (iou, mn)
+            assert all(abs(d["score"] - w["score"]) <= ATOL + RTOL * abs(w["score"]) for d, w in zip(det, want))
+        print("   merge at iou %.1f, min_neighbors %d: %d regions -> %d detections (%s)"
+              % (iou, mn, len(faces), len(det), "equal to the oracle's" if same_input else "valid merge of the GPU's own list"),
+              flush=True)
     ctx.close()
     print("   %d positions listed, %d compared, %d faces, %d with a response inside the band" % (len(recs), n_cmp, n_face, n_banded),
           flush=True)
@@ -121,14 +145,32 @@ def test_select_errors_and_degenerate_cases():
     ctx.build_pyramid(torch.from_numpy(frame).cuda())
     with pytest.raises(P.CnncError):
         ctx.select_fetch(16)                          # nothing run
+    with pytest.raises(P.CnncError):
+        ctx.select_merge()
     ctx.scan_scoremap()
     with pytest.raises(P.CnncError):
         ctx.select_run(float("nan"), 0.0, 0.0, 1)
     ctx.select_run(1e30, 0.0, 0.0, 1)                 # nothing passes T_1
     assert ctx.select_fetch(16) == []
+    assert ctx.select_merge() == []
+    with pytest.raises(P.CnncError):
+        ctx.select_merge(iou=1.5)
+    t_few = float(np.sort(ctx.get_scan_scoremap())[-9])   # eight positions (fewer with ties) lie above it
+    ctx.select_run(t_few, 1e30, 1e30, 1)              # positions listed, none accepted
+    assert 0 < len(ctx.select_fetch(16)) <= 8 and ctx.select_merge() == []
+    ctx.select_run(t_few, -1e30, -1e30, 1)            # all of them accepted
+    n_acc = len(ctx.select_fetch(16))
+    det = ctx.select_merge(iou=0.0, min_neighbors=1)
+    assert 0 < len(det) <= n_acc and sum(d.neighbors + 1 for d in det) == n_acc
+    with pytest.raises(P.CnncError) as e:
+        ctx.select_merge(iou=1.0, cap=0)              # nothing can be absorbed at iou 1: n_acc detections, no room
+    assert e.value.code == -3
     ctx.select_run(-1e30, 0.0, 0.0, 1)                # everything passes: more than the capacity of 16
     with pytest.raises(P.CnncError) as e:
         ctx.select_fetch(16)
+    assert e.value.code == -3
+    with pytest.raises(P.CnncError) as e:
+        ctx.select_merge()
     assert e.value.code == -3
     # a new pyramid invalidates the unit's results
     ctx.build_pyramid(torch.from_numpy(frame).cuda())
