@@ -25,8 +25,8 @@
  * hand-computed one-hot window, definition vs single pass, translation by
  * one step; for the selective unit in that geometry: exact special cases and
  * library bilinear for the region, closed forms of histogram equalisation,
- * library convolution for the mirrored response maps, the truth table of
- * eq. (2), and the merge of the accepted rectangles against the square merge
+ * library convolution for the mirrored response maps, the truth tables of
+ * eq. (2) and eq. (3), and the merge of the accepted rectangles against the square merge
  * and a brute force in exact fractions.  The choice of the readings
  * themselves (resampling convention, crop rectangle, merge rule; in the
  * paper's geometry the layer shapes, the width of the neighbourhood, the
@@ -699,11 +699,15 @@ void orc_histeq(uint8_t *img, int n)
 /* the analysis stops (paper: "further analysis of the region stops"), else   */
 /* CNN_3 gives K3 the same way with t3, and eq. (2) decides:                  */
 /*   face = (K2 >= t_nn and K3 > 0) or (K2 > 0 and K3 >= t_nn).               */
+/* rule = 3 selects the weaker rule of Section 4.3, eq. (3):                  */
+/*   face = K2 >= t_nn or K3 >= t_nn                                          */
+/* (reading: the stop at K2 = 0 belongs to the unit, not to the rule, so it   */
+/* stays; K3 is then 0).                                                      */
 /* r2, r3: the combined response maps (nh x nw doubles each; r3 is zero when  */
 /* CNN_3 was not run).  Returns 0, -1 if a network does not fit the region.   */
 int orc_select_region(const uint8_t *region, int rw, int rh,
                       const orc_rlayer *l2, int n2, const float *w2, const orc_rlayer *l3, int n3, const float *w3,
-                      int win_w, int win_h, float t2, float t3, int t_nn,
+                      int win_w, int win_h, float t2, float t3, int t_nn, int rule,
                       int32_t *k2, int32_t *k3, int32_t *face, double *r2, double *r3)
 {
     int step = 1;
@@ -732,7 +736,8 @@ int orc_select_region(const uint8_t *region, int rw, int rh,
                         if ((float)r3[v * nw + u] > t3) ++*k3;
                     }
         }
-        *face = (*k2 >= t_nn && *k3 > 0) || (*k2 > 0 && *k3 >= t_nn);
+        if (rule == 3) *face = *k2 >= t_nn || *k3 >= t_nn;
+        else *face = (*k2 >= t_nn && *k3 > 0) || (*k2 > 0 && *k3 >= t_nn);
     }
     free(mir); free(a);
     return rc;

@@ -224,8 +224,9 @@ def histeq(img: np.ndarray) -> np.ndarray:
     return out
 
 
-def select_region(reg: np.ndarray, net2, w2: np.ndarray, net3, w3: np.ndarray, t2: float, t3: float, t_nn: int):
-    """One equalised region through CNN_2 / CNN_3 and the decision rule: (K2, K3, face, r2, r3)."""
+def select_region(reg: np.ndarray, net2, w2: np.ndarray, net3, w3: np.ndarray, t2: float, t3: float, t_nn: int,
+                  rule: int = 2):
+    """One equalised region through CNN_2 / CNN_3 and the decision rule (2) or (3): (K2, K3, face, r2, r3)."""
     reg = np.ascontiguousarray(reg, np.uint8)
     w2 = np.ascontiguousarray(w2, np.float32)
     w3 = np.ascontiguousarray(w3, np.float32)
@@ -237,7 +238,7 @@ def select_region(reg: np.ndarray, net2, w2: np.ndarray, net3, w3: np.ndarray, t
     r3 = np.zeros((nh, nw), np.float64)
     rc = lib().orc_select_region(_p(reg), C.c_int(rw), C.c_int(rh), _rlayers(net2), C.c_int(len(net2.layers)), _p(w2),
                                  _rlayers(net3), C.c_int(len(net3.layers)), _p(w3), C.c_int(net2.win_w), C.c_int(net2.win_h),
-                                 C.c_float(t2), C.c_float(t3), C.c_int(t_nn), C.byref(k2), C.byref(k3), C.byref(face),
+                                 C.c_float(t2), C.c_float(t3), C.c_int(t_nn), C.c_int(rule), C.byref(k2), C.byref(k3), C.byref(face),
                                  _p(r2), _p(r3))
     if rc != 0:
         raise ValueError("a network does not fit the region")
@@ -245,7 +246,7 @@ def select_region(reg: np.ndarray, net2, w2: np.ndarray, net3, w3: np.ndarray, t
 
 
 def select_unit(frame: np.ndarray, pyr: Pyramid, scan_idx: np.ndarray, net1, net2, w2, net3, w3, t2: float, t3: float,
-                t_nn: int, rw: int = 51, rh: int = 55, margin: int = 12):
+                t_nn: int, rw: int = 51, rh: int = 55, margin: int = 12, rule: int = 2):
     """The selective unit for the scan responses with flat indices scan_idx: list of dicts (index, level, i, j, k2, k3,
     face, r2, r3) in that order.  The region of window (i, j) of a level is the window plus `margin` level pixels."""
     sizes = [((l.shape[0] - net1.win_h) // net1.step + 1, (l.shape[1] - net1.win_w) // net1.step + 1)
@@ -257,7 +258,7 @@ def select_unit(frame: np.ndarray, pyr: Pyramid, scan_idx: np.ndarray, net1, net
         rel = int(g - off[lvl])
         j, i = divmod(rel, sizes[lvl][1])
         reg = histeq(region(frame, net1.step * i - margin, net1.step * j - margin, pyr.scale[lvl], rw, rh))
-        k2, k3, face, r2, r3 = select_region(reg, net2, w2, net3, w3, t2, t3, t_nn)
+        k2, k3, face, r2, r3 = select_region(reg, net2, w2, net3, w3, t2, t3, t_nn, rule)
         out.append(dict(index=int(g), level=lvl, i=i, j=j, k2=k2, k3=k3, face=face, r2=r2, r3=r3))
     return out
 

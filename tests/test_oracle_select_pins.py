@@ -83,6 +83,13 @@ def test_decision_rule_truth_table():
     assert O.select_region(reg, n2, hi2, n3, lo3, 0.0, 0.0, 1)[:3] == (25, 0, False)
     k2, k3, face, r2, r3 = O.select_region(reg, n2, lo2, n3, hi3, 0.0, 0.0, 1)
     assert (k2, k3, face) == (0, 0, False) and np.all(r3 == 0) and np.all(r2 == -1.0)     # CNN_3 is not run
+    # eq. (3), the weaker rule of Section 4.3: face = K2 >= T_nn or K3 >= T_nn
+    assert O.select_region(reg, n2, hi2, n3, lo3, 0.0, 0.0, 1, rule=3)[:3] == (25, 0, True)      # rule (2) said no
+    assert O.select_region(reg, n2, hi2, n3, lo3, 0.0, 0.0, 26, rule=3)[:3] == (25, 0, False)
+    assert O.select_region(reg, n2, hi2, n3, hi3, 0.0, 0.0, 25, rule=3)[:3] == (25, 25, True)
+    assert O.select_region(reg, n2, lo2, n3, hi3, 0.0, 0.0, 1, rule=3)[:3] == (0, 0, False)      # CNN_3 still not run
+    k23 = [(a, b) for a in range(0, 26, 5) for b in range(0, 26, 5)]
+    assert all(((a >= 10) or (b >= 10)) >= ((a >= 10 and b > 0) or (a > 0 and b >= 10)) for a, b in k23)   # (3) is weaker
     # the comparison is strict and made in fp32
     assert O.select_region(reg, n2, hi2, n3, hi3, 1.0, 0.0, 1)[:3] == (0, 0, False)
     assert O.select_region(reg, n2, hi2, n3, hi3, float(np.nextafter(np.float32(1.0), np.float32(0.0))), 0.0, 1)[0] == 25
@@ -109,6 +116,11 @@ def test_response_maps_mirror_and_counts_against_torch(act):
     assert k3 == int((want["3"].astype(np.float32) > np.float32(t3)).sum()) and k3 in (3, 4)
     assert face is True                               # K2 >= 5 and K3 > 0
     assert O.select_region(reg, n2, w2, n3, w3, np.float32(t2), np.float32(t3), 9)[2] is False
+    # eq. (3) through its CNN_3 branch: few votes of CNN_2, many of CNN_3
+    t2b, t3b = float(np.sort(want["2"].ravel())[-3]), float(np.sort(want["3"].ravel())[-21])
+    k2, k3, face = O.select_region(reg, n2, w2, n3, w3, np.float32(t2b), np.float32(t3b), 10, rule=3)[:3]
+    assert k2 in (2, 3) and k3 in (20, 21) and face is True
+    assert O.select_region(reg, n2, w2, n3, w3, np.float32(t2b), np.float32(t3b), 22, rule=3)[2] is False
 
 
 def test_unit_geometry_window_sits_in_the_middle_of_its_region():
