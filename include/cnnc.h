@@ -234,6 +234,9 @@ int cnnc_get_scan_scoremap(cnnc_ctx *ctx, const float **d_scores, int64_t *n);
  *
  * cnnc_select_set_weights: host blobs (per conv layer w[cout][cin][kh][kw] then bias[cout]), n2 = 1836, n3 = 2942,
  *   act = hidden activation kind; copied; synchronises; allocates the unit's buffers on first use.
+ * cnnc_select_set_rule: rule = 2 (default) is eq. (2) above; rule = 3 the weaker rule of Section 4.3, eq. (3):
+ *   face = K2 >= T_nn or K3 >= T_nn (more recall, less precision).  The stop at K2 = 0 stays under either rule.
+ *   Applies to later cnnc_select_run calls; CNNC_E_INVAL for another value.
  * cnnc_select_run: needs cnnc_scan_scoremap of the current frame (CNNC_E_STATE otherwise), whose frame must still be
  *   alive.  Lists the positions with response > t1 in ascending flat order and runs the unit on each; K2 counts
  *   responses > t2, K3 responses > t3 (fp32, strict).  Enqueued on `stream`.
@@ -244,10 +247,11 @@ typedef struct {
     int32_t index;          /* flat index of the position in the response map of cnnc_scan_scoremap */
     int32_t level, i, j;    /* pyramid level, column and row of the position (window corner = pixel (4 i, 4 j)) */
     int32_t k2, k3;         /* responses above the threshold in the 5 x 5 maps of CNN_2 and CNN_3 */
-    int32_t face;           /* decision rule (2) */
+    int32_t face;           /* decision by rule (2), or rule (3) when selected */
     float response;         /* first-stage response of the position */
 } cnnc_region;
 int cnnc_select_set_weights(cnnc_ctx *ctx, const float *w2, int n2, const float *w3, int n3, int act);
+int cnnc_select_set_rule(cnnc_ctx *ctx, int rule);
 int cnnc_select_run(cnnc_ctx *ctx, float t1, float t2, float t3, int t_nn, void *stream);
 int cnnc_select_fetch(cnnc_ctx *ctx, cnnc_region *out, int cap, int *n_out, float *maps2, float *maps3);
 

@@ -21,7 +21,7 @@ EXPORTS = [
     "cnnc_get_timings", "cnnc_set_eval_impl", "cnnc_measure_peaks", "cnnc_last_error", "cnnc_version",
     "cnnc_stage1_survivors", "cnnc_set_fused_stage1",
     "cnnc_scan_set_weights", "cnnc_scan_layout", "cnnc_scan_scoremap", "cnnc_get_scan_scoremap",
-    "cnnc_select_set_weights", "cnnc_select_run", "cnnc_select_fetch", "cnnc_select_merge", "cnnc_abi_sizes",
+    "cnnc_select_set_weights", "cnnc_select_set_rule", "cnnc_select_run", "cnnc_select_fetch", "cnnc_select_merge", "cnnc_abi_sizes",
     "cnnc_pipe_create", "cnnc_pipe_destroy", "cnnc_pipe_set_params", "cnnc_pipe_frame_buffer", "cnnc_pipe_submit",
     "cnnc_pipe_fetch", "cnnc_pipe_last_error",
 ]
@@ -300,6 +300,9 @@ class Context:
         recs = list(out[:n.value])
         return (recs, m2[:n.value], m3[:n.value]) if maps else recs
 
+    def select_set_rule(self, rule: int):
+        self._check(lib().cnnc_select_set_rule(self._h, C.c_int(rule)))
+
     def select_merge(self, iou: float = 0.3, min_neighbors: int = 1, cap: int = 4096, stream=None):
         """Greedy merge of the regions the last select_run accepted (list of RegionDetection, kept order)."""
         out = (RegionDetection * cap)()
@@ -421,6 +424,10 @@ def cnnc_select_set_weights(ctx, w2, w3, act=1):
 
 def cnnc_select_run(ctx, t1, t2, t3, t_nn, stream=None):
     return ctx.select_run(t1, t2, t3, t_nn, stream)
+
+
+def cnnc_select_set_rule(ctx, rule):
+    return ctx.select_set_rule(rule)
 
 
 def cnnc_select_merge(ctx, iou=0.3, min_neighbors=1, cap=4096, stream=None):

@@ -137,7 +137,7 @@ __global__ __launch_bounds__(kThreads)
 void select_kernel(const uint8_t *__restrict__ frame, int fw, int fh, int pitch, const LevelDev *__restrict__ levels,
                    const ScanLevel *__restrict__ slev, int n_levels, const uint32_t *__restrict__ idx,
                    const float *__restrict__ resp, const int32_t *__restrict__ d_n, int n_max,
-                   const float *__restrict__ w2, const float *__restrict__ w3, float t2, float t3, int t_nn,
+                   const float *__restrict__ w2, const float *__restrict__ w3, float t2, float t3, int t_nn, int rule,
                    cnnc_region *__restrict__ rec, float *__restrict__ maps2, float *__restrict__ maps3)
 {
     __shared__ float sReg[kRegH * kRegP];
@@ -224,7 +224,8 @@ void select_kernel(const uint8_t *__restrict__ frame, int fw, int fh, int pitch,
         if (tid == 0) {
             cnnc_region R;
             R.index = (int32_t)g; R.level = l; R.i = wi; R.j = wj; R.k2 = k2; R.k3 = k3;
-            R.face = ((k2 >= t_nn && k3 > 0) || (k2 > 0 && k3 >= t_nn)) ? 1 : 0;
+            if (rule == 3) R.face = (k2 >= t_nn || k3 >= t_nn) ? 1 : 0;                          // eq. (3), Section 4.3
+            else R.face = ((k2 >= t_nn && k3 > 0) || (k2 > 0 && k3 >= t_nn)) ? 1 : 0;              // eq. (2)
             R.response = resp[s];
             rec[s] = R;
         }
@@ -283,6 +284,14 @@ int cnnc_select_set_weights(cnnc_ctx *c, const float *w2, int n2, const float *w
     return CNNC_OK;
 }
 
+int cnnc_select_set_rule(cnnc_ctx *c, int rule)
+{
+    if (!c) return CNNC_E_INVAL;
+    if (rule != 2 && rule != 3) return fail(c, CNNC_E_INVAL, "decision rule must be 2 or 3");
+    c->sel_rule = rule;
+    return CNNC_OK;
+}
+
 int cnnc_select_run(cnnc_ctx *c, float t1, float t2, float t3, int t_nn, void *stream)
 {
     if (!c) return CNNC_E_INVAL;
@@ -300,7 +309,7 @@ int cnnc_select_run(cnnc_ctx *c, float t1, float t2, float t3, int t_nn, void *s
 #define CNNC_SEL(ACT)                                                                                             \
     hipLaunchKernelGGL(select_kernel<ACT>, grid, block, 0, st, c->d_frame, c->fw, c->fh, c->fpitch, c->d_levels,  \
                        c->d_scan_levels, c->n_levels, c->d_sel_idx, c->d_sel_sc, c->d_sel_cnt, c->max_surv,       \
-                       c->d_sel_w2, c->d_sel_w3, t2, t3, t_nn, c->d_sel_rec, m2, m3)
+                       c->d_sel_w2, c->d_sel_w3, t2, t3, t_nn, c->sel_rule, c->d_sel_rec, m2, m3)
     switch (c->sel_act) {
     case CNNC_ACT_RATIONAL: CNNC_SEL(CNNC_ACT_RATIONAL); break;
     case CNNC_ACT_SCALED_TANH: CNNC_SEL(CNNC_ACT_SCALED_TANH); break;

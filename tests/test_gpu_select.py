@@ -11,7 +11,7 @@ from parity import ATOL, BAND, RTOL, greedy_merge_rect_check
 pytestmark = pytest.mark.gpu
 
 
-def _select_case(frame, min_face, step, act, seed, q1, q2, t_nn, bias_sd=0.0, name=""):
+def _select_case(frame, min_face, step, act, seed, q1, q2, t_nn, bias_sd=0.0, name="", rule=2, q3=None):
     import torch
     import paper_1508_01292_amd as P
     print("select case", name, frame.shape, "act", act, "q1", q1, flush=True)
@@ -24,8 +24,8 @@ def _select_case(frame, min_face, step, act, seed, q1, q2, t_nn, bias_sd=0.0, na
     # thresholds of the response maps: a quantile of CNN_2's responses over all listed regions
     ref = O.select_unit(frame, pyr, want_idx, n1, n2, w2, n3, w3, -1e30, -1e30, 1)
     t2 = float(np.float32(np.quantile(np.concatenate([r["r2"].ravel() for r in ref]), 1 - q2)))
-    t3 = float(np.float32(np.quantile(np.concatenate([r["r3"].ravel() for r in ref]), 1 - q2)))
-    ref = O.select_unit(frame, pyr, want_idx, n1, n2, w2, n3, w3, t2, t3, t_nn)
+    t3 = float(np.float32(np.quantile(np.concatenate([r["r3"].ravel() for r in ref]), 1 - (q2 if q3 is None else q3))))
+    ref = O.select_unit(frame, pyr, want_idx, n1, n2, w2, n3, w3, t2, t3, t_nn, rule=rule)
 
     casc = I.default_cascade()
     ctx = P.Context(casc, I.draw_weights(casc, seed), frame.shape[1], frame.shape[0], 50000)
@@ -34,6 +34,8 @@ def _select_case(frame, min_face, step, act, seed, q1, q2, t_nn, bias_sd=0.0, na
     ctx.select_set_weights(w2, w3, act)
     ctx.build_pyramid(torch.from_numpy(frame).cuda())
     ctx.scan_scoremap()
+    if rule != 2:
+        ctx.select_set_rule(rule)
     ctx.select_run(t1, t2, t3, t_nn)
     recs, m2, m3 = ctx.select_fetch(50000, maps=True)
     # positions: equal outside the band around t1
@@ -66,7 +68,10 @@ def _select_case(frame, min_face, step, act, seed, q1, q2, t_nn, bias_sd=0.0, na
         else:
             n_banded += 1
         # the record's own consistency with rule (2)
-        assert bool(r.face) == ((r.k2 >= t_nn and r.k3 > 0) or (r.k2 > 0 and r.k3 >= t_nn))
+        if rule == 3:
+            assert bool(r.face) == (r.k2 >= t_nn or r.k3 >= t_nn)
+        else:
+            assert bool(r.face) == ((r.k2 >= t_nn and r.k3 > 0) or (r.k2 > 0 and r.k3 >= t_nn))
         n_cmp += 1
     # ---- merge of the accepted regions
     faces = [k for k, r in enumerate(recs) if r.face]
@@ -109,6 +114,18 @@ def test_select_vga(act):
     assert any(r["face"] for r in ref) and not all(r["face"] for r in ref)
 
 
+def test_select_weaker_rule_of_eq_3():
+    """The same frame under eq. (3): every region eq. (2) accepts stays accepted, and some are added."""
+    c = I.CONFIGS[0]
+    frame = I.make_frame(c["width"], c["height"], I.config_seed(0))
+    # CNN_3's threshold sits high in its responses, so that many regions have K2 >= T_nn and K3 = 0: there the rules differ
+    args = (frame, c["min_face"], c["scale_step"], I.ACT_RATIONAL, 40, 0.1, 0.3, 4)
+    _, ref3 = _select_case(*args, name="vga, rule 3", rule=3, q3=0.004)
+    _, ref2 = _select_case(*args, name="vga, rule 2", rule=2, q3=0.004)
+    f2, f3 = {r["index"] for r in ref2 if r["face"]}, {r["index"] for r in ref3 if r["face"]}
+    assert f2 < f3
+
+
 def test_select_ragged_frame_regions_cut_by_the_border():
     # small levels: most regions reach over the level edge, where the frame edge is repeated
     frame = I.make_frame(333, 251, 5)
@@ -138,6 +155,8 @@ def test_select_errors_and_degenerate_cases():
         ctx.select_set_weights(w2[:-1], w3, 1)
     with pytest.raises(P.CnncError):
         ctx.select_set_weights(w2, w3, 4)
+    with pytest.raises(P.CnncError):
+        ctx.select_set_rule(1)
     ctx.select_set_weights(w2, w3, 1)
     with pytest.raises(P.CnncError):
         ctx.select_run(0.0, 0.0, 0.0, 1)              # no scan of this frame
