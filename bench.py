@@ -199,6 +199,18 @@ def main():
     for _ in range(20):
         c0.select_merge(0.3, 1, 32768, streams[0])
     ms_sel_merge = (time.perf_counter() - t0) / 20 * 1e3
+    # the paper-geometry path end to end, one frame at a time: pyramid, scan, selective unit, merge (which waits)
+    n_paper = 50
+    with torch.cuda.stream(streams[0]):
+        for it in range(n_paper + 5):
+            if it == 5:
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+            c0.build_pyramid(dev_frame, streams[0])
+            c0.scan_scoremap(streams[0])
+            c0.select_run(t1_scan, t2_sel, t3_sel, 5, streams[0])
+            c0.select_merge(0.3, 1, 32768, streams[0])
+    ms_paper_frame = (time.perf_counter() - t0) / n_paper * 1e3
     sel_flop = 2.0 * sum(2 * SEL_MAC_CNN2 + (2 * SEL_MAC_CNN3 if r.k2 > 0 else 0) for r in sel)
     c0.detect(dev_frame, 8192)           # leaves the context with the cascade's own survivor lists again
     n1, n2, n3 = (c0.survivor_count(s) for s in (1, 2, 3))
@@ -296,7 +308,8 @@ def main():
                                  "regions_per_s": len(sel) / (ms_sel * 1e-3) if ms_sel > 0 else None, "bound": "alu",
                                  "achieved": tflops(sel_flop, ms_sel), "peak": PEAK_FP32_VECTOR, "unit": "TFLOP/s",
                                  "frac": tflops(sel_flop, ms_sel) / PEAK_FP32_VECTOR,
-                                 "merge": {"detections": len(sel_det), "ms_per_call_with_wait_and_readback": ms_sel_merge}},
+                                 "merge": {"detections": len(sel_det), "ms_per_call_with_wait_and_readback": ms_sel_merge},
+                                 "whole_path_ms_per_frame_one_at_a_time": ms_paper_frame},
         "sum_of_kernel_ms": sum(v for k, v in ms.items() if not k.endswith("_conv") and k not in ("scan", "select")),
         "roofline": roof,
         "kernels": kernels,
