@@ -10,11 +10,12 @@
 //   C_k = f(b2_k + sum w2_k[c][a][b] M_c(y+2a, x+2b))              conv 3x3, 4 -> 8, spacing 2
 //   score = b3 + sum w3[k][i][j] C_k(y+2i, x+2j)                    fc over 8x3x3, spacing 2
 //
-// Register blocking: a thread computes four neighbouring positions at a time, so every LDS value is
-// read once per four outputs and with 16-byte loads.  For the spacing-2 layers the maps M and C are
-// stored with even and odd columns apart ([channel][row][column parity][column / 2]); the four
-// positions of a thread are then four consecutive entries of one parity, and their taps are
-// consecutive too.  Weights are wave-uniform and come through scalar loads.
+// Register blocking: a thread computes four (conv2: three) neighbouring positions at a time, so every
+// LDS value is read once per unit.  For the spacing-2 layers the maps M and C are stored with even and
+// odd columns apart ([channel][row][column parity][column / 2]); the positions of a thread are then
+// consecutive entries of one parity, and their taps are consecutive too.  The unit sizes are chosen so
+// that every phase fills the 256 threads (250, 240, 240, 256 units).  Weights are wave-uniform and come
+// through scalar loads.
 #include "act.h"
 #include "cnnc_internal.h"
 
@@ -73,7 +74,7 @@ void stage1_kernel(const uint8_t *__restrict__ pyr, const LevelDev *__restrict__
     }
     __syncthreads();
 
-    // ---- conv1 + f: 25 rows x 10 groups of four columns, then the single column 40
+    // ---- conv1 + f: 25 rows x 10 groups of four columns, then the single column 40 by 25 threads of the last wave
     if (tid < A_H * 10) {
         const int r = tid / 10, x0 = 4 * (tid % 10);
         float acc[4][4];
@@ -95,17 +96,23 @@ void stage1_kernel(const uint8_t *__restrict__ pyr, const LevelDev *__restrict__
         for (int ch = 0; ch < 4; ++ch)
             *reinterpret_cast<float4 *>(sA + (ch * A_H + r) * A_P + x0) =
                 make_float4(act_f<ACT>(acc[ch][0]), act_f<ACT>(acc[ch][1]), act_f<ACT>(acc[ch][2]), act_f<ACT>(acc[ch][3]));
-    } else if (tid - A_H * 10 < 4) {
-        // the last thread group does column 40: one channel each, 25 rows
-        const int ch = tid - A_H * 10;
-        for (int r = 0; r < A_H; ++r) {
-            float acc = wt[s1::B1 + ch];
+    }
+    if (tid >= 192 && tid < 192 + A_H) {
+        // column 40: a row each, all four channels
+        const int r = tid - 192;
+        float acc[4];
 #pragma unroll
-            for (int a = 0; a < 3; ++a)
+        for (int ch = 0; ch < 4; ++ch) acc[ch] = wt[s1::B1 + ch];
 #pragma unroll
-                for (int b = 0; b < 3; ++b) acc = fmaf(wt[s1::W1 + ch * 9 + a * 3 + b], sIn[(r + a) * IN_P + 40 + b], acc);
-            sA[(ch * A_H + r) * A_P + 40] = act_f<ACT>(acc);
-        }
+        for (int a = 0; a < 3; ++a)
+#pragma unroll
+            for (int b = 0; b < 3; ++b) {
+                const float v = sIn[(r + a) * IN_P + 40 + b];
+#pragma unroll
+                for (int ch = 0; ch < 4; ++ch) acc[ch] = fmaf(wt[s1::W1 + ch * 9 + a * 3 + b], v, acc[ch]);
+            }
+#pragma unroll
+        for (int ch = 0; ch < 4; ++ch) sA[(ch * A_H + r) * A_P + 40] = act_f<ACT>(acc[ch]);
     }
     __syncthreads();
 
@@ -126,31 +133,35 @@ void stage1_kernel(const uint8_t *__restrict__ pyr, const LevelDev *__restrict__
     }
     __syncthreads();
 
-    // ---- conv2 (tap spacing 2) + f: 20 rows x 2 parities x 5 groups of four same-parity columns, all 8 channels
-    if (tid < C_H * 10) {
-        const int r = tid / 10, px = (tid % 10) / 5, j0 = 4 * (tid % 5);
-        float acc[8][4];
+    // ---- conv2 (tap spacing 2) + f: 20 rows x 2 parities x 6 groups of three same-parity columns (18 per parity
+    // are needed), all 8 channels: 240 units for the 256 threads
+    if (tid < C_H * 12) {
+        const int r = tid / 12, px = (tid % 12) / 6, j0 = 3 * (tid % 6);
+        float acc[8][3];
 #pragma unroll
         for (int k = 0; k < 8; ++k)
 #pragma unroll
-            for (int p = 0; p < 4; ++p) acc[k][p] = wt[s1::B2 + k];
+            for (int p = 0; p < 3; ++p) acc[k][p] = wt[s1::B2 + k];
 #pragma unroll
         for (int ch = 0; ch < 4; ++ch)
 #pragma unroll
             for (int a = 0; a < 3; ++a) {
-                const f6 m = load6(sM + (ch * M_H + r + 2 * a) * M_P + px * 20 + j0);
+                const float *mp = sM + (ch * M_H + r + 2 * a) * M_P + px * 20 + j0;
+                float m[5];
+#pragma unroll
+                for (int b = 0; b < 5; ++b) m[b] = mp[b];
 #pragma unroll
                 for (int b = 0; b < 3; ++b)
 #pragma unroll
                     for (int k = 0; k < 8; ++k)
 #pragma unroll
-                        for (int p = 0; p < 4; ++p)
-                            acc[k][p] = fmaf(wt[s1::W2 + ((k * 4 + ch) * 3 + a) * 3 + b], m.v[p + b], acc[k][p]);
+                        for (int p = 0; p < 3; ++p)
+                            acc[k][p] = fmaf(wt[s1::W2 + ((k * 4 + ch) * 3 + a) * 3 + b], m[p + b], acc[k][p]);
             }
 #pragma unroll
         for (int k = 0; k < 8; ++k)
-            *reinterpret_cast<float4 *>(sC + (k * C_H + r) * C_P + px * 20 + j0) =
-                make_float4(act_f<ACT>(acc[k][0]), act_f<ACT>(acc[k][1]), act_f<ACT>(acc[k][2]), act_f<ACT>(acc[k][3]));
+#pragma unroll
+            for (int p = 0; p < 3; ++p) sC[(k * C_H + r) * C_P + px * 20 + j0 + p] = act_f<ACT>(acc[k][p]);
     }
     __syncthreads();
 
