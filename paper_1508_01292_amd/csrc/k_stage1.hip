@@ -32,6 +32,8 @@ constexpr int C_H = TH + 4, C_P = 40;             // conv2 map: 2 parities x 20 
 constexpr int kIn = IN_H * IN_P + 4, kA = 4 * A_H * A_P, kM = 4 * M_H * M_P, kC = 8 * C_H * C_P;
 constexpr int kRegionX = kC > kA + kIn ? kC : kA + kIn;   // A maps + input, later the C maps
 
+typedef uint32_t __attribute__((aligned(1))) pixel_quad;        // four neighbouring pixels of a row, any address
+
 struct f6 { float v[6]; };
 // six consecutive floats starting at a 16-byte aligned LDS address
 __device__ __forceinline__ f6 load6(const float *p)
@@ -67,10 +69,22 @@ void stage1_kernel(const uint8_t *__restrict__ pyr, const LevelDev *__restrict__
 
     // ---- input patch, normalised; positions past the level edge repeat the edge (they only feed
     // outputs that are not written)
-    for (int e = tid; e < kIn; e += kThreads) {
-        const int r = min(e / IN_P, IN_H - 1), c = e % IN_P;
-        const int y = min(oy + r, L.h - 1), x = min(ox + c, L.w - 1);
-        sIn[e] = normalise((float)img[(size_t)y * L.w + x]);
+    if (ox + IN_P <= L.w && oy + IN_H <= L.h) {
+        // the whole patch lies inside the level: four pixels a load
+        for (int e = tid; e < IN_H * (IN_P / 4); e += kThreads) {
+            const int r = e / (IN_P / 4), c = 4 * (e % (IN_P / 4));
+            const uint32_t p = *reinterpret_cast<const pixel_quad *>(img + (size_t)(oy + r) * L.w + ox + c);
+            *reinterpret_cast<float4 *>(sIn + r * IN_P + c) =
+                make_float4(normalise((float)(p & 255u)), normalise((float)((p >> 8) & 255u)),
+                            normalise((float)((p >> 16) & 255u)), normalise((float)(p >> 24)));
+        }
+        if (tid < 4) sIn[IN_H * IN_P + tid] = 0.0f;
+    } else {
+        for (int e = tid; e < kIn; e += kThreads) {
+            const int r = min(e / IN_P, IN_H - 1), c = e % IN_P;
+            const int y = min(oy + r, L.h - 1), x = min(ox + c, L.w - 1);
+            sIn[e] = normalise((float)img[(size_t)y * L.w + x]);
+        }
     }
     __syncthreads();
 
