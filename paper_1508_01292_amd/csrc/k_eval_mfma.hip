@@ -16,6 +16,8 @@
 //
 // The fully connected layers are batched over crops in a second kernel (M = crops), so their
 // weights are read once per 16 crops instead of once per crop.
+#include <type_traits>
+
 #include "eval_common.h"
 
 namespace cnnc {
@@ -775,37 +777,40 @@ void eval2_conv_kernel(const uint8_t *__restrict__ frame, int fw, int fh, int pi
 
         // ---- conv1 5x5 1->8 + pool.  A tile is 16 base positions (even columns) = 8 pooling blocks:
         // row i of the tile = pooling block 8 t + 2 (i / 4) + (i / 2) % 2, line i % 2 of the block.
-        // 100 blocks = 12.5 tiles, done as two rounds of seven (the 14th is a clamped duplicate).
-#pragma unroll 1
-        for (int t0 = 0; t0 < 14; t0 += 7) {
-            floatx4 acc[7];
-            int base[7];
+        // 100 blocks = 12.5 tiles, done as a round of seven and a round of six (half of the 13th tile is a clamped
+        // duplicate that is not stored).
+        auto conv1_round = [&](auto n_tiles, int t0) {
+            constexpr int NT = decltype(n_tiles)::value;
+            floatx4 acc[NT];
+            int base[NT];
 #pragma unroll
-            for (int u = 0; u < 7; ++u) {
+            for (int u = 0; u < NT; ++u) {
                 acc[u] = floatx4{0, 0, 0, 0};
                 base[u] = (int)(sLut[8 * (t0 + u) + in_blk] & 0xFFFFu) + in_lane;
             }
 #pragma unroll
             for (int s = 0; s < 5; ++s)
 #pragma unroll
-                for (int u = 0; u < 7; ++u) acc[u] = CNNC_MFMA(sCrop[base[u] + s * kC2W], b1f[s], acc[u]);
+                for (int u = 0; u < NT; ++u) acc[u] = CNNC_MFMA(sCrop[base[u] + s * kC2W], b1f[s], acc[u]);
 #pragma unroll
-            for (int u = 0; u < 7; ++u) acc[u] = CNNC_MFMA(sCrop[base[u] + off5], b1f[5], acc[u]);
+            for (int u = 0; u < NT; ++u) acc[u] = CNNC_MFMA(sCrop[base[u] + off5], b1f[5], acc[u]);
 #pragma unroll
-            for (int u = 0; u < 7; ++u) acc[u] = CNNC_MFMA(sCrop[base[u] + off6], b1f[6], acc[u]);
+            for (int u = 0; u < NT; ++u) acc[u] = CNNC_MFMA(sCrop[base[u] + off6], b1f[6], acc[u]);
 #pragma unroll
-            for (int u = 0; u < 7; ++u) acc[u] = CNNC_MFMA(sCrop[base[u] + off7], b1f[7], acc[u]);
+            for (int u = 0; u < NT; ++u) acc[u] = CNNC_MFMA(sCrop[base[u] + off7], b1f[7], acc[u]);
             // lane (g, j = 2 channel + column): registers 0,1 = the two lines of block 8t + 2g, registers 2,3 of
             // block 8t + 2g + 1; the other column of each block sits in lane j ^ 1
 #pragma unroll
-            for (int u = 0; u < 7; ++u) {
+            for (int u = 0; u < NT; ++u) {
                 float lo = fmaxf(acc[u][0], acc[u][1]), hi = fmaxf(acc[u][2], acc[u][3]);
                 lo = fmaxf(lo, __shfl_xor(lo, 1, 64));
                 hi = fmaxf(hi, __shfl_xor(hi, 1, 64));
                 const int pb = 8 * (t0 + u) + out_blk;                // even lanes finish the first block, odd the second
                 if (pb < 100) sP1[(j >> 1) * kQ1Ch + (sLut[pb] >> 16)] = act_f<ACT>(((j & 1) ? hi : lo) + bias1);
             }
-        }
+        };
+        conv1_round(std::integral_constant<int, 7>{}, 0);
+        conv1_round(std::integral_constant<int, 6>{}, 7);
         wave_sync();
 
         // ---- conv2 3x3 8->16 + pool
