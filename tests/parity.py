@@ -121,7 +121,7 @@ def run_gpu_steps(ctx, frame_t, thr, stream=None):
     return out
 
 
-def compare_with_trace(g, tr: "O.Trace", frame, cascade, weights):
+def compare_with_trace(g, tr: "O.Trace", frame, cascade, weights, iou=0.3, min_neighbors=1):
     """Element-by-element comparison of run_gpu_steps output with an oracle trace.  Where a band
     window makes the two paths take different survivors, downstream steps are compared on the
     windows both paths evaluated (the oracle evaluates extra windows on demand)."""
@@ -176,6 +176,6 @@ def compare_with_trace(g, tr: "O.Trace", frame, cascade, weights):
         assert band1 or band2 or band3 or near_tie, "detections differ from the oracle's with no band window or near tie"
         bx, by, bs, lvl = boxes_of(pyr, g["idx3"])
         valid = [(int(bx[p]), int(by[p]), int(bs[p]), int(lvl[p]), int(n), int(g["idx3"][p]))
-                 for p, n in greedy_merge_check(bx, by, bs, g["sc3"], g["idx3"])]
+                 for p, n in greedy_merge_check(bx, by, bs, g["sc3"], g["idx3"], iou, min_neighbors)]
         assert got == valid, "merged detections are not a greedy merge of the accepted windows"
     return dict(band=(len(band1), len(band2), len(band3)), merge_exact=exact)
