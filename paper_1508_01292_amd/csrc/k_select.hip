@@ -11,8 +11,12 @@
 //   at the 4 pixel step of the two pools, (c1, c2) = (4, 19) and (5, 28);
 //   response (v, u) of the region and response (v, 4 - u) of the mirror image are averaged.
 //
-// One workgroup per surviving position, everything of a region in LDS; workgroups stride over the survivor list whose
-// length is read from device memory.
+// One workgroup per surviving position, everything of a region in 40 KiB of LDS (four workgroups per compute unit);
+// workgroups stride over the survivor list whose length is read from device memory.  Per network pass: first
+// convolution on the vector ALU with a thread per pooled position, second convolution on the matrix cores, output
+// convolution split over ten groups of threads.
+#include <vector>
+
 #include "act.h"
 #include "cnnc_internal.h"
 
@@ -34,39 +38,102 @@ constexpr int kNet2C1 = 4, kNet2C2 = 19, kNet3C1 = 5, kNet3C2 = 28;
 constexpr int kNet2Params = net_params(kNet2C1, kNet2C2), kNet3Params = net_params(kNet3C1, kNet3C2);
 static_assert(kNet2Params == 1836 && kNet3Params == 2942, "parameter counts of the chosen shapes");
 
-// conv (KW x KH, stride 1) + 2x2 max-pool of the pre-activations + bias + f.  in: [CIN][.][IN_P], out: [COUT][PO_H][OUT_P].
-// MIRROR reads the input columns right to left (the mirror image of a one-channel input).
-template <int CIN, int COUT, int KW, int KH, int IN_W, int IN_H, int IN_P, int OUT_P, bool MIRROR, int ACT>
-__device__ void conv_pool(const float *in, float *out, const float *__restrict__ w, const float *__restrict__ bias)
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+
+// conv 4x4 1 -> C1 + 2x2 max-pool of the pre-activations + bias + f.  A thread takes a pooled position and all C1
+// maps, so each of its 25 inputs is read once and the weights are wave-uniform (scalar loads).
+// in: the region [kRegH][kRegP]; out: [C1][kP1H][kP1W].  MIRROR reads the columns right to left (the mirror image).
+template <int C1, bool MIRROR, int ACT>
+__device__ void conv1_pool(const float *in, float *out, const float *__restrict__ w, const float *__restrict__ bias)
 {
-    constexpr int PO_W = (IN_W - KW + 1) / 2, PO_H = (IN_H - KH + 1) / 2;
-    for (int e = threadIdx.x; e < COUT * PO_H * PO_W; e += kThreads) {
-        const int oc = e / (PO_H * PO_W), py = (e / PO_W) % PO_H, px = e % PO_W;
-        float a00 = 0.0f, a01 = 0.0f, a10 = 0.0f, a11 = 0.0f;
-        const float *wp = w + oc * CIN * KW * KH;
-        for (int ic = 0; ic < CIN; ++ic) {
-            const float *ip = in + (ic * IN_H + 2 * py) * IN_P;
+    for (int p = threadIdx.x; p < kP1H * kP1W; p += kThreads) {
+        const int py = p / kP1W, px = p % kP1W;
+        float acc[C1][4];                                         // the four positions of the pooling block: 2 dy + dx
 #pragma unroll
-            for (int a = 0; a < KH + 1; ++a) {
-                float v[KW + 1];
+        for (int ch = 0; ch < C1; ++ch)
 #pragma unroll
-                for (int b = 0; b < KW + 1; ++b) v[b] = ip[a * IN_P + (MIRROR ? IN_W - 1 - (2 * px + b) : 2 * px + b)];
+            for (int q = 0; q < 4; ++q) acc[ch][q] = 0.0f;
 #pragma unroll
-                for (int b = 0; b < KW; ++b) {
-                    if (a < KH) {
-                        const float wv = wp[(ic * KH + a) * KW + b];
-                        a00 = fmaf(wv, v[b], a00);
-                        a01 = fmaf(wv, v[b + 1], a01);
+        for (int r = 0; r < 5; ++r) {                            // region rows 2 py .. 2 py + 4, columns 2 px .. 2 px + 4
+            float v[5];
+#pragma unroll
+            for (int c = 0; c < 5; ++c) v[c] = in[(2 * py + r) * kRegP + (MIRROR ? kRegW - 1 - (2 * px + c) : 2 * px + c)];
+#pragma unroll
+            for (int dy = 0; dy < 2; ++dy) {
+                const int a = r - dy;
+                if (a < 0 || a > 3) continue;
+#pragma unroll
+                for (int ch = 0; ch < C1; ++ch)
+#pragma unroll
+                    for (int b = 0; b < 4; ++b) {
+                        const float wv = w[(ch * 4 + a) * 4 + b];
+                        acc[ch][2 * dy] = fmaf(wv, v[b], acc[ch][2 * dy]);
+                        acc[ch][2 * dy + 1] = fmaf(wv, v[b + 1], acc[ch][2 * dy + 1]);
                     }
-                    if (a > 0) {
-                        const float wv = wp[(ic * KH + a - 1) * KW + b];
-                        a10 = fmaf(wv, v[b], a10);
-                        a11 = fmaf(wv, v[b + 1], a11);
-                    }
-                }
             }
         }
-        out[(oc * PO_H + py) * OUT_P + px] = act_f<ACT>(fmaxf(fmaxf(a00, a01), fmaxf(a10, a11)) + bias[oc]);
+#pragma unroll
+        for (int ch = 0; ch < C1; ++ch)
+            out[(ch * kP1H + py) * kP1W + px] =
+                act_f<ACT>(fmaxf(fmaxf(acc[ch][0], acc[ch][1]), fmaxf(acc[ch][2], acc[ch][3])) + bias[ch]);
+    }
+    __syncthreads();
+}
+
+// conv 3x3 C1 -> C2 + 2x2 max-pool + bias + f on the matrix cores (it is 70 % of a network's arithmetic).
+// GEMM rows = positions of the 22 x 24 map, sixteen a tile = four pooling blocks with their four positions each, so
+// that a lane's four result registers are one block and the pooling stays in registers; K = C1 x 9 taps in steps of
+// four (padded with zero weights), N = the C2 maps in two tiles of sixteen.  132 pooling blocks = 33 tiles, dealt
+// round-robin to the waves and taken two at a time.  frag: the B operand in lane order, [n tile][k step][64].
+constexpr int kConv2Tiles = kP2W * kP2H / 4;
+static_assert(kConv2Tiles * 4 == kP2W * kP2H && kConv2Tiles == 33, "pooling blocks come in fours");
+constexpr int conv2_steps(int c1) { return (c1 * 9 + 3) / 4; }
+
+template <int C1, int C2, int ACT>
+__device__ void conv2_pool_mfma(const float *in, float *out, const float *__restrict__ frag, const float *__restrict__ bias)
+{
+    constexpr int K = C1 * 9, KS = conv2_steps(C1);
+    static_assert(C2 > 16 && C2 <= 32, "two tiles of output maps");
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, g = lane >> 4, i = lane & 15;
+    float bf[2][KS];
+    int koff[KS];
+#pragma unroll
+    for (int st = 0; st < KS; ++st) {
+        bf[0][st] = frag[st * 64 + lane];
+        bf[1][st] = frag[(KS + st) * 64 + lane];
+        const int k = min(4 * st + g, K - 1), c = k / 9, a = (k % 9) / 3, b = k % 3;     // padded taps have zero weights
+        koff[st] = (c * kP1H + a) * kP1W + b;
+    }
+    const int sub_off = ((i >> 1) & 1) * kP1W + (i & 1);          // position (i % 4) inside its pooling block
+    const float bias0 = bias[i], bias1 = 16 + i < C2 ? bias[16 + i] : 0.0f;
+    for (int t0 = wave; t0 < kConv2Tiles; t0 += 8) {
+        floatx4 acc[2][2];
+        int base[2];
+#pragma unroll
+        for (int v = 0; v < 2; ++v) {
+            const int t = min(t0 + 4 * v, kConv2Tiles - 1);      // past the end: the last tile again, not stored
+            const int pb = 4 * t + (i >> 2), by = pb / kP2W, bx = pb % kP2W;
+            base[v] = 2 * by * kP1W + 2 * bx + sub_off;
+            acc[v][0] = acc[v][1] = floatx4{0.0f, 0.0f, 0.0f, 0.0f};
+        }
+#pragma unroll
+        for (int st = 0; st < KS; ++st)
+#pragma unroll
+            for (int v = 0; v < 2; ++v) {
+                const float av = in[base[v] + koff[st]];
+                acc[v][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(av, bf[0][st], acc[v][0], 0, 0, 0);
+                acc[v][1] = __builtin_amdgcn_mfma_f32_16x16x4f32(av, bf[1][st], acc[v][1], 0, 0, 0);
+            }
+#pragma unroll
+        for (int v = 0; v < 2; ++v) {
+            const int t = t0 + 4 * v;
+            if (t >= kConv2Tiles) continue;
+            const int pb = 4 * t + g, by = pb / kP2W, bx = pb % kP2W;               // lane (g, i): block g of the tile, map i
+            const floatx4 lo = acc[v][0], hi = acc[v][1];
+            out[(i * kP2H + by) * kP2P + bx] = act_f<ACT>(fmaxf(fmaxf(lo[0], lo[1]), fmaxf(lo[2], lo[3])) + bias0);
+            if (16 + i < C2)
+                out[((16 + i) * kP2H + by) * kP2P + bx] = act_f<ACT>(fmaxf(fmaxf(hi[0], hi[1]), fmaxf(hi[2], hi[3])) + bias1);
+        }
     }
     __syncthreads();
 }
@@ -99,21 +166,23 @@ __device__ void conv_out(const float *in, const float *__restrict__ w, const flo
 
 // One network on the region (and on its mirror image): res[25].
 template <int C1, int C2, bool MIRROR, int ACT>
-__device__ void region_net(const float *sReg, float *sP1, float *sP2, float *sPart, const float *__restrict__ wt, float *res)
+__device__ void region_net(const float *sReg, float *sP1, float *sP2, float *sPart, const float *__restrict__ wt,
+                           const float *__restrict__ frag, float *res)
 {
     constexpr int W1 = 0, B1 = W1 + C1 * 16, W2 = B1 + C1, B2 = W2 + C2 * C1 * 9, W3 = B2 + C2, B3 = W3 + C2 * kK3W * kK3H;
-    conv_pool<1, C1, 4, 4, kRegW, kRegH, kRegP, kP1W, MIRROR, ACT>(sReg, sP1, wt + W1, wt + B1);
-    conv_pool<C1, C2, 3, 3, kP1W, kP1H, kP1W, kP2P, false, ACT>(sP1, sP2, wt + W2, wt + B2);
+    (void)W2;
+    conv1_pool<C1, MIRROR, ACT>(sReg, sP1, wt + W1, wt + B1);
+    conv2_pool_mfma<C1, C2, ACT>(sP1, sP2, frag, wt + B2);
     conv_out<C2>(sP2, wt + W3, wt + B3, sPart, res);
 }
 
 // region + mirror -> combined map in sComb[25], written to `map`, and the count of responses above thr.
 template <int C1, int C2, int ACT>
 __device__ int region_votes(const float *sReg, float *sP1, float *sP2, float *sPart, float *sRes, const float *__restrict__ wt,
-                            float thr, float *__restrict__ map)
+                            const float *__restrict__ frag, float thr, float *__restrict__ map)
 {
-    region_net<C1, C2, false, ACT>(sReg, sP1, sP2, sPart, wt, sRes);
-    region_net<C1, C2, true, ACT>(sReg, sP1, sP2, sPart, wt, sRes + kMap);
+    region_net<C1, C2, false, ACT>(sReg, sP1, sP2, sPart, wt, frag, sRes);
+    region_net<C1, C2, true, ACT>(sReg, sP1, sP2, sPart, wt, frag, sRes + kMap);
     int votes = 0;
     if (threadIdx.x < 64) {
         const int o = threadIdx.x, v = o / kMapW, u = o % kMapW;
@@ -133,22 +202,28 @@ __device__ int region_votes(const float *sReg, float *sP1, float *sP2, float *sP
 }  // namespace
 
 template <int ACT>
-__global__ __launch_bounds__(kThreads)
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(4, 4)))
 void select_kernel(const uint8_t *__restrict__ frame, int fw, int fh, int pitch, const LevelDev *__restrict__ levels,
                    const ScanLevel *__restrict__ slev, int n_levels, const uint32_t *__restrict__ idx,
                    const float *__restrict__ resp, const int32_t *__restrict__ d_n, int n_max,
-                   const float *__restrict__ w2, const float *__restrict__ w3, float t2, float t3, int t_nn, int rule,
+                   const float *__restrict__ w2, const float *__restrict__ w3, const float *__restrict__ f2,
+                   const float *__restrict__ f3, float t2, float t3, int t_nn, int rule,
                    cnnc_region *__restrict__ rec, float *__restrict__ maps2, float *__restrict__ maps3)
 {
+    // 40 KiB in all, so that four workgroups share a compute unit.  The sample tables, the histogram and the uint8
+    // region are only needed until the equalised region is written and live in the (then idle) second map buffer;
+    // the partial sums of the output convolution live in the first map buffer, which is idle by then.
     __shared__ float sReg[kRegH * kRegP];
     __shared__ float sP1[kC1Max * kP1H * kP1W];
     __shared__ float sP2[kC2Max * kP2H * kP2P];
-    __shared__ float sPart[10 * kMap];
     __shared__ float sRes[2 * kMap];
-    __shared__ uint32_t sTab[kRegW + kRegH];
-    __shared__ int sHist[256];
     __shared__ int sC0;
-    __shared__ uint8_t sPix[kRegW * kRegH];
+    float *sPart = sP1;
+    uint32_t *sTab = reinterpret_cast<uint32_t *>(sP2);
+    int *sHist = reinterpret_cast<int *>(sP2) + 128;
+    uint8_t *sPix = reinterpret_cast<uint8_t *>(sP2 + 128 + 256);
+    static_assert(kRegW + kRegH <= 128 && (128 + 256) * 4 + kRegW * kRegH <= (int)sizeof(float) * kC2Max * kP2H * kP2P &&
+                  10 * kMap <= kC1Max * kP1H * kP1W, "scratch arrays fit in the map buffers");
     const int tid = threadIdx.x;
     const int n = min(*d_n, n_max);
     for (int s = blockIdx.x; s < n; s += gridDim.x) {
@@ -217,9 +292,9 @@ void select_kernel(const uint8_t *__restrict__ frame, int fw, int fh, int pitch,
 
         // ---- CNN_2 on the region and its mirror image; CNN_3 only if CNN_2 left a vote; decision rule (2)
         float *m2 = maps2 + (size_t)s * kMap, *m3 = maps3 + (size_t)s * kMap;
-        const int k2 = region_votes<kNet2C1, kNet2C2, ACT>(sReg, sP1, sP2, sPart, sRes, w2, t2, m2);
+        const int k2 = region_votes<kNet2C1, kNet2C2, ACT>(sReg, sP1, sP2, sPart, sRes, w2, f2, t2, m2);
         int k3 = 0;
-        if (k2 > 0) k3 = region_votes<kNet3C1, kNet3C2, ACT>(sReg, sP1, sP2, sPart, sRes, w3, t3, m3);
+        if (k2 > 0) k3 = region_votes<kNet3C1, kNet3C2, ACT>(sReg, sP1, sP2, sPart, sRes, w3, f3, t3, m3);
         else if (tid < kMap) m3[tid] = 0.0f;
         if (tid == 0) {
             cnnc_region R;
@@ -233,8 +308,26 @@ void select_kernel(const uint8_t *__restrict__ frame, int fw, int fh, int pitch,
     }
 }
 
+namespace {
+// B operand of a network's second convolution in lane order: [n tile][k step][lane], lane (g = lane / 16, j = lane % 16)
+// holds the weight of tap k = 4 step + g (k = 9 c + 3 a + b) for map n = 16 tile + j; zero beyond K and C2.
+void conv2_fragments(const float *blob, int c1, int c2, std::vector<float> &f)
+{
+    const int K = c1 * 9, KS = conv2_steps(c1), W2 = c1 * 17;
+    f.assign((size_t)2 * KS * 64, 0.0f);
+    for (int nt = 0; nt < 2; ++nt)
+        for (int st = 0; st < KS; ++st)
+            for (int lane = 0; lane < 64; ++lane) {
+                const int k = 4 * st + (lane >> 4), n = 16 * nt + (lane & 15);
+                if (k < K && n < c2) f[((size_t)nt * KS + st) * 64 + lane] = blob[W2 + n * K + k];
+            }
+}
+}  // namespace
+
 void select_release(cnnc_ctx *c)
 {
+    (void)hipFree(c->d_sel_f2); (void)hipFree(c->d_sel_f3);
+    c->d_sel_f2 = c->d_sel_f3 = nullptr;
     (void)hipFree(c->d_sel_w2); (void)hipFree(c->d_sel_w3); (void)hipFree(c->d_sel_idx); (void)hipFree(c->d_sel_sc);
     (void)hipFree(c->d_sel_rec); (void)hipFree(c->d_sel_maps); (void)hipFree(c->d_sel_cnt);
     (void)hipFree(c->d_sel_fsc); (void)hipFree(c->d_sel_pick); (void)hipFree(c->d_sel_det);
@@ -267,6 +360,8 @@ int cnnc_select_set_weights(cnnc_ctx *c, const float *w2, int n2, const float *w
         const size_t cap = (size_t)c->max_surv;
         HIP_TRY(c, hipMalloc((void **)&c->d_sel_w2, sizeof(float) * kNet2Params));
         HIP_TRY(c, hipMalloc((void **)&c->d_sel_w3, sizeof(float) * kNet3Params));
+        HIP_TRY(c, hipMalloc((void **)&c->d_sel_f2, sizeof(float) * 2 * conv2_steps(kNet2C1) * 64));
+        HIP_TRY(c, hipMalloc((void **)&c->d_sel_f3, sizeof(float) * 2 * conv2_steps(kNet3C1) * 64));
         HIP_TRY(c, hipMalloc((void **)&c->d_sel_idx, sizeof(uint32_t) * cap));
         HIP_TRY(c, hipMalloc((void **)&c->d_sel_sc, sizeof(float) * cap));
         HIP_TRY(c, hipMalloc((void **)&c->d_sel_rec, sizeof(cnnc_region) * cap));
@@ -279,6 +374,11 @@ int cnnc_select_set_weights(cnnc_ctx *c, const float *w2, int n2, const float *w
     }
     HIP_TRY(c, hipMemcpy(c->d_sel_w2, w2, sizeof(float) * kNet2Params, hipMemcpyHostToDevice));
     HIP_TRY(c, hipMemcpy(c->d_sel_w3, w3, sizeof(float) * kNet3Params, hipMemcpyHostToDevice));
+    std::vector<float> f;
+    conv2_fragments(w2, kNet2C1, kNet2C2, f);
+    HIP_TRY(c, hipMemcpy(c->d_sel_f2, f.data(), sizeof(float) * f.size(), hipMemcpyHostToDevice));
+    conv2_fragments(w3, kNet3C1, kNet3C2, f);
+    HIP_TRY(c, hipMemcpy(c->d_sel_f3, f.data(), sizeof(float) * f.size(), hipMemcpyHostToDevice));
     c->sel_act = act;
     c->sel_done = false;
     return CNNC_OK;
@@ -304,12 +404,12 @@ int cnnc_select_run(cnnc_ctx *c, float t1, float t2, float t3, int t_nn, void *s
     c->last_stream = st;
     ScopedTimer tm(c, CNNC_T_SELECT, st);
     HIP_TRY(c, launch_compact(c, c->d_scan_map, nullptr, nullptr, c->n_scan, t1, c->d_sel_idx, c->d_sel_sc, c->d_sel_cnt, st));
-    dim3 grid(256 * 3), block(kThreads);
+    dim3 grid(256 * 4), block(kThreads);
     float *m2 = c->d_sel_maps, *m3 = c->d_sel_maps + (size_t)kMap * c->max_surv;
 #define CNNC_SEL(ACT)                                                                                             \
     hipLaunchKernelGGL(select_kernel<ACT>, grid, block, 0, st, c->d_frame, c->fw, c->fh, c->fpitch, c->d_levels,  \
                        c->d_scan_levels, c->n_levels, c->d_sel_idx, c->d_sel_sc, c->d_sel_cnt, c->max_surv,       \
-                       c->d_sel_w2, c->d_sel_w3, t2, t3, t_nn, c->sel_rule, c->d_sel_rec, m2, m3)
+                       c->d_sel_w2, c->d_sel_w3, c->d_sel_f2, c->d_sel_f3, t2, t3, t_nn, c->sel_rule, c->d_sel_rec, m2, m3)
     switch (c->sel_act) {
     case CNNC_ACT_RATIONAL: CNNC_SEL(CNNC_ACT_RATIONAL); break;
     case CNNC_ACT_SCALED_TANH: CNNC_SEL(CNNC_ACT_SCALED_TANH); break;
