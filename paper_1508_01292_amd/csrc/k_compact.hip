@@ -1,8 +1,9 @@
 // Survivor compaction (paper, Section 3.3: the coordinates of the windows whose response exceeded
 // the threshold are handed on).  Deterministic: the output keeps ascending input order, so no
-// atomics on the output position.  Three small launches: per-workgroup counts, a scan of the
-// counts, and the scatter; inside a workgroup each wave owns a contiguous run of the input and
-// ranks its survivors with ballots.
+// atomics on the output position.  Two small launches: per-workgroup counts, and the scatter, in
+// which every workgroup first adds up the counts of the workgroups before it (a separate scan
+// launch takes over for very long inputs); inside a workgroup each wave owns a contiguous run of
+// the input and ranks its survivors with ballots.
 #include "cnnc_internal.h"
 
 namespace cnnc {
@@ -81,9 +82,9 @@ __global__ __launch_bounds__(kCompactBlock)
 void compact_scatter_kernel(const float *__restrict__ vals, const uint32_t *__restrict__ src_idx,
                             const int32_t *__restrict__ d_n, int64_t n_literal, int64_t n_max, float thr,
                             const int32_t *__restrict__ blockoff, uint32_t *__restrict__ out_idx,
-                            float *__restrict__ out_sc, int cap)
+                            float *__restrict__ out_sc, int cap, int32_t *__restrict__ d_count_if_unscanned)
 {
-    __shared__ int wsum[kWaves];
+    __shared__ int wsum[kWaves], wpre[kWaves];
     const int64_t n = source_count(d_n, n_literal, n_max);
     const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
     const int64_t base = (int64_t)blockIdx.x * kCompactPerBlock + (int64_t)wave * kPerWave;
@@ -97,9 +98,24 @@ void compact_scatter_kernel(const float *__restrict__ vals, const uint32_t *__re
         mask[it] = __ballot(e < n && v[it] > thr);
         cnt += __popcll(mask[it]);
     }
-    if (lane == 0) wsum[wave] = cnt;
-    __syncthreads();
-    int pos = blockoff[blockIdx.x];
+    int pos;
+    if (d_count_if_unscanned) {
+        // blockoff holds the raw counts of the workgroups: this one sums those before it (a few KB from L2), and
+        // the last one also leaves the total
+        int before = 0;
+        for (int b = threadIdx.x; b < (int)blockIdx.x; b += kCompactBlock) before += blockoff[b];
+        for (int d = 32; d >= 1; d >>= 1) before += __shfl_xor(before, d, 64);
+        if (lane == 0) { wsum[wave] = cnt; wpre[wave] = before; }
+        __syncthreads();
+        pos = 0;
+        int own = 0;
+        for (int w = 0; w < kWaves; ++w) { pos += wpre[w]; own += wsum[w]; }
+        if (blockIdx.x == gridDim.x - 1 && threadIdx.x == 0) *d_count_if_unscanned = pos + own;
+    } else {
+        if (lane == 0) wsum[wave] = cnt;
+        __syncthreads();
+        pos = blockoff[blockIdx.x];
+    }
     for (int w = 0; w < wave; ++w) pos += wsum[w];
 #pragma unroll
     for (int it = 0; it < kIters; ++it) {
@@ -188,9 +204,13 @@ hipError_t launch_compact(const cnnc_ctx *c, const float *vals, const uint32_t *
     if (nblocks < 1) nblocks = 1;   // an empty input still has to write a zero count
     hipLaunchKernelGGL(compact_count_kernel, dim3(nblocks), dim3(kCompactBlock), 0, st, vals, d_n, n_literal, n_max,
                        thr, c->d_blockcnt);
-    hipLaunchKernelGGL(compact_scan_kernel, dim3(1), dim3(1024), 0, st, c->d_blockcnt, nblocks, d_count);
+    // Up to a few thousand workgroups each scatter workgroup adds up the counts before it by itself, which saves
+    // the launch of the scan in between; beyond that the scan kernel is cheaper than the repeated sums.
+    const bool scan_in_scatter = nblocks <= 4096;
+    if (!scan_in_scatter) hipLaunchKernelGGL(compact_scan_kernel, dim3(1), dim3(1024), 0, st, c->d_blockcnt, nblocks, d_count);
     hipLaunchKernelGGL(compact_scatter_kernel, dim3(nblocks), dim3(kCompactBlock), 0, st, vals, src_idx, d_n,
-                       n_literal, n_max, thr, c->d_blockcnt, out_idx, out_sc, c->max_surv);
+                       n_literal, n_max, thr, c->d_blockcnt, out_idx, out_sc, c->max_surv,
+                       scan_in_scatter ? d_count : (int32_t *)nullptr);
     return hipGetLastError();
 }
 
