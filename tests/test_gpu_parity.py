@@ -448,3 +448,37 @@ def test_uhd_small_faces_sampled():
     assert [(d["index"], d["neighbors"]) for d in det] == \
         [(int(idx3[p]), n) for p, n in greedy_merge_check(bx, by, bs, s3k, idx3)]
     ctx.close()
+
+
+def test_compaction_of_a_very_long_score_map():
+    """More than 4,096 compaction workgroups (8.4 M values): the form with a separate scan of the workgroup counts.
+    The list must hold exactly the windows whose fp32 score exceeds the threshold, in ascending order, with their
+    scores (a property of the GPU's own score map, whose values the other tests compare with the oracle)."""
+    torch = _torch()
+    casc = I.default_cascade()
+    W = I.draw_weights(casc, 77)
+    w, h = 4400, 2100
+    frame = I.make_frame(w, h, 77)
+    n = O.pyramid_layout(w, h, 12.0, 2.0).score_off[-1]
+    assert n > 4096 * 2048
+    print("case long score map: %d windows" % n, flush=True)
+    ctx = _ctx(casc, W, w, h, 300000)
+    ctx.set_params(12.0, 2.0, (0.0, 0.0, 0.0))
+    ctx.build_pyramid(torch.from_numpy(frame).cuda())
+    ctx.stage1_scoremap()
+    s = ctx.get_scoremap()
+    assert s.size == n
+    thr = float(np.partition(s, n - 200000)[n - 200000])      # about 200,000 windows lie above it
+    ctx.compact_survivors(1, thr)
+    idx, sc = ctx.get_survivors(1)
+    want = np.nonzero(s > np.float32(thr))[0]
+    assert np.array_equal(idx, want) and np.array_equal(sc, s[want])
+    # and the two-launch form on the same context: a later, shorter list
+    ctx.eval_stage(2)
+    s2 = ctx.get_stage_scores(2)
+    t2 = float(np.median(s2))
+    ctx.compact_survivors(2, t2)
+    idx2, sc2 = ctx.get_survivors(2)
+    keep = s2 > np.float32(t2)
+    assert np.array_equal(idx2, idx[keep]) and np.array_equal(sc2, s2[keep])
+    ctx.close()
