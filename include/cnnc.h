@@ -41,7 +41,8 @@ extern "C" {
 #define CNNC_OK          0
 #define CNNC_E_INVAL    -1  /* bad argument (null pointer, size, stage index, unsupported network shape) */
 #define CNNC_E_NOMEM    -2  /* host or device allocation failed */
-#define CNNC_E_OVERFLOW -3  /* a survivor or detection list did not fit; contents up to the capacity are valid */
+#define CNNC_E_OVERFLOW -3  /* a survivor or detection list did not fit; contents up to the capacity are valid, and the
+                               steps after a truncated list ran on the truncated list */
 #define CNNC_E_HIP      -4  /* a HIP runtime call failed */
 #define CNNC_E_STATE    -5  /* call out of order (e.g. score map before pyramid) */
 
@@ -224,7 +225,7 @@ int cnnc_get_scan_scoremap(cnnc_ctx *ctx, const float **d_scores, int64_t *n);
  * with a neighbourhood and scaled to 51 x 55 pixels; its histogram is equalised; the region and its mirror image
  * (reflection about the vertical axis) go through CNN_2 and CNN_3, each giving a 5 x 5 response map; with K2, K3 the
  * numbers of responses above the threshold, rule (2) decides: face = (K2 >= T_nn and K3 > 0) or (K2 > 0 and
- * K3 >= T_nn); a region with K2 = 0 is not shown to CNN_3.
+ * K3 >= T_nn); under that rule a region with K2 = 0 is not shown to CNN_3.
  * What the paper leaves open is fixed as follows: neighbourhood = 12 level pixels on every side of the 27 x 31 window;
  * region samples in 16.16 fixed point with 8-bit weights, rounded to uint8; equalisation v -> round((cdf(v) - c0) * 255
  * / (n - c0)) with c0 the cdf of the smallest value present (a constant region is left alone); networks
@@ -235,7 +236,8 @@ int cnnc_get_scan_scoremap(cnnc_ctx *ctx, const float **d_scores, int64_t *n);
  * cnnc_select_set_weights: host blobs (per conv layer w[cout][cin][kh][kw] then bias[cout]), n2 = 1836, n3 = 2942,
  *   act = hidden activation kind; copied; synchronises; allocates the unit's buffers on first use.
  * cnnc_select_set_rule: rule = 2 (default) is eq. (2) above; rule = 3 the weaker rule of Section 4.3, eq. (3):
- *   face = K2 >= T_nn or K3 >= T_nn (more recall, less precision).  The stop at K2 = 0 stays under either rule.
+ *   face = K2 >= T_nn or K3 >= T_nn (more recall, less precision).  CNN_3's count alone can accept a region there, so
+ *   under rule 3 CNN_3 runs on every listed region, whatever K2 is.
  *   Applies to later cnnc_select_run calls; CNNC_E_INVAL for another value.
  * cnnc_select_run: needs cnnc_scan_scoremap of the current frame (CNNC_E_STATE otherwise), whose frame must still be
  *   alive.  Lists the positions with response > t1 in ascending flat order and runs the unit on each; K2 counts
@@ -281,8 +283,9 @@ int cnnc_select_merge(cnnc_ctx *ctx, float iou, int min_neighbors, cnnc_rdet *ou
  * the others.  use_graph != 0: from a slot's second frame on, its copy + kernels + read-back run as one captured
  * HIP graph launch.  All frames of a pipe have the size given at creation.  One thread per pipe.
  *
- * cnnc_pipe_frame_buffer: the pinned buffer the next submit will send, for producers that write frames in place
- *   (CNNC_E_STATE while that slot's previous frame has not been fetched).
+ * cnnc_pipe_frame_buffer: the pinned buffer the next submit will send (that of the free slot that has been free
+ *   longest), for producers that write frames in place; valid until the next submit or fetch.  CNNC_E_STATE when
+ *   every slot is in flight.
  * cnnc_pipe_submit: h_frame = NULL or the pointer from cnnc_pipe_frame_buffer: send the buffer as it is; any other
  *   host pointer: its w x h bytes (row pitch `pitch`) are copied into the buffer first.  Enqueues and returns a
  *   ticket; CNNC_E_STATE when every slot is in flight.
@@ -298,6 +301,12 @@ int cnnc_pipe_frame_buffer(cnnc_pipe *pipe, uint8_t **h_frame);
 int cnnc_pipe_submit(cnnc_pipe *pipe, const uint8_t *h_frame, int pitch, int64_t *ticket);
 int cnnc_pipe_fetch(cnnc_pipe *pipe, int64_t ticket, cnnc_det *out, int cap, int *n_out);
 const char *cnnc_pipe_last_error(const cnnc_pipe *pipe);
+
+/* Measurement aid: how many 16x16x4 fp32 matrix instructions (1024 multiply-adds each) the convolution kernel of
+ * cnnc_eval_stage(k), k = 2 or 3, issues per crop under the current cnnc_set_eval_impl choice, padded tiles and the
+ * Winograd forms included (0 for the vector-ALU kernels).  Lets a benchmark report the executed matrix work beside
+ * the algorithmic work of the layer definitions.  Host only. */
+int cnnc_executed_mfma(const cnnc_ctx *ctx, int k, int64_t *per_crop);
 
 /* Measurement aid for benchmarks: what this GPU sustains on three synthetic probes (dense fp32 MFMA loop,
  * fp32 FMA loop on the vector ALU, 1 GiB device-to-device copy counted as read + write).  Runs on the

@@ -52,7 +52,18 @@ typedef struct {
     int32_t act; /* ORC_ACT_* applied to the output */
 } orc_layer;
 
-/* Threads the parallel loops below will use (for reporting timings).        */
+/* Threads the parallel loops below will use (for reporting timings), and a   */
+/* way to set that number (the benchmark reports one-thread and all-core      */
+/* timings of the same routines).                                             */
+void orc_set_num_threads(int n)
+{
+#ifdef _OPENMP
+    if (n > 0) omp_set_num_threads(n);
+#else
+    (void)n;
+#endif
+}
+
 int orc_num_threads(void)
 {
 #ifdef _OPENMP
@@ -700,9 +711,10 @@ void orc_histeq(uint8_t *img, int n)
 /* CNN_3 gives K3 the same way with t3, and eq. (2) decides:                  */
 /*   face = (K2 >= t_nn and K3 > 0) or (K2 > 0 and K3 >= t_nn).               */
 /* rule = 3 selects the weaker rule of Section 4.3, eq. (3):                  */
-/*   face = K2 >= t_nn or K3 >= t_nn                                          */
-/* (reading: the stop at K2 = 0 belongs to the unit, not to the rule, so it   */
-/* stays; K3 is then 0).                                                      */
+/*   face = K2 >= t_nn or K3 >= t_nn.                                         */
+/* There CNN_3's count alone can accept a region, so no outcome of CNN_2      */
+/* "disagrees with the rule" (the stop of Section 3.3 is stated for rule      */
+/* (2), under which K2 = 0 already decides): CNN_3 runs on every region.      */
 /* r2, r3: the combined response maps (nh x nw doubles each; r3 is zero when  */
 /* CNN_3 was not run).  Returns 0, -1 if a network does not fit the region.   */
 int orc_select_region(const uint8_t *region, int rw, int rh,
@@ -727,7 +739,7 @@ int orc_select_region(const uint8_t *region, int rw, int rh,
                 r2[v * nw + u] = 0.5 * (a[v * nw + u] + b[v * nw + (nw - 1 - u)]);
                 if ((float)r2[v * nw + u] > t2) ++*k2;
             }
-        if (*k2 > 0) {
+        if (*k2 > 0 || rule == 3) {
             if (orc_scan_fcn(region, rw, rh, l3, n3, w3, win_w, win_h, a) || orc_scan_fcn(mir, rw, rh, l3, n3, w3, win_w, win_h, b)) rc = -1;
             if (rc == 0)
                 for (int v = 0; v < nh; ++v)

@@ -60,6 +60,11 @@ def num_threads() -> int:
     return int(lib().orc_num_threads())
 
 
+def set_num_threads(n: int) -> None:
+    """Threads of the oracle's parallel loops from now on (timing reports only; results do not depend on it)."""
+    lib().orc_set_num_threads(C.c_int(int(n)))
+
+
 def rational_tanh(y: float) -> float:
     return lib().orc_rational_tanh(float(y))
 

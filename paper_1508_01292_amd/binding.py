@@ -18,7 +18,7 @@ EXPORTS = [
     "cnnc_stage1_scoremap", "cnnc_compact_survivors", "cnnc_eval_stage", "cnnc_merge_detections",
     "cnnc_detect", "cnnc_detect_async", "cnnc_fetch_detections", "cnnc_get_pyramid", "cnnc_get_scoremap",
     "cnnc_get_survivors", "cnnc_get_stage_scores", "cnnc_survivor_count", "cnnc_set_timing",
-    "cnnc_get_timings", "cnnc_set_eval_impl", "cnnc_measure_peaks", "cnnc_last_error", "cnnc_version",
+    "cnnc_get_timings", "cnnc_set_eval_impl", "cnnc_executed_mfma", "cnnc_measure_peaks", "cnnc_last_error", "cnnc_version",
     "cnnc_stage1_survivors", "cnnc_set_fused_stage1",
     "cnnc_scan_set_weights", "cnnc_scan_layout", "cnnc_scan_scoremap", "cnnc_get_scan_scoremap",
     "cnnc_select_set_weights", "cnnc_select_set_rule", "cnnc_select_run", "cnnc_select_fetch", "cnnc_select_merge", "cnnc_abi_sizes",
@@ -314,6 +314,11 @@ class Context:
     def set_eval_impl(self, impl: int):
         self._check(lib().cnnc_set_eval_impl(self._h, C.c_int(impl)))
 
+    def executed_mfma(self, k: int) -> int:
+        n = C.c_int64(0)
+        self._check(lib().cnnc_executed_mfma(self._h, C.c_int(k), C.byref(n)))
+        return n.value
+
     def set_timing(self, on: bool):
         self._check(lib().cnnc_set_timing(self._h, C.c_int(1 if on else 0)))
 
@@ -410,94 +415,29 @@ def cnnc_measure_peaks():
     return a.value, b.value, c.value
 
 
-def cnnc_stage1_survivors(ctx, thr, stream=None):
-    return ctx.stage1_survivors(thr, stream)
+# The C spelling of every context call: cnnc_<name>(ctx, ...) is Context.<name>(...).
+_CTX_CALLS = ("set_params", "pyramid_layout", "build_pyramid", "stage1_scoremap", "stage1_survivors", "set_fused_stage1",
+              "compact_survivors", "eval_stage", "merge_detections", "detect", "detect_async", "fetch_detections",
+              "get_pyramid", "get_scoremap", "get_survivors", "get_stage_scores", "survivor_count", "set_eval_impl",
+              "executed_mfma", "set_timing", "get_timings", "scan_set_weights", "scan_layout", "scan_scoremap",
+              "get_scan_scoremap", "select_set_weights", "select_set_rule", "select_run", "select_fetch", "select_merge")
 
 
-def cnnc_set_fused_stage1(ctx, on):
-    return ctx.set_fused_stage1(on)
+def _c_spelling(method):
+    def call(ctx, *a, **k):
+        return getattr(ctx, method)(*a, **k)
+    call.__name__ = "cnnc_" + method
+    call.__doc__ = "Context.%s" % method
+    return call
 
 
-def cnnc_select_set_weights(ctx, w2, w3, act=1):
-    return ctx.select_set_weights(w2, w3, act)
+for _m in _CTX_CALLS:
+    globals()["cnnc_" + _m] = _c_spelling(_m)
 
 
-def cnnc_select_run(ctx, t1, t2, t3, t_nn, stream=None):
-    return ctx.select_run(t1, t2, t3, t_nn, stream)
-
-
-def cnnc_select_set_rule(ctx, rule):
-    return ctx.select_set_rule(rule)
-
-
-def cnnc_select_merge(ctx, iou=0.3, min_neighbors=1, cap=4096, stream=None):
-    return ctx.select_merge(iou, min_neighbors, cap, stream)
-
-
-def cnnc_select_fetch(ctx, cap=65536, maps=False):
-    return ctx.select_fetch(cap, maps)
-
-
-def cnnc_scan_set_weights(ctx, weights, act=1):
-    return ctx.scan_set_weights(weights, act)
-
-
-def cnnc_scan_layout(ctx, w, h):
-    return ctx.scan_layout(w, h)
-
-
-def cnnc_scan_scoremap(ctx, stream=None):
-    return ctx.scan_scoremap(stream)
-
-
-def cnnc_get_scan_scoremap(ctx):
-    return ctx.get_scan_scoremap()
-
-
-# Same-named thin functions for callers that prefer the C spelling.
 def cnnc_create(cascade, weights, max_w, max_h, max_survivors) -> Context:
     return Context(cascade, weights, max_w, max_h, max_survivors)
 
 
 def cnnc_destroy(ctx: Context):
     ctx.close()
-
-
-def cnnc_set_params(ctx: Context, *a, **k):
-    return ctx.set_params(*a, **k)
-
-
-def cnnc_pyramid_layout(ctx: Context, w, h):
-    return ctx.pyramid_layout(w, h)
-
-
-def cnnc_build_pyramid(ctx: Context, frame, stream=None):
-    return ctx.build_pyramid(frame, stream)
-
-
-def cnnc_stage1_scoremap(ctx: Context, stream=None):
-    return ctx.stage1_scoremap(stream)
-
-
-def cnnc_compact_survivors(ctx: Context, stage, thr, stream=None):
-    return ctx.compact_survivors(stage, thr, stream)
-
-
-def cnnc_eval_stage(ctx: Context, k, stream=None):
-    return ctx.eval_stage(k, stream)
-
-
-def cnnc_merge_detections(ctx: Context, cap=4096, stream=None):
-    return ctx.merge_detections(cap, stream)
-
-
-def cnnc_detect(ctx: Context, frame, cap=4096):
-    return ctx.detect(frame, cap)
-
-
-def cnnc_detect_async(ctx: Context, frame, stream=None):
-    return ctx.detect_async(frame, stream)
-
-
-def cnnc_fetch_detections(ctx: Context, cap=4096):
-    return ctx.fetch_detections(cap)

@@ -187,13 +187,8 @@ int fetch(cnnc_ctx *c, cnnc_det *out, int cap, int *n_out)
 {
     HIP_TRY(c, hipStreamSynchronize(c->last_stream));
     const Counters &k = *c->h_cnt;
-    for (int s = 0; s < 3; ++s)
-        if (k.n[s] > c->max_surv) {
-            if (n_out) *n_out = 0;
-            return fail(c, CNNC_E_OVERFLOW, "survivor list of stage " + std::to_string(s + 1) + " needs " +
-                                                std::to_string(k.n[s]) + " entries");
-        }
-    if (k.n[2] > c->merge_cap) return fail(c, CNNC_E_OVERFLOW, "merge input exceeds its capacity");
+    // The detections made from the (possibly truncated) lists are handed over in every case; an overflow is reported
+    // after the copy, so that "contents up to the capacity are valid" holds for this call too.
     const int n = k.n[3];
     if (n_out) *n_out = n;
     const int m = std::min(std::min(n, cap), c->merge_cap);
@@ -201,6 +196,13 @@ int fetch(cnnc_ctx *c, cnnc_det *out, int cap, int *n_out)
         HIP_TRY(c, hipMemcpy(c->h_det + kFastDets, c->d_det + kFastDets, sizeof(cnnc_det) * (size_t)(m - kFastDets),
                              hipMemcpyDeviceToHost));
     if (m > 0) memcpy(out, c->h_det, sizeof(cnnc_det) * (size_t)m);
+    for (int s = 0; s < 3; ++s)
+        if (k.n[s] > c->max_surv)
+            return fail(c, CNNC_E_OVERFLOW, "survivor list of stage " + std::to_string(s + 1) + " needs " +
+                                                std::to_string(k.n[s]) + " entries; detections come from the truncated list");
+    if (k.n[2] > c->merge_cap)
+        return fail(c, CNNC_E_OVERFLOW, "merge input of " + std::to_string(k.n[2]) + " windows exceeds its capacity; "
+                                        "detections come from the first " + std::to_string(c->merge_cap));
     return n > cap ? fail(c, CNNC_E_OVERFLOW, "detection array too small") : CNNC_OK;
 }
 
@@ -549,6 +551,8 @@ int cnnc_get_survivors(cnnc_ctx *c, int stage, const uint32_t **d_index, const f
 {
     if (!c) return CNNC_E_INVAL;
     if (stage < 1 || stage > 3) return fail(c, CNNC_E_INVAL, "stage must be 1, 2 or 3");
+    const int done[3] = {DONE_C1, DONE_C2, DONE_C3};
+    if (!(c->progress & done[stage - 1])) return fail(c, CNNC_E_STATE, "that stage was not compacted");
     if (d_index) *d_index = c->d_idx[stage - 1];
     if (d_score) *d_score = c->d_sc[stage - 1];
     return CNNC_OK;
@@ -558,6 +562,7 @@ int cnnc_get_stage_scores(cnnc_ctx *c, int k, const float **d_score)
 {
     if (!c) return CNNC_E_INVAL;
     if (k != 2 && k != 3) return fail(c, CNNC_E_INVAL, "stage must be 2 or 3");
+    if (!(c->progress & (k == 2 ? DONE_E2 : DONE_E3))) return fail(c, CNNC_E_STATE, "that stage was not evaluated");
     if (d_score) *d_score = c->d_eval[k - 2];
     return CNNC_OK;
 }
@@ -580,6 +585,13 @@ int cnnc_set_eval_impl(cnnc_ctx *c, int impl)
     if (!c) return CNNC_E_INVAL;
     if (impl < 0 || impl > 3) return fail(c, CNNC_E_INVAL, "implementation must be 0, 1, 2 or 3");
     c->eval_impl = impl;
+    return CNNC_OK;
+}
+
+int cnnc_executed_mfma(const cnnc_ctx *c, int k, int64_t *per_crop)
+{
+    if (!c || !per_crop || (k != 2 && k != 3)) return CNNC_E_INVAL;
+    *per_crop = c->eval_impl == 0 ? 0 : (k == 2 ? eval2_mfma_per_crop(c->eval_impl) : eval3_mfma_per_crop(c->eval_impl));
     return CNNC_OK;
 }
 

@@ -201,6 +201,8 @@ void eval2_make_fragments(const float *blob, float *frag);
 size_t eval3_frag_floats();
 size_t eval3_feat_floats();
 void eval3_make_fragments(const float *blob, float *frag);
+int64_t eval3_mfma_per_crop(int impl);
+int64_t eval2_mfma_per_crop(int impl);
 hipError_t launch_merge(const cnnc_ctx *c, hipStream_t st);
 size_t merge_workspace_bytes(int merge_cap);
 hipError_t merge_init_workspace(const cnnc_ctx *c);

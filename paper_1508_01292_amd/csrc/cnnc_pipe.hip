@@ -31,7 +31,6 @@ struct cnnc_pipe {
     std::vector<Slot> slots;
     int w = 0, h = 0;
     bool use_graph = false;
-    int next = 0;                 // slot the next submit uses
     int64_t next_ticket = 0;
     std::string err;
 };
@@ -50,6 +49,15 @@ int pfail(cnnc_pipe *p, int code, const std::string &msg)
         if (e_ != hipSuccess) return pfail((p), e_ == hipErrorOutOfMemory ? CNNC_E_NOMEM : CNNC_E_HIP, \
                                            std::string(#expr) + ": " + hipGetErrorString(e_));    \
     } while (0)
+
+// The slot the next submit uses: the free slot that has waited longest (slots are fetched in any order).
+Slot *free_slot(cnnc_pipe *p)
+{
+    Slot *best = nullptr;
+    for (Slot &s : p->slots)
+        if (!s.busy && (!best || s.ticket < best->ticket)) best = &s;
+    return best;
+}
 
 void drop_graph(Slot &s)
 {
@@ -124,17 +132,18 @@ int cnnc_pipe_set_params(cnnc_pipe *p, const cnnc_params *prm)
 int cnnc_pipe_frame_buffer(cnnc_pipe *p, uint8_t **h_frame)
 {
     if (!p || !h_frame) return CNNC_E_INVAL;
-    Slot &s = p->slots[(size_t)p->next];
-    if (s.busy) return pfail(p, CNNC_E_STATE, "the ring is full: fetch the oldest frame first");
-    *h_frame = s.h_frame;
+    Slot *fs = free_slot(p);
+    if (!fs) return pfail(p, CNNC_E_STATE, "every slot is in flight: fetch a frame first");
+    *h_frame = fs->h_frame;
     return CNNC_OK;
 }
 
 int cnnc_pipe_submit(cnnc_pipe *p, const uint8_t *h_frame, int pitch, int64_t *ticket)
 {
     if (!p || !ticket) return CNNC_E_INVAL;
-    Slot &s = p->slots[(size_t)p->next];
-    if (s.busy) return pfail(p, CNNC_E_STATE, "the ring is full: fetch the oldest frame first");
+    Slot *fs = free_slot(p);
+    if (!fs) return pfail(p, CNNC_E_STATE, "every slot is in flight: fetch a frame first");
+    Slot &s = *fs;
     if (h_frame && h_frame != s.h_frame) {
         if (pitch < p->w) return pfail(p, CNNC_E_INVAL, "pitch < width");
         for (int y = 0; y < p->h; ++y) memcpy(s.h_frame + (size_t)y * p->w, h_frame + (size_t)y * pitch, (size_t)p->w);
@@ -151,8 +160,13 @@ int cnnc_pipe_submit(cnnc_pipe *p, const uint8_t *h_frame, int pitch, int64_t *t
             const hipError_t e = hipStreamEndCapture(s.st, &g);
             if (rc == CNNC_OK && e != hipSuccess) rc = pfail(p, CNNC_E_HIP, std::string("hipStreamEndCapture: ") + hipGetErrorString(e));
             if (rc) { if (g) (void)hipGraphDestroy(g); return rc; }
+            const hipError_t ei = hipGraphInstantiate(&s.exec, g, nullptr, nullptr, 0);
+            if (ei != hipSuccess) {
+                (void)hipGraphDestroy(g);
+                s.exec = nullptr;
+                return pfail(p, CNNC_E_HIP, std::string("hipGraphInstantiate: ") + hipGetErrorString(ei));
+            }
             s.graph = g;
-            PIPE_HIP(p, hipGraphInstantiate(&s.exec, s.graph, nullptr, nullptr, 0));
         }
         PIPE_HIP(p, hipGraphLaunch(s.exec, s.st));
     }
@@ -161,7 +175,6 @@ int cnnc_pipe_submit(cnnc_pipe *p, const uint8_t *h_frame, int pitch, int64_t *t
     s.busy = true;
     s.ticket = p->next_ticket++;
     *ticket = s.ticket;
-    p->next = (p->next + 1) % (int)p->slots.size();
     return CNNC_OK;
 }
 

@@ -22,21 +22,6 @@
 
 namespace cnnc {
 
-#ifdef CNNC_PHASE_PROBE
-__device__ unsigned long long g_probe[16];
-__device__ unsigned long long g_span[2 * 1024];
-#define CNNC_PROBE(k)                                                                     \
-    do {                                                                                  \
-        if (threadIdx.x == 0 && blockIdx.x == 0) {                                        \
-            const unsigned long long now_ = clock64();                                    \
-            g_probe[k] += now_ - probe_t_;                                                \
-            probe_t_ = now_;                                                              \
-        }                                                                                 \
-    } while (0)
-#else
-#define CNNC_PROBE(k) do {} while (0)
-#endif
-
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 #define CNNC_MFMA(a, b, c) __builtin_amdgcn_mfma_f32_16x16x4f32((a), (b), (c), 0, 0, 0)
 
@@ -436,10 +421,6 @@ void eval3_conv_kernel(const uint8_t *__restrict__ frame, int fw, int fh, int pi
 
     const int n = min(*d_n, n_max);
     int rot = 0;
-#ifdef CNNC_PHASE_PROBE
-    unsigned long long probe_t_ = clock64();
-    const unsigned long long probe_c0_ = probe_t_, probe_w0_ = wall_clock64();
-#endif
     // Static striding over the list.  (Handing windows out through an atomic ticket counter was measured:
     // it does not shorten the kernel, the device-scope atomics cost more than the balance gains.)
     // The gather of a window is software-pipelined: its tables are computed during conv1 of the previous
@@ -451,7 +432,6 @@ void eval3_conv_kernel(const uint8_t *__restrict__ frame, int fw, int fh, int pi
     }
     for (; crop < n; crop += gridDim.x, ++rot) {
         const int next = crop + gridDim.x;
-        CNNC_PROBE(0);
 
         // ---- conv1 5x5 1->16 + pool: 121 tiles of four pooling blocks, four tiles in flight per wave
         // (small per-layer constants are re-read per window instead of living in registers through the other layers)
@@ -487,9 +467,7 @@ void eval3_conv_kernel(const uint8_t *__restrict__ frame, int fw, int fh, int pi
             const Survivor sv = decode(idx[next], levels, n_levels);
             crop_tables<kS3In>(sv.x, sv.y, levels[sv.level].scale_q16, fw, fh, sTab);
         }
-        CNNC_PROBE(3);
         __syncthreads();
-        CNNC_PROBE(4);
 
         // ---- conv2 5x5 16->32 + pool (overwrites the crop with the pooled map)
         const int wslot = (wave + rot + blockIdx.x + (blockIdx.x >> 8)) & 3;
@@ -510,9 +488,7 @@ void eval3_conv_kernel(const uint8_t *__restrict__ frame, int fw, int fh, int pi
         } else {
             s3_conv2<5, ACT>(sB, sA, frag + kS3F2, wslot, lane, bias2_lo, bias2_hi);
         }
-        CNNC_PROBE(5);
         __syncthreads();
-        CNNC_PROBE(6);
 
         // ---- pixel loads of the next window go out now and stay in flight during conv3
         CropPixels<kS3In> px;
@@ -522,24 +498,11 @@ void eval3_conv_kernel(const uint8_t *__restrict__ frame, int fw, int fh, int pi
         float *dst = feat + (size_t)crop * kS3Feat;
         if (WINO) s3_conv3_wino<ACT>(sA, frag + kS3F6, wt, dst, wave, fresh(lane));
         else s3_conv3_direct(sA, sB, frag + kS3F3, wave, lane);
-        CNNC_PROBE(7);
         __syncthreads();                                   // conv3 has released the pooled map (and, direct form, written its partial sums)
-        CNNC_PROBE(8);
         if (!WINO) s3_conv3_direct_finish<ACT>(sB, wt, dst);
         if (next < n) crop_finish<kS3In>(px, sTab, sA);
-        CNNC_PROBE(9);
         __syncthreads();                                   // next crop in place; partial sums consumed before conv1 rewrites sB
     }
-#ifdef CNNC_PHASE_PROBE
-    if (threadIdx.x == 0 && blockIdx.x == 0) {
-        g_probe[10] += clock64() - probe_c0_;
-        g_probe[11] += wall_clock64() - probe_w0_;
-    }
-    if (threadIdx.x == 0 && blockIdx.x < 1024) {
-        g_span[2 * blockIdx.x] = probe_w0_;
-        g_span[2 * blockIdx.x + 1] = wall_clock64();
-    }
-#endif
 }
 
 // fc 1568->64 + f, fc 64->1 for 16 windows per workgroup: eight waves split K (the loop is bound by the latency of its
@@ -967,6 +930,19 @@ void eval2_make_fragments(const float *w, float *f)
                 }
 }
 
+// Matrix instructions (16x16x4, 1024 multiply-adds each) the convolution kernels issue per crop, padding tiles and
+// Winograd forms included: what "executed" work means next to the algorithmic count of the layer definitions.
+int64_t eval3_mfma_per_crop(int impl)
+{
+    const int64_t conv1 = 8 * 4 * 4 * 7;                                      // 8 rounds x 4 tiles x 4 waves, 7 k-steps
+    const int64_t conv2 = impl == 3 ? 4 * (20 * 16 + 20 * 8)                   // F(4,5): a whole and a half tile per wave
+                        : impl == 2 ? (int64_t)kWinoTiles * 20 * 12            // F(2,5)
+                                    : 21 * 25 * 4 * 2;                         // direct: 21 tiles, 25 taps x 4 channel quads, 2 n-tiles
+    const int64_t conv3 = impl >= 2 ? 4 * 24 * 4 : 4 * 9 * 2 * 4 * 2;
+    return conv1 + conv2 + conv3;
+}
+int64_t eval2_mfma_per_crop(int impl) { return 13 * 8 + (impl == 3 ? 36 : 72); }
+
 namespace {
 int conv_grid(const cnnc_ctx *c)
 {
@@ -980,22 +956,6 @@ int fc_grid(const cnnc_ctx *c)
 }
 }  // namespace
 
-#ifdef CNNC_PHASE_PROBE
-extern "C" void cnnc_debug_read_probe(unsigned long long *out, int reset)
-{
-    (void)hipDeviceSynchronize();
-    (void)hipMemcpyFromSymbol(out, HIP_SYMBOL(g_probe), sizeof(unsigned long long) * 16);
-    if (reset) {
-        unsigned long long z[16] = {0};
-        (void)hipMemcpyToSymbol(HIP_SYMBOL(g_probe), z, sizeof(z));
-    }
-}
-extern "C" void cnnc_debug_read_span(unsigned long long *out)
-{
-    (void)hipDeviceSynchronize();
-    (void)hipMemcpyFromSymbol(out, HIP_SYMBOL(g_span), sizeof(unsigned long long) * 2048);
-}
-#endif
 
 hipError_t launch_eval3_mfma(cnnc_ctx *c, hipStream_t st)
 {

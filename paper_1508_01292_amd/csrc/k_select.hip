@@ -290,11 +290,12 @@ void select_kernel(const uint8_t *__restrict__ frame, int fw, int fh, int pitch,
             sReg[(e / kRegW) * kRegP + e % kRegW] = normalise((float)sHist[sPix[e]]);
         __syncthreads();
 
-        // ---- CNN_2 on the region and its mirror image; CNN_3 only if CNN_2 left a vote; decision rule (2)
+        // ---- CNN_2 on the region and its mirror image; under rule (2) CNN_3 only if CNN_2 left a vote (K2 = 0 already
+        // decides); under rule (3) CNN_3's count alone can accept a region, so it always runs
         float *m2 = maps2 + (size_t)s * kMap, *m3 = maps3 + (size_t)s * kMap;
         const int k2 = region_votes<kNet2C1, kNet2C2, ACT>(sReg, sP1, sP2, sPart, sRes, w2, f2, t2, m2);
         int k3 = 0;
-        if (k2 > 0) k3 = region_votes<kNet3C1, kNet3C2, ACT>(sReg, sP1, sP2, sPart, sRes, w3, f3, t3, m3);
+        if (k2 > 0 || rule == 3) k3 = region_votes<kNet3C1, kNet3C2, ACT>(sReg, sP1, sP2, sPart, sRes, w3, f3, t3, m3);
         else if (tid < kMap) m3[tid] = 0.0f;
         if (tid == 0) {
             cnnc_region R;

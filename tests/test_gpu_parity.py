@@ -22,16 +22,16 @@ def _ctx(cascade, weights, w, h, max_surv=200000):
     return P.Context(cascade, weights, w, h, max_surv)
 
 
-def _full_case(frame, cascade, weights, min_face, step, quantiles=(0.02, 0.2), name=""):
+def _full_case(frame, cascade, weights, min_face, step, quantiles=(0.02, 0.2), name="", det_cap=8192):
     torch = _torch()
     print("case", name, frame.shape, "min_face", min_face, "step", step, flush=True)
     tr = O.detect(frame, cascade, weights, min_face, step, quantiles=quantiles)
     ctx = _ctx(cascade, weights, frame.shape[1], frame.shape[0])
     ctx.set_params(min_face, step, tr.thr)
-    g = run_gpu_steps(ctx, torch.from_numpy(frame).cuda(), tr.thr)
+    g = run_gpu_steps(ctx, torch.from_numpy(frame).cuda(), tr.thr, det_cap=det_cap)
     info = compare_with_trace(g, tr, frame, cascade, weights)
     # the one-call wrapper gives the same detections as the step-by-step calls
-    det = [d.as_dict() for d in ctx.detect(torch.from_numpy(frame).cuda(), 8192)]
+    det = [d.as_dict() for d in ctx.detect(torch.from_numpy(frame).cuda(), det_cap)]
     assert det == g["det"]
     ctx.close()
     print("   windows %d -> %d -> %d -> %d -> %d detections; band %s merge_exact %s"
@@ -190,6 +190,12 @@ def test_every_window_survives_and_capacity_overflow():
     P.lib().cnnc_get_survivors(small._h, C.c_int(1), C.byref(pi), C.byref(ps))
     from paper_1508_01292_amd.binding import _d2h
     assert _d2h(pi.value, 400, np.uint32).tolist() == list(range(100))
+    # the overflowing call still hands over the detections made from the truncated lists, and their count
+    from paper_1508_01292_amd.binding import Detection
+    out, n = (Detection * 256)(), C.c_int(-7)
+    rc = P.lib().cnnc_detect(small._h, *small._frame_args(ft), out, C.c_int(256), C.byref(n))
+    assert rc == -3 and 0 < n.value <= 100
+    assert all(0 <= out[k].index < 100 for k in range(n.value)) and sum(out[k].neighbors + 1 for k in range(n.value)) == 100
     small.close()
 
 
@@ -403,51 +409,16 @@ def test_uhd_headline_workload_full_oracle():
     assert tr.score1.size == 856540 and len(tr.idx1) == 17130 and len(tr.idx2) == 3426
 
 
-def test_uhd_small_faces_sampled():
-    """3840x2160 with 24-pixel faces (6.6 M windows): full score map and stage-1 survivors against the
-    dense oracle; later stages on a sample of the windows the GPU evaluated."""
-    torch = _torch()
+def test_uhd_small_faces_full_oracle():
+    """3840x2160 with 24-pixel faces (6.6 M windows, 131,773 / 26,354 survivors at the 2 % / 20 % quantiles of the
+    oracle's scores): every intermediate of every step against the full oracle, merge included."""
     c = I.CONFIGS[3]
     casc = I.default_cascade()
     W = I.draw_weights(casc, I.config_seed(3))
     frame = I.make_frame(c["width"], c["height"], I.config_seed(3))
-    print("case uhd small faces", flush=True)
-    pyr = O.build_pyramid(frame, c["min_face"], c["scale_step"])
-    s1 = O.stage1_scores(pyr, casc[0], W[0])
-    assert s1.size == 6588676
-    t1 = O.threshold_from_quantile(s1, 0.02)
-    ctx = _ctx(casc, W, 3840, 2160, 200000)
-    ctx.set_params(c["min_face"], c["scale_step"], (t1, 0.0, 0.0))
-    ft = torch.from_numpy(frame).cuda()
-    ctx.build_pyramid(ft)
-    assert np.array_equal(ctx.get_pyramid(), np.concatenate([l.ravel() for l in pyr.levels]))
-    ctx.stage1_scoremap()
-    assert_scores(ctx.get_scoremap(), s1, "stage-1 score map")
-    ctx.compact_survivors(1, float(t1))
-    idx1, _ = ctx.get_survivors(1)
-    assert_survivors(idx1, s1, np.arange(s1.size), t1, "stage-1 survivors")
-    assert abs(len(idx1) - 131773) <= 3
-    ctx.eval_stage(2)
-    sc2 = ctx.get_stage_scores(2)
-    rng = np.random.default_rng(0)
-    pick = np.sort(rng.choice(len(idx1), 1500, replace=False))
-    assert_scores(sc2[pick], O.eval_stage(frame, pyr, idx1[pick], casc[1], W[1]), "stage-2 scores (sample)")
-    t2 = float(np.sort(sc2)[::-1][len(sc2) // 5])            # any threshold: survivors checked by property
-    ctx.compact_survivors(2, t2)
-    idx2, s2k = ctx.get_survivors(2)
-    assert np.array_equal(idx2, idx1[sc2 > np.float32(t2)]) and np.array_equal(s2k, sc2[sc2 > np.float32(t2)])
-    ctx.eval_stage(3)
-    sc3 = ctx.get_stage_scores(3)
-    pick = np.sort(rng.choice(len(idx2), 200, replace=False))
-    assert_scores(sc3[pick], O.eval_stage(frame, pyr, idx2[pick], casc[2], W[2]), "stage-3 scores (sample)")
-    ctx.compact_survivors(3, 0.0)
-    idx3, s3k = ctx.get_survivors(3)
-    assert np.array_equal(idx3, idx2[sc3 > 0]) and np.array_equal(s3k, sc3[sc3 > 0])
-    det = [d.as_dict() for d in ctx.merge_detections(32768)]
-    bx, by, bs, _ = boxes_of(pyr, idx3)
-    assert [(d["index"], d["neighbors"]) for d in det] == \
-        [(int(idx3[p]), n) for p, n in greedy_merge_check(bx, by, bs, s3k, idx3)]
-    ctx.close()
+    tr, g, _ = _full_case(frame, casc, W, c["min_face"], c["scale_step"], name="uhd small faces", det_cap=32768)
+    assert tr.score1.size == 6588676 and len(tr.idx1) == 131773 and len(tr.idx2) == 26354
+    assert len(g["det"]) > 4096        # the long form of the merge (several chunks of sorted boxes)
 
 
 def test_compaction_of_a_very_long_score_map():

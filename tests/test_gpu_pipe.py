@@ -93,7 +93,9 @@ def test_pipe_errors_and_parameter_change():
         pipe.fetch(99)
     assert e.value.code == -1
     a = [d.as_dict() for d in pipe.fetch(t1)]         # any order
+    t2 = pipe.submit(frame)                           # the slot freed out of order takes the next frame at once
     b = [d.as_dict() for d in pipe.fetch(t0)]
+    assert [d.as_dict() for d in pipe.fetch(t2)] == a
     assert a == b and [(d["index"], d["neighbors"]) for d in a] == [(d["index"], d["neighbors"]) for d in tr.det]
     with pytest.raises(P.CnncError):                  # already fetched
         pipe.fetch(t0)

@@ -54,7 +54,7 @@ def _select_case(frame, min_face, step, act, seed, q1, q2, t_nn, bias_sd=0.0, na
         assert np.all(np.abs(a2 - w["r2"]) <= ATOL + RTOL * np.abs(w["r2"])), "CNN_2 map of %d: %g" % (r.index, np.abs(a2 - w["r2"]).max())
         near2 = int((np.abs(w["r2"] - t2) <= BAND).sum())
         assert abs(r.k2 - w["k2"]) <= near2
-        if near2 == 0 and w["k2"] > 0:
+        if near2 == 0 and (w["k2"] > 0 or rule == 3):
             assert np.all(np.abs(a3 - w["r3"]) <= ATOL + RTOL * np.abs(w["r3"])), "CNN_3 map of %d" % r.index
             near3 = int((np.abs(w["r3"] - t3) <= BAND).sum())
             assert abs(r.k3 - w["k3"]) <= near3

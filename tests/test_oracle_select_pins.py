@@ -74,7 +74,8 @@ def _constant_net(net, value):
 
 
 def test_decision_rule_truth_table():
-    """Eq. (2): face = (K2 >= T_nn and K3 > 0) or (K2 > 0 and K3 >= T_nn); K3 is not computed when K2 = 0."""
+    """Eq. (2): face = (K2 >= T_nn and K3 > 0) or (K2 > 0 and K3 >= T_nn); K3 is not computed when K2 = 0.
+    Eq. (3): face = K2 >= T_nn or K3 >= T_nn, CNN_3 always evaluated."""
     n2, n3 = I.paper_stage2(), I.paper_stage3()
     reg = np.random.default_rng(0).integers(0, 256, (55, 51), dtype=np.uint8)
     hi2, lo2, hi3, lo3 = _constant_net(n2, 1.0), _constant_net(n2, -1.0), _constant_net(n3, 1.0), _constant_net(n3, -1.0)
@@ -87,7 +88,9 @@ def test_decision_rule_truth_table():
     assert O.select_region(reg, n2, hi2, n3, lo3, 0.0, 0.0, 1, rule=3)[:3] == (25, 0, True)      # rule (2) said no
     assert O.select_region(reg, n2, hi2, n3, lo3, 0.0, 0.0, 26, rule=3)[:3] == (25, 0, False)
     assert O.select_region(reg, n2, hi2, n3, hi3, 0.0, 0.0, 25, rule=3)[:3] == (25, 25, True)
-    assert O.select_region(reg, n2, lo2, n3, hi3, 0.0, 0.0, 1, rule=3)[:3] == (0, 0, False)      # CNN_3 still not run
+    assert O.select_region(reg, n2, lo2, n3, hi3, 0.0, 0.0, 1, rule=3)[:3] == (0, 25, True)      # CNN_3's votes alone accept
+    assert O.select_region(reg, n2, lo2, n3, hi3, 0.0, 0.0, 26, rule=3)[:3] == (0, 25, False)
+    assert O.select_region(reg, n2, lo2, n3, lo3, 0.0, 0.0, 1, rule=3)[:3] == (0, 0, False)
     k23 = [(a, b) for a in range(0, 26, 5) for b in range(0, 26, 5)]
     assert all(((a >= 10) or (b >= 10)) >= ((a >= 10 and b > 0) or (a > 0 and b >= 10)) for a, b in k23)   # (3) is weaker
     # the comparison is strict and made in fp32
@@ -121,6 +124,21 @@ def test_response_maps_mirror_and_counts_against_torch(act):
     k2, k3, face = O.select_region(reg, n2, w2, n3, w3, np.float32(t2b), np.float32(t3b), 10, rule=3)[:3]
     assert k2 in (2, 3) and k3 in (20, 21) and face is True
     assert O.select_region(reg, n2, w2, n3, w3, np.float32(t2b), np.float32(t3b), 22, rule=3)[2] is False
+    # eq. (2), second disjunct alone: 0 < K2 < T_nn and K3 >= T_nn is a face ...
+    k2, k3, face = O.select_region(reg, n2, w2, n3, w3, np.float32(t2b), np.float32(t3b), 10)[:3]
+    assert 0 < k2 < 10 <= k3 and face is True
+    # ... and stops being one when K3 falls below T_nn as well (neither disjunct holds)
+    assert O.select_region(reg, n2, w2, n3, w3, np.float32(t2b), np.float32(t3b), 22)[2] is False
+    # eq. (2), first disjunct needs a vote of CNN_3: K2 >= T_nn with K3 = 0 is no face, though CNN_3 was run
+    t3top = float(want["3"].max()) + 1.0
+    k2, k3, face, _, r3c = O.select_region(reg, n2, w2, n3, w3, np.float32(t2), np.float32(t3top), 5)
+    assert k2 >= 5 and k3 == 0 and face is False and np.abs(r3c - want["3"]).max() <= 1e-12
+    # under eq. (3) the same region with K2 = 0 is accepted by CNN_3's votes: CNN_3 is evaluated whatever K2 is
+    t2top = float(want["2"].max()) + 1.0
+    k2, k3, face, _, r3c = O.select_region(reg, n2, w2, n3, w3, np.float32(t2top), np.float32(t3b), 10, rule=3)
+    assert k2 == 0 and k3 in (20, 21) and face is True and np.abs(r3c - want["3"]).max() <= 1e-12
+    k2, k3, face, _, r3c = O.select_region(reg, n2, w2, n3, w3, np.float32(t2top), np.float32(t3b), 10)
+    assert (k2, k3, face) == (0, 0, False) and np.all(r3c == 0)         # eq. (2): stopped after CNN_2
 
 
 def test_unit_geometry_window_sits_in_the_middle_of_its_region():
