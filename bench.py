@@ -6,6 +6,11 @@ stage 3 -> compaction -> merge -> detections on the host) over one synthetic 384
 already resident in device memory.  Prints ONE JSON line.
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--inflight F] [--workload uhd|uhd_small_faces|fhd|vga]
+
+Every timed leg is preceded by an untimed, time-based pre-warm of the same loop (--prewarm seconds) so that a short
+run (--steps 20) measures the same state of the GPU as a long one; the W warm-up steps follow it and the K timed
+steps are bracketed by device synchronisation.  The headline is timed twice over exactly K steps, with F frames in
+flight on F contexts / streams and one frame at a time; `value` is the faster and both are reported.
 """
 import argparse
 import json
@@ -25,17 +30,30 @@ S2_FLOP_PER_CROP = 2 * 161952
 S3_FLOP_PER_CROP = 2 * 5473600
 S2_CONV_FLOP_PER_CROP = 2 * (80000 + 73728)            # conv kernel of stage 2 (conv1 + conv2)
 S3_CONV_FLOP_PER_CROP = 2 * (774400 + 4147200 + 451584)  # conv kernel of stage 3 (conv1..conv3)
+MFMA_FLOP = 2 * 16 * 16 * 4                            # one 16x16x4 matrix instruction
 SEL_MAC_CNN2 = 48 * 52 * 4 * 16 + 22 * 24 * 19 * 36 + 25 * 19 * 56      # one pass of CNN_2 over a 51x55 region
 SEL_MAC_CNN3 = 48 * 52 * 5 * 16 + 22 * 24 * 28 * 45 + 25 * 28 * 56      # one pass of CNN_3
 SCAN_FLOP_PER_POSITION = 2 * (1024 + 1584 + 330)       # 27x31 scan: conv1 + conv2 + conv3 MACs per window position at step 4
 PEAK_HBM = 8000.0          # GB/s
 PEAK_FP32_VECTOR = 157.3   # TFLOP/s, published vector fp32 figure
 PEAK_FP32_MFMA = 157.3     # TFLOP/s, published dense fp32 matrix figure
-# HBM bytes per launch from the rocprofv3 FETCH_SIZE / WRITE_SIZE passes summarised in
-# profiles/hbm_traffic_uhd_pmc.txt (read + written, scaled by the copy-kernel calibration); None where
-# that workload was not measured.
-MEASURED_TRAFFIC = {("stage3_conv", "uhd"): 38.41e6 + 30.14e6, ("stage2_conv", "uhd"): 70.46e6 + 17.54e6,
-                    ("stage1", "uhd"): 5.72e6 + 4.21e6, ("pyramid", "uhd"): 17.02e6 + 1.22e6}
+KERNEL_NAMES = {"stage1": "stage1_kernel", "stage2_conv": "eval2_conv_kernel", "stage3_conv": "eval3_conv_kernel",
+                "pyramid": "pyramid_kernel"}
+
+
+def measured_traffic(workload, kernel):
+    """HBM bytes per launch (read + written) of `kernel` from the committed rocprofv3 FETCH_SIZE / WRITE_SIZE
+    summary of this workload, or None when no such summary exists.  Returns (bytes, file name)."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic_%s_pmc.txt" % workload)
+    try:
+        with open(path) as f:
+            for line in f:
+                if line.startswith(kernel):
+                    cols = line.split()
+                    return (float(cols[-2]) + float(cols[-1])) * 1e6, os.path.relpath(path, ROOT)
+    except (OSError, ValueError, IndexError):
+        pass
+    return None, None
 
 
 def main():
@@ -44,11 +62,13 @@ def main():
     ap.add_argument("--steps", type=int, default=2000)
     ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--inflight", type=int, default=3, help="frames in flight on separate streams")
+    ap.add_argument("--prewarm", type=float, default=1.0, help="seconds of untimed running before each timed leg")
     ap.add_argument("--workload", default="uhd")
     ap.add_argument("--q1", type=float, default=0.02, help="stage-1 survival quantile (the benchmark's rule: 2 %%)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-ingest", action="store_true", help="skip the host-memory ingest leg (its frames overlap on several "
                     "streams, which stretches per-kernel durations in a profiler trace)")
+    ap.add_argument("--no-paper-path", action="store_true", help="skip the legs in the paper's own geometry")
     ap.add_argument("--eval-impl", type=int, default=None, help="cnnc_set_eval_impl value (default: the library's)")
     ap.add_argument("--fused-stage1", type=int, default=None, help="cnnc_set_fused_stage1 value (default: the library's)")
     a = ap.parse_args()
@@ -80,22 +100,60 @@ def main():
         t1 = O.threshold_from_quantile(np.concatenate(s1), a.q1)
         s2 = [O.eval_stage(f, p, O.survivors(s, t1), casc[1], W[1]) for f, p, s in zip(frames, pyrs, s1)]
         thr_pooled = (float(t1), float(O.threshold_from_quantile(np.concatenate(s2), 0.2)), 0.0)
+    n_cores = O.num_threads()
     t0 = time.perf_counter()
     tr = O.detect(frame, casc, W, cfg["min_face"], cfg["scale_step"], thr=thr_pooled, quantiles=(a.q1, 0.2))
     t_cpu = time.perf_counter() - t0
     n_windows = int(tr.score1.size)
     cpu = None
     if not a.no_cpu_baseline:
-        cpu = {"value": 1.0 / t_cpu, "unit": "frames/s", "cores": O.num_threads(), "kind": "oracle",
-               "sample": "1 whole %dx%d frame through the oracle (dense stage-1 form, fp64, OpenMP): %.2f s; "
-                         "stage-1 windows/s on the CPU = %.3g" % (cfg["width"], cfg["height"], t_cpu, n_windows / t_cpu)}
+        # the first stage in both forms of the oracle (dense single pass; per-window definition), all cores and one
+        # thread, and the whole frame on one thread; the per-window form at one thread runs on a sample of levels
+        pyr_o = tr.pyramid
+
+        def timed(fn):
+            t = time.perf_counter()
+            r = fn()
+            return time.perf_counter() - t, r
+
+        def level_set(budget_windows):
+            """Coarsest levels first until about `budget_windows` windows are covered."""
+            lv, n = [], 0
+            for l in reversed(pyr_o.levels):
+                lv.append(l)
+                n += (l.shape[0] - 11) * (l.shape[1] - 11)
+                if n >= budget_windows:
+                    break
+            return lv, n
+
+        s1_forms = {}
+        for form, budget1 in (("dense", n_windows), ("windows", 200000)):
+            t_all, _ = timed(lambda: [O.stage1_level(l, casc[0], W[0], form) for l in pyr_o.levels])
+            lv1, n1w = level_set(budget1)
+            O.set_num_threads(1)
+            t_one, _ = timed(lambda: [O.stage1_level(l, casc[0], W[0], form) for l in lv1])
+            O.set_num_threads(n_cores)
+            s1_forms[form] = {"all_cores_windows_per_s": n_windows / t_all, "all_cores_s": t_all, "cores": n_cores,
+                              "one_thread_windows_per_s": n1w / t_one, "one_thread_s": t_one,
+                              "one_thread_sample_windows": n1w}
+        O.set_num_threads(1)
+        t_cpu1, _ = timed(lambda: O.detect(frame, casc, W, cfg["min_face"], cfg["scale_step"], thr=tr.thr))
+        O.set_num_threads(n_cores)
+        cpu = {"value": 1.0 / t_cpu, "unit": "frames/s", "cores": n_cores, "kind": "oracle",
+               "sample": "1 whole %dx%d frame through the oracle (dense stage-1 form, fp64, OpenMP): %.2f s on %d threads, "
+                         "%.2f s on one thread; stage 1 alone in stage1_forms: 'dense' = single pass over each level, "
+                         "'windows' = the per-window definition (its one-thread figure on the coarsest levels holding "
+                         "%d windows)" % (cfg["width"], cfg["height"], t_cpu, n_cores, t_cpu1,
+                                          s1_forms["windows"]["one_thread_sample_windows"]),
+               "one_thread_frames_per_s": 1.0 / t_cpu1, "stage1_forms": s1_forms}
 
     # ---- GPU
     torch.cuda.set_device(0)
     dev_frames = [torch.from_numpy(f).cuda() for f in frames]
     dev_frame = dev_frames[0]
     F = max(1, a.inflight)
-    ctxs = [P.Context(casc, W, cfg["width"], cfg["height"], 262144) for _ in range(F)]
+    max_surv = max(32768, 1 << int(np.ceil(np.log2(2 * max(1, len(tr.idx1))))))
+    ctxs = [P.Context(casc, W, cfg["width"], cfg["height"], max_surv) for _ in range(F)]
     streams = [torch.cuda.Stream() for _ in range(F)]
     for c in ctxs:
         c.set_params(cfg["min_face"], cfg["scale_step"], tr.thr)
@@ -103,8 +161,9 @@ def main():
             c.set_eval_impl(a.eval_impl)
         if a.fused_stage1 is not None:
             c.set_fused_stage1(bool(a.fused_stage1))
+    c0 = ctxs[0]
 
-    def run(n_steps):
+    def run_inflight(n_steps):
         busy = [False] * F
         n_det = 0
         for i in range(n_steps):
@@ -118,25 +177,38 @@ def main():
                 n_det = len(ctxs[j].fetch_detections(8192))
         return n_det
 
-    run(a.warmup)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    n_det = run(a.steps)
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
-    fps = a.steps / elapsed
+    def run_serial(n_steps):
+        n_det = 0
+        for i in range(n_steps):
+            n_det = len(c0.detect(dev_frames[i % len(dev_frames)], 8192))
+        return n_det
 
-    # one frame at a time (latency), same context
-    c0 = ctxs[0]
-    for _ in range(3):
-        c0.detect(dev_frame, 8192)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    n_lat = max(10, a.steps // 4)
-    for _ in range(n_lat):
-        c0.detect(dev_frame, 8192)
-    torch.cuda.synchronize()
-    latency_ms = (time.perf_counter() - t0) / n_lat * 1e3
+    def prewarm(fn, chunk):
+        """Untimed: run the leg's own loop until --prewarm seconds have passed (clocks, caches, first-use costs)."""
+        t_end = time.perf_counter() + a.prewarm
+        while True:
+            fn(chunk)
+            if time.perf_counter() >= t_end:
+                break
+        torch.cuda.synchronize()
+
+    def timed_leg(fn, chunk):
+        prewarm(fn, chunk)
+        if a.warmup > 0:
+            fn(a.warmup)
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        n = fn(a.steps)
+        torch.cuda.synchronize()
+        return time.perf_counter() - t, n
+
+    el_inflight, n_det = timed_leg(run_inflight, 4 * F)
+    el_serial, n_det_serial = timed_leg(run_serial, 4)
+    assert n_det == n_det_serial
+    fps_inflight, fps_serial = a.steps / el_inflight, a.steps / el_serial
+    elapsed = min(el_inflight, el_serial)
+    fps = a.steps / elapsed
+    latency_ms = el_serial / a.steps * 1e3
     # a stream: every frame on its own, to show how much the time depends on the content of the frame
     per_frame = None
     if len(dev_frames) > 1:
@@ -152,76 +224,29 @@ def main():
         per_frame = {"min": min(lat), "mean": sum(lat) / len(lat), "max": max(lat)}
 
     # per-kernel times: HIP events recorded by the library on the stream the kernels run on
+    n_timed = max(a.steps, 200)
     c0.set_timing(True)
     c0.get_timings()
-    for _ in range(a.steps):
+    for _ in range(n_timed):
         c0.detect_async(dev_frame, streams[0])
         c0.fetch_detections(8192)
     tm = c0.get_timings()
     c0.set_timing(False)
     ms = {k: (v[0] / v[1] if v[1] else 0.0) for k, v in tm.items()}
-    # first stage in the paper's own geometry (27 x 31 window, 4 pixel step) on the same pyramid: reported beside the
-    # headline, in the paper's unit (window positions at step 4)
-    scan_net = I.paper_stage1()
-    c0.scan_set_weights(I.draw_scan_weights(scan_net, seed), 1)
-    c0.build_pyramid(dev_frame, streams[0])
-    c0.set_timing(True)
-    c0.get_timings()
-    for _ in range(a.steps):
-        c0.scan_scoremap(streams[0])
-    tm_scan = c0.get_timings()["scan"]
-    c0.set_timing(False)
-    ms_scan = tm_scan[0] / tm_scan[1] if tm_scan[1] else 0.0
-    n_scan = int(c0.scan_layout(cfg["width"], cfg["height"])["out_off"][-1])
-    # the selective unit in that geometry on the positions above the 2 % quantile of the scan; thresholds of the two
-    # response maps at their medians over a sample of regions (oracle), T_nn = 5
-    n2_net, n3_net = I.paper_stage2(), I.paper_stage3()
-    w2_sel, w3_sel = I.draw_scan_weights(n2_net, seed + 1), I.draw_scan_weights(n3_net, seed + 2)
-    c0.select_set_weights(w2_sel, w3_sel, 1)
-    pyr_o = O.build_pyramid(frame, cfg["min_face"], cfg["scale_step"])
-    scan_o = O.scan_scores(pyr_o, scan_net, I.draw_scan_weights(scan_net, seed))
-    t1_scan = float(O.threshold_from_quantile(scan_o, 0.02))
-    sample = np.nonzero(scan_o.astype(np.float32) > np.float32(t1_scan))[0][::24]
-    ref_sel = O.select_unit(frame, pyr_o, sample, scan_net, n2_net, w2_sel, n3_net, w3_sel, -1e30, -1e30, 1)
-    t2_sel = float(np.median(np.concatenate([r["r2"].ravel() for r in ref_sel])))
-    t3_sel = float(np.median(np.concatenate([r["r3"].ravel() for r in ref_sel])))
-    c0.set_timing(True)
-    c0.get_timings()
-    for _ in range(max(10, a.steps // 4)):
-        c0.select_run(t1_scan, t2_sel, t3_sel, 5, streams[0])
-    tm_sel = c0.get_timings()["select"]
-    c0.set_timing(False)
-    ms_sel = tm_sel[0] / tm_sel[1] if tm_sel[1] else 0.0
-    sel = c0.select_fetch(65536)
-    # merge of the accepted regions: the call waits for its result, so this is wall-clock time per call
-    sel_det = c0.select_merge(0.3, 1, 32768, streams[0])
-    t0 = time.perf_counter()
-    for _ in range(20):
-        c0.select_merge(0.3, 1, 32768, streams[0])
-    ms_sel_merge = (time.perf_counter() - t0) / 20 * 1e3
-    # the paper-geometry path end to end, one frame at a time: pyramid, scan, selective unit, merge (which waits)
-    n_paper = 50
-    with torch.cuda.stream(streams[0]):
-        for it in range(n_paper + 5):
-            if it == 5:
-                torch.cuda.synchronize()
-                t0 = time.perf_counter()
-            c0.build_pyramid(dev_frame, streams[0])
-            c0.scan_scoremap(streams[0])
-            c0.select_run(t1_scan, t2_sel, t3_sel, 5, streams[0])
-            c0.select_merge(0.3, 1, 32768, streams[0])
-    ms_paper_frame = (time.perf_counter() - t0) / n_paper * 1e3
-    sel_flop = 2.0 * sum(2 * SEL_MAC_CNN2 + (2 * SEL_MAC_CNN3 if r.k2 > 0 else 0) for r in sel)
-    c0.detect(dev_frame, 8192)           # leaves the context with the cascade's own survivor lists again
     n1, n2, n3 = (c0.survivor_count(s) for s in (1, 2, 3))
     lay = c0.pyramid_layout(cfg["width"], cfg["height"])
     pyr_bytes = lay["pyr_off"][-1]
+    mfma2, mfma3 = c0.executed_mfma(2), c0.executed_mfma(3)
 
     def tflops(flop, t_ms):
         return flop / (t_ms * 1e-3) / 1e12 if t_ms > 0 else 0.0
 
     def gbs(nbytes, t_ms):
         return nbytes / (t_ms * 1e-3) / 1e9 if t_ms > 0 else 0.0
+
+    paper = None
+    if not a.no_paper_path:
+        paper = paper_geometry_legs(a, c0, streams[0], dev_frame, frame, cfg, seed, tr, I, O, np, torch, time, tflops)
 
     kernels = {
         "pyramid": {"bound": "hbm", "ms": ms["pyramid"], "achieved": gbs(cfg["width"] * cfg["height"] + pyr_bytes, ms["pyramid"]),
@@ -233,24 +258,31 @@ def main():
         "stage2": {"bound": "mfma", "ms": ms["stage2"], "achieved": tflops(S2_FLOP_PER_CROP * n1, ms["stage2"]),
                    "peak": PEAK_FP32_MFMA, "unit": "TFLOP/s"},
         "stage2_conv": {"bound": "mfma", "ms": ms["stage2_conv"], "achieved": tflops(S2_CONV_FLOP_PER_CROP * n1, ms["stage2_conv"]),
-                        "peak": PEAK_FP32_MFMA, "unit": "TFLOP/s"},
+                        "peak": PEAK_FP32_MFMA, "unit": "TFLOP/s",
+                        "executed": tflops(MFMA_FLOP * mfma2 * n1, ms["stage2_conv"]), "mfma_per_crop": mfma2},
         "stage3": {"bound": "mfma", "ms": ms["stage3"], "achieved": tflops(S3_FLOP_PER_CROP * n2, ms["stage3"]),
                    "peak": PEAK_FP32_MFMA, "unit": "TFLOP/s"},
         "stage3_conv": {"bound": "mfma", "ms": ms["stage3_conv"], "achieved": tflops(S3_CONV_FLOP_PER_CROP * n2, ms["stage3_conv"]),
-                        "peak": PEAK_FP32_MFMA, "unit": "TFLOP/s"},
+                        "peak": PEAK_FP32_MFMA, "unit": "TFLOP/s",
+                        "executed": tflops(MFMA_FLOP * mfma3 * n2, ms["stage3_conv"]), "mfma_per_crop": mfma3},
         "compact2": {"ms": ms["compact2"]}, "compact3": {"ms": ms["compact3"]}, "merge": {"ms": ms["merge"]},
     }
     for k in kernels.values():
         if "achieved" in k:
             k["frac"] = k["achieved"] / k["peak"]
+        if "executed" in k:
+            k["executed_frac"] = k["executed"] / k["peak"]
     # the dominant single kernel: the convolution kernel of the slowest step, or the step's own kernel
     dom = max(("stage1", "stage2_conv", "stage3_conv", "pyramid"), key=lambda k: ms[k])
-    kernel_names = {"stage1": "stage1_kernel", "stage2_conv": "eval2_conv_kernel", "stage3_conv": "eval3_conv_kernel",
-                    "pyramid": "pyramid_kernel"}
+    traffic, traffic_src = measured_traffic(a.workload, KERNEL_NAMES[dom])
     roof = {"bound": kernels[dom]["bound"], "achieved": kernels[dom]["achieved"], "peak": kernels[dom]["peak"],
             "unit": kernels[dom]["unit"], "frac": kernels[dom]["frac"],
-            "traffic": MEASURED_TRAFFIC.get((dom, a.workload)), "kernel": kernel_names[dom],
-            "avg_launch_ms": ms[dom]}
+            "traffic": traffic, "traffic_from": traffic_src, "kernel": KERNEL_NAMES[dom], "avg_launch_ms": ms[dom]}
+    if "executed" in kernels[dom]:
+        # `achieved` counts the multiply-adds of the layer definitions; the Winograd forms execute fewer.  `executed`
+        # counts the matrix instructions the kernel really issues: that fraction is the utilisation of the matrix cores.
+        roof["executed"] = kernels[dom]["executed"]
+        roof["executed_frac"] = kernels[dom]["executed_frac"]
     try:
         mf, vf, hb = P.cnnc_measure_peaks()
         roof["sustained_on_this_gpu"] = {"mfma_f32_tflops": mf, "valu_f32_tflops": vf, "hbm_copy_gbs": hb}
@@ -261,7 +293,7 @@ def main():
     ingest = {}
     D = F + 1                                    # one slot more than frames computing: its copy runs ahead
     for use_graph in (() if a.no_ingest else (False, True)):
-        pipe = P.Pipe(casc, W, cfg["width"], cfg["height"], 262144, depth=D, use_graph=use_graph)
+        pipe = P.Pipe(casc, W, cfg["width"], cfg["height"], max_surv, depth=D, use_graph=use_graph)
         pipe.set_params(cfg["min_face"], cfg["scale_step"], tr.thr)
         for j in range(D):                       # the producer's frames sit in the pinned buffers already
             pipe.frame_buffer()[:] = frames[j % len(frames)]
@@ -278,10 +310,7 @@ def main():
                 n = len(pipe.fetch(t, 8192))
             return n
 
-        run_pipe(a.warmup)
-        t0 = time.perf_counter()
-        n_det_pipe = run_pipe(a.steps)
-        dt = time.perf_counter() - t0
+        dt, n_det_pipe = timed_leg(run_pipe, 4 * D)
         ingest["graph" if use_graph else "eager"] = {"frames_per_s": a.steps / dt, "detections": n_det_pipe,
                                                      "h2d_gb_per_s": a.steps / dt * cfg["width"] * cfg["height"] / 1e9}
         pipe.close()
@@ -294,22 +323,14 @@ def main():
         "config": {"workload": "%s: %d %dx%d uint8 frame(s), min face %g px, scale step %g, %g%% / 20%% survival quantiles, T3 = 0"
                                % (cfg["name"], len(frames), cfg["width"], cfg["height"], cfg["min_face"], cfg["scale_step"],
                                   100 * a.q1),
-                   "frames_in_flight": F, "windows": n_windows, "survivors": [n1, n2, n3], "detections": n_det},
+                   "frames_in_flight": F if el_inflight <= el_serial else 1, "windows": n_windows,
+                   "survivors": [n1, n2, n3], "detections": n_det, "prewarm_s": a.prewarm},
+        "frames_per_s": {"in_flight_%d" % F: fps_inflight, "one_at_a_time": fps_serial},
         "stage1_windows_per_s": n_windows / (ms["stage1"] * 1e-3) if ms["stage1"] > 0 else None,
         "latency_ms_single_frame": latency_ms,
         "latency_ms_per_frame_of_stream": per_frame,
-        "paper_geometry_stage1": {"window": "27x31", "step": 4, "positions": n_scan, "ms": ms_scan,
-                                  "positions_per_s": n_scan / (ms_scan * 1e-3) if ms_scan > 0 else None,
-                                  "bound": "alu", "achieved": tflops(SCAN_FLOP_PER_POSITION * n_scan, ms_scan),
-                                  "peak": PEAK_FP32_VECTOR, "unit": "TFLOP/s",
-                                  "frac": tflops(SCAN_FLOP_PER_POSITION * n_scan, ms_scan) / PEAK_FP32_VECTOR},
+        "paper_geometry": paper,
         "ingest_from_pinned_host_memory": ingest,
-        "paper_selective_unit": {"regions": len(sel), "faces": sum(r.face for r in sel), "ms": ms_sel,
-                                 "regions_per_s": len(sel) / (ms_sel * 1e-3) if ms_sel > 0 else None, "bound": "alu",
-                                 "achieved": tflops(sel_flop, ms_sel), "peak": PEAK_FP32_VECTOR, "unit": "TFLOP/s",
-                                 "frac": tflops(sel_flop, ms_sel) / PEAK_FP32_VECTOR,
-                                 "merge": {"detections": len(sel_det), "ms_per_call_with_wait_and_readback": ms_sel_merge},
-                                 "whole_path_ms_per_frame_one_at_a_time": ms_paper_frame},
         "sum_of_kernel_ms": sum(v for k, v in ms.items() if not k.endswith("_conv") and k not in ("scan", "select")),
         "roofline": roof,
         "kernels": kernels,
@@ -318,6 +339,84 @@ def main():
     for c in ctxs:
         c.close()
     print(json.dumps(out))
+
+
+def paper_geometry_legs(a, c0, stream, dev_frame, frame, cfg, seed, tr, I, O, np, torch, time, tflops):
+    """The first stage in the paper's own geometry (27 x 31 window, 4 pixel step) on the same pyramid, the selective
+    unit on the positions above the 2 % quantile of that scan, and the merge of what it accepts: reported beside the
+    headline, in the paper's unit (window positions at step 4, regions)."""
+    scan_net = I.paper_stage1()
+    w_scan = I.draw_scan_weights(scan_net, seed)
+    c0.scan_set_weights(w_scan, 1)
+    c0.build_pyramid(dev_frame, stream)
+    n_rep = max(a.steps, 200)
+    t_end = time.perf_counter() + min(a.prewarm, 0.3)
+    while time.perf_counter() < t_end:
+        c0.scan_scoremap(stream)
+    c0.set_timing(True)
+    c0.get_timings()
+    for _ in range(n_rep):
+        c0.scan_scoremap(stream)
+    tm_scan = c0.get_timings()["scan"]
+    c0.set_timing(False)
+    ms_scan = tm_scan[0] / tm_scan[1] if tm_scan[1] else 0.0
+    n_scan = int(c0.scan_layout(cfg["width"], cfg["height"])["out_off"][-1])
+    # Thresholds of the unit from a sample of regions (oracle): T_2 so that CNN_2 leaves no vote in about a third
+    # of the regions (they stop there, eq. (2)), T_3 at the median of CNN_3's responses, T_nn = 5.
+    n2_net, n3_net = I.paper_stage2(), I.paper_stage3()
+    w2_sel, w3_sel = I.draw_scan_weights(n2_net, seed + 1), I.draw_scan_weights(n3_net, seed + 2)
+    c0.select_set_weights(w2_sel, w3_sel, 1)
+    pyr_o = tr.pyramid
+    scan_o = O.scan_scores(pyr_o, scan_net, w_scan)
+    t1_scan = float(O.threshold_from_quantile(scan_o, 0.02))
+    sample = np.nonzero(scan_o.astype(np.float32) > np.float32(t1_scan))[0][::24]
+    ref_sel = O.select_unit(frame, pyr_o, sample, scan_net, n2_net, w2_sel, n3_net, w3_sel, -1e30, -1e30, 1)
+    t2_sel = float(np.quantile([r["r2"].max() for r in ref_sel], 0.33))
+    t3_sel = float(np.median(np.concatenate([r["r3"].ravel() for r in ref_sel])))
+    t_end = time.perf_counter() + min(a.prewarm, 0.3)
+    while time.perf_counter() < t_end:
+        c0.select_run(t1_scan, t2_sel, t3_sel, 5, stream)
+    c0.set_timing(True)
+    c0.get_timings()
+    for _ in range(max(50, a.steps // 4)):
+        c0.select_run(t1_scan, t2_sel, t3_sel, 5, stream)
+    tm_sel = c0.get_timings()["select"]
+    c0.set_timing(False)
+    ms_sel = tm_sel[0] / tm_sel[1] if tm_sel[1] else 0.0
+    sel = c0.select_fetch(65536)
+    # merge of the accepted regions: the call waits for its result, so this is wall-clock time per call
+    sel_det = c0.select_merge(0.3, 1, 32768, stream)
+    t0 = time.perf_counter()
+    for _ in range(50):
+        c0.select_merge(0.3, 1, 32768, stream)
+    ms_sel_merge = (time.perf_counter() - t0) / 50 * 1e3
+    # the path in the paper's geometry end to end, one frame at a time: pyramid, scan, selective unit, merge (which waits)
+    n_paper = max(50, a.steps // 4)
+    with torch.cuda.stream(stream):
+        for it in range(n_paper + 20):
+            if it == 20:
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+            c0.build_pyramid(dev_frame, stream)
+            c0.scan_scoremap(stream)
+            c0.select_run(t1_scan, t2_sel, t3_sel, 5, stream)
+            c0.select_merge(0.3, 1, 32768, stream)
+    ms_paper_frame = (time.perf_counter() - t0) / n_paper * 1e3
+    sel_flop = 2.0 * sum(2 * SEL_MAC_CNN2 + (2 * SEL_MAC_CNN3 if r.k2 > 0 else 0) for r in sel)
+    c0.detect(dev_frame, 8192)           # leaves the context with the cascade's own survivor lists again
+    return {
+        "stage1": {"window": "27x31", "step": 4, "positions": n_scan, "ms": ms_scan,
+                   "positions_per_s": n_scan / (ms_scan * 1e-3) if ms_scan > 0 else None,
+                   "bound": "alu", "achieved": tflops(SCAN_FLOP_PER_POSITION * n_scan, ms_scan),
+                   "peak": PEAK_FP32_VECTOR, "unit": "TFLOP/s",
+                   "frac": tflops(SCAN_FLOP_PER_POSITION * n_scan, ms_scan) / PEAK_FP32_VECTOR},
+        "selective_unit": {"regions": len(sel), "stopped_after_cnn2": sum(r.k2 == 0 for r in sel),
+                           "faces": sum(r.face for r in sel), "ms": ms_sel,
+                           "regions_per_s": len(sel) / (ms_sel * 1e-3) if ms_sel > 0 else None, "bound": "alu",
+                           "achieved": tflops(sel_flop, ms_sel), "peak": PEAK_FP32_VECTOR, "unit": "TFLOP/s",
+                           "frac": tflops(sel_flop, ms_sel) / PEAK_FP32_VECTOR},
+        "merge": {"detections": len(sel_det), "ms_per_call_with_wait_and_readback": ms_sel_merge},
+        "whole_path_ms_per_frame_one_at_a_time": ms_paper_frame}
 
 
 if __name__ == "__main__":
