@@ -45,6 +45,7 @@ extern "C" {
                                steps after a truncated list ran on the truncated list */
 #define CNNC_E_HIP      -4  /* a HIP runtime call failed */
 #define CNNC_E_STATE    -5  /* call out of order (e.g. score map before pyramid) */
+#define CNNC_E_TOOBIG   -6  /* input larger than the fixed scratch of cnnc_compact_noalloc (CNNC_NOALLOC_MAX_VALUES) */
 
 #define CNNC_WINDOW      12 /* side of the stage-1 window */
 #define CNNC_MAX_LEVELS  64
@@ -149,6 +150,23 @@ int cnnc_set_fused_stage1(cnnc_ctx *ctx, int on);
  * survivors of stage k - 1.  The count stays on the device; lists longer than max_survivors are
  * truncated and reported by cnnc_survivor_count / cnnc_merge_detections as CNNC_E_OVERFLOW. */
 int cnnc_compact_survivors(cnnc_ctx *ctx, int stage, float thr, void *stream);
+
+/* The compaction of cnnc_compact_survivors for callers that cannot allocate device memory: code running under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  No context: the caller passes the input and
+ * the outputs, and the per-workgroup counts the kernels need in between live in a fixed 32 KiB array inside the
+ * library's device image (one copy per GPU, held until the process ends).  The call makes no hipMalloc / hipFree and
+ * no allocating library call; it only launches kernels (no memset nodes), so it may be captured into a graph.
+ *   d_values: device, n float32 (n >= 0).  Lists, in ascending order, the positions i with d_values[i] > thr (fp32,
+ *   strict): d_index[k] = i, d_score[k] = d_values[i] for the first `cap` of them (device arrays of capacity cap),
+ *   and *d_count (device) = their untruncated number.  Enqueued on `stream` of the current device, not waited for.
+ *   Same kernels and same result, bit for bit, as cnnc_compact_survivors(1) on the same values.
+ * CNNC_E_TOOBIG when n > CNNC_NOALLOC_MAX_VALUES (nothing is launched); CNNC_E_INVAL for null pointers, negative
+ * sizes or a NaN threshold; CNNC_E_HIP when the array's address cannot be obtained or a launch fails.
+ * All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (different streams or threads)
+ * race and must be serialised by the caller.  Nothing in the array has to start at zero. */
+#define CNNC_NOALLOC_MAX_VALUES (1 << 24)
+int cnnc_compact_noalloc(const float *d_values, int64_t n, float thr, uint32_t *d_index, float *d_score, int32_t cap,
+                         int32_t *d_count, void *stream);
 
 /* k = 2 or 3: for every survivor of stage k - 1 cut its window rectangle
  * [x s, (x + 12) s) x [y s, (y + 12) s) from the frame given to cnnc_build_pyramid (which must

@@ -19,7 +19,7 @@ EXPORTS = [
     "cnnc_detect", "cnnc_detect_async", "cnnc_fetch_detections", "cnnc_get_pyramid", "cnnc_get_scoremap",
     "cnnc_get_survivors", "cnnc_get_stage_scores", "cnnc_survivor_count", "cnnc_set_timing",
     "cnnc_get_timings", "cnnc_set_eval_impl", "cnnc_executed_mfma", "cnnc_measure_peaks", "cnnc_last_error", "cnnc_version",
-    "cnnc_stage1_survivors", "cnnc_set_fused_stage1",
+    "cnnc_stage1_survivors", "cnnc_set_fused_stage1", "cnnc_compact_noalloc",
     "cnnc_scan_set_weights", "cnnc_scan_layout", "cnnc_scan_scoremap", "cnnc_get_scan_scoremap",
     "cnnc_select_set_weights", "cnnc_select_set_rule", "cnnc_select_run", "cnnc_select_fetch", "cnnc_select_merge", "cnnc_abi_sizes",
     "cnnc_pipe_create", "cnnc_pipe_destroy", "cnnc_pipe_set_params", "cnnc_pipe_frame_buffer", "cnnc_pipe_submit",
@@ -404,6 +404,15 @@ def cnnc_abi_sizes():
     out = (C.c_int32 * 7)()
     n = lib().cnnc_abi_sizes(out, C.c_int(7))
     return tuple(out[:n])
+
+
+def cnnc_compact_noalloc(values, n: int, thr: float, index, score, count, stream=None) -> int:
+    """cnnc_compact_noalloc on torch device tensors: values float32, index int32 / uint32 storage and score float32 of
+    equal capacity, count a one-element int32 tensor.  Returns the C return code (0, or a negative CNNC_E_*)."""
+    cap = min(int(index.numel()), int(score.numel()))
+    return lib().cnnc_compact_noalloc(C.c_void_p(values.data_ptr() if values is not None else 0), C.c_int64(n), C.c_float(thr),
+                                      C.c_void_p(index.data_ptr()), C.c_void_p(score.data_ptr()), C.c_int32(cap),
+                                      C.c_void_p(count.data_ptr()), _stream(stream))
 
 
 def cnnc_measure_peaks():

@@ -4,6 +4,8 @@
 // which every workgroup first adds up the counts of the workgroups before it (a separate scan
 // launch takes over for very long inputs); inside a workgroup each wave owns a contiguous run of
 // the input and ranks its survivors with ballots.
+#include <mutex>
+
 #include "cnnc_internal.h"
 
 namespace cnnc {
@@ -215,3 +217,55 @@ hipError_t launch_compact(const cnnc_ctx *c, const float *vals, const uint32_t *
 }
 
 }  // namespace cnnc
+
+// ---- the compaction for callers that must not allocate ------------------------------------------------------------
+// Per-workgroup counts live in a fixed array in the library's device image instead of a context's buffer.  Every GPU
+// holds its own copy at its own address; the name below is only the host-side handle of the symbol, the address that
+// kernels and copies may use comes from hipGetSymbolAddress with that GPU current.
+namespace {
+constexpr int kStaticMaxBlocks = CNNC_NOALLOC_MAX_VALUES / cnnc::kCompactPerBlock;
+static_assert(CNNC_NOALLOC_MAX_VALUES % cnnc::kCompactPerBlock == 0, "the limit is a whole number of workgroups");
+constexpr int kMaxDevices = 64;
+static __device__ __align__(256) __attribute__((used)) int32_t scratch[kStaticMaxBlocks];     // 32 KiB per GPU, held until the process ends
+
+std::mutex g_scratch_mutex;
+int32_t *g_scratch_ptr[kMaxDevices];       // device address of `scratch` on each GPU, looked up once
+
+// Device address of the scratch array on the current GPU (nullptr on failure).
+int32_t *scratch_on_current_device()
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess) return nullptr;
+        g_scratch_ptr[dev] = static_cast<int32_t *>(p);
+    }
+    return g_scratch_ptr[dev];
+}
+}  // namespace
+
+extern "C" int cnnc_compact_noalloc(const float *d_values, int64_t n, float thr, uint32_t *d_index, float *d_score,
+                                    int32_t cap, int32_t *d_count, void *stream)
+{
+    if (!d_count || n < 0 || cap < 0 || (n > 0 && !d_values) || (cap > 0 && (!d_index || !d_score)) || thr != thr)
+        return CNNC_E_INVAL;
+    if (n > CNNC_NOALLOC_MAX_VALUES) return CNNC_E_TOOBIG;
+    int32_t *blockcnt = scratch_on_current_device();
+    if (!blockcnt) return CNNC_E_HIP;
+    hipStream_t st = (hipStream_t)stream;
+    int nblocks = (int)((n + cnnc::kCompactPerBlock - 1) / cnnc::kCompactPerBlock);
+    if (nblocks < 1) nblocks = 1;           // an empty input still writes a zero count
+    // every entry of blockcnt[0, nblocks) is written by the count kernel before it is read: nothing to clear
+    hipLaunchKernelGGL(cnnc::compact_count_kernel, dim3(nblocks), dim3(cnnc::kCompactBlock), 0, st, d_values,
+                       (const int32_t *)nullptr, n, n, thr, blockcnt);
+    const bool scan_in_scatter = nblocks <= 4096;
+    if (!scan_in_scatter)
+        hipLaunchKernelGGL(cnnc::compact_scan_kernel, dim3(1), dim3(1024), 0, st, blockcnt, nblocks, d_count);
+    hipLaunchKernelGGL(cnnc::compact_scatter_kernel, dim3(nblocks), dim3(cnnc::kCompactBlock), 0, st, d_values,
+                       (const uint32_t *)nullptr, (const int32_t *)nullptr, n, n, thr, blockcnt, d_index, d_score, (int)cap,
+                       scan_in_scatter ? d_count : (int32_t *)nullptr);
+    return hipGetLastError() == hipSuccess ? CNNC_OK : CNNC_E_HIP;
+}
+
