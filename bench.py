@@ -69,6 +69,8 @@ def main():
     ap.add_argument("--no-ingest", action="store_true", help="skip the host-memory ingest leg (its frames overlap on several "
                     "streams, which stretches per-kernel durations in a profiler trace)")
     ap.add_argument("--no-paper-path", action="store_true", help="skip the legs in the paper's own geometry")
+    ap.add_argument("--chunks", type=int, default=2, help="cnnc_set_async_chunks value of the extra one-frame-at-a-time leg "
+                    "(asynchronous mode inside a frame; 0 skips the leg)")
     ap.add_argument("--eval-impl", type=int, default=None, help="cnnc_set_eval_impl value (default: the library's)")
     ap.add_argument("--fused-stage1", type=int, default=None, help="cnnc_set_fused_stage1 value (default: the library's)")
     a = ap.parse_args()
@@ -209,6 +211,17 @@ def main():
     elapsed = min(el_inflight, el_serial)
     fps = a.steps / elapsed
     latency_ms = el_serial / a.steps * 1e3
+    # asynchronous mode inside a frame: stage 1 of the next chunk of pyramid levels overlaps stages 2-3 of the last one
+    chunked = None
+    if a.chunks > 1:
+        c0.set_async_chunks(a.chunks)
+        c0.set_params(cfg["min_face"], cfg["scale_step"], tr.thr)
+        el_chunked, n_det_chunked = timed_leg(run_serial, 4)
+        assert n_det_chunked == n_det
+        chunked = {"chunks": a.chunks, "ms_per_frame_one_at_a_time": el_chunked / a.steps * 1e3}
+        c0.set_async_chunks(1)
+        c0.set_params(cfg["min_face"], cfg["scale_step"], tr.thr)
+        run_serial(4)
     # a stream: every frame on its own, to show how much the time depends on the content of the frame
     per_frame = None
     if len(dev_frames) > 1:
@@ -329,6 +342,7 @@ def main():
         "stage1_windows_per_s": n_windows / (ms["stage1"] * 1e-3) if ms["stage1"] > 0 else None,
         "latency_ms_single_frame": latency_ms,
         "latency_ms_per_frame_of_stream": per_frame,
+        "asynchronous_mode_inside_a_frame": chunked,
         "paper_geometry": paper,
         "ingest_from_pinned_host_memory": ingest,
         "sum_of_kernel_ms": sum(v for k, v in ms.items() if not k.endswith("_conv") and k not in ("scan", "select")),

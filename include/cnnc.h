@@ -190,6 +190,19 @@ int cnnc_detect(cnnc_ctx *ctx, const uint8_t *d_frame, int w, int h, int pitch, 
 int cnnc_detect_async(cnnc_ctx *ctx, const uint8_t *d_frame, int w, int h, int pitch, void *stream);
 int cnnc_fetch_detections(cnnc_ctx *ctx, cnnc_det *out, int cap, int *n_out);
 
+/* Asynchronous mode inside a frame (Section 3.4: the first stage moves on to the next pyramid level while the regions
+ * it has found are still being analysed).  chunks = 1 (default): cnnc_detect / cnnc_detect_async run every step on
+ * the caller's stream.  chunks = 2..8: the pyramid levels are cut into that many runs of consecutive levels with
+ * about equal numbers of windows (fewer when the frame has fewer levels); stage 1 and its compaction go chunk by
+ * chunk on the caller's stream, stages 2 and 3 of a chunk start on a second stream as soon as that chunk's survivors
+ * are listed, ordered by HIP events only; the merge follows the last chunk and the caller's stream then waits for it,
+ * so the call keeps its contract (work enqueued, cnnc_fetch_detections waits).  Survivor lists and detections are
+ * exactly those of chunks = 1.  The second stream belongs to the context (default priority).  On one GPU whose later
+ * stages already fill the chip the overlap buys less than the extra launches and cross-stream waits cost, so 1 is
+ * the default; the mode is there for cascades whose first stage dominates, as in the paper.
+ * Ignored (one stream) with cnnc_set_eval_impl(0) or cnnc_set_fused_stage1(1), and inside cnnc_pipe graphs. */
+int cnnc_set_async_chunks(cnnc_ctx *ctx, int chunks);
+
 /* Read-only device views for tests and callers that chain their own kernels. */
 int cnnc_get_pyramid(cnnc_ctx *ctx, const uint8_t **d_pyramid, int64_t *n_bytes);
 int cnnc_get_scoremap(cnnc_ctx *ctx, const float **d_scores, int64_t *n_windows);

@@ -19,7 +19,7 @@ EXPORTS = [
     "cnnc_detect", "cnnc_detect_async", "cnnc_fetch_detections", "cnnc_get_pyramid", "cnnc_get_scoremap",
     "cnnc_get_survivors", "cnnc_get_stage_scores", "cnnc_survivor_count", "cnnc_set_timing",
     "cnnc_get_timings", "cnnc_set_eval_impl", "cnnc_executed_mfma", "cnnc_measure_peaks", "cnnc_last_error", "cnnc_version",
-    "cnnc_stage1_survivors", "cnnc_set_fused_stage1", "cnnc_compact_noalloc",
+    "cnnc_stage1_survivors", "cnnc_set_fused_stage1", "cnnc_set_async_chunks", "cnnc_compact_noalloc",
     "cnnc_scan_set_weights", "cnnc_scan_layout", "cnnc_scan_scoremap", "cnnc_get_scan_scoremap",
     "cnnc_select_set_weights", "cnnc_select_set_rule", "cnnc_select_run", "cnnc_select_fetch", "cnnc_select_merge", "cnnc_abi_sizes",
     "cnnc_pipe_create", "cnnc_pipe_destroy", "cnnc_pipe_set_params", "cnnc_pipe_frame_buffer", "cnnc_pipe_submit",
@@ -192,6 +192,9 @@ class Context:
 
     def stage1_survivors(self, thr: float, stream=None):
         self._check(lib().cnnc_stage1_survivors(self._h, C.c_float(thr), _stream(stream)))
+
+    def set_async_chunks(self, chunks: int):
+        self._check(lib().cnnc_set_async_chunks(self._h, C.c_int(chunks)))
 
     def set_fused_stage1(self, on: bool):
         self._check(lib().cnnc_set_fused_stage1(self._h, C.c_int(1 if on else 0)))
@@ -425,7 +428,7 @@ def cnnc_measure_peaks():
 
 
 # The C spelling of every context call: cnnc_<name>(ctx, ...) is Context.<name>(...).
-_CTX_CALLS = ("set_params", "pyramid_layout", "build_pyramid", "stage1_scoremap", "stage1_survivors", "set_fused_stage1",
+_CTX_CALLS = ("set_params", "pyramid_layout", "build_pyramid", "stage1_scoremap", "stage1_survivors", "set_fused_stage1", "set_async_chunks",
               "compact_survivors", "eval_stage", "merge_detections", "detect", "detect_async", "fetch_detections",
               "get_pyramid", "get_scoremap", "get_survivors", "get_stage_scores", "survivor_count", "set_eval_impl",
               "executed_mfma", "set_timing", "get_timings", "scan_set_weights", "scan_layout", "scan_scoremap",

@@ -127,8 +127,10 @@ int prepare_layout(cnnc_ctx *c, int w, int h)
         return fail(c, CNNC_E_INVAL, "frame has no pyramid level at these parameters");
 
     std::vector<uint32_t> taps, tiles_pyr, tiles_s1;
+    std::vector<int> s1_tile_of_level(lv.size() + 1, 0);
     for (size_t l = 0; l < lv.size(); ++l) {
         const LevelDev &L = lv[l];
+        s1_tile_of_level[l] = (int)tiles_s1.size();
         const size_t base = taps.size();
         taps.resize(base + L.w + L.h);
         axis_taps(L.w, w, L.scale, taps.data() + base);
@@ -137,6 +139,19 @@ int prepare_layout(cnnc_ctx *c, int w, int h)
             for (int tx = 0; tx * kPyrTileW < L.w; ++tx) tiles_pyr.push_back(pack_tile((int)l, ty, tx));
         for (int ty = 0; ty * kS1TileH < L.oh; ++ty)
             for (int tx = 0; tx * kS1TileW < L.ow; ++tx) tiles_s1.push_back(pack_tile((int)l, ty, tx));
+    }
+
+    s1_tile_of_level[lv.size()] = (int)tiles_s1.size();
+    // Chunks of the asynchronous mode: consecutive levels, cut where the running number of windows passes k / K of all
+    {
+        const int K = std::max(1, std::min(std::min(c->async_chunks, kMaxLevelChunks), (int)lv.size()));
+        int k = 0;
+        c->chunk_level[0] = 0;
+        for (size_t l = 1; l < lv.size() && k + 1 < K; ++l)
+            if ((int64_t)lv[l].score_off * K >= (int64_t)(k + 1) * n_windows) c->chunk_level[++k] = (int)l;
+        c->n_chunks = k + 1;
+        c->chunk_level[c->n_chunks] = (int)lv.size();
+        for (int q = 0; q <= c->n_chunks; ++q) c->chunk_tile[q] = s1_tile_of_level[c->chunk_level[q]];
     }
 
     // buffers may be in use by work still queued on the last stream
@@ -154,9 +169,11 @@ int prepare_layout(cnnc_ctx *c, int w, int h)
     const int64_t nblocks = std::max<int64_t>(std::max<int64_t>((n_windows + kCompactPerBlock - 1) / kCompactPerBlock,
                                                                 (c->max_surv + kCompactPerBlock - 1) / kCompactPerBlock),
                                               (n_words + kCompactBlock - 1) / kCompactBlock) + 1;
-    int64_t cap_blocks = c->cap_blocks;
-    if ((rc = ensure(c, c->d_blockcnt, cap_blocks, nblocks))) return rc;
-    c->cap_blocks = (int32_t)cap_blocks;
+    for (int k = 0; k < 3; ++k) {            // one per stage: their compactions may run on different streams
+        int64_t cap_blocks = c->cap_blocks;
+        if ((rc = ensure(c, c->d_blockcnt[k], cap_blocks, nblocks))) return rc;
+        if (k == 2) c->cap_blocks = (int32_t)cap_blocks;
+    }
 
     HIP_TRY(c, hipMemcpy(c->d_levels, lv.data(), sizeof(LevelDev) * lv.size(), hipMemcpyHostToDevice));
     HIP_TRY(c, hipMemcpy(c->d_taps, taps.data(), sizeof(uint32_t) * taps.size(), hipMemcpyHostToDevice));
@@ -302,6 +319,10 @@ int cnnc_create(cnnc_ctx **out, const cnnc_stage_desc stages[3], int max_w, int 
     }
     for (int s = 0; s < 2; ++s)
         if (hipMalloc((void **)&c->d_eval[s], sizeof(float) * (size_t)max_survivors) != hipSuccess) return bail(CNNC_E_NOMEM);
+    if (hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking) != hipSuccess) return bail(CNNC_E_HIP);
+    for (int k = 0; k < kMaxLevelChunks; ++k)
+        if (hipEventCreateWithFlags(&c->ev_s1[k], hipEventDisableTiming) != hipSuccess) return bail(CNNC_E_HIP);
+    if (hipEventCreateWithFlags(&c->ev_done, hipEventDisableTiming) != hipSuccess) return bail(CNNC_E_HIP);
     if (hipMalloc((void **)&c->d_cnt, sizeof(Counters)) != hipSuccess) return bail(CNNC_E_NOMEM);
     if (hipMemset(c->d_cnt, 0, sizeof(Counters)) != hipSuccess) return bail(CNNC_E_HIP);
     if (hipHostMalloc((void **)&c->h_cnt, sizeof(Counters), hipHostMallocDefault) != hipSuccess) return bail(CNNC_E_NOMEM);
@@ -324,10 +345,15 @@ int cnnc_destroy(cnnc_ctx *c)
     scan_release(c);
     select_release(c);
     (void)hipFree(c->d_levels); (void)hipFree(c->d_taps); (void)hipFree(c->d_tiles_pyr); (void)hipFree(c->d_tiles_s1);
-    (void)hipFree(c->d_pyr); (void)hipFree(c->d_score1); (void)hipFree(c->d_mask1); (void)hipFree(c->d_blockcnt); (void)hipFree(c->d_cnt);
+    (void)hipFree(c->d_pyr); (void)hipFree(c->d_score1); (void)hipFree(c->d_mask1); (void)hipFree(c->d_cnt);
+    for (int k = 0; k < 3; ++k) (void)hipFree(c->d_blockcnt[k]);
     (void)hipFree(c->d_merge_ws); (void)hipFree(c->d_det);
     if (c->h_cnt) (void)hipHostFree(c->h_cnt);
     if (c->h_det) (void)hipHostFree(c->h_det);
+    if (c->side) (void)hipStreamDestroy(c->side);
+    for (int k = 0; k < kMaxLevelChunks; ++k)
+        if (c->ev_s1[k]) (void)hipEventDestroy(c->ev_s1[k]);
+    if (c->ev_done) (void)hipEventDestroy(c->ev_done);
     for (auto &t : c->timers) {
         for (auto e : t.begin) (void)hipEventDestroy(e);
         for (auto e : t.end) (void)hipEventDestroy(e);
@@ -400,7 +426,7 @@ int cnnc_stage1_scoremap(cnnc_ctx *c, void *stream)
     c->last_stream = st;
     {
         Timed t(c, CNNC_T_STAGE1, st);
-        HIP_TRY(c, launch_stage1(c, st));
+        HIP_TRY(c, launch_stage1(c, 0, c->n_tiles_s1, st));
     }
     c->progress = DONE_PYR | DONE_S1;
     return CNNC_OK;
@@ -443,12 +469,16 @@ int cnnc_compact_survivors(cnnc_ctx *c, int stage, float thr, void *stream)
     c->last_stream = st;
     {
         Timed t(c, CNNC_T_COMPACT1 + 2 * (stage - 1), st);
-        if (stage == 1)
-            HIP_TRY(c, launch_compact(c, c->d_score1, nullptr, nullptr, c->n_windows, thr, c->d_idx[0], c->d_sc[0],
-                                      &c->d_cnt->n[0], st));
-        else
-            HIP_TRY(c, launch_compact(c, c->d_eval[stage - 2], c->d_idx[stage - 2], &c->d_cnt->n[stage - 2], 0, thr,
-                                      c->d_idx[stage - 1], c->d_sc[stage - 1], &c->d_cnt->n[stage - 1], st));
+        CompactJob job{};
+        job.slot = stage - 1; job.thr = thr;
+        job.out_idx = c->d_idx[stage - 1]; job.out_sc = c->d_sc[stage - 1]; job.d_count = &c->d_cnt->n[stage - 1];
+        if (stage == 1) {
+            job.vals = c->d_score1; job.n_literal = c->n_windows;
+        } else {
+            job.vals = c->d_eval[stage - 2]; job.src_idx = c->d_idx[stage - 2];
+            job.d_begin = &c->d_cnt->end[stage - 2][0]; job.d_end = &c->d_cnt->n[stage - 2];     // end[.][0] is always 0
+        }
+        HIP_TRY(c, launch_compact(c, job, st));
     }
     const int done[3] = {DONE_C1, DONE_C2, DONE_C3};
     const int keep[3] = {DONE_PYR | DONE_S1, DONE_PYR | DONE_S1 | DONE_C1 | DONE_E2,
@@ -466,8 +496,9 @@ int cnnc_eval_stage(cnnc_ctx *c, int k, void *stream)
     c->last_stream = st;
     {
         Timed t(c, k == 2 ? CNNC_T_STAGE2 : CNNC_T_STAGE3, st);
-        if (k == 2) HIP_TRY(c, c->eval_impl ? launch_eval2_mfma(c, st) : launch_eval2(c, st));
-        else HIP_TRY(c, c->eval_impl ? launch_eval3_mfma(c, st) : launch_eval3(c, st));
+        const ListRange all{&c->d_cnt->end[k - 2][0], &c->d_cnt->n[k - 2]};                      // end[.][0] is always 0
+        if (k == 2) HIP_TRY(c, c->eval_impl ? launch_eval2_mfma(c, all, st) : launch_eval2(c, all, st));
+        else HIP_TRY(c, c->eval_impl ? launch_eval3_mfma(c, all, st) : launch_eval3(c, all, st));
     }
     const int keep = k == 2 ? (DONE_PYR | DONE_S1 | DONE_C1) : (DONE_PYR | DONE_S1 | DONE_C1 | DONE_E2 | DONE_C2);
     c->progress = (c->progress & keep) | (k == 2 ? DONE_E2 : DONE_E3);
@@ -495,10 +526,90 @@ int cnnc_merge_detections(cnnc_ctx *c, cnnc_det *out, int cap, int *n_out, void 
     return fetch(c, out, cap, n_out);
 }
 
+// The path in chunks of pyramid levels (paper, Section 3.4, asynchronous mode: the first stage moves on to the next
+// level while the regions it has found are still being analysed).  Stage 1 and its compaction run chunk by chunk on
+// the caller's stream and append to the stage-1 list; stages 2 and 3 of a chunk wait only for that chunk's event and
+// run on the context's own stream; the lists grow in chunk order, so they are exactly the lists of the one-stream
+// path.  No host wait anywhere: the caller's stream finally waits for the event behind the merge.  (A third stream
+// for stage 3 was measured: every extra cross-stream dependency costs more than the overlap it buys.)
+static int detect_chunked(cnnc_ctx *c, hipStream_t sa)
+{
+    Counters *k = c->d_cnt;
+    const hipStream_t sb = c->side, sc = c->side;       // stages 2 and 3 share the context's stream (see below)
+    const int K = c->n_chunks;
+    for (int q = 0; q < K; ++q) {
+        const bool last = q + 1 == K;
+        const LevelDev &L0 = c->levels[c->chunk_level[q]];
+        const int64_t off = L0.score_off;
+        const int64_t len = (last ? c->n_windows : (int64_t)c->levels[c->chunk_level[q + 1]].score_off) - off;
+        {
+            Timed t(c, CNNC_T_STAGE1, sa);
+            HIP_TRY(c, launch_stage1(c, c->chunk_tile[q], c->chunk_tile[q + 1], sa));
+        }
+        {
+            Timed t(c, CNNC_T_COMPACT1, sa);
+            CompactJob job{};
+            job.slot = 0; job.vals = c->d_score1 + off; job.idx_base = (uint32_t)off; job.n_literal = len;
+            job.thr = c->params.thr[0]; job.out_idx = c->d_idx[0]; job.out_sc = c->d_sc[0];
+            job.d_base = &k->end[0][q]; job.d_count = &k->end[0][q + 1]; job.d_count2 = last ? &k->n[0] : nullptr;
+            HIP_TRY(c, launch_compact(c, job, sa));
+        }
+        HIP_TRY(c, hipEventRecord(c->ev_s1[q], sa));
+        HIP_TRY(c, hipStreamWaitEvent(sb, c->ev_s1[q], 0));
+        const ListRange r1{&k->end[0][q], &k->end[0][q + 1]};
+        {
+            Timed t(c, CNNC_T_STAGE2, sb);
+            HIP_TRY(c, launch_eval2_mfma(c, r1, sb));
+        }
+        {
+            Timed t(c, CNNC_T_COMPACT2, sb);
+            CompactJob job{};
+            job.slot = 1; job.vals = c->d_eval[0]; job.src_idx = c->d_idx[0]; job.d_begin = r1.d_begin; job.d_end = r1.d_end;
+            job.thr = c->params.thr[1]; job.out_idx = c->d_idx[1]; job.out_sc = c->d_sc[1];
+            job.d_base = &k->end[1][q]; job.d_count = &k->end[1][q + 1]; job.d_count2 = last ? &k->n[1] : nullptr;
+            HIP_TRY(c, launch_compact(c, job, sb));
+        }
+        const ListRange r2{&k->end[1][q], &k->end[1][q + 1]};
+        {
+            Timed t(c, CNNC_T_STAGE3, sc);
+            HIP_TRY(c, launch_eval3_mfma(c, r2, sc));
+        }
+        {
+            Timed t(c, CNNC_T_COMPACT3, sc);
+            CompactJob job{};
+            job.slot = 2; job.vals = c->d_eval[1]; job.src_idx = c->d_idx[1]; job.d_begin = r2.d_begin; job.d_end = r2.d_end;
+            job.thr = c->params.thr[2]; job.out_idx = c->d_idx[2]; job.out_sc = c->d_sc[2];
+            job.d_base = &k->end[2][q]; job.d_count = &k->end[2][q + 1]; job.d_count2 = last ? &k->n[2] : nullptr;
+            HIP_TRY(c, launch_compact(c, job, sc));
+        }
+    }
+    c->progress = DONE_PYR | DONE_S1 | DONE_C1 | DONE_E2 | DONE_C2 | DONE_E3 | DONE_C3;
+    {
+        Timed t(c, CNNC_T_MERGE, sc);
+        HIP_TRY(c, launch_merge(c, sc));
+    }
+    c->progress |= DONE_MERGE;
+    int rc = enqueue_readback(c, sc);
+    if (rc) return rc;
+    HIP_TRY(c, hipEventRecord(c->ev_done, sc));
+    HIP_TRY(c, hipStreamWaitEvent(sa, c->ev_done, 0));
+    c->last_stream = sa;
+    return CNNC_OK;
+}
+
+int cnnc_set_async_chunks(cnnc_ctx *c, int chunks)
+{
+    if (!c) return CNNC_E_INVAL;
+    if (chunks < 1 || chunks > kMaxLevelChunks) return fail(c, CNNC_E_INVAL, "chunks must be 1..8");
+    if (chunks != c->async_chunks) { c->async_chunks = chunks; c->layout_valid = false; c->progress = 0; }
+    return CNNC_OK;
+}
+
 int cnnc_detect_async(cnnc_ctx *c, const uint8_t *d_frame, int w, int h, int pitch, void *stream)
 {
     int rc;
     if ((rc = cnnc_build_pyramid(c, d_frame, w, h, pitch, stream))) return rc;
+    if (c->n_chunks > 1 && c->eval_impl != 0 && !c->fused_stage1) return detect_chunked(c, (hipStream_t)stream);
     if (c->fused_stage1) {
         if ((rc = cnnc_stage1_survivors(c, c->params.thr[0], stream))) return rc;
     } else {

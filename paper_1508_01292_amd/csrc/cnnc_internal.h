@@ -44,9 +44,20 @@ struct LevelDev {
     int32_t words_per_row; // ceil(ow / 32)
 };
 
+// A frame may go through the stages in chunks of pyramid levels (asynchronous mode): at most this many.
+constexpr int kMaxLevelChunks = 8;
+
 // Small device-resident counters.
 struct Counters {
     int32_t n[4];          // survivors of stage 1, 2, 3 and merged detections (untruncated counts)
+    // end[s][k]: length of the stage-(s+1) survivor list once chunk k - 1 has been appended; end[s][0] stays 0, so
+    // [end[s][k], end[s][k+1]) is the part of the list that chunk k added
+    int32_t end[3][kMaxLevelChunks + 1];
+};
+
+// A range [*d_begin, *d_end) of a survivor list, both bounds living on the device.
+struct ListRange {
+    const int32_t *d_begin, *d_end;
 };
 
 // Completed steps of the current frame (cnnc_ctx::progress), for the call-order checks.
@@ -138,7 +149,7 @@ struct cnnc_ctx {
     uint32_t *d_idx[3] = {nullptr, nullptr, nullptr};
     float *d_sc[3] = {nullptr, nullptr, nullptr};
     float *d_eval[2] = {nullptr, nullptr};   // scores of stage 2 / 3, aligned with the previous list
-    int32_t *d_blockcnt = nullptr;           // compaction: per-block counts and offsets
+    int32_t *d_blockcnt[3] = {nullptr, nullptr, nullptr};   // compaction of stage 1 / 2 / 3: per-block counts and offsets
     int32_t cap_blocks = 0;
     cnnc::Counters *d_cnt = nullptr;
     cnnc::Counters *h_cnt = nullptr;         // pinned
@@ -155,6 +166,15 @@ struct cnnc_ctx {
     int progress = 0;                        // bit mask of completed steps for CNNC_E_STATE checks
     hipStream_t last_stream = nullptr;
 
+    // asynchronous mode inside a frame: chunks of pyramid levels, stage 1 of a chunk on the caller's stream while the
+    // later stages of earlier chunks run on a stream of the context, ordered by events only
+    int async_chunks = 1;                    // 1: the whole frame on the caller's stream
+    int n_chunks = 1;                        // chunks of the current layout (<= async_chunks, <= levels)
+    int chunk_level[cnnc::kMaxLevelChunks + 1] = {0};   // first level of each chunk, then n_levels
+    int chunk_tile[cnnc::kMaxLevelChunks + 1] = {0};    // first stage-1 tile of each chunk, then n_tiles_s1
+    hipStream_t side = nullptr;
+    hipEvent_t ev_s1[cnnc::kMaxLevelChunks] = {nullptr}, ev_done = nullptr;
+
     bool timing = false;
     cnnc::StepTimer timers[CNNC_T_COUNT];
 };
@@ -163,21 +183,33 @@ namespace cnnc {
 
 // Kernel launchers (one translation unit each).  All enqueue on `st` and return the launch status.
 hipError_t launch_pyramid(const cnnc_ctx *c, hipStream_t st);
-hipError_t launch_stage1(const cnnc_ctx *c, hipStream_t st);
+// Stage 1 over tiles [tile_begin, tile_end) of the (level, tile) table (levels are contiguous in it).
+hipError_t launch_stage1(const cnnc_ctx *c, int tile_begin, int tile_end, hipStream_t st);
 // Stage 1 that keeps only what passes `thr`: one bit per window in d_mask1 and the score of each passing window
 // at its place in d_score1 (all other entries of d_score1 are left as they were).
 hipError_t launch_stage1_emit(const cnnc_ctx *c, float thr, hipStream_t st);
 // Ordered survivor list from d_mask1 / d_score1.
 hipError_t launch_compact_mask(const cnnc_ctx *c, uint32_t *out_idx, float *out_sc, int32_t *d_count, hipStream_t st);
-// Compaction of `vals[0 .. n)`; n = *d_n clamped to n_max if d_n != nullptr, else n_literal.
-// src_idx == nullptr: the position itself is the index written.
-hipError_t launch_compact(const cnnc_ctx *c, const float *vals, const uint32_t *src_idx, const int32_t *d_n,
-                          int64_t n_literal, float thr, uint32_t *out_idx, float *out_sc, int32_t *d_count,
-                          hipStream_t st);
-hipError_t launch_eval2(const cnnc_ctx *c, hipStream_t st);
-hipError_t launch_eval3(const cnnc_ctx *c, hipStream_t st);
-hipError_t launch_eval3_mfma(cnnc_ctx *c, hipStream_t st);
-hipError_t launch_eval2_mfma(cnnc_ctx *c, hipStream_t st);
+// One ordered compaction: the values above `thr` of a source, appended to an output list.
+struct CompactJob {
+    int slot;                     // which of the context's per-block count buffers to use (0..2: one per stage)
+    const float *vals;            // source values
+    const uint32_t *src_idx;      // index written for source element e: src_idx[e], or idx_base + e when nullptr
+    uint32_t idx_base;
+    const int32_t *d_begin, *d_end;   // source = elements [*d_begin, *d_end) clamped to max_surv; d_end == nullptr:
+    int64_t n_literal;                // the first n_literal elements
+    float thr;
+    uint32_t *out_idx;            // output list (capacity max_surv) ...
+    float *out_sc;
+    const int32_t *d_base;        // ... which already holds *d_base entries (nullptr: none)
+    int32_t *d_count, *d_count2;  // receive the new length of the list (d_count2 may be nullptr)
+};
+hipError_t launch_compact(const cnnc_ctx *c, const CompactJob &job, hipStream_t st);
+// Stage 2 / 3 on the entries [*r.d_begin, *r.d_end) of the previous stage's survivor list.
+hipError_t launch_eval2(const cnnc_ctx *c, ListRange r, hipStream_t st);
+hipError_t launch_eval3(const cnnc_ctx *c, ListRange r, hipStream_t st);
+hipError_t launch_eval3_mfma(cnnc_ctx *c, ListRange r, hipStream_t st);
+hipError_t launch_eval2_mfma(cnnc_ctx *c, ListRange r, hipStream_t st);
 
 // Brackets the launches made during its lifetime with a pair of events on the stream when the context's
 // timing is on; the pair is read back by cnnc_get_timings.

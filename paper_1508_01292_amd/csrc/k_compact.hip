@@ -15,20 +15,26 @@ constexpr int kWaves = kCompactBlock / 64;
 constexpr int kPerWave = kCompactPerBlock / kWaves;   // contiguous values per wave
 constexpr int kIters = kPerWave / 64;
 
-__device__ __forceinline__ int64_t source_count(const int32_t *d_n, int64_t n_literal, int64_t n_max)
+// The part of the source this call covers: elements [begin, begin + n).  With device counters (d_end != nullptr) it
+// is the list range [*d_begin, *d_end) clamped to the list's capacity n_max; otherwise the first n_literal values.
+struct SourceRange { int64_t begin, n; };
+__device__ __forceinline__ SourceRange source_range(const int32_t *d_begin, const int32_t *d_end, int64_t n_literal, int64_t n_max)
 {
-    if (d_n == nullptr) return n_literal;
-    const int64_t n = *d_n;
-    return n < n_max ? n : n_max;
+    if (d_end == nullptr) return {0, n_literal};
+    const int64_t b = d_begin ? min((int64_t)*d_begin, n_max) : 0, e = min((int64_t)*d_end, n_max);
+    return {b, e > b ? e - b : 0};
 }
 }  // namespace
 
 __global__ __launch_bounds__(kCompactBlock)
-void compact_count_kernel(const float *__restrict__ vals, const int32_t *__restrict__ d_n, int64_t n_literal,
-                          int64_t n_max, float thr, int32_t *__restrict__ blockcnt)
+void compact_count_kernel(const float *__restrict__ vals, const int32_t *__restrict__ d_begin,
+                          const int32_t *__restrict__ d_end, int64_t n_literal, int64_t n_max, float thr,
+                          int32_t *__restrict__ blockcnt)
 {
     __shared__ int wsum[kWaves];
-    const int64_t n = source_count(d_n, n_literal, n_max);
+    const SourceRange R = source_range(d_begin, d_end, n_literal, n_max);
+    const int64_t n = R.n;
+    vals += R.begin;
     const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
     const int64_t base = (int64_t)blockIdx.x * kCompactPerBlock + (int64_t)wave * kPerWave;
     int cnt = 0;
@@ -47,9 +53,10 @@ void compact_count_kernel(const float *__restrict__ vals, const int32_t *__restr
 }
 
 // Exclusive scan of the per-workgroup counts (one workgroup, chunks of 1024 with a carry) and the
-// total into *d_count.
+// total, plus the entries already in the output list (*d_base, if given), into *d_count (and *d_count2).
 __global__ __launch_bounds__(1024)
-void compact_scan_kernel(int32_t *__restrict__ blockcnt, int nblocks, int32_t *__restrict__ d_count)
+void compact_scan_kernel(int32_t *__restrict__ blockcnt, int nblocks, const int32_t *__restrict__ d_base,
+                         int32_t *__restrict__ d_count, int32_t *__restrict__ d_count2)
 {
     __shared__ int wtot[16];
     __shared__ int carry_s;
@@ -77,17 +84,27 @@ void compact_scan_kernel(int32_t *__restrict__ blockcnt, int nblocks, int32_t *_
         if (threadIdx.x == 0) carry_s = carry + total;
         __syncthreads();
     }
-    if (threadIdx.x == 0) *d_count = carry_s;
+    if (threadIdx.x == 0) {
+        const int total = carry_s + (d_base ? *d_base : 0);
+        *d_count = total;
+        if (d_count2) *d_count2 = total;
+    }
 }
 
 __global__ __launch_bounds__(kCompactBlock)
-void compact_scatter_kernel(const float *__restrict__ vals, const uint32_t *__restrict__ src_idx,
-                            const int32_t *__restrict__ d_n, int64_t n_literal, int64_t n_max, float thr,
-                            const int32_t *__restrict__ blockoff, uint32_t *__restrict__ out_idx,
-                            float *__restrict__ out_sc, int cap, int32_t *__restrict__ d_count_if_unscanned)
+void compact_scatter_kernel(const float *__restrict__ vals, const uint32_t *__restrict__ src_idx, uint32_t idx_base,
+                            const int32_t *__restrict__ d_begin, const int32_t *__restrict__ d_end, int64_t n_literal,
+                            int64_t n_max, float thr, const int32_t *__restrict__ blockoff,
+                            uint32_t *__restrict__ out_idx, float *__restrict__ out_sc, int cap,
+                            const int32_t *__restrict__ d_base, int32_t *__restrict__ d_count_if_unscanned,
+                            int32_t *__restrict__ d_count2)
 {
     __shared__ int wsum[kWaves], wpre[kWaves];
-    const int64_t n = source_count(d_n, n_literal, n_max);
+    const SourceRange R = source_range(d_begin, d_end, n_literal, n_max);
+    const int64_t n = R.n;
+    vals += R.begin;
+    if (src_idx) src_idx += R.begin;
+    const int base_out = d_base ? *d_base : 0;       // entries already in the output list (appending a later chunk)
     const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
     const int64_t base = (int64_t)blockIdx.x * kCompactPerBlock + (int64_t)wave * kPerWave;
     float v[kIters];
@@ -112,13 +129,17 @@ void compact_scatter_kernel(const float *__restrict__ vals, const uint32_t *__re
         pos = 0;
         int own = 0;
         for (int w = 0; w < kWaves; ++w) { pos += wpre[w]; own += wsum[w]; }
-        if (blockIdx.x == gridDim.x - 1 && threadIdx.x == 0) *d_count_if_unscanned = pos + own;
+        if (blockIdx.x == gridDim.x - 1 && threadIdx.x == 0) {
+            *d_count_if_unscanned = base_out + pos + own;
+            if (d_count2) *d_count2 = base_out + pos + own;
+        }
     } else {
         if (lane == 0) wsum[wave] = cnt;
         __syncthreads();
         pos = blockoff[blockIdx.x];
     }
     for (int w = 0; w < wave; ++w) pos += wsum[w];
+    pos += base_out;
 #pragma unroll
     for (int it = 0; it < kIters; ++it) {
         const uint64_t m = mask[it];
@@ -126,7 +147,7 @@ void compact_scatter_kernel(const float *__restrict__ vals, const uint32_t *__re
             const int p = pos + __popcll(m & ((1ull << lane) - 1ull));
             if (p < cap) {
                 const int64_t e = base + it * 64 + lane;
-                out_idx[p] = src_idx ? src_idx[e] : (uint32_t)e;
+                out_idx[p] = src_idx ? src_idx[e] : idx_base + (uint32_t)e;
                 out_sc[p] = v[it];
             }
         }
@@ -190,29 +211,31 @@ hipError_t launch_compact_mask(const cnnc_ctx *c, uint32_t *out_idx, float *out_
 {
     const int n_words = (int)c->n_words;
     const int nblocks = (n_words + kCompactBlock - 1) / kCompactBlock;
-    hipLaunchKernelGGL(mask_count_kernel, dim3(nblocks), dim3(kCompactBlock), 0, st, c->d_mask1, n_words, c->d_blockcnt);
-    hipLaunchKernelGGL(compact_scan_kernel, dim3(1), dim3(1024), 0, st, c->d_blockcnt, nblocks, d_count);
+    hipLaunchKernelGGL(mask_count_kernel, dim3(nblocks), dim3(kCompactBlock), 0, st, c->d_mask1, n_words, c->d_blockcnt[0]);
+    hipLaunchKernelGGL(compact_scan_kernel, dim3(1), dim3(1024), 0, st, c->d_blockcnt[0], nblocks, (const int32_t *)nullptr,
+                       d_count, (int32_t *)nullptr);
     hipLaunchKernelGGL(mask_scatter_kernel, dim3(nblocks), dim3(kCompactBlock), 0, st, c->d_mask1, n_words, c->d_score1,
-                       c->d_levels, c->n_levels, c->d_blockcnt, out_idx, out_sc, c->max_surv);
+                       c->d_levels, c->n_levels, c->d_blockcnt[0], out_idx, out_sc, c->max_surv);
     return hipGetLastError();
 }
 
-hipError_t launch_compact(const cnnc_ctx *c, const float *vals, const uint32_t *src_idx, const int32_t *d_n,
-                          int64_t n_literal, float thr, uint32_t *out_idx, float *out_sc, int32_t *d_count,
-                          hipStream_t st)
+hipError_t launch_compact(const cnnc_ctx *c, const CompactJob &job, hipStream_t st)
 {
-    const int64_t n_max = d_n ? (int64_t)c->max_surv : n_literal;
+    const int64_t n_max = job.d_end ? (int64_t)c->max_surv : job.n_literal;
     int nblocks = (int)((n_max + kCompactPerBlock - 1) / kCompactPerBlock);
     if (nblocks < 1) nblocks = 1;   // an empty input still has to write a zero count
-    hipLaunchKernelGGL(compact_count_kernel, dim3(nblocks), dim3(kCompactBlock), 0, st, vals, d_n, n_literal, n_max,
-                       thr, c->d_blockcnt);
+    int32_t *blockcnt = c->d_blockcnt[job.slot];
+    hipLaunchKernelGGL(compact_count_kernel, dim3(nblocks), dim3(kCompactBlock), 0, st, job.vals, job.d_begin, job.d_end,
+                       job.n_literal, n_max, job.thr, blockcnt);
     // Up to a few thousand workgroups each scatter workgroup adds up the counts before it by itself, which saves
     // the launch of the scan in between; beyond that the scan kernel is cheaper than the repeated sums.
     const bool scan_in_scatter = nblocks <= 4096;
-    if (!scan_in_scatter) hipLaunchKernelGGL(compact_scan_kernel, dim3(1), dim3(1024), 0, st, c->d_blockcnt, nblocks, d_count);
-    hipLaunchKernelGGL(compact_scatter_kernel, dim3(nblocks), dim3(kCompactBlock), 0, st, vals, src_idx, d_n,
-                       n_literal, n_max, thr, c->d_blockcnt, out_idx, out_sc, c->max_surv,
-                       scan_in_scatter ? d_count : (int32_t *)nullptr);
+    if (!scan_in_scatter)
+        hipLaunchKernelGGL(compact_scan_kernel, dim3(1), dim3(1024), 0, st, blockcnt, nblocks, job.d_base, job.d_count, job.d_count2);
+    hipLaunchKernelGGL(compact_scatter_kernel, dim3(nblocks), dim3(kCompactBlock), 0, st, job.vals, job.src_idx, job.idx_base,
+                       job.d_begin, job.d_end, job.n_literal, n_max, job.thr, blockcnt, job.out_idx, job.out_sc, c->max_surv,
+                       job.d_base, scan_in_scatter ? job.d_count : (int32_t *)nullptr,
+                       scan_in_scatter ? job.d_count2 : (int32_t *)nullptr);
     return hipGetLastError();
 }
 
@@ -259,13 +282,15 @@ extern "C" int cnnc_compact_noalloc(const float *d_values, int64_t n, float thr,
     if (nblocks < 1) nblocks = 1;           // an empty input still writes a zero count
     // every entry of blockcnt[0, nblocks) is written by the count kernel before it is read: nothing to clear
     hipLaunchKernelGGL(cnnc::compact_count_kernel, dim3(nblocks), dim3(cnnc::kCompactBlock), 0, st, d_values,
-                       (const int32_t *)nullptr, n, n, thr, blockcnt);
+                       (const int32_t *)nullptr, (const int32_t *)nullptr, n, n, thr, blockcnt);
     const bool scan_in_scatter = nblocks <= 4096;
     if (!scan_in_scatter)
-        hipLaunchKernelGGL(cnnc::compact_scan_kernel, dim3(1), dim3(1024), 0, st, blockcnt, nblocks, d_count);
+        hipLaunchKernelGGL(cnnc::compact_scan_kernel, dim3(1), dim3(1024), 0, st, blockcnt, nblocks, (const int32_t *)nullptr,
+                           d_count, (int32_t *)nullptr);
     hipLaunchKernelGGL(cnnc::compact_scatter_kernel, dim3(nblocks), dim3(cnnc::kCompactBlock), 0, st, d_values,
-                       (const uint32_t *)nullptr, (const int32_t *)nullptr, n, n, thr, blockcnt, d_index, d_score, (int)cap,
-                       scan_in_scatter ? d_count : (int32_t *)nullptr);
+                       (const uint32_t *)nullptr, 0u, (const int32_t *)nullptr, (const int32_t *)nullptr, n, n, thr, blockcnt,
+                       d_index, d_score, (int)cap, (const int32_t *)nullptr, scan_in_scatter ? d_count : (int32_t *)nullptr,
+                       (int32_t *)nullptr);
     return hipGetLastError() == hipSuccess ? CNNC_OK : CNNC_E_HIP;
 }
 

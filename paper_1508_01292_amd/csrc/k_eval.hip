@@ -68,8 +68,8 @@ __device__ void fc_layer(const float *in, float *out, const float *__restrict__ 
 template <int ACT>
 __global__ __launch_bounds__(kThreads)
 void eval2_kernel(const uint8_t *__restrict__ frame, int fw, int fh, int pitch, const LevelDev *__restrict__ levels,
-                  int n_levels, const uint32_t *__restrict__ idx, const int32_t *__restrict__ d_n, int n_max,
-                  const float *__restrict__ wt, float *__restrict__ out)
+                  int n_levels, const uint32_t *__restrict__ idx, const int32_t *__restrict__ d_begin,
+                  const int32_t *__restrict__ d_n, int n_max, const float *__restrict__ wt, float *__restrict__ out)
 {
     __shared__ uint32_t sTab[2 * kS2In];
     __shared__ float sCrop[24 * 24];
@@ -77,7 +77,7 @@ void eval2_kernel(const uint8_t *__restrict__ frame, int fw, int fh, int pitch, 
     __shared__ float sP2[16 * 4 * 4];
     __shared__ float sF[32];
     const int n = min(*d_n, n_max);
-    for (int i = blockIdx.x; i < n; i += gridDim.x) {
+    for (int i = min(*d_begin, n_max) + blockIdx.x; i < n; i += gridDim.x) {
         const Survivor s = decode(idx[i], levels, n_levels);
         gather_crop<kS2In>(frame, fw, fh, pitch, s.x, s.y, levels[s.level].scale_q16, sTab, sCrop);
         conv_layer<1, 8, 5, 24, true, ACT>(sCrop, sP1, wt + s2::W1, wt + s2::B1);
@@ -96,8 +96,8 @@ void eval2_kernel(const uint8_t *__restrict__ frame, int fw, int fh, int pitch, 
 template <int ACT>
 __global__ __launch_bounds__(kThreads)
 void eval3_kernel(const uint8_t *__restrict__ frame, int fw, int fh, int pitch, const LevelDev *__restrict__ levels,
-                  int n_levels, const uint32_t *__restrict__ idx, const int32_t *__restrict__ d_n, int n_max,
-                  const float *__restrict__ wt, float *__restrict__ out)
+                  int n_levels, const uint32_t *__restrict__ idx, const int32_t *__restrict__ d_begin,
+                  const int32_t *__restrict__ d_n, int n_max, const float *__restrict__ wt, float *__restrict__ out)
 {
     __shared__ uint32_t sTab[2 * kS3In];
     __shared__ float sCrop[48 * 48];
@@ -106,7 +106,7 @@ void eval3_kernel(const uint8_t *__restrict__ frame, int fw, int fh, int pitch, 
     __shared__ float sP3[32 * 7 * 7];
     __shared__ float sF[64];
     const int n = min(*d_n, n_max);
-    for (int i = blockIdx.x; i < n; i += gridDim.x) {
+    for (int i = min(*d_begin, n_max) + blockIdx.x; i < n; i += gridDim.x) {
         const Survivor s = decode(idx[i], levels, n_levels);
         gather_crop<kS3In>(frame, fw, fh, pitch, s.x, s.y, levels[s.level].scale_q16, sTab, sCrop);
         conv_layer<1, 16, 5, 48, true, ACT>(sCrop, sP1, wt + s3::W1, wt + s3::B1);
@@ -131,26 +131,26 @@ int eval_grid(const cnnc_ctx *c)
 }
 }  // namespace
 
-#define CNNC_EVAL(KERNEL, ACT, IDX, CNT, WT, OUT)                                                            \
+#define CNNC_EVAL(KERNEL, ACT, IDX, WT, OUT)                                                                 \
     hipLaunchKernelGGL(KERNEL<ACT>, dim3(eval_grid(c)), dim3(kThreads), 0, st, c->d_frame, c->fw, c->fh,     \
-                       c->fpitch, c->d_levels, c->n_levels, IDX, CNT, c->max_surv, WT, OUT)
+                       c->fpitch, c->d_levels, c->n_levels, IDX, r.d_begin, r.d_end, c->max_surv, WT, OUT)
 
-hipError_t launch_eval2(const cnnc_ctx *c, hipStream_t st)
+hipError_t launch_eval2(const cnnc_ctx *c, ListRange r, hipStream_t st)
 {
     switch (c->act) {
-    case CNNC_ACT_RATIONAL: CNNC_EVAL(eval2_kernel, CNNC_ACT_RATIONAL, c->d_idx[0], &c->d_cnt->n[0], c->d_wt[1], c->d_eval[0]); break;
-    case CNNC_ACT_SCALED_TANH: CNNC_EVAL(eval2_kernel, CNNC_ACT_SCALED_TANH, c->d_idx[0], &c->d_cnt->n[0], c->d_wt[1], c->d_eval[0]); break;
-    default: CNNC_EVAL(eval2_kernel, CNNC_ACT_TANH, c->d_idx[0], &c->d_cnt->n[0], c->d_wt[1], c->d_eval[0]); break;
+    case CNNC_ACT_RATIONAL: CNNC_EVAL(eval2_kernel, CNNC_ACT_RATIONAL, c->d_idx[0], c->d_wt[1], c->d_eval[0]); break;
+    case CNNC_ACT_SCALED_TANH: CNNC_EVAL(eval2_kernel, CNNC_ACT_SCALED_TANH, c->d_idx[0], c->d_wt[1], c->d_eval[0]); break;
+    default: CNNC_EVAL(eval2_kernel, CNNC_ACT_TANH, c->d_idx[0], c->d_wt[1], c->d_eval[0]); break;
     }
     return hipGetLastError();
 }
 
-hipError_t launch_eval3(const cnnc_ctx *c, hipStream_t st)
+hipError_t launch_eval3(const cnnc_ctx *c, ListRange r, hipStream_t st)
 {
     switch (c->act) {
-    case CNNC_ACT_RATIONAL: CNNC_EVAL(eval3_kernel, CNNC_ACT_RATIONAL, c->d_idx[1], &c->d_cnt->n[1], c->d_wt[2], c->d_eval[1]); break;
-    case CNNC_ACT_SCALED_TANH: CNNC_EVAL(eval3_kernel, CNNC_ACT_SCALED_TANH, c->d_idx[1], &c->d_cnt->n[1], c->d_wt[2], c->d_eval[1]); break;
-    default: CNNC_EVAL(eval3_kernel, CNNC_ACT_TANH, c->d_idx[1], &c->d_cnt->n[1], c->d_wt[2], c->d_eval[1]); break;
+    case CNNC_ACT_RATIONAL: CNNC_EVAL(eval3_kernel, CNNC_ACT_RATIONAL, c->d_idx[1], c->d_wt[2], c->d_eval[1]); break;
+    case CNNC_ACT_SCALED_TANH: CNNC_EVAL(eval3_kernel, CNNC_ACT_SCALED_TANH, c->d_idx[1], c->d_wt[2], c->d_eval[1]); break;
+    default: CNNC_EVAL(eval3_kernel, CNNC_ACT_TANH, c->d_idx[1], c->d_wt[2], c->d_eval[1]); break;
     }
     return hipGetLastError();
 }

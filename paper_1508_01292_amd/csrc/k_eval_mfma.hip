@@ -400,8 +400,9 @@ constexpr int kS3Feat = 1568;
 template <int ACT, int WINO>
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(3, 3)))
 void eval3_conv_kernel(const uint8_t *__restrict__ frame, int fw, int fh, int pitch, const LevelDev *__restrict__ levels,
-                       int n_levels, const uint32_t *__restrict__ idx, const int32_t *__restrict__ d_n, int n_max,
-                       const float *__restrict__ wt, const float *__restrict__ frag, float *__restrict__ feat)
+                       int n_levels, const uint32_t *__restrict__ idx, const int32_t *__restrict__ d_begin,
+                       const int32_t *__restrict__ d_n, int n_max, const float *__restrict__ wt,
+                       const float *__restrict__ frag, float *__restrict__ feat)
 {
     __shared__ __attribute__((aligned(16))) float sA[kRegionA];
     __shared__ __attribute__((aligned(16))) float sB[kRegionB];
@@ -425,7 +426,7 @@ void eval3_conv_kernel(const uint8_t *__restrict__ frame, int fw, int fh, int pi
     // it does not shorten the kernel, the device-scope atomics cost more than the balance gains.)
     // The gather of a window is software-pipelined: its tables are computed during conv1 of the previous
     // window, its pixel loads are in flight during conv3, and it lands in LDS once conv3 has released the buffer.
-    int crop = blockIdx.x;
+    int crop = min(*d_begin, n_max) + blockIdx.x;
     if (crop < n) {
         const Survivor sv = decode(idx[crop], levels, n_levels);
         gather_crop<kS3In>(frame, fw, fh, pitch, sv.x, sv.y, levels[sv.level].scale_q16, sTab, sA);
@@ -510,15 +511,16 @@ void eval3_conv_kernel(const uint8_t *__restrict__ frame, int fw, int fh, int pi
 constexpr int kFcThreads = 512, kFcWaves = kFcThreads / 64;
 template <int ACT>
 __global__ __launch_bounds__(kFcThreads)
-void eval3_fc_kernel(const float *__restrict__ feat, const int32_t *__restrict__ d_n, int n_max,
+void eval3_fc_kernel(const float *__restrict__ feat, const int32_t *__restrict__ d_begin, const int32_t *__restrict__ d_n, int n_max,
                      const float *__restrict__ wt, const float *__restrict__ frag, float *__restrict__ out)
 {
     __shared__ float sPart[kFcWaves][16][65];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, g = lane >> 4, j = lane & 15;
     const int n = min(*d_n, n_max);
     const float4 *wf = reinterpret_cast<const float4 *>(frag + kS3F4) + lane;     // [chunk][n-tile][lane] float4
-    for (int tile = blockIdx.x; tile * 16 < n; tile += gridDim.x) {
-        const int row = min(tile * 16 + j, n - 1);
+    const int first = min(*d_begin, n_max);            // tiles of sixteen windows are counted from the range's first one
+    for (int tile = blockIdx.x; first + tile * 16 < n; tile += gridDim.x) {
+        const int row = min(first + tile * 16 + j, n - 1);
         const float4 *ap = reinterpret_cast<const float4 *>(feat + (size_t)row * kS3Feat) + g;
         floatx4 acc[4] = {floatx4{0, 0, 0, 0}, floatx4{0, 0, 0, 0}, floatx4{0, 0, 0, 0}, floatx4{0, 0, 0, 0}};
         for (int ch = wave; ch < 98; ch += kFcWaves) {
@@ -553,7 +555,7 @@ void eval3_fc_kernel(const float *__restrict__ feat, const int32_t *__restrict__
             }
 #pragma unroll
             for (int d = 8; d >= 1; d >>= 1) part += __shfl_xor(part, d, 64);
-            if (c0 == 0 && tile * 16 + r < n) out[tile * 16 + r] = part + wt[s3::B5];
+            if (c0 == 0 && first + tile * 16 + r < n) out[first + tile * 16 + r] = part + wt[s3::B5];
         }
         __syncthreads();
     }
@@ -679,8 +681,9 @@ constexpr int kS2Feat = 256;
 template <int ACT, bool WINO>
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(3, 3)))
 void eval2_conv_kernel(const uint8_t *__restrict__ frame, int fw, int fh, int pitch, const LevelDev *__restrict__ levels,
-                       int n_levels, const uint32_t *__restrict__ idx, const int32_t *__restrict__ d_n, int n_max,
-                       const float *__restrict__ wt, const float *__restrict__ frag, float *__restrict__ feat)
+                       int n_levels, const uint32_t *__restrict__ idx, const int32_t *__restrict__ d_begin,
+                       const int32_t *__restrict__ d_n, int n_max, const float *__restrict__ wt,
+                       const float *__restrict__ frag, float *__restrict__ feat)
 {
     __shared__ __attribute__((aligned(16))) float sMem[4][kS2WaveFloats];
     // per pooling block of conv1 (clamped to the last one): crop offset of its corner | pooled-map offset << 16
@@ -711,7 +714,7 @@ void eval2_conv_kernel(const uint8_t *__restrict__ frame, int fw, int fh, int pi
     const int in_lane = (j & 1) * kC2W + g, in_blk = 2 * (j >> 2) + ((j >> 1) & 1), out_blk = 2 * g + (j & 1);
 
     const int n = min(*d_n, n_max);
-    for (int crop = __builtin_amdgcn_readfirstlane(blockIdx.x * 4 + wave); crop < n; crop += gridDim.x * 4) {
+    for (int crop = __builtin_amdgcn_readfirstlane(min(*d_begin, n_max) + blockIdx.x * 4 + wave); crop < n; crop += gridDim.x * 4) {
         const Survivor sv = decode(idx[crop], levels, n_levels);
         const int64_t S = levels[sv.level].scale_q16;
         if (lane < 24) crop_axis<kS2In>(sv.x, S, fw, sTab, lane);
@@ -842,15 +845,16 @@ void eval2_conv_kernel(const uint8_t *__restrict__ frame, int fw, int fh, int pi
 // fc 256->32 + f, fc 32->1 for 16 windows per workgroup; the four waves split K.
 template <int ACT>
 __global__ __launch_bounds__(kThreads)
-void eval2_fc_kernel(const float *__restrict__ feat, const int32_t *__restrict__ d_n, int n_max,
+void eval2_fc_kernel(const float *__restrict__ feat, const int32_t *__restrict__ d_begin, const int32_t *__restrict__ d_n, int n_max,
                      const float *__restrict__ wt, const float *__restrict__ frag, float *__restrict__ out)
 {
     __shared__ float sPart[4][16][33];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, g = lane >> 4, j = lane & 15;
     const int n = min(*d_n, n_max);
     const float4 *wf = reinterpret_cast<const float4 *>(frag + kS2F3) + lane;     // [chunk][n-tile][lane] float4
-    for (int tile = blockIdx.x; tile * 16 < n; tile += gridDim.x) {
-        const int row = min(tile * 16 + j, n - 1);
+    const int first = min(*d_begin, n_max);            // tiles of sixteen windows are counted from the range's first one
+    for (int tile = blockIdx.x; first + tile * 16 < n; tile += gridDim.x) {
+        const int row = min(first + tile * 16 + j, n - 1);
         const float4 *ap = reinterpret_cast<const float4 *>(feat + (size_t)row * kS2Feat) + g;
         floatx4 acc[2] = {floatx4{0, 0, 0, 0}, floatx4{0, 0, 0, 0}};
 #pragma unroll
@@ -879,7 +883,7 @@ void eval2_fc_kernel(const float *__restrict__ feat, const int32_t *__restrict__
             }
 #pragma unroll
             for (int d = 8; d >= 1; d >>= 1) part += __shfl_xor(part, d, 64);
-            if (c0 == 0 && tile * 16 + r < n) out[tile * 16 + r] = part + wt[s2::B4];
+            if (c0 == 0 && first + tile * 16 + r < n) out[first + tile * 16 + r] = part + wt[s2::B4];
         }
         __syncthreads();
     }
@@ -957,16 +961,16 @@ int fc_grid(const cnnc_ctx *c)
 }  // namespace
 
 
-hipError_t launch_eval3_mfma(cnnc_ctx *c, hipStream_t st)
+hipError_t launch_eval3_mfma(cnnc_ctx *c, ListRange r, hipStream_t st)
 {
 #define CNNC_E3(ACT)                                                                                              \
     {                                                                                                             \
         ScopedTimer timer_(c, CNNC_T_STAGE3_CONV, st);                                                            \
         hipLaunchKernelGGL((eval3_conv_kernel<ACT, WINO>), dim3(conv_grid(c)), dim3(kThreads), 0, st, c->d_frame, c->fw, c->fh, \
-                       c->fpitch, c->d_levels, c->n_levels, c->d_idx[1], &c->d_cnt->n[1], c->max_surv, c->d_wt[2], \
+                       c->fpitch, c->d_levels, c->n_levels, c->d_idx[1], r.d_begin, r.d_end, c->max_surv, c->d_wt[2], \
                        c->d_frag[1], c->d_feat[1]);                                                                \
     }                                                                                                             \
-    hipLaunchKernelGGL(eval3_fc_kernel<ACT>, dim3(fc_grid(c)), dim3(kFcThreads), 0, st, c->d_feat[1], &c->d_cnt->n[1], \
+    hipLaunchKernelGGL(eval3_fc_kernel<ACT>, dim3(fc_grid(c)), dim3(kFcThreads), 0, st, c->d_feat[1], r.d_begin, r.d_end, \
                        c->max_surv, c->d_wt[2], c->d_frag[1], c->d_eval[1])
 #define CNNC_E3W(ACT)                     \
     if (c->eval_impl == 3) {              \
@@ -989,7 +993,7 @@ hipError_t launch_eval3_mfma(cnnc_ctx *c, hipStream_t st)
     return hipGetLastError();
 }
 
-hipError_t launch_eval2_mfma(cnnc_ctx *c, hipStream_t st)
+hipError_t launch_eval2_mfma(cnnc_ctx *c, ListRange r, hipStream_t st)
 {
     const int waves = c->max_surv < 256 * 3 * 4 ? c->max_surv : 256 * 3 * 4;   // three workgroups of four crops per compute unit (register limit)
     const int grid = (waves + 3) / 4;
@@ -997,10 +1001,10 @@ hipError_t launch_eval2_mfma(cnnc_ctx *c, hipStream_t st)
     {                                                                                                             \
         ScopedTimer timer_(c, CNNC_T_STAGE2_CONV, st);                                                            \
         hipLaunchKernelGGL((eval2_conv_kernel<ACT, WINO>), dim3(grid), dim3(kThreads), 0, st, c->d_frame, c->fw, c->fh, \
-                       c->fpitch, c->d_levels, c->n_levels, c->d_idx[0], &c->d_cnt->n[0], c->max_surv, c->d_wt[1], \
+                       c->fpitch, c->d_levels, c->n_levels, c->d_idx[0], r.d_begin, r.d_end, c->max_surv, c->d_wt[1], \
                        c->d_frag[0], c->d_feat[0]);                                                                \
     }                                                                                                             \
-    hipLaunchKernelGGL(eval2_fc_kernel<ACT>, dim3(fc_grid(c)), dim3(kThreads), 0, st, c->d_feat[0], &c->d_cnt->n[0], \
+    hipLaunchKernelGGL(eval2_fc_kernel<ACT>, dim3(fc_grid(c)), dim3(kThreads), 0, st, c->d_feat[0], r.d_begin, r.d_end, \
                        c->max_surv, c->d_wt[1], c->d_frag[0], c->d_eval[0])
 #define CNNC_E2W(ACT)                     \
     if (c->eval_impl == 3) {              \

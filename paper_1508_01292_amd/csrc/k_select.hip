@@ -404,7 +404,12 @@ int cnnc_select_run(cnnc_ctx *c, float t1, float t2, float t3, int t_nn, void *s
     hipStream_t st = (hipStream_t)stream;
     c->last_stream = st;
     ScopedTimer tm(c, CNNC_T_SELECT, st);
-    HIP_TRY(c, launch_compact(c, c->d_scan_map, nullptr, nullptr, c->n_scan, t1, c->d_sel_idx, c->d_sel_sc, c->d_sel_cnt, st));
+    {
+        CompactJob job{};
+        job.slot = 0; job.vals = c->d_scan_map; job.n_literal = c->n_scan; job.thr = t1;
+        job.out_idx = c->d_sel_idx; job.out_sc = c->d_sel_sc; job.d_count = c->d_sel_cnt;
+        HIP_TRY(c, launch_compact(c, job, st));
+    }
     dim3 grid(256 * 4), block(kThreads);
     float *m2 = c->d_sel_maps, *m3 = c->d_sel_maps + (size_t)kMap * c->max_surv;
 #define CNNC_SEL(ACT)                                                                                             \

@@ -228,12 +228,13 @@ void stage1_kernel(const uint8_t *__restrict__ pyr, const LevelDev *__restrict__
 }
 
 #define CNNC_S1(ACT, EMIT, THR, MASK)                                                                        \
-    hipLaunchKernelGGL((stage1_kernel<ACT, EMIT>), grid, block, 0, st, c->d_pyr, c->d_levels, c->d_tiles_s1, \
+    hipLaunchKernelGGL((stage1_kernel<ACT, EMIT>), grid, block, 0, st, c->d_pyr, c->d_levels, c->d_tiles_s1 + tile_begin, \
                        c->d_wt[0], c->d_score1, THR, MASK)
 
-hipError_t launch_stage1(const cnnc_ctx *c, hipStream_t st)
+hipError_t launch_stage1(const cnnc_ctx *c, int tile_begin, int tile_end, hipStream_t st)
 {
-    dim3 grid(c->n_tiles_s1), block(kThreads);
+    if (tile_end <= tile_begin) return hipSuccess;
+    dim3 grid(tile_end - tile_begin), block(kThreads);
     switch (c->act) {
     case CNNC_ACT_RATIONAL: CNNC_S1(CNNC_ACT_RATIONAL, false, 0.0f, (uint32_t *)nullptr); break;
     case CNNC_ACT_SCALED_TANH: CNNC_S1(CNNC_ACT_SCALED_TANH, false, 0.0f, (uint32_t *)nullptr); break;
@@ -244,6 +245,7 @@ hipError_t launch_stage1(const cnnc_ctx *c, hipStream_t st)
 
 hipError_t launch_stage1_emit(const cnnc_ctx *c, float thr, hipStream_t st)
 {
+    const int tile_begin = 0;
     dim3 grid(c->n_tiles_s1), block(kThreads);
     switch (c->act) {
     case CNNC_ACT_RATIONAL: CNNC_S1(CNNC_ACT_RATIONAL, true, thr, c->d_mask1); break;
