@@ -126,6 +126,7 @@ int prepare_layout(cnnc_ctx *c, int w, int h)
     if (compute_levels(c, w, h, lv, pyr_bytes, n_windows) != CNNC_OK)
         return fail(c, CNNC_E_INVAL, "frame has no pyramid level at these parameters");
 
+    const int pyr_ntx = (w + kPyrTileW - 1) / kPyrTileW, pyr_nty = (h + kPyrTileH - 1) / kPyrTileH;
     std::vector<uint32_t> taps, tiles_pyr, tiles_s1;
     std::vector<int> s1_tile_of_level(lv.size() + 1, 0);
     for (size_t l = 0; l < lv.size(); ++l) {
@@ -135,8 +136,16 @@ int prepare_layout(cnnc_ctx *c, int w, int h)
         taps.resize(base + L.w + L.h);
         axis_taps(L.w, w, L.scale, taps.data() + base);
         axis_taps(L.h, h, L.scale, taps.data() + base + L.w);
-        for (int ty = 0; ty * kPyrTileH < L.h; ++ty)
-            for (int tx = 0; tx * kPyrTileW < L.w; ++tx) tiles_pyr.push_back(pack_tile((int)l, ty, tx));
+        // which level columns / rows each frame tile produces: those whose left / upper source pixel lies in it
+        for (int axis = 0; axis < 2; ++axis) {
+            const uint32_t *tp = taps.data() + base + (axis ? L.w : 0);
+            const int n = axis ? L.h : L.w, nt = axis ? pyr_nty : pyr_ntx, T = axis ? kPyrTileH : kPyrTileW;
+            int i = 0;
+            for (int t = 0; t <= nt; ++t) {
+                while (i < n && (int)(tp[i] >> 9) < t * T) ++i;
+                tiles_pyr.push_back((uint32_t)i);
+            }
+        }
         for (int ty = 0; ty * kS1TileH < L.oh; ++ty)
             for (int tx = 0; tx * kS1TileW < L.ow; ++tx) tiles_s1.push_back(pack_tile((int)l, ty, tx));
     }
@@ -184,6 +193,7 @@ int prepare_layout(cnnc_ctx *c, int w, int h)
     c->n_levels = (int)lv.size();
     c->pyr_bytes = pyr_bytes; c->n_windows = n_windows; c->n_words = n_words;
     c->n_tiles_pyr = (int)tiles_pyr.size(); c->n_tiles_s1 = (int)tiles_s1.size();
+    c->pyr_ntx = pyr_ntx; c->pyr_nty = pyr_nty;
     c->lay_w = w; c->lay_h = h; c->layout_valid = true;
     ++c->layout_serial;
     return CNNC_OK;

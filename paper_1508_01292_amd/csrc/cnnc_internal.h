@@ -136,7 +136,8 @@ struct cnnc_ctx {
     // device buffers that depend on the layout
     cnnc::LevelDev *d_levels = nullptr;
     uint32_t *d_taps = nullptr;      // column / row tap tables of all levels
-    uint32_t *d_tiles_pyr = nullptr; // (level, tile) table of the pyramid kernel
+    uint32_t *d_tiles_pyr = nullptr; // pyramid kernel: per level, the first level column / row of every frame tile
+    int pyr_ntx = 0, pyr_nty = 0;    // frame tiles per row / column of tiles
     uint32_t *d_tiles_s1 = nullptr;  // (level, tile) table of the stage-1 kernel
     uint8_t *d_pyr = nullptr;
     float *d_score1 = nullptr;
@@ -245,7 +246,7 @@ constexpr int kCompactPerBlock = 2048;   // values handled by one workgroup
 
 // Stage-1 tile (outputs per workgroup) and pyramid tile.
 constexpr int kS1TileW = 32, kS1TileH = 16;
-constexpr int kPyrTileW = 64, kPyrTileH = 4;
+constexpr int kPyrTileW = 128, kPyrTileH = 32;   // pyramid: FRAME pixels staged per workgroup
 
 // tile table entry: level in the top 8 bits, tile row in the next 12, tile column in the low 12
 inline uint32_t pack_tile(int level, int ty, int tx) { return (uint32_t(level) << 24) | (uint32_t(ty) << 12) | uint32_t(tx); }
