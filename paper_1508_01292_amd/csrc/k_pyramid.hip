@@ -10,7 +10,7 @@
 namespace cnnc {
 
 namespace {
-constexpr int FW = kPyrTileW, FH = kPyrTileH, kPitch = FW + 16;     // LDS row: 128 pixels, the halo pixel, padding
+constexpr int FW = kPyrTileW, FH = kPyrTileH, kPitch = FW + 16;     // LDS row: the tile's pixels, the halo pixel, padding
 constexpr int kThreads = 256;
 }  // namespace
 
@@ -25,7 +25,12 @@ void pyramid_kernel(const uint8_t *__restrict__ frame, int fw, int fh, int pitch
 {
     __shared__ __attribute__((aligned(16))) uint8_t sT[(FH + 1) * kPitch];
     const int tid = threadIdx.x;
-    const int tx = blockIdx.x % ntx, ty = blockIdx.x / ntx, x0 = tx * FW, y0 = ty * FH;
+    // Workgroups go to the eight XCDs (each with its own L2) in turn.  Neighbouring tiles share their halo lines, so
+    // every XCD gets a run of consecutive tiles: the line one tile reads as halo is in that L2 for the tile that owns it.
+    const int n_tiles = ntx * nty, per_xcd = (n_tiles + 7) / 8;
+    const int tile = (int)(blockIdx.x & 7) * per_xcd + (int)(blockIdx.x >> 3);
+    if (tile >= n_tiles) return;
+    const int tx = tile % ntx, ty = tile / ntx, x0 = tx * FW, y0 = ty * FH;
 
     // ---- per level: which of its columns and rows this tile produces, and where the level lives (one lane a level,
     // so that these dependent loads are in flight together with the tile's pixels)
@@ -50,18 +55,19 @@ void pyramid_kernel(const uint8_t *__restrict__ frame, int fw, int fh, int pitch
         if (tid == 0) sCum[0] = 0;
     }
 
-    // ---- the tile: rows y0 .. y0 + FH, columns x0 .. x0 + FW, both clamped to the frame
-    if (x0 + FW <= fw && (pitch & 15) == 0 && (reinterpret_cast<uintptr_t>(frame) & 15) == 0) {
-        for (int e = tid; e < (FH + 1) * (FW / 16); e += kThreads) {
-            const int r = e / (FW / 16), q = e % (FW / 16);
-            const uint8_t *src = frame + (size_t)min(y0 + r, fh - 1) * pitch + x0 + 16 * q;
-            *reinterpret_cast<uint4 *>(sT + r * kPitch + 16 * q) = *reinterpret_cast<const uint4 *>(src);
-        }
-        if (tid < FH + 1) sT[tid * kPitch + FW] = frame[(size_t)min(y0 + tid, fh - 1) * pitch + min(x0 + FW, fw - 1)];
-    } else {
-        for (int e = tid; e < (FH + 1) * (FW + 1); e += kThreads) {
-            const int r = e / (FW + 1), q = e % (FW + 1);
-            sT[r * kPitch + q] = frame[(size_t)min(y0 + r, fh - 1) * pitch + min(x0 + q, fw - 1)];
+    // ---- the tile: rows y0 .. y0 + FH, columns x0 .. x0 + FW, both clamped to the frame; sixteen pixels a load where
+    // the frame's alignment allows it
+    const bool wide = (pitch & 15) == 0 && (reinterpret_cast<uintptr_t>(frame) & 15) == 0;
+    for (int e = tid; e < (FH + 1) * (FW / 16 + 1); e += kThreads) {
+        const int r = e / (FW / 16 + 1), q = e % (FW / 16 + 1);
+        const uint8_t *row = frame + (size_t)min(y0 + r, fh - 1) * pitch;
+        uint8_t *dst = sT + r * kPitch + 16 * q;
+        if (q == FW / 16) {
+            dst[0] = row[min(x0 + FW, fw - 1)];                       // the halo pixel
+        } else if (wide && x0 + 16 * q + 16 <= fw) {
+            *reinterpret_cast<uint4 *>(dst) = *reinterpret_cast<const uint4 *>(row + x0 + 16 * q);
+        } else {
+            for (int k = 0; k < 16; ++k) dst[k] = row[min(x0 + 16 * q + k, fw - 1)];
         }
     }
     __syncthreads();
@@ -87,7 +93,7 @@ void pyramid_kernel(const uint8_t *__restrict__ frame, int fw, int fh, int pitch
 
 hipError_t launch_pyramid(const cnnc_ctx *c, hipStream_t st)
 {
-    hipLaunchKernelGGL(pyramid_kernel, dim3(c->pyr_ntx * c->pyr_nty), dim3(kThreads), 0, st, c->d_frame, c->fw, c->fh,
+    hipLaunchKernelGGL(pyramid_kernel, dim3(8 * ((c->pyr_ntx * c->pyr_nty + 7) / 8)), dim3(kThreads), 0, st, c->d_frame, c->fw, c->fh,
                        c->fpitch, c->d_levels, c->n_levels, c->d_taps, c->d_tiles_pyr, c->pyr_ntx, c->pyr_nty, c->d_pyr);
     return hipGetLastError();
 }
