@@ -259,7 +259,7 @@ def main():
 
     paper = None
     if not a.no_paper_path:
-        paper = paper_geometry_legs(a, c0, streams[0], dev_frame, frame, cfg, seed, tr, I, O, np, torch, time, tflops)
+        paper = paper_geometry_legs(a, ctxs, streams, dev_frame, frame, cfg, seed, tr, I, O, np, torch, time, tflops)
 
     kernels = {
         "pyramid": {"bound": "hbm", "ms": ms["pyramid"], "achieved": gbs(cfg["width"] * cfg["height"] + pyr_bytes, ms["pyramid"]),
@@ -355,13 +355,15 @@ def main():
     print(json.dumps(out))
 
 
-def paper_geometry_legs(a, c0, stream, dev_frame, frame, cfg, seed, tr, I, O, np, torch, time, tflops):
+def paper_geometry_legs(a, ctxs, streams, dev_frame, frame, cfg, seed, tr, I, O, np, torch, time, tflops):
     """The first stage in the paper's own geometry (27 x 31 window, 4 pixel step) on the same pyramid, the selective
     unit on the positions above the 2 % quantile of that scan, and the merge of what it accepts: reported beside the
     headline, in the paper's unit (window positions at step 4, regions)."""
+    c0, stream = ctxs[0], streams[0]
     scan_net = I.paper_stage1()
     w_scan = I.draw_scan_weights(scan_net, seed)
-    c0.scan_set_weights(w_scan, 1)
+    for c in ctxs:
+        c.scan_set_weights(w_scan, 1)
     c0.build_pyramid(dev_frame, stream)
     n_rep = max(a.steps, 200)
     t_end = time.perf_counter() + min(a.prewarm, 0.3)
@@ -379,7 +381,8 @@ def paper_geometry_legs(a, c0, stream, dev_frame, frame, cfg, seed, tr, I, O, np
     # of the regions (they stop there, eq. (2)), T_3 at the median of CNN_3's responses, T_nn = 5.
     n2_net, n3_net = I.paper_stage2(), I.paper_stage3()
     w2_sel, w3_sel = I.draw_scan_weights(n2_net, seed + 1), I.draw_scan_weights(n3_net, seed + 2)
-    c0.select_set_weights(w2_sel, w3_sel, 1)
+    for c in ctxs:
+        c.select_set_weights(w2_sel, w3_sel, 1)
     pyr_o = tr.pyramid
     scan_o = O.scan_scores(pyr_o, scan_net, w_scan)
     t1_scan = float(O.threshold_from_quantile(scan_o, 0.02))
@@ -404,18 +407,35 @@ def paper_geometry_legs(a, c0, stream, dev_frame, frame, cfg, seed, tr, I, O, np
     for _ in range(50):
         c0.select_merge(0.3, 1, 32768, stream)
     ms_sel_merge = (time.perf_counter() - t0) / 50 * 1e3
-    # the path in the paper's geometry end to end, one frame at a time: pyramid, scan, selective unit, merge (which waits)
-    n_paper = max(50, a.steps // 4)
-    with torch.cuda.stream(stream):
-        for it in range(n_paper + 20):
-            if it == 20:
-                torch.cuda.synchronize()
-                t0 = time.perf_counter()
-            c0.build_pyramid(dev_frame, stream)
-            c0.scan_scoremap(stream)
-            c0.select_run(t1_scan, t2_sel, t3_sel, 5, stream)
-            c0.select_merge(0.3, 1, 32768, stream)
+    # the path in the paper's geometry end to end through cnnc_detect_paper: one frame at a time, and frames in flight
+    n_paper = max(100, a.steps // 4)
+    for it in range(n_paper + 20):
+        if it == 20:
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+        n_paper_det = len(c0.detect_paper(dev_frame, t1_scan, t2_sel, t3_sel, 5, 0.3, 1, 32768))
     ms_paper_frame = (time.perf_counter() - t0) / n_paper * 1e3
+    assert n_paper_det == len(sel_det)
+    F = len(ctxs)
+
+    def run_paper(n_steps):
+        busy = [False] * F
+        for i in range(n_steps):
+            j = i % F
+            if busy[j]:
+                ctxs[j].fetch_paper(32768)
+            ctxs[j].detect_paper_async(dev_frame, t1_scan, t2_sel, t3_sel, 5, 0.3, 1, streams[j])
+            busy[j] = True
+        for j in range(F):
+            if busy[j]:
+                ctxs[j].fetch_paper(32768)
+
+    run_paper(10 * F)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    run_paper(4 * n_paper)
+    torch.cuda.synchronize()
+    ms_paper_inflight = (time.perf_counter() - t0) / (4 * n_paper) * 1e3
     sel_flop = 2.0 * sum(2 * SEL_MAC_CNN2 + (2 * SEL_MAC_CNN3 if r.k2 > 0 else 0) for r in sel)
     c0.detect(dev_frame, 8192)           # leaves the context with the cascade's own survivor lists again
     return {
@@ -430,7 +450,8 @@ def paper_geometry_legs(a, c0, stream, dev_frame, frame, cfg, seed, tr, I, O, np
                            "achieved": tflops(sel_flop, ms_sel), "peak": PEAK_FP32_VECTOR, "unit": "TFLOP/s",
                            "frac": tflops(sel_flop, ms_sel) / PEAK_FP32_VECTOR},
         "merge": {"detections": len(sel_det), "ms_per_call_with_wait_and_readback": ms_sel_merge},
-        "whole_path_ms_per_frame_one_at_a_time": ms_paper_frame}
+        "whole_path_ms_per_frame_one_at_a_time": ms_paper_frame,
+        "whole_path_frames_per_s_%d_in_flight" % F: 1e3 / ms_paper_inflight}
 
 
 if __name__ == "__main__":

@@ -307,6 +307,26 @@ typedef struct {
 } cnnc_rdet;
 int cnnc_select_merge(cnnc_ctx *ctx, float iou, int min_neighbors, cnnc_rdet *out, int cap, int *n_out, void *stream);
 
+/* The whole path in the paper's geometry on one frame (Section 3.3, in its order): cnnc_build_pyramid,
+ * cnnc_scan_scoremap, cnnc_select_run, and the merge of cnnc_select_merge, with counts staying on the device between
+ * the steps.  Needs cnnc_scan_set_weights and cnnc_select_set_weights (CNNC_E_STATE otherwise); the rule is the one set
+ * by cnnc_select_set_rule; pyramid parameters are the context's (cnnc_set_params: min_face maps to the 12-pixel base
+ * of the pyramid as for the other path).  cnnc_detect_paper synchronises and returns the detections (host array `out`
+ * of capacity cap, kept order; *n_out = their number; CNNC_E_OVERFLOW rules as for cnnc_select_merge);
+ * cnnc_detect_paper_async only enqueues on `stream`, and cnnc_fetch_paper later waits for that work and returns its
+ * detections.  The frame must stay alive and unchanged until then.  Uses the context's merge workspace. */
+typedef struct {
+    float t1, t2, t3;       /* thresholds of the scan and of the two response maps (fp32, strict) */
+    int32_t t_nn;           /* T_nn of the decision rule, >= 1 */
+    float merge_iou;        /* 0.3 */
+    int32_t min_neighbors;  /* >= 1 */
+} cnnc_paper_params;
+int cnnc_detect_paper(cnnc_ctx *ctx, const uint8_t *d_frame, int w, int h, int pitch, const cnnc_paper_params *p,
+                      cnnc_rdet *out, int cap, int *n_out);
+int cnnc_detect_paper_async(cnnc_ctx *ctx, const uint8_t *d_frame, int w, int h, int pitch, const cnnc_paper_params *p,
+                            void *stream);
+int cnnc_fetch_paper(cnnc_ctx *ctx, cnnc_rdet *out, int cap, int *n_out);
+
 /* ---- Frame ingest from host memory ------------------------------------------------------------
  * The paper's detector is fed video (Section 4.2) and overlaps its stages (Section 3.4, asynchronous mode).
  * A pipe is a ring of `depth` slots (1..16); each slot owns a context, a HIP stream, a pinned host frame

@@ -22,6 +22,7 @@ EXPORTS = [
     "cnnc_stage1_survivors", "cnnc_set_fused_stage1", "cnnc_set_async_chunks", "cnnc_compact_noalloc",
     "cnnc_scan_set_weights", "cnnc_scan_layout", "cnnc_scan_scoremap", "cnnc_get_scan_scoremap",
     "cnnc_select_set_weights", "cnnc_select_set_rule", "cnnc_select_run", "cnnc_select_fetch", "cnnc_select_merge", "cnnc_abi_sizes",
+    "cnnc_detect_paper", "cnnc_detect_paper_async", "cnnc_fetch_paper",
     "cnnc_pipe_create", "cnnc_pipe_destroy", "cnnc_pipe_set_params", "cnnc_pipe_frame_buffer", "cnnc_pipe_submit",
     "cnnc_pipe_fetch", "cnnc_pipe_last_error",
 ]
@@ -44,6 +45,11 @@ class _Layer(C.Structure):
 class _StageDesc(C.Structure):
     _fields_ = [("in_size", C.c_int32), ("n_layers", C.c_int32), ("layers", C.POINTER(_Layer)),
                 ("weights", C.POINTER(C.c_float))]
+
+
+class _PaperParams(C.Structure):
+    _fields_ = [("t1", C.c_float), ("t2", C.c_float), ("t3", C.c_float), ("t_nn", C.c_int32), ("merge_iou", C.c_float),
+                ("min_neighbors", C.c_int32)]
 
 
 class _Params(C.Structure):
@@ -314,6 +320,30 @@ class Context:
                                             C.byref(n), _stream(stream)))
         return list(out[:n.value])
 
+    @staticmethod
+    def _paper_params(t1, t2, t3, t_nn, iou, min_neighbors):
+        return _PaperParams(float(t1), float(t2), float(t3), int(t_nn), float(iou), int(min_neighbors))
+
+    def detect_paper(self, frame, t1: float, t2: float, t3: float, t_nn: int, iou: float = 0.3, min_neighbors: int = 1,
+                     cap: int = 4096):
+        """The whole path in the paper's geometry on one frame (list of RegionDetection, kept order)."""
+        out = (RegionDetection * cap)()
+        n = C.c_int(0)
+        p = self._paper_params(t1, t2, t3, t_nn, iou, min_neighbors)
+        self._check(lib().cnnc_detect_paper(self._h, *self._frame_args(frame), C.byref(p), out, C.c_int(cap), C.byref(n)))
+        return list(out[:n.value])
+
+    def detect_paper_async(self, frame, t1: float, t2: float, t3: float, t_nn: int, iou: float = 0.3, min_neighbors: int = 1,
+                           stream=None):
+        p = self._paper_params(t1, t2, t3, t_nn, iou, min_neighbors)
+        self._check(lib().cnnc_detect_paper_async(self._h, *self._frame_args(frame), C.byref(p), _stream(stream)))
+
+    def fetch_paper(self, cap: int = 4096):
+        out = (RegionDetection * cap)()
+        n = C.c_int(0)
+        self._check(lib().cnnc_fetch_paper(self._h, out, C.c_int(cap), C.byref(n)))
+        return list(out[:n.value])
+
     def set_eval_impl(self, impl: int):
         self._check(lib().cnnc_set_eval_impl(self._h, C.c_int(impl)))
 
@@ -432,7 +462,8 @@ _CTX_CALLS = ("set_params", "pyramid_layout", "build_pyramid", "stage1_scoremap"
               "compact_survivors", "eval_stage", "merge_detections", "detect", "detect_async", "fetch_detections",
               "get_pyramid", "get_scoremap", "get_survivors", "get_stage_scores", "survivor_count", "set_eval_impl",
               "executed_mfma", "set_timing", "get_timings", "scan_set_weights", "scan_layout", "scan_scoremap",
-              "get_scan_scoremap", "select_set_weights", "select_set_rule", "select_run", "select_fetch", "select_merge")
+              "get_scan_scoremap", "select_set_weights", "select_set_rule", "select_run", "select_fetch", "select_merge", "detect_paper",
+              "detect_paper_async", "fetch_paper")
 
 
 def _c_spelling(method):

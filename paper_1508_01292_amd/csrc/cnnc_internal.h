@@ -131,6 +131,8 @@ struct cnnc_ctx {
     float *d_sel_fsc = nullptr;              // [merge_cap] score of each accepted region
     uint32_t *d_sel_pick = nullptr;          // [merge_cap] its number in the list of regions
     cnnc_rdet *d_sel_det = nullptr;          // [merge_cap] merged detections of the unit
+    cnnc_rdet *h_sel_det = nullptr;          // pinned: the first of them, copied back with the counters by the whole-path call
+    bool paper_pending = false;              // a cnnc_detect_paper_async pass is enqueued
     bool sel_done = false;
 
     // device buffers that depend on the layout

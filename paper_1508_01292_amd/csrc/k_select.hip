@@ -17,6 +17,8 @@
 // convolution split over ten groups of threads.
 #include <vector>
 
+#include <string.h>
+
 #include "act.h"
 #include "cnnc_internal.h"
 
@@ -310,6 +312,8 @@ void select_kernel(const uint8_t *__restrict__ frame, int fw, int fh, int pitch,
 }
 
 namespace {
+constexpr int kPaperFastDets = 2048;      // detections of the whole-path call that come back with the counters
+
 // B operand of a network's second convolution in lane order: [n tile][k step][lane], lane (g = lane / 16, j = lane % 16)
 // holds the weight of tap k = 4 step + g (k = 9 c + 3 a + b) for map n = 16 tile + j; zero beyond K and C2.
 void conv2_fragments(const float *blob, int c1, int c2, std::vector<float> &f)
@@ -334,6 +338,8 @@ void select_release(cnnc_ctx *c)
     (void)hipFree(c->d_sel_fsc); (void)hipFree(c->d_sel_pick); (void)hipFree(c->d_sel_det);
     c->d_sel_fsc = nullptr; c->d_sel_pick = nullptr; c->d_sel_det = nullptr;
     if (c->h_sel_cnt) (void)hipHostFree(c->h_sel_cnt);
+    if (c->h_sel_det) (void)hipHostFree(c->h_sel_det);
+    c->h_sel_det = nullptr;
     c->d_sel_w2 = c->d_sel_w3 = nullptr; c->d_sel_idx = nullptr; c->d_sel_sc = nullptr; c->d_sel_rec = nullptr;
     c->d_sel_maps = nullptr; c->d_sel_cnt = nullptr; c->h_sel_cnt = nullptr;
 }
@@ -372,6 +378,7 @@ int cnnc_select_set_weights(cnnc_ctx *c, const float *w2, int n2, const float *w
         HIP_TRY(c, hipMalloc((void **)&c->d_sel_fsc, sizeof(float) * (size_t)c->merge_cap));
         HIP_TRY(c, hipMalloc((void **)&c->d_sel_pick, sizeof(uint32_t) * (size_t)c->merge_cap));
         HIP_TRY(c, hipMalloc((void **)&c->d_sel_det, sizeof(cnnc_rdet) * (size_t)c->merge_cap));
+        HIP_TRY(c, hipHostMalloc((void **)&c->h_sel_det, sizeof(cnnc_rdet) * (size_t)kPaperFastDets, hipHostMallocDefault));
     }
     HIP_TRY(c, hipMemcpy(c->d_sel_w2, w2, sizeof(float) * kNet2Params, hipMemcpyHostToDevice));
     HIP_TRY(c, hipMemcpy(c->d_sel_w3, w3, sizeof(float) * kNet3Params, hipMemcpyHostToDevice));
@@ -467,6 +474,62 @@ int cnnc_select_merge(cnnc_ctx *c, float iou, int min_neighbors, cnnc_rdet *out,
     if (m > 0) HIP_TRY(c, hipMemcpy(out, c->d_sel_det, sizeof(cnnc_rdet) * (size_t)m, hipMemcpyDeviceToHost));
     if (total > cap) return fail(c, CNNC_E_OVERFLOW, "output array too small");
     return CNNC_OK;
+}
+
+// ---- the whole path in the paper's geometry: pyramid, scan, selective unit, merge (Section 3.3) ----------------
+static int paper_fetch(cnnc_ctx *c, cnnc_rdet *out, int cap, int *n_out)
+{
+    HIP_TRY(c, hipStreamSynchronize(c->last_stream));
+    *n_out = 0;
+    if (c->h_sel_cnt[0] > c->max_surv) return fail(c, CNNC_E_OVERFLOW, "more positions passed T_1 than the context's survivor capacity");
+    if (c->h_sel_cnt[1] > c->merge_cap) return fail(c, CNNC_E_OVERFLOW, "more regions accepted than the merge can take");
+    const int total = c->h_sel_cnt[2], m = std::min(total, cap);
+    *n_out = total;
+    if (m > 0) memcpy(out, c->h_sel_det, sizeof(cnnc_rdet) * (size_t)std::min(m, kPaperFastDets));
+    if (m > kPaperFastDets)      // the enqueued copy only brought the first kPaperFastDets
+        HIP_TRY(c, hipMemcpy(out + kPaperFastDets, c->d_sel_det + kPaperFastDets, sizeof(cnnc_rdet) * (size_t)(m - kPaperFastDets),
+                             hipMemcpyDeviceToHost));
+    if (total > cap) return fail(c, CNNC_E_OVERFLOW, "output array too small");
+    return CNNC_OK;
+}
+
+int cnnc_detect_paper_async(cnnc_ctx *c, const uint8_t *d_frame, int w, int h, int pitch, const cnnc_paper_params *p, void *stream)
+{
+    if (!c) return CNNC_E_INVAL;
+    if (!p) return fail(c, CNNC_E_INVAL, "null parameters");
+    if (!(p->merge_iou >= 0.0f && p->merge_iou <= 1.0f) || p->min_neighbors < 1 || p->t_nn < 1)
+        return fail(c, CNNC_E_INVAL, "iou outside [0, 1], min_neighbors < 1 or t_nn < 1");
+    if (!c->d_scan_wt || !c->d_sel_w2) return fail(c, CNNC_E_STATE, "cnnc_scan_set_weights / cnnc_select_set_weights have not been called");
+    int rc;
+    c->paper_pending = false;
+    if ((rc = cnnc_build_pyramid(c, d_frame, w, h, pitch, stream))) return rc;
+    if ((rc = cnnc_scan_scoremap(c, stream))) return rc;
+    if ((rc = cnnc_select_run(c, p->t1, p->t2, p->t3, p->t_nn, stream))) return rc;
+    hipStream_t st = (hipStream_t)stream;
+    HIP_TRY(c, launch_merge_regions(c, p->merge_iou, p->min_neighbors, st));
+    HIP_TRY(c, hipMemcpyAsync(c->h_sel_cnt, c->d_sel_cnt, sizeof(int32_t) * 3, hipMemcpyDeviceToHost, st));
+    HIP_TRY(c, hipMemcpyAsync(c->h_sel_det, c->d_sel_det, sizeof(cnnc_rdet) * (size_t)std::min(c->merge_cap, kPaperFastDets),
+                              hipMemcpyDeviceToHost, st));
+    c->paper_pending = true;
+    return CNNC_OK;
+}
+
+int cnnc_fetch_paper(cnnc_ctx *c, cnnc_rdet *out, int cap, int *n_out)
+{
+    if (!c) return CNNC_E_INVAL;
+    if (!n_out || cap < 0 || (!out && cap > 0)) return fail(c, CNNC_E_INVAL, "null output");
+    if (!c->paper_pending) return fail(c, CNNC_E_STATE, "no cnnc_detect_paper_async pass was enqueued");
+    return paper_fetch(c, out, cap, n_out);
+}
+
+int cnnc_detect_paper(cnnc_ctx *c, const uint8_t *d_frame, int w, int h, int pitch, const cnnc_paper_params *p, cnnc_rdet *out,
+                      int cap, int *n_out)
+{
+    if (!c) return CNNC_E_INVAL;
+    if (!n_out || cap < 0 || (!out && cap > 0)) return fail(c, CNNC_E_INVAL, "null output");
+    const int rc = cnnc_detect_paper_async(c, d_frame, w, h, pitch, p, nullptr);
+    if (rc) return rc;
+    return paper_fetch(c, out, cap, n_out);
 }
 
 }  // extern "C"

@@ -32,7 +32,8 @@ def _select_case(frame, min_face, step, act, seed, q1, q2, t_nn, bias_sd=0.0, na
     ctx.set_params(min_face, step, (0.0, 0.0, 0.0))
     ctx.scan_set_weights(w1, act)
     ctx.select_set_weights(w2, w3, act)
-    ctx.build_pyramid(torch.from_numpy(frame).cuda())
+    ft = torch.from_numpy(frame).cuda()
+    ctx.build_pyramid(ft)
     ctx.scan_scoremap()
     if rule != 2:
         ctx.select_set_rule(rule)
@@ -94,6 +95,11 @@ def _select_case(frame, min_face, step, act, seed, q1, q2, t_nn, bias_sd=0.0, na
             assert [(d["index"], d["neighbors"], d["x"], d["y"], d["w"], d["h"], d["level"]) for d in det] == \
                 [(w["index"], w["neighbors"], w["x"], w["y"], w["w"], w["h"], w["level"]) for w in want], (iou, mn)
             assert all(abs(d["score"] - w["score"]) <= ATOL + RTOL * abs(w["score"]) for d, w in zip(det, want))
+        # the whole path in one call, synchronous and enqueued on a stream: the same detections
+        assert [d.as_dict() for d in ctx.detect_paper(ft, t1, t2, t3, t_nn, iou, mn, cap=50000)] == det
+        side = torch.cuda.Stream()
+        ctx.detect_paper_async(ft, t1, t2, t3, t_nn, iou, mn, stream=side)
+        assert [d.as_dict() for d in ctx.fetch_paper(50000)] == det
         print("   merge at iou %.1f, min_neighbors %d: %d regions -> %d detections (%s)"
               % (iou, mn, len(faces), len(det), "equal to the oracle's" if same_input else "valid merge of the GPU's own list"),
               flush=True)
@@ -160,7 +166,17 @@ def test_select_errors_and_degenerate_cases():
     ctx.select_set_weights(w2, w3, 1)
     with pytest.raises(P.CnncError):
         ctx.select_run(0.0, 0.0, 0.0, 1)              # no scan of this frame
+    with pytest.raises(P.CnncError) as e:
+        ctx.detect_paper(torch.from_numpy(frame).cuda(), 0.0, 0.0, 0.0, 1)     # whole path without the scan's weights
+    assert e.value.code == -5
+    with pytest.raises(P.CnncError) as e:
+        ctx.fetch_paper()                             # nothing enqueued
+    assert e.value.code == -5
     ctx.scan_set_weights(w1, 1)
+    with pytest.raises(P.CnncError) as e:
+        ctx.detect_paper(torch.from_numpy(frame).cuda(), 0.0, 0.0, 0.0, 0)     # T_nn < 1
+    assert e.value.code == -1
+    assert ctx.detect_paper(torch.from_numpy(frame).cuda(), 1e30, 0.0, 0.0, 1) == []
     ctx.build_pyramid(torch.from_numpy(frame).cuda())
     with pytest.raises(P.CnncError):
         ctx.select_fetch(16)                          # nothing run
