@@ -320,7 +320,7 @@ int cnnc_create(cnnc_ctx **out, const cnnc_stage_desc stages[3], int max_w, int 
         if (hipMalloc((void **)&c->d_frag[1], sizeof(float) * frag.size()) != hipSuccess) return bail(CNNC_E_NOMEM);
         if (hipMemcpy(c->d_frag[1], frag.data(), sizeof(float) * frag.size(), hipMemcpyHostToDevice) != hipSuccess)
             return bail(CNNC_E_HIP);
-        if (hipMalloc((void **)&c->d_feat[1], sizeof(float) * eval3_feat_floats() * (size_t)max_survivors) != hipSuccess)
+        if (hipMalloc((void **)&c->d_feat[1], sizeof(float) * eval3_feat_floats() * (size_t)eval3_feat_rows(max_survivors)) != hipSuccess)
             return bail(CNNC_E_NOMEM);
     }
     for (int s = 0; s < 3; ++s) {

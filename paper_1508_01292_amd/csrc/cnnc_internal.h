@@ -235,6 +235,7 @@ size_t eval2_feat_floats();
 void eval2_make_fragments(const float *blob, float *frag);
 size_t eval3_frag_floats();
 size_t eval3_feat_floats();
+int eval3_feat_rows(int max_surv);      // windows the stage-3 hand-over buffer holds
 void eval3_make_fragments(const float *blob, float *frag);
 int64_t eval3_mfma_per_crop(int impl);
 int64_t eval2_mfma_per_crop(int impl);

@@ -394,6 +394,9 @@ constexpr int kS3F1 = 0, kS3F2 = kS3F1 + 7 * 64, kS3F3 = kS3F2 + 25 * 2 * 64 * 4
               kS3F5 = kS3F4 + 98 * 4 * 64 * 4, kS3F6 = kS3F5 + 20 * 64 * 12, kS3F7 = kS3F6 + 2 * 24 * 64 * 4, kS3FragFloats = kS3F7 + 20 * 64 * 16;
 static_assert(kS3F5 % 4 == 0 && kS3F6 % 4 == 0 && kS3F7 % 4 == 0, "16-byte loads from the Winograd filter blocks");
 constexpr int kS3Feat = 1568;
+// The conv3 activations go from the convolution kernel to the fully connected kernel through a buffer of this many
+// windows; a longer survivor list is worked off in segments of that length, one pair of launches each.
+constexpr int kS3Segment = 65536;
 
 // Crop -> conv1 -> pool -> conv2 -> pool -> conv3 for each surviving window; writes the 1568 conv3
 // activations of the window (order [channel][row][col]) to `feat`.
@@ -401,7 +404,7 @@ template <int ACT, int WINO>
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(3, 3)))
 void eval3_conv_kernel(const uint8_t *__restrict__ frame, int fw, int fh, int pitch, const LevelDev *__restrict__ levels,
                        int n_levels, const uint32_t *__restrict__ idx, const int32_t *__restrict__ d_begin,
-                       const int32_t *__restrict__ d_n, int n_max, const float *__restrict__ wt,
+                       const int32_t *__restrict__ d_n, int seg_lo, int n_max, const float *__restrict__ wt,
                        const float *__restrict__ frag, float *__restrict__ feat)
 {
     __shared__ __attribute__((aligned(16))) float sA[kRegionA];
@@ -426,7 +429,7 @@ void eval3_conv_kernel(const uint8_t *__restrict__ frame, int fw, int fh, int pi
     // it does not shorten the kernel, the device-scope atomics cost more than the balance gains.)
     // The gather of a window is software-pipelined: its tables are computed during conv1 of the previous
     // window, its pixel loads are in flight during conv3, and it lands in LDS once conv3 has released the buffer.
-    int crop = min(*d_begin, n_max) + blockIdx.x;
+    int crop = max(min(*d_begin, n_max), seg_lo) + blockIdx.x;      // the launch covers list entries seg_lo .. n_max - 1 of the range
     if (crop < n) {
         const Survivor sv = decode(idx[crop], levels, n_levels);
         gather_crop<kS3In>(frame, fw, fh, pitch, sv.x, sv.y, levels[sv.level].scale_q16, sTab, sA);
@@ -496,7 +499,7 @@ void eval3_conv_kernel(const uint8_t *__restrict__ frame, int fw, int fh, int pi
         if (next < n) crop_issue<kS3In>(frame, pitch, sTab, px);
 
         // ---- conv3 3x3 32->32 and out to global memory
-        float *dst = feat + (size_t)crop * kS3Feat;
+        float *dst = feat + (size_t)(crop - seg_lo) * kS3Feat;
         if (WINO) s3_conv3_wino<ACT>(sA, frag + kS3F6, wt, dst, wave, fresh(lane));
         else s3_conv3_direct(sA, sB, frag + kS3F3, wave, lane);
         __syncthreads();                                   // conv3 has released the pooled map (and, direct form, written its partial sums)
@@ -511,17 +514,17 @@ void eval3_conv_kernel(const uint8_t *__restrict__ frame, int fw, int fh, int pi
 constexpr int kFcThreads = 512, kFcWaves = kFcThreads / 64;
 template <int ACT>
 __global__ __launch_bounds__(kFcThreads)
-void eval3_fc_kernel(const float *__restrict__ feat, const int32_t *__restrict__ d_begin, const int32_t *__restrict__ d_n, int n_max,
+void eval3_fc_kernel(const float *__restrict__ feat, const int32_t *__restrict__ d_begin, const int32_t *__restrict__ d_n, int seg_lo, int n_max,
                      const float *__restrict__ wt, const float *__restrict__ frag, float *__restrict__ out)
 {
     __shared__ float sPart[kFcWaves][16][65];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, g = lane >> 4, j = lane & 15;
     const int n = min(*d_n, n_max);
     const float4 *wf = reinterpret_cast<const float4 *>(frag + kS3F4) + lane;     // [chunk][n-tile][lane] float4
-    const int first = min(*d_begin, n_max);            // tiles of sixteen windows are counted from the range's first one
+    const int first = max(min(*d_begin, n_max), seg_lo);   // tiles of sixteen windows are counted from the range's first one
     for (int tile = blockIdx.x; first + tile * 16 < n; tile += gridDim.x) {
         const int row = min(first + tile * 16 + j, n - 1);
-        const float4 *ap = reinterpret_cast<const float4 *>(feat + (size_t)row * kS3Feat) + g;
+        const float4 *ap = reinterpret_cast<const float4 *>(feat + (size_t)(row - seg_lo) * kS3Feat) + g;
         floatx4 acc[4] = {floatx4{0, 0, 0, 0}, floatx4{0, 0, 0, 0}, floatx4{0, 0, 0, 0}, floatx4{0, 0, 0, 0}};
         for (int ch = wave; ch < 98; ch += kFcWaves) {
             const float4 a4 = ap[ch * 4];
@@ -564,6 +567,7 @@ void eval3_fc_kernel(const float *__restrict__ feat, const int32_t *__restrict__
 // ---- host: weight fragments ---------------------------------------------------------------------
 size_t eval3_frag_floats() { return kS3FragFloats; }
 size_t eval3_feat_floats() { return kS3Feat; }
+int eval3_feat_rows(int max_surv) { return max_surv < kS3Segment ? max_surv : kS3Segment; }
 
 // Re-order the stage-3 weights (blob layout: [cout][cin][k][k] per layer) into MFMA B fragments.
 void eval3_make_fragments(const float *w, float *f)
@@ -964,14 +968,17 @@ int fc_grid(const cnnc_ctx *c)
 hipError_t launch_eval3_mfma(cnnc_ctx *c, ListRange r, hipStream_t st)
 {
 #define CNNC_E3(ACT)                                                                                              \
-    {                                                                                                             \
-        ScopedTimer timer_(c, CNNC_T_STAGE3_CONV, st);                                                            \
-        hipLaunchKernelGGL((eval3_conv_kernel<ACT, WINO>), dim3(conv_grid(c)), dim3(kThreads), 0, st, c->d_frame, c->fw, c->fh, \
-                       c->fpitch, c->d_levels, c->n_levels, c->d_idx[1], r.d_begin, r.d_end, c->max_surv, c->d_wt[2], \
-                       c->d_frag[1], c->d_feat[1]);                                                                \
-    }                                                                                                             \
-    hipLaunchKernelGGL(eval3_fc_kernel<ACT>, dim3(fc_grid(c)), dim3(kFcThreads), 0, st, c->d_feat[1], r.d_begin, r.d_end, \
-                       c->max_surv, c->d_wt[2], c->d_frag[1], c->d_eval[1])
+    for (int seg_lo = 0; seg_lo < c->max_surv; seg_lo += kS3Segment) {                                            \
+        const int seg_hi = std::min(seg_lo + kS3Segment, c->max_surv);                                            \
+        {                                                                                                         \
+            ScopedTimer timer_(c, CNNC_T_STAGE3_CONV, st);                                                        \
+            hipLaunchKernelGGL((eval3_conv_kernel<ACT, WINO>), dim3(std::min(conv_grid(c), seg_hi - seg_lo)), dim3(kThreads), 0, st, \
+                           c->d_frame, c->fw, c->fh, c->fpitch, c->d_levels, c->n_levels, c->d_idx[1], r.d_begin, r.d_end, \
+                           seg_lo, seg_hi, c->d_wt[2], c->d_frag[1], c->d_feat[1]);                               \
+        }                                                                                                         \
+        hipLaunchKernelGGL(eval3_fc_kernel<ACT>, dim3(std::min(fc_grid(c), (seg_hi - seg_lo + 15) / 16)), dim3(kFcThreads), 0, st, \
+                           c->d_feat[1], r.d_begin, r.d_end, seg_lo, seg_hi, c->d_wt[2], c->d_frag[1], c->d_eval[1]); \
+    }
 #define CNNC_E3W(ACT)                     \
     if (c->eval_impl == 3) {              \
         constexpr int WINO = 2;           \

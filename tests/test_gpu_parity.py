@@ -421,6 +421,42 @@ def test_uhd_small_faces_full_oracle():
     assert len(g["det"]) > 4096        # the long form of the merge (several chunks of sorted boxes)
 
 
+def test_stage3_on_a_list_longer_than_its_hand_over_buffer():
+    """Stage 3 works a long survivor list off in segments of 65,536 windows (the buffer between its convolution and its
+    fully connected kernel holds that many): 131,773 windows reach it here, two full segments and a short one.  Scores
+    around the segment boundaries and a random sample against the oracle; every window must have been written."""
+    torch = _torch()
+    c = I.CONFIGS[3]
+    casc = I.default_cascade()
+    W = I.draw_weights(casc, I.config_seed(3))
+    frame = I.make_frame(c["width"], c["height"], I.config_seed(3))
+    pyr = O.build_pyramid(frame, c["min_face"], c["scale_step"])
+    t1 = O.threshold_from_quantile(O.stage1_scores(pyr, casc[0], W[0]), 0.02)
+    ctx = _ctx(casc, W, 3840, 2160, 200000)
+    thr = (float(t1), -1e30, 1e30)                    # everything passes stage 2, nothing passes stage 3
+    ctx.set_params(c["min_face"], c["scale_step"], thr)
+    ft = torch.from_numpy(frame).cuda()
+    ctx.build_pyramid(ft)
+    ctx.stage1_scoremap()
+    ctx.compact_survivors(1, thr[0])
+    ctx.eval_stage(2)
+    ctx.compact_survivors(2, thr[1])
+    idx2, _ = ctx.get_survivors(2)
+    assert abs(len(idx2) - 131773) <= 3 and len(idx2) > 2 * 65536
+    ctx.eval_stage(3)
+    sc3 = ctx.get_stage_scores(3)
+    assert sc3.size == len(idx2)
+    rng = np.random.default_rng(5)
+    pick = np.unique(np.concatenate([np.arange(0, 40), np.arange(65536 - 40, 65536 + 40), np.arange(131072 - 40, 131072 + 40),
+                                     np.arange(len(idx2) - 40, len(idx2)), rng.choice(len(idx2), 400, replace=False)]))
+    print("case long stage-3 list: %d windows, %d compared" % (len(idx2), pick.size), flush=True)
+    assert_scores(sc3[pick], O.eval_stage(frame, pyr, idx2[pick], casc[2], W[2]), "stage-3 scores across segments")
+    # a second pass over the same list gives the same bits (no window left unwritten or written twice differently)
+    ctx.eval_stage(3)
+    assert np.array_equal(ctx.get_stage_scores(3), sc3)
+    ctx.close()
+
+
 def test_compaction_of_a_very_long_score_map():
     """More than 4,096 compaction workgroups (8.4 M values): the form with a separate scan of the workgroup counts.
     The list must hold exactly the windows whose fp32 score exceeds the threshold, in ascending order, with their
