@@ -24,6 +24,7 @@ constexpr int kScanParams = 806;
 constexpr int W1 = 0, B1 = W1 + kC1 * 16, W2 = B1 + kC1, B2 = W2 + kC2 * kC1 * 9, W3 = B2 + kC2, B3 = W3 + kC2 * 30;
 static_assert(B3 + 1 == kScanParams, "blob layout");
 
+typedef uint32_t __attribute__((aligned(1))) pixel_quad;        // four neighbouring pixels of a row, any address
 constexpr int kThreads = 256;
 constexpr int TO = 8;                                           // responses per tile side
 constexpr int IN_W = kStep * (TO - 1) + kWinW, IN_H = kStep * (TO - 1) + kWinH, IN_P = 56;   // 55 x 59 patch, row pitch 56
@@ -50,11 +51,37 @@ void scan_kernel(const uint8_t *__restrict__ pyr, const ScanLevel *__restrict__ 
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int x_in = kStep * TO * tx, y_in = kStep * TO * ty;
 
-    // ---- patch, normalised; positions past the level edge repeat the edge (they feed only responses that are not written)
-    for (int e = tid; e < IN_H * IN_P; e += kThreads) {
-        const int r = e / IN_P, c = e % IN_P;
-        const int y = min(y_in + r, L.h - 1), x = min(x_in + c, L.w - 1);
-        sIn[e] = normalise((float)img[(size_t)y * L.w + x]);
+    // ---- patch, normalised; positions past the level edge repeat the edge (they feed only responses that are not
+    // written).  All loads of a thread are issued before the first is used.
+    if (x_in + IN_P <= L.w && y_in + IN_H <= L.h) {
+        constexpr int kQuads = IN_H * (IN_P / 4), kIt = (kQuads + kThreads - 1) / kThreads;
+        uint32_t px[kIt];
+#pragma unroll
+        for (int it = 0; it < kIt; ++it) {
+            const int e = min(it * kThreads + tid, kQuads - 1), r = e / (IN_P / 4), c = 4 * (e % (IN_P / 4));
+            px[it] = *reinterpret_cast<const pixel_quad *>(img + (size_t)(y_in + r) * L.w + x_in + c);
+        }
+#pragma unroll
+        for (int it = 0; it < kIt; ++it) {
+            const int e = it * kThreads + tid;
+            if (e < kQuads)
+                *reinterpret_cast<float4 *>(sIn + 4 * e) =
+                    make_float4(normalise((float)(px[it] & 255u)), normalise((float)((px[it] >> 8) & 255u)),
+                                normalise((float)((px[it] >> 16) & 255u)), normalise((float)(px[it] >> 24)));
+        }
+    } else {
+        constexpr int kIt = (IN_H * IN_P + kThreads - 1) / kThreads;
+        uint8_t pb[kIt];
+#pragma unroll
+        for (int it = 0; it < kIt; ++it) {
+            const int e = min(it * kThreads + tid, IN_H * IN_P - 1), r = e / IN_P, c = e % IN_P;
+            pb[it] = img[(size_t)min(y_in + r, L.h - 1) * L.w + min(x_in + c, L.w - 1)];
+        }
+#pragma unroll
+        for (int it = 0; it < kIt; ++it) {
+            const int e = it * kThreads + tid;
+            if (e < IN_H * IN_P) sIn[e] = normalise((float)pb[it]);
+        }
     }
     __syncthreads();
 
