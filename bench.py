@@ -237,7 +237,7 @@ def main():
         per_frame = {"min": min(lat), "mean": sum(lat) / len(lat), "max": max(lat)}
 
     # per-kernel times: HIP events recorded by the library on the stream the kernels run on
-    n_timed = max(a.steps, 200)
+    n_timed = max(a.steps, 200) if a.steps >= 20 else a.steps      # (a profiler's counter passes ask for a few steps only)
     c0.set_timing(True)
     c0.get_timings()
     for _ in range(n_timed):
@@ -245,7 +245,8 @@ def main():
         c0.fetch_detections(8192)
     tm = c0.get_timings()
     c0.set_timing(False)
-    ms = {k: (v[0] / v[1] if v[1] else 0.0) for k, v in tm.items()}
+    # per frame: a step may consist of several launches (a long stage-3 list goes through its kernels in segments)
+    ms = {k: v[0] / n_timed for k, v in tm.items()}
     n1, n2, n3 = (c0.survivor_count(s) for s in (1, 2, 3))
     lay = c0.pyramid_layout(cfg["width"], cfg["height"])
     pyr_bytes = lay["pyr_off"][-1]
@@ -365,7 +366,8 @@ def paper_geometry_legs(a, ctxs, streams, dev_frame, frame, cfg, seed, tr, I, O,
     for c in ctxs:
         c.scan_set_weights(w_scan, 1)
     c0.build_pyramid(dev_frame, stream)
-    n_rep = max(a.steps, 200)
+    few = a.steps < 20                       # a profiler's counter passes: a handful of launches of everything
+    n_rep = a.steps if few else max(a.steps, 200)
     t_end = time.perf_counter() + min(a.prewarm, 0.3)
     while time.perf_counter() < t_end:
         c0.scan_scoremap(stream)
@@ -395,7 +397,7 @@ def paper_geometry_legs(a, ctxs, streams, dev_frame, frame, cfg, seed, tr, I, O,
         c0.select_run(t1_scan, t2_sel, t3_sel, 5, stream)
     c0.set_timing(True)
     c0.get_timings()
-    for _ in range(max(50, a.steps // 4)):
+    for _ in range(a.steps if few else max(50, a.steps // 4)):
         c0.select_run(t1_scan, t2_sel, t3_sel, 5, stream)
     tm_sel = c0.get_timings()["select"]
     c0.set_timing(False)
@@ -403,14 +405,15 @@ def paper_geometry_legs(a, ctxs, streams, dev_frame, frame, cfg, seed, tr, I, O,
     sel = c0.select_fetch(65536)
     # merge of the accepted regions: the call waits for its result, so this is wall-clock time per call
     sel_det = c0.select_merge(0.3, 1, 32768, stream)
+    n_merge = a.steps if few else 50
     t0 = time.perf_counter()
-    for _ in range(50):
+    for _ in range(n_merge):
         c0.select_merge(0.3, 1, 32768, stream)
-    ms_sel_merge = (time.perf_counter() - t0) / 50 * 1e3
+    ms_sel_merge = (time.perf_counter() - t0) / n_merge * 1e3
     # the path in the paper's geometry end to end through cnnc_detect_paper: one frame at a time, and frames in flight
-    n_paper = max(100, a.steps // 4)
-    for it in range(n_paper + 20):
-        if it == 20:
+    n_paper, n_skip = (a.steps, 1) if few else (max(100, a.steps // 4), 20)
+    for it in range(n_paper + n_skip):
+        if it == n_skip:
             torch.cuda.synchronize()
             t0 = time.perf_counter()
         n_paper_det = len(c0.detect_paper(dev_frame, t1_scan, t2_sel, t3_sel, 5, 0.3, 1, 32768))
@@ -430,12 +433,13 @@ def paper_geometry_legs(a, ctxs, streams, dev_frame, frame, cfg, seed, tr, I, O,
             if busy[j]:
                 ctxs[j].fetch_paper(32768)
 
-    run_paper(10 * F)
+    n_fly = n_paper if few else 4 * n_paper
+    run_paper(F if few else 10 * F)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    run_paper(4 * n_paper)
+    run_paper(n_fly)
     torch.cuda.synchronize()
-    ms_paper_inflight = (time.perf_counter() - t0) / (4 * n_paper) * 1e3
+    ms_paper_inflight = (time.perf_counter() - t0) / n_fly * 1e3
     sel_flop = 2.0 * sum(2 * SEL_MAC_CNN2 + (2 * SEL_MAC_CNN3 if r.k2 > 0 else 0) for r in sel)
     c0.detect(dev_frame, 8192)           # leaves the context with the cascade's own survivor lists again
     return {
