@@ -96,7 +96,11 @@ __device__ void conv2_pool_mfma(const float *in, float *out, const float *__rest
 {
     constexpr int K = C1 * 9, KS = conv2_steps(C1);
     static_assert(C2 > 16 && C2 <= 32, "two tiles of output maps");
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, g = lane >> 4, i = lane & 15;
+    int lane = threadIdx.x & 63;
+    // opaque per call: otherwise the weight fragments and tap offsets of all four network passes are hoisted out of
+    // the loop over regions and kept alive across it, which spills 40 registers per lane
+    asm volatile("" : "+v"(lane));
+    const int wave = threadIdx.x >> 6, g = lane >> 4, i = lane & 15;
     float bf[2][KS];
     int koff[KS];
 #pragma unroll
