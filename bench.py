@@ -260,7 +260,8 @@ def main():
 
     paper = None
     if not a.no_paper_path:
-        paper = paper_geometry_legs(a, ctxs, streams, dev_frame, frame, cfg, seed, tr, I, O, np, torch, time, tflops)
+        make_pipe = None if a.no_ingest else (lambda: P.Pipe(casc, W, cfg["width"], cfg["height"], max_surv, depth=F + 1, use_graph=False))
+        paper = paper_geometry_legs(a, ctxs, streams, dev_frame, frame, cfg, seed, tr, I, O, np, torch, time, tflops, make_pipe)
 
     kernels = {
         "pyramid": {"bound": "hbm", "ms": ms["pyramid"], "achieved": gbs(cfg["width"] * cfg["height"] + pyr_bytes, ms["pyramid"]),
@@ -356,7 +357,7 @@ def main():
     print(json.dumps(out))
 
 
-def paper_geometry_legs(a, ctxs, streams, dev_frame, frame, cfg, seed, tr, I, O, np, torch, time, tflops):
+def paper_geometry_legs(a, ctxs, streams, dev_frame, frame, cfg, seed, tr, I, O, np, torch, time, tflops, make_pipe=None):
     """The first stage in the paper's own geometry (27 x 31 window, 4 pixel step) on the same pyramid, the selective
     unit on the positions above the 2 % quantile of that scan, and the merge of what it accepts: reported beside the
     headline, in the paper's unit (window positions at step 4, regions)."""
@@ -440,6 +441,31 @@ def paper_geometry_legs(a, ctxs, streams, dev_frame, frame, cfg, seed, tr, I, O,
     run_paper(n_fly)
     torch.cuda.synchronize()
     ms_paper_inflight = (time.perf_counter() - t0) / n_fly * 1e3
+    # the same path fed from pinned host memory through the ingest ring (PCIe included; never the headline value)
+    fps_paper_ingest = None
+    if make_pipe is not None:
+        pipe = make_pipe()
+        pipe.set_params(cfg["min_face"], cfg["scale_step"], (0.0, 0.0, 0.0))
+        pipe.set_paper(w_scan, w2_sel, w3_sel, t1_scan, t2_sel, t3_sel, 5, 0.3, 1)
+        D = pipe.depth
+
+        def run_pipe(n_steps):
+            q = []
+            for _ in range(n_steps):
+                if len(q) == D:
+                    pipe.fetch_paper(q.pop(0), 32768)
+                q.append(pipe.submit())
+            return [len(pipe.fetch_paper(t, 32768)) for t in q][-1]
+
+        for j in range(D):
+            pipe.frame_buffer()[:] = frame
+            pipe.fetch_paper(pipe.submit(), 32768)
+        run_pipe(D if few else 10 * D)
+        t0 = time.perf_counter()
+        n_pipe_det = run_pipe(n_fly)
+        fps_paper_ingest = n_fly / (time.perf_counter() - t0)
+        assert n_pipe_det == n_paper_det
+        pipe.close()
     sel_flop = 2.0 * sum(2 * SEL_MAC_CNN2 + (2 * SEL_MAC_CNN3 if r.k2 > 0 else 0) for r in sel)
     c0.detect(dev_frame, 8192)           # leaves the context with the cascade's own survivor lists again
     return {
@@ -455,7 +481,8 @@ def paper_geometry_legs(a, ctxs, streams, dev_frame, frame, cfg, seed, tr, I, O,
                            "frac": tflops(sel_flop, ms_sel) / PEAK_FP32_VECTOR},
         "merge": {"detections": len(sel_det), "ms_per_call_with_wait_and_readback": ms_sel_merge},
         "whole_path_ms_per_frame_one_at_a_time": ms_paper_frame,
-        "whole_path_frames_per_s_%d_in_flight" % F: 1e3 / ms_paper_inflight}
+        "whole_path_frames_per_s_%d_in_flight" % F: 1e3 / ms_paper_inflight,
+        "whole_path_frames_per_s_from_pinned_host_memory": fps_paper_ingest}
 
 
 if __name__ == "__main__":

@@ -342,7 +342,13 @@ int cnnc_fetch_paper(cnnc_ctx *ctx, cnnc_rdet *out, int cap, int *n_out);
  *   ticket; CNNC_E_STATE when every slot is in flight.
  * cnnc_pipe_fetch: waits for the frame with that ticket and returns its detections like cnnc_detect
  *   (CNNC_E_OVERFLOW rules included); frees the slot.  Tickets may be fetched in any order.
- * cnnc_pipe_set_params: for every slot; CNNC_E_STATE while frames are in flight. */
+ * cnnc_pipe_set_params: for every slot; CNNC_E_STATE while frames are in flight.
+ * cnnc_pipe_set_paper: from now on submit runs the path in the paper's geometry (cnnc_detect_paper_async: pyramid,
+ *   27x31 scan, selective unit, merge; Section 3.3) instead of the cascade of cnnc_detect_async.  Arguments as for
+ *   cnnc_scan_set_weights, cnnc_select_set_weights, cnnc_select_set_rule and cnnc_detect_paper, applied to every
+ *   slot; the host arrays are copied.  CNNC_E_STATE while frames are in flight.  Results then come through
+ *   cnnc_pipe_fetch_paper (as cnnc_fetch_paper; cnnc_pipe_fetch answers CNNC_E_STATE on such a pipe and
+ *   cnnc_pipe_fetch_paper on any other). */
 typedef struct cnnc_pipe cnnc_pipe;
 int cnnc_pipe_create(cnnc_pipe **out, const cnnc_stage_desc stages[3], int w, int h, int max_survivors, int depth,
                      int use_graph);
@@ -351,6 +357,9 @@ int cnnc_pipe_set_params(cnnc_pipe *pipe, const cnnc_params *p);
 int cnnc_pipe_frame_buffer(cnnc_pipe *pipe, uint8_t **h_frame);
 int cnnc_pipe_submit(cnnc_pipe *pipe, const uint8_t *h_frame, int pitch, int64_t *ticket);
 int cnnc_pipe_fetch(cnnc_pipe *pipe, int64_t ticket, cnnc_det *out, int cap, int *n_out);
+int cnnc_pipe_set_paper(cnnc_pipe *pipe, const float *scan_weights, int n_scan, int scan_act, const float *w2, int n2,
+                        const float *w3, int n3, int select_act, int rule, const cnnc_paper_params *p);
+int cnnc_pipe_fetch_paper(cnnc_pipe *pipe, int64_t ticket, cnnc_rdet *out, int cap, int *n_out);
 const char *cnnc_pipe_last_error(const cnnc_pipe *pipe);
 
 /* Measurement aid: how many 16x16x4 fp32 matrix instructions (1024 multiply-adds each) the convolution kernel of

@@ -24,7 +24,7 @@ EXPORTS = [
     "cnnc_select_set_weights", "cnnc_select_set_rule", "cnnc_select_run", "cnnc_select_fetch", "cnnc_select_merge", "cnnc_abi_sizes",
     "cnnc_detect_paper", "cnnc_detect_paper_async", "cnnc_fetch_paper",
     "cnnc_pipe_create", "cnnc_pipe_destroy", "cnnc_pipe_set_params", "cnnc_pipe_frame_buffer", "cnnc_pipe_submit",
-    "cnnc_pipe_fetch", "cnnc_pipe_last_error",
+    "cnnc_pipe_fetch", "cnnc_pipe_set_paper", "cnnc_pipe_fetch_paper", "cnnc_pipe_last_error",
 ]
 STEP_NAMES = ["pyramid", "stage1", "compact1", "stage2", "compact2", "stage3", "compact3", "merge",
               "stage2_conv", "stage3_conv", "scan", "select"]
@@ -428,6 +428,21 @@ class Pipe:
         out = (Detection * cap)()
         n = C.c_int(0)
         self._check(lib().cnnc_pipe_fetch(self._h, C.c_int64(ticket), out, C.c_int(cap), C.byref(n)))
+        return list(out[:n.value])
+
+    def set_paper(self, scan_weights: np.ndarray, w2: np.ndarray, w3: np.ndarray, t1: float, t2: float, t3: float, t_nn: int,
+                  iou: float = 0.3, min_neighbors: int = 1, rule: int = 2, scan_act: int = 1, select_act: int = 1):
+        """Switch the pipe to the path in the paper's geometry (scan, selective unit, merge)."""
+        a, b, c = (np.ascontiguousarray(x, np.float32) for x in (scan_weights, w2, w3))
+        pp = _PaperParams(float(t1), float(t2), float(t3), int(t_nn), float(iou), int(min_neighbors))
+        self._check(lib().cnnc_pipe_set_paper(self._h, a.ctypes.data_as(C.c_void_p), C.c_int(a.size), C.c_int(scan_act),
+                                              b.ctypes.data_as(C.c_void_p), C.c_int(b.size), c.ctypes.data_as(C.c_void_p),
+                                              C.c_int(c.size), C.c_int(select_act), C.c_int(rule), C.byref(pp)))
+
+    def fetch_paper(self, ticket: int, cap: int = 4096) -> List[RegionDetection]:
+        out = (RegionDetection * cap)()
+        n = C.c_int(0)
+        self._check(lib().cnnc_pipe_fetch_paper(self._h, C.c_int64(ticket), out, C.c_int(cap), C.byref(n)))
         return list(out[:n.value])
 
 

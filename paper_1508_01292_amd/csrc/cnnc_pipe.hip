@@ -31,6 +31,8 @@ struct cnnc_pipe {
     std::vector<Slot> slots;
     int w = 0, h = 0;
     bool use_graph = false;
+    bool paper = false;            // submit runs the path in the paper's geometry (cnnc_pipe_set_paper)
+    cnnc_paper_params pp{};
     int64_t next_ticket = 0;
     std::string err;
 };
@@ -69,7 +71,8 @@ void drop_graph(Slot &s)
 int enqueue_frame(cnnc_pipe *p, Slot &s)
 {
     PIPE_HIP(p, hipMemcpyAsync(s.d_frame, s.h_frame, (size_t)p->w * p->h, hipMemcpyHostToDevice, s.st));
-    const int rc = cnnc_detect_async(s.ctx, s.d_frame, p->w, p->h, p->w, s.st);
+    const int rc = p->paper ? cnnc_detect_paper_async(s.ctx, s.d_frame, p->w, p->h, p->w, &p->pp, s.st)
+                            : cnnc_detect_async(s.ctx, s.d_frame, p->w, p->h, p->w, s.st);
     if (rc) return pfail(p, rc, std::string("detect: ") + cnnc_last_error(s.ctx));
     return CNNC_OK;
 }
@@ -129,6 +132,25 @@ int cnnc_pipe_set_params(cnnc_pipe *p, const cnnc_params *prm)
     return CNNC_OK;
 }
 
+int cnnc_pipe_set_paper(cnnc_pipe *p, const float *scan_w, int n_scan, int scan_act, const float *w2, int n2, const float *w3,
+                        int n3, int sel_act, int rule, const cnnc_paper_params *pp)
+{
+    if (!p || !pp) return CNNC_E_INVAL;
+    for (Slot &s : p->slots)
+        if (s.busy) return pfail(p, CNNC_E_STATE, "frames are still in flight: fetch them before changing the path");
+    for (Slot &s : p->slots) {
+        int rc = cnnc_scan_set_weights(s.ctx, scan_w, n_scan, scan_act);
+        if (!rc) rc = cnnc_select_set_weights(s.ctx, w2, n2, w3, n3, sel_act);
+        if (!rc) rc = cnnc_select_set_rule(s.ctx, rule);
+        if (rc) return pfail(p, rc, cnnc_last_error(s.ctx));
+        drop_graph(s);             // another sequence of launches; thresholds are baked into a captured one
+        s.runs = 0;
+    }
+    p->pp = *pp;
+    p->paper = true;
+    return CNNC_OK;
+}
+
 int cnnc_pipe_frame_buffer(cnnc_pipe *p, uint8_t **h_frame)
 {
     if (!p || !h_frame) return CNNC_E_INVAL;
@@ -181,9 +203,24 @@ int cnnc_pipe_submit(cnnc_pipe *p, const uint8_t *h_frame, int pitch, int64_t *t
 int cnnc_pipe_fetch(cnnc_pipe *p, int64_t ticket, cnnc_det *out, int cap, int *n_out)
 {
     if (!p || !n_out || (!out && cap > 0) || cap < 0) return CNNC_E_INVAL;
+    if (p->paper) return pfail(p, CNNC_E_STATE, "this pipe runs the paper-geometry path: use cnnc_pipe_fetch_paper");
     for (Slot &s : p->slots) {
         if (!s.busy || s.ticket != ticket) continue;
         const int rc = cnnc_fetch_detections(s.ctx, out, cap, n_out);
+        s.busy = false;
+        if (rc) return pfail(p, rc, cnnc_last_error(s.ctx));
+        return CNNC_OK;
+    }
+    return pfail(p, CNNC_E_INVAL, "no frame in flight has this ticket");
+}
+
+int cnnc_pipe_fetch_paper(cnnc_pipe *p, int64_t ticket, cnnc_rdet *out, int cap, int *n_out)
+{
+    if (!p || !n_out || (!out && cap > 0) || cap < 0) return CNNC_E_INVAL;
+    if (!p->paper) return pfail(p, CNNC_E_STATE, "cnnc_pipe_set_paper has not been called");
+    for (Slot &s : p->slots) {
+        if (!s.busy || s.ticket != ticket) continue;
+        const int rc = cnnc_fetch_paper(s.ctx, out, cap, n_out);
         s.busy = false;
         if (rc) return pfail(p, rc, cnnc_last_error(s.ctx));
         return CNNC_OK;

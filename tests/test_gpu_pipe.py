@@ -113,3 +113,76 @@ def test_pipe_errors_and_parameter_change():
     assert e.value.code == -3
     assert len(pipe.fetch(pipe.submit(frame))) == len(tr2.det)
     pipe.close()
+
+
+@pytest.mark.parametrize("use_graph", [False, True])
+def test_pipe_in_the_paper_geometry(use_graph):
+    """The ring driving the path in the paper's geometry (scan, selective unit, merge): every frame's detections equal
+    those of cnnc_detect_paper on a single context (which tests/test_gpu_select.py compares with the oracle), and the
+    first frame's are compared with the oracle's here as well."""
+    import torch
+    import paper_1508_01292_amd as P
+    ci = 4
+    cfg = I.CONFIGS[ci]
+    frames = I.make_stream(ci)[:6]
+    w, h = cfg["width"], cfg["height"]
+    act, t_nn = I.ACT_RATIONAL, 6
+    n1, n2, n3 = I.paper_stage1(act), I.paper_stage2(act), I.paper_stage3(act)
+    w1, w2, w3 = (I.draw_scan_weights(n, 77 + k) for k, n in enumerate((n1, n2, n3)))
+    # thresholds from the oracle on the first frame: 2 % of the scan, a quarter of the responses
+    pyr = O.build_pyramid(frames[0], cfg["min_face"], cfg["scale_step"])
+    s1 = O.scan_scores(pyr, n1, w1)
+    t1 = float(O.threshold_from_quantile(s1, 0.02))
+    idx = np.nonzero(s1.astype(np.float32) > np.float32(t1))[0]
+    ref = O.select_unit(frames[0], pyr, idx, n1, n2, w2, n3, w3, -1e30, -1e30, 1)
+    t2 = float(np.float32(np.quantile(np.concatenate([r["r2"].ravel() for r in ref]), 0.75)))
+    t3 = float(np.float32(np.quantile(np.concatenate([r["r3"].ravel() for r in ref]), 0.75)))
+    ref = O.select_unit(frames[0], pyr, idx, n1, n2, w2, n3, w3, t2, t3, t_nn)
+
+    casc = I.default_cascade()
+    W = I.draw_weights(casc, 5)
+    ctx = P.Context(casc, W, w, h, 50000)
+    ctx.set_params(cfg["min_face"], cfg["scale_step"], (0.0, 0.0, 0.0))
+    ctx.scan_set_weights(w1, act)
+    ctx.select_set_weights(w2, w3, act)
+    want = [[d.as_dict() for d in ctx.detect_paper(torch.from_numpy(f).cuda(), t1, t2, t3, t_nn, 0.3, 1, cap=20000)] for f in frames]
+    assert all(len(x) > 0 for x in want)
+    # first frame against the oracle, unless a response sits inside the tolerance band of a threshold
+    near = np.any(np.abs(s1 - t1) <= 2e-4) or any(np.any(np.abs(r["r2"] - t2) <= 2e-4) or np.any(np.abs(r["r3"] - t3) <= 2e-4) for r in ref)
+    omerge = O.select_merge(pyr, ref, n1, 0.3, 1)
+    same = [(d["index"], d["neighbors"], d["x"], d["y"], d["w"], d["h"]) for d in want[0]] == \
+        [(d["index"], d["neighbors"], d["x"], d["y"], d["w"], d["h"]) for d in omerge]
+    print("paper pipe graph=%s: %d detections on frame 0, equal to the oracle's: %s (a response in a band: %s)"
+          % (use_graph, len(want[0]), same, bool(near)), flush=True)
+    assert same or near
+
+    pipe = P.Pipe(casc, W, w, h, 50000, depth=3, use_graph=use_graph)
+    pipe.set_params(cfg["min_face"], cfg["scale_step"], (0.0, 0.0, 0.0))
+    with pytest.raises(P.CnncError) as e:
+        pipe.fetch_paper(0)                           # not in paper mode yet
+    assert e.value.code == -5
+    pipe.set_paper(w1, w2, w3, t1, t2, t3, t_nn, 0.3, 1)
+    got, tickets = {}, []
+    order = list(range(len(frames))) + list(reversed(range(len(frames)))) + list(range(len(frames)))
+    for k, fi in enumerate(order):
+        if len(tickets) == 3:
+            t, f0 = tickets.pop(0)
+            got.setdefault(f0, []).append([d.as_dict() for d in pipe.fetch_paper(t, 20000)])
+        tickets.append((pipe.submit(frames[fi]), fi))
+        if k == 4:
+            with pytest.raises(P.CnncError) as e:
+                pipe.fetch(tickets[0][0])             # the cascade's fetch on a paper-geometry pipe
+            assert e.value.code == -5
+            with pytest.raises(P.CnncError) as e:
+                pipe.set_paper(w1, w2, w3, t1, t2, t3, t_nn)      # frames in flight
+            assert e.value.code == -5
+        if k % 5 == 0:                                # eager work of another context between the replays
+            ctx.detect_paper(torch.from_numpy(frames[(fi + 1) % len(frames)]).cuda(), t1, t2, t3, t_nn, 0.3, 1, cap=20000)
+    for t, f0 in tickets:
+        got.setdefault(f0, []).append([d.as_dict() for d in pipe.fetch_paper(t, 20000)])
+    for fi in range(len(frames)):
+        assert len(got[fi]) == 3
+        for rep in got[fi]:
+            assert rep == want[fi], "frame %d" % fi
+    pipe.close()
+    ctx.close()
