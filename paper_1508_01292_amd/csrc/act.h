@@ -27,6 +27,13 @@ __device__ __forceinline__ float act_f(float x)
     return x;
 }
 
+// The value that the neighbouring lane (lane ^ 1) holds: a DPP move inside the quad, on the vector ALU, instead of the
+// trip through the LDS crossbar that a general shuffle takes.
+__device__ __forceinline__ float lane_xor1(float v)
+{
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0xB1 /* quad_perm [1, 0, 3, 2] */, 0xF, 0xF, true));
+}
+
 // Pixel value (possibly a blend, 0..255) to network input.
 __device__ __forceinline__ float normalise(float p) { return (p - 128.0f) * 0.0078125f; }
 

@@ -773,8 +773,8 @@ void eval2_conv_kernel(const uint8_t *__restrict__ frame, int fw, int fh, int pi
 #pragma unroll
             for (int u = 0; u < NT; ++u) {
                 float lo = fmaxf(acc[u][0], acc[u][1]), hi = fmaxf(acc[u][2], acc[u][3]);
-                lo = fmaxf(lo, __shfl_xor(lo, 1, 64));
-                hi = fmaxf(hi, __shfl_xor(hi, 1, 64));
+                lo = fmaxf(lo, lane_xor1(lo));
+                hi = fmaxf(hi, lane_xor1(hi));
                 const int pb = 8 * (t0 + u) + out_blk;                // even lanes finish the first block, odd the second
                 if (pb < 100) sP1[(j >> 1) * kQ1Ch + (sLut[pb] >> 16)] = act_f<ACT>(((j & 1) ? hi : lo) + bias1);
             }

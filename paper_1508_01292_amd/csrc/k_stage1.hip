@@ -200,7 +200,7 @@ void stage1_kernel(const uint8_t *__restrict__ pyr, const LevelDev *__restrict__
             }
         }
 #pragma unroll
-        for (int p = 0; p < 4; ++p) acc[p] += __shfl_xor(acc[p], 1, 64);
+        for (int p = 0; p < 4; ++p) acc[p] += lane_xor1(acc[p]);
         const int y = oy + r;
         float *row = score + (size_t)L.score_off + (size_t)y * L.ow;
         const float b3 = wt[s1::B3];
