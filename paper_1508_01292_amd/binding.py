@@ -20,6 +20,7 @@ EXPORTS = [
     "cnnc_get_survivors", "cnnc_get_stage_scores", "cnnc_survivor_count", "cnnc_set_timing",
     "cnnc_get_timings", "cnnc_set_eval_impl", "cnnc_executed_mfma", "cnnc_measure_peaks", "cnnc_last_error", "cnnc_version",
     "cnnc_stage1_survivors", "cnnc_set_fused_stage1", "cnnc_set_async_chunks", "cnnc_compact_noalloc",
+    "cnnc_set_literal_weights", "cnnc_literal_weights",
     "cnnc_scan_set_weights", "cnnc_scan_layout", "cnnc_scan_scoremap", "cnnc_get_scan_scoremap",
     "cnnc_select_set_weights", "cnnc_select_set_rule", "cnnc_select_run", "cnnc_select_fetch", "cnnc_select_merge", "cnnc_abi_sizes",
     "cnnc_detect_paper", "cnnc_detect_paper_async", "cnnc_fetch_paper",
@@ -344,6 +345,13 @@ class Context:
         self._check(lib().cnnc_fetch_paper(self._h, out, C.c_int(cap), C.byref(n)))
         return list(out[:n.value])
 
+    def set_literal_weights(self, on: bool):
+        self._check(lib().cnnc_set_literal_weights(self._h, C.c_int(1 if on else 0)))
+
+    def literal_weights(self) -> bool:
+        """True when stage 1 runs the build of its kernel that carries this context's weights as instruction literals."""
+        return bool(lib().cnnc_literal_weights(self._h))
+
     def set_eval_impl(self, impl: int):
         self._check(lib().cnnc_set_eval_impl(self._h, C.c_int(impl)))
 
@@ -478,7 +486,7 @@ _CTX_CALLS = ("set_params", "pyramid_layout", "build_pyramid", "stage1_scoremap"
               "get_pyramid", "get_scoremap", "get_survivors", "get_stage_scores", "survivor_count", "set_eval_impl",
               "executed_mfma", "set_timing", "get_timings", "scan_set_weights", "scan_layout", "scan_scoremap",
               "get_scan_scoremap", "select_set_weights", "select_set_rule", "select_run", "select_fetch", "select_merge", "detect_paper",
-              "detect_paper_async", "fetch_paper")
+              "detect_paper_async", "fetch_paper", "set_literal_weights", "literal_weights")
 
 
 def _c_spelling(method):

@@ -305,6 +305,7 @@ int cnnc_create(cnnc_ctx **out, const cnnc_stage_desc stages[3], int max_w, int 
         if (hipMemcpy(c->d_wt[s], stages[s].weights, sizeof(float) * n_params[s], hipMemcpyHostToDevice) != hipSuccess)
             return bail(CNNC_E_HIP);
     }
+    c->s1_literal = stage1_literal_create(stages[0].weights);    // optional: without it stage 1 reads its weights from memory
     {
         std::vector<float> frag(eval2_frag_floats());
         eval2_make_fragments(stages[1].weights, frag.data());
@@ -352,6 +353,8 @@ int cnnc_destroy(cnnc_ctx *c)
     (void)hipDeviceSynchronize();
     for (int s = 0; s < 3; ++s) { (void)hipFree(c->d_wt[s]); (void)hipFree(c->d_idx[s]); (void)hipFree(c->d_sc[s]); }
     for (int s = 0; s < 2; ++s) { (void)hipFree(c->d_eval[s]); (void)hipFree(c->d_frag[s]); (void)hipFree(c->d_feat[s]); }
+    stage1_literal_destroy(c->s1_literal);
+    c->s1_literal = nullptr;
     scan_release(c);
     select_release(c);
     (void)hipFree(c->d_levels); (void)hipFree(c->d_taps); (void)hipFree(c->d_tiles_pyr); (void)hipFree(c->d_tiles_s1);
@@ -460,6 +463,15 @@ int cnnc_stage1_survivors(cnnc_ctx *c, float thr, void *stream)
     c->progress = DONE_PYR | DONE_C1;      // no score map: cnnc_get_scoremap reports CNNC_E_STATE
     return CNNC_OK;
 }
+
+int cnnc_set_literal_weights(cnnc_ctx *c, int on)
+{
+    if (!c) return CNNC_E_INVAL;
+    c->use_literals = on != 0;
+    return CNNC_OK;
+}
+
+int cnnc_literal_weights(const cnnc_ctx *c) { return c && c->use_literals && c->s1_literal ? 1 : 0; }
 
 int cnnc_set_fused_stage1(cnnc_ctx *c, int on)
 {

@@ -81,6 +81,8 @@ struct StepTimer {
     int calls = 0;
 };
 
+struct Stage1Literal;
+
 }  // namespace cnnc
 
 struct cnnc_ctx {
@@ -147,6 +149,8 @@ struct cnnc_ctx {
     int64_t cap_pyr = 0, cap_score1 = 0, cap_taps = 0, cap_tiles_pyr = 0, cap_tiles_s1 = 0, cap_mask1 = 0;
     int64_t n_words = 0;
     bool fused_stage1 = false;       // cnnc_detect uses cnnc_stage1_survivors instead of score map + compaction
+    cnnc::Stage1Literal *s1_literal = nullptr;   // stage 1 with this context's weights as instruction literals (or none)
+    bool use_literals = true;        // cnnc_set_literal_weights
 
     // survivor lists (capacity max_surv each)
     uint32_t *d_idx[3] = {nullptr, nullptr, nullptr};
@@ -183,6 +187,10 @@ struct cnnc_ctx {
 };
 
 namespace cnnc {
+
+// Stage 1 with a weight set written into its code (k_stage1.hip); nullptr when that module does not load.
+Stage1Literal *stage1_literal_create(const float *weights);
+void stage1_literal_destroy(Stage1Literal *s);
 
 // Kernel launchers (one translation unit each).  All enqueue on `st` and return the launch status.
 hipError_t launch_pyramid(const cnnc_ctx *c, hipStream_t st);

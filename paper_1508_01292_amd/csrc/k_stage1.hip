@@ -1,231 +1,73 @@
 // Stage 1 (paper, Section 3.3: the first CNN densely scans every pyramid image; Section 3.4: the
 // network is coded as one fused routine instead of a stack of layers).
 //
-// One launch covers every level through a (level, tile) table.  A workgroup produces a
-// kS1TileW x kS1TileH tile of the score map from the (tile + 11)^2 input patch, all intermediates
-// in LDS.  The stride-2 pool of the 12x12 network becomes a stride-1 max map M and a tap spacing
-// of 2 in everything after it, which gives exactly the per-window result at every position:
-//   A_c = f(b1_c + sum w1_c[a][b] X(y+a, x+b))                      conv 3x3, 1 -> 4
-//   M_c = max of A_c over (y..y+1, x..x+1)
-//   C_k = f(b2_k + sum w2_k[c][a][b] M_c(y+2a, x+2b))              conv 3x3, 4 -> 8, spacing 2
-//   score = b3 + sum w3[k][i][j] C_k(y+2i, x+2j)                    fc over 8x3x3, spacing 2
-//
-// Register blocking: a thread computes four (conv2: three) neighbouring positions at a time, so every
-// LDS value is read once per unit.  For the spacing-2 layers the maps M and C are stored with even and
-// odd columns apart ([channel][row][column parity][column / 2]); the positions of a thread are then
-// consecutive entries of one parity, and their taps are consecutive too.  The unit sizes are chosen so
-// that every phase fills the 256 threads (250, 240, 240, 256 units).  Weights are wave-uniform and come
-// through scalar loads.
-#include "act.h"
-#include "cnnc_internal.h"
+// One launch covers every level through a (level, tile) table; the work of a workgroup is in stage1_body.h.
+// Two builds of it exist: stage1_kernel reads its weights from memory (wave-uniform scalar loads), and the code
+// object of k_stage1_lit.hip carries them as instruction literals, written in by the host for the context's weight
+// set (literal_weights.h).  The second issues its multiply-adds at up to twice the rate and gives the same bits; it
+// is used whenever its module loads.
+#include "literal_weights.h"
+#include "stage1_body.h"
+
+#include "stage1_lit_image.inc"      // written by the build: kStage1LitImage, kStage1LitPatch
 
 namespace cnnc {
 
-namespace {
-constexpr int TW = kS1TileW, TH = kS1TileH;
-static_assert(TW == 32 && TH == 16, "the unit decomposition below is written for 32 x 16 tiles");
-constexpr int kThreads = 256;
-constexpr int IN_H = TH + 11, IN_P = 44;          // input patch rows, row pitch (43 columns used)
-constexpr int A_H = TH + 9, A_P = 44;             // conv1 map: 41 columns used
-constexpr int M_H = TH + 8, M_P = 40;             // max map: 2 parities x 20 columns
-constexpr int C_H = TH + 4, C_P = 40;             // conv2 map: 2 parities x 20 columns (18 used)
-constexpr int kIn = IN_H * IN_P + 4, kA = 4 * A_H * A_P, kM = 4 * M_H * M_P, kC = 8 * C_H * C_P;
-constexpr int kRegionX = kC > kA + kIn ? kC : kA + kIn;   // A maps + input, later the C maps
+using s1body::kThreads;
 
-typedef uint32_t __attribute__((aligned(1))) pixel_quad;        // four neighbouring pixels of a row, any address
-
-struct f6 { float v[6]; };
-// six consecutive floats starting at a 16-byte aligned LDS address
-__device__ __forceinline__ f6 load6(const float *p)
-{
-    const float4 a = *reinterpret_cast<const float4 *>(p);
-    const float2 b = *reinterpret_cast<const float2 *>(p + 4);
-    return {{a.x, a.y, a.z, a.w, b.x, b.y}};
-}
-}  // namespace
-
-// EMIT = false: every score goes to the score map.  EMIT = true: only windows with score > thr leave the kernel,
-// as one bit per window (a word per 32-window row of the tile, so each word has one writer and needs no clearing)
-// plus the score at the window's place in the map.
 template <int ACT, bool EMIT>
 __global__ __launch_bounds__(kThreads)
 void stage1_kernel(const uint8_t *__restrict__ pyr, const LevelDev *__restrict__ levels,
                    const uint32_t *__restrict__ tiles, const float *__restrict__ wt,
                    float *__restrict__ score, float thr, uint32_t *__restrict__ mask)
 {
-    // 40 KiB: four workgroups share a compute unit's LDS.  sM sits first so that the two floats some lanes
-    // read past its end (feeding only discarded columns) fall inside the same array.
-    __shared__ __attribute__((aligned(16))) float sAll[kM + kRegionX];
-    float *sM = sAll, *sX = sAll + kM;
-    float *sA = sX;                 // [4][A_H][A_P]
-    float *sIn = sX + kA;           // [IN_H][IN_P]
-    float *sC = sX;                 // [8][C_H][2][20], written after A and the input are dead
-
-    const uint32_t t = tiles[blockIdx.x];
-    const int lvl = t >> 24, oy = ((t >> 12) & 0xFFF) * TH, ox = (t & 0xFFF) * TW;
-    const LevelDev L = levels[lvl];
-    const uint8_t *img = pyr + L.pyr_off;
-    const int tid = threadIdx.x;
-
-    // ---- input patch, normalised; positions past the level edge repeat the edge (they only feed
-    // outputs that are not written)
-    if (ox + IN_P <= L.w && oy + IN_H <= L.h) {
-        // the whole patch lies inside the level: four pixels a load
-        for (int e = tid; e < IN_H * (IN_P / 4); e += kThreads) {
-            const int r = e / (IN_P / 4), c = 4 * (e % (IN_P / 4));
-            const uint32_t p = *reinterpret_cast<const pixel_quad *>(img + (size_t)(oy + r) * L.w + ox + c);
-            *reinterpret_cast<float4 *>(sIn + r * IN_P + c) =
-                make_float4(normalise((float)(p & 255u)), normalise((float)((p >> 8) & 255u)),
-                            normalise((float)((p >> 16) & 255u)), normalise((float)(p >> 24)));
-        }
-        if (tid < 4) sIn[IN_H * IN_P + tid] = 0.0f;
-    } else {
-        for (int e = tid; e < kIn; e += kThreads) {
-            const int r = min(e / IN_P, IN_H - 1), c = e % IN_P;
-            const int y = min(oy + r, L.h - 1), x = min(ox + c, L.w - 1);
-            sIn[e] = normalise((float)img[(size_t)y * L.w + x]);
-        }
-    }
-    __syncthreads();
-
-    // ---- conv1 + f: 25 rows x 10 groups of four columns, then the single column 40 by 25 threads of the last wave
-    if (tid < A_H * 10) {
-        const int r = tid / 10, x0 = 4 * (tid % 10);
-        float acc[4][4];
-#pragma unroll
-        for (int ch = 0; ch < 4; ++ch)
-#pragma unroll
-            for (int p = 0; p < 4; ++p) acc[ch][p] = wt[s1::B1 + ch];
-#pragma unroll
-        for (int a = 0; a < 3; ++a) {
-            const f6 in = load6(sIn + (r + a) * IN_P + x0);
-#pragma unroll
-            for (int b = 0; b < 3; ++b)
-#pragma unroll
-                for (int ch = 0; ch < 4; ++ch)
-#pragma unroll
-                    for (int p = 0; p < 4; ++p) acc[ch][p] = fmaf(wt[s1::W1 + ch * 9 + a * 3 + b], in.v[p + b], acc[ch][p]);
-        }
-#pragma unroll
-        for (int ch = 0; ch < 4; ++ch)
-            *reinterpret_cast<float4 *>(sA + (ch * A_H + r) * A_P + x0) =
-                make_float4(act_f<ACT>(acc[ch][0]), act_f<ACT>(acc[ch][1]), act_f<ACT>(acc[ch][2]), act_f<ACT>(acc[ch][3]));
-    }
-    if (tid >= 192 && tid < 192 + A_H) {
-        // column 40: a row each, all four channels
-        const int r = tid - 192;
-        float acc[4];
-#pragma unroll
-        for (int ch = 0; ch < 4; ++ch) acc[ch] = wt[s1::B1 + ch];
-#pragma unroll
-        for (int a = 0; a < 3; ++a)
-#pragma unroll
-            for (int b = 0; b < 3; ++b) {
-                const float v = sIn[(r + a) * IN_P + 40 + b];
-#pragma unroll
-                for (int ch = 0; ch < 4; ++ch) acc[ch] = fmaf(wt[s1::W1 + ch * 9 + a * 3 + b], v, acc[ch]);
-            }
-#pragma unroll
-        for (int ch = 0; ch < 4; ++ch) sA[(ch * A_H + r) * A_P + 40] = act_f<ACT>(acc[ch]);
-    }
-    __syncthreads();
-
-    // ---- stride-1 2x2 max, stored with even and odd columns apart: 24 rows x 10 groups of four columns
-    if (tid < M_H * 10) {
-        const int r = tid / 10, g = tid % 10, x0 = 4 * g;
-#pragma unroll
-        for (int ch = 0; ch < 4; ++ch) {
-            const float *p0 = sA + (ch * A_H + r) * A_P + x0, *p1 = p0 + A_P;
-            const float4 u = *reinterpret_cast<const float4 *>(p0), v = *reinterpret_cast<const float4 *>(p1);
-            const float u4 = p0[4], v4 = p1[4];
-            const float c0 = fmaxf(u.x, v.x), c1 = fmaxf(u.y, v.y), c2 = fmaxf(u.z, v.z), c3 = fmaxf(u.w, v.w),
-                        c4 = fmaxf(u4, v4);
-            float *m = sM + (ch * M_H + r) * M_P + 2 * g;
-            *reinterpret_cast<float2 *>(m) = make_float2(fmaxf(c0, c1), fmaxf(c2, c3));        // even columns x0, x0+2
-            *reinterpret_cast<float2 *>(m + 20) = make_float2(fmaxf(c1, c2), fmaxf(c3, c4));   // odd columns x0+1, x0+3
-        }
-    }
-    __syncthreads();
-
-    // ---- conv2 (tap spacing 2) + f: 20 rows x 2 parities x 6 groups of three same-parity columns (18 per parity
-    // are needed), all 8 channels: 240 units for the 256 threads
-    if (tid < C_H * 12) {
-        const int r = tid / 12, px = (tid % 12) / 6, j0 = 3 * (tid % 6);
-        float acc[8][3];
-#pragma unroll
-        for (int k = 0; k < 8; ++k)
-#pragma unroll
-            for (int p = 0; p < 3; ++p) acc[k][p] = wt[s1::B2 + k];
-#pragma unroll
-        for (int ch = 0; ch < 4; ++ch)
-#pragma unroll
-            for (int a = 0; a < 3; ++a) {
-                const float *mp = sM + (ch * M_H + r + 2 * a) * M_P + px * 20 + j0;
-                float m[5];
-#pragma unroll
-                for (int b = 0; b < 5; ++b) m[b] = mp[b];
-#pragma unroll
-                for (int b = 0; b < 3; ++b)
-#pragma unroll
-                    for (int k = 0; k < 8; ++k)
-#pragma unroll
-                        for (int p = 0; p < 3; ++p)
-                            acc[k][p] = fmaf(wt[s1::W2 + ((k * 4 + ch) * 3 + a) * 3 + b], m[p + b], acc[k][p]);
-            }
-#pragma unroll
-        for (int k = 0; k < 8; ++k)
-#pragma unroll
-            for (int p = 0; p < 3; ++p) sC[(k * C_H + r) * C_P + px * 20 + j0 + p] = act_f<ACT>(acc[k][p]);
-    }
-    __syncthreads();
-
-    // ---- fc over the 8x3x3 block at tap spacing 2: 16 rows x 2 parities x 4 groups of four columns, and
-    // two threads per unit that take four channels each and add their halves
-    {
-        const int half = tid & 1, u = tid >> 1;
-        const int r = u / 8, px = (u % 8) / 4, j0 = 4 * (u % 4);
-        float acc[4] = {0.0f, 0.0f, 0.0f, 0.0f};
-#pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
-            const int k = 4 * half + kk;
-#pragma unroll
-            for (int i = 0; i < 3; ++i) {
-                const f6 c = load6(sC + (k * C_H + r + 2 * i) * C_P + px * 20 + j0);
-#pragma unroll
-                for (int j = 0; j < 3; ++j) {
-                    const float w = half ? wt[s1::W3 + ((4 + kk) * 3 + i) * 3 + j] : wt[s1::W3 + (kk * 3 + i) * 3 + j];
-#pragma unroll
-                    for (int p = 0; p < 4; ++p) acc[p] = fmaf(w, c.v[p + j], acc[p]);
-                }
-            }
-        }
-#pragma unroll
-        for (int p = 0; p < 4; ++p) acc[p] += lane_xor1(acc[p]);
-        const int y = oy + r;
-        float *row = score + (size_t)L.score_off + (size_t)y * L.ow;
-        const float b3 = wt[s1::B3];
-        uint32_t bits = 0;                       // EMIT: this thread's two windows of the row's 32-bit word
-#pragma unroll
-        for (int q = 0; q < 2; ++q) {            // this thread writes two of the unit's four outputs
-            const int p = 2 * half + q, x = ox + 2 * (j0 + p) + px;
-            const float sc = (half ? (q ? acc[3] : acc[2]) : (q ? acc[1] : acc[0])) + b3;
-            if (y < L.oh && x < L.ow) {
-                if (!EMIT) {
-                    row[x] = sc;
-                } else if (sc > thr) {
-                    row[x] = sc;
-                    bits |= 1u << (x - ox);
-                }
-            }
-        }
-        if (EMIT) {
-            // a row of the tile belongs to sixteen consecutive lanes: OR their bits, one of them stores the word
-#pragma unroll
-            for (int d = 1; d < 16; d <<= 1) bits |= __shfl_xor(bits, d, 64);
-            if ((tid & 15) == 0 && y < L.oh) mask[L.word_off + y * L.words_per_row + ox / TW] = bits;
-        }
-    }
+    s1body::stage1_tile<ACT, EMIT>(pyr, levels, tiles, wt, score, thr, mask);
 }
+
+// ---- the build with literal weights ---------------------------------------------------------------------------
+struct Stage1Literal {
+    LiteralModule *mod = nullptr;
+    hipFunction_t fn[3][2] = {{nullptr, nullptr}, {nullptr, nullptr}, {nullptr, nullptr}};   // [activation - 1][emit]
+};
+
+Stage1Literal *stage1_literal_create(const float *weights)
+{
+    static const LiteralImage img = {kStage1LitImage, sizeof(kStage1LitImage), kStage1LitPatch,
+                                     sizeof(kStage1LitPatch) / sizeof(kStage1LitPatch[0]), kS1Params};
+    LiteralModule *m = literal_acquire(img, weights);
+    if (!m) return nullptr;
+    Stage1Literal *s = new Stage1Literal();
+    s->mod = m;
+    static const char *const names[3][2] = {{"cnnc_s1_lit_act1", "cnnc_s1_lit_act1_emit"},
+                                            {"cnnc_s1_lit_act2", "cnnc_s1_lit_act2_emit"},
+                                            {"cnnc_s1_lit_act3", "cnnc_s1_lit_act3_emit"}};
+    for (int a = 0; a < 3; ++a)
+        for (int e = 0; e < 2; ++e)
+            if (!(s->fn[a][e] = literal_function(m, names[a][e]))) {
+                stage1_literal_destroy(s);
+                return nullptr;
+            }
+    return s;
+}
+
+void stage1_literal_destroy(Stage1Literal *s)
+{
+    if (!s) return;
+    literal_release(s->mod);
+    delete s;
+}
+
+namespace {
+hipError_t launch_literal(const cnnc_ctx *c, bool emit, int tile_begin, int n_tiles, float thr, uint32_t *mask, hipStream_t st)
+{
+    const uint8_t *pyr = c->d_pyr;
+    const LevelDev *levels = c->d_levels;
+    const uint32_t *tiles = c->d_tiles_s1 + tile_begin;
+    float *score = c->d_score1;
+    void *args[] = {&pyr, &levels, &tiles, &score, &thr, &mask};
+    return hipModuleLaunchKernel(c->s1_literal->fn[c->act - 1][emit ? 1 : 0], (unsigned)n_tiles, 1, 1, kThreads, 1, 1, 0, st, args, nullptr);
+}
+}  // namespace
 
 #define CNNC_S1(ACT, EMIT, THR, MASK)                                                                        \
     hipLaunchKernelGGL((stage1_kernel<ACT, EMIT>), grid, block, 0, st, c->d_pyr, c->d_levels, c->d_tiles_s1 + tile_begin, \
@@ -234,6 +76,7 @@ void stage1_kernel(const uint8_t *__restrict__ pyr, const LevelDev *__restrict__
 hipError_t launch_stage1(const cnnc_ctx *c, int tile_begin, int tile_end, hipStream_t st)
 {
     if (tile_end <= tile_begin) return hipSuccess;
+    if (c->s1_literal && c->use_literals) return launch_literal(c, false, tile_begin, tile_end - tile_begin, 0.0f, nullptr, st);
     dim3 grid(tile_end - tile_begin), block(kThreads);
     switch (c->act) {
     case CNNC_ACT_RATIONAL: CNNC_S1(CNNC_ACT_RATIONAL, false, 0.0f, (uint32_t *)nullptr); break;
@@ -246,6 +89,7 @@ hipError_t launch_stage1(const cnnc_ctx *c, int tile_begin, int tile_end, hipStr
 hipError_t launch_stage1_emit(const cnnc_ctx *c, float thr, hipStream_t st)
 {
     const int tile_begin = 0;
+    if (c->s1_literal && c->use_literals) return launch_literal(c, true, 0, c->n_tiles_s1, thr, c->d_mask1, st);
     dim3 grid(c->n_tiles_s1), block(kThreads);
     switch (c->act) {
     case CNNC_ACT_RATIONAL: CNNC_S1(CNNC_ACT_RATIONAL, true, thr, c->d_mask1); break;

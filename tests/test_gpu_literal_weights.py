@@ -1,0 +1,82 @@
+"""GPU tests of stage 1 with its weights as instruction literals: the build of the kernel whose literals the host
+overwrites with a context's weight set gives the same bits as the kernel that reads the weights from memory, for
+every activation, on ragged sizes, for the score map and for the fused survivor form; the scores are compared with
+the oracle as well.  Contexts with equal weights share a module, contexts with other weights get their own, and a
+module outlives the other contexts that used it."""
+import numpy as np
+import pytest
+
+import cnnc_inputs as I
+from oracle import oracle as O
+
+from parity import assert_scores
+
+pytestmark = pytest.mark.gpu
+
+
+def _scoremap(ctx, ft):
+    ctx.build_pyramid(ft)
+    ctx.stage1_scoremap()
+    return ctx.get_scoremap()
+
+
+@pytest.mark.parametrize("act", [I.ACT_RATIONAL, I.ACT_SCALED_TANH, I.ACT_TANH])
+def test_literal_build_equals_memory_build_and_oracle(act):
+    import torch
+    import paper_1508_01292_amd as P
+    for (w, h, mf, step, seed, bias_sd) in ((640, 480, 24.0, 1.25, 11, 0.0), (333, 257, 20.0, 1.31, 12, 0.5), (97, 61, 12.0, 1.5, 13, 1.0)):
+        print("literal weights: act", act, (w, h), flush=True)
+        frame = I.make_frame(w, h, seed)
+        casc = I.default_cascade(act)
+        W = I.draw_weights(casc, seed, bias_sd=bias_sd)
+        ctx = P.Context(casc, W, w, h, 100000)
+        ctx.set_params(mf, step, (0.0, 0.0, 0.0))
+        assert ctx.literal_weights(), "the literal build of stage 1 did not load"
+        ft = torch.from_numpy(frame).cuda()
+        lit = _scoremap(ctx, ft)
+        ctx.set_literal_weights(False)
+        assert not ctx.literal_weights()
+        mem = _scoremap(ctx, ft)
+        np.testing.assert_array_equal(lit, mem)
+        pyr = O.build_pyramid(frame, mf, step)
+        assert_scores(lit, O.stage1_scores(pyr, casc[0], W[0]), "stage 1, literal weights")
+        # the fused survivor form in both builds
+        thr = float(np.sort(mem)[-max(1, mem.size // 50)])
+        lists = []
+        for on in (True, False):
+            ctx.set_literal_weights(on)
+            ctx.build_pyramid(ft)
+            ctx.stage1_survivors(thr)
+            lists.append(ctx.get_survivors(1))
+        np.testing.assert_array_equal(lists[0][0], lists[1][0])
+        np.testing.assert_array_equal(lists[0][1], lists[1][1])
+        assert len(lists[0][0]) == int((mem > np.float32(thr)).sum())
+        ctx.close()
+
+
+def test_modules_are_per_weight_set_and_outlive_other_contexts():
+    import torch
+    import paper_1508_01292_amd as P
+    frame = I.make_frame(320, 240, 5)
+    ft = torch.from_numpy(frame).cuda()
+    casc = I.default_cascade()
+    Wa, Wb = I.draw_weights(casc, 1), I.draw_weights(casc, 2)
+    pyr = O.build_pyramid(frame, 24.0, 1.25)
+    want_a, want_b = O.stage1_scores(pyr, casc[0], Wa[0]), O.stage1_scores(pyr, casc[0], Wb[0])
+    a1 = P.Context(casc, Wa, 320, 240, 1000)
+    a2 = P.Context(casc, Wa, 320, 240, 1000)          # same weights: the same module
+    b = P.Context(casc, Wb, 320, 240, 1000)
+    for c in (a1, a2, b):
+        c.set_params(24.0, 1.25, (0.0, 0.0, 0.0))
+        assert c.literal_weights()
+    assert_scores(_scoremap(a1, ft), want_a, "a1")
+    assert_scores(_scoremap(b, ft), want_b, "b")
+    a1.close()                                         # a2 still holds the module of these weights
+    assert_scores(_scoremap(a2, ft), want_a, "a2 after a1 closed")
+    assert_scores(_scoremap(b, ft), want_b, "b again")
+    a2.close()
+    a3 = P.Context(casc, Wa, 320, 240, 1000)           # the module is built again
+    a3.set_params(24.0, 1.25, (0.0, 0.0, 0.0))
+    assert_scores(_scoremap(a3, ft), want_a, "a3")
+    a3.close()
+    b.close()
