@@ -300,12 +300,19 @@ int cnnc_create(cnnc_ctx **out, const cnnc_stage_desc stages[3], int max_w, int 
     auto bail = [&](int rc) { cnnc_destroy(c); return rc; };
     if (hipGetDevice(&c->device) != hipSuccess) return bail(CNNC_E_HIP);
     const int n_params[3] = {kS1Params, kS2Params, kS3Params};
-    for (int s = 0; s < 3; ++s) {
+    for (int s = 1; s < 3; ++s) {
         if (hipMalloc((void **)&c->d_wt[s], sizeof(float) * n_params[s]) != hipSuccess) return bail(CNNC_E_NOMEM);
         if (hipMemcpy(c->d_wt[s], stages[s].weights, sizeof(float) * n_params[s], hipMemcpyHostToDevice) != hipSuccess)
             return bail(CNNC_E_HIP);
     }
-    c->s1_literal = stage1_literal_create(stages[0].weights);    // optional: without it stage 1 reads its weights from memory
+    {
+        std::vector<float> prepared(kS1Prepared);
+        stage1_prepare_weights(stages[0].weights, prepared.data());
+        if (hipMalloc((void **)&c->d_wt[0], sizeof(float) * kS1Prepared) != hipSuccess) return bail(CNNC_E_NOMEM);
+        if (hipMemcpy(c->d_wt[0], prepared.data(), sizeof(float) * kS1Prepared, hipMemcpyHostToDevice) != hipSuccess)
+            return bail(CNNC_E_HIP);
+        c->s1_literal = stage1_literal_create(prepared.data());  // optional: without it stage 1 reads its weights from memory
+    }
     {
         std::vector<float> frag(eval2_frag_floats());
         eval2_make_fragments(stages[1].weights, frag.data());

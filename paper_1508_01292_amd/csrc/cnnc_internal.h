@@ -22,6 +22,10 @@ constexpr int kS3In = 48, kS3Params = 122977;
 
 // Offsets (in floats) of each layer's weights / biases inside a stage's blob.
 namespace s1 { constexpr int W1 = 0, B1 = 36, W2 = 40, B2 = 328, W3 = 336, B3 = 408; }
+// Stage 1 as its kernel reads it: the second convolution's kernels in the Winograd F(3,3) domain along their rows,
+// U2[k][c][a][5 points] in place of w2[k][c][a][3 taps] (stage1_prepare_weights); everything else as in the blob.
+namespace s1p { constexpr int W1 = 0, B1 = 36, U2 = 40, B2 = 520, W3 = 528, B3 = 600; }
+constexpr int kS1Prepared = 601;
 namespace s2 {
 constexpr int W1 = 0, B1 = 200, W2 = 208, B2 = 1360, W3 = 1376, B3 = 9568, W4 = 9600, B4 = 9632;
 }
@@ -188,8 +192,10 @@ struct cnnc_ctx {
 
 namespace cnnc {
 
-// Stage 1 with a weight set written into its code (k_stage1.hip); nullptr when that module does not load.
-Stage1Literal *stage1_literal_create(const float *weights);
+// blob (kS1Params floats, layout s1) -> what the stage-1 kernels read (kS1Prepared floats, layout s1p)
+void stage1_prepare_weights(const float *blob, float *prepared);
+// Stage 1 with a prepared weight set written into its code (k_stage1.hip); nullptr when that module does not load.
+Stage1Literal *stage1_literal_create(const float *prepared);
 void stage1_literal_destroy(Stage1Literal *s);
 
 // Kernel launchers (one translation unit each).  All enqueue on `st` and return the launch status.

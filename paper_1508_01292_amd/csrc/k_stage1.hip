@@ -30,10 +30,25 @@ struct Stage1Literal {
     hipFunction_t fn[3][2] = {{nullptr, nullptr}, {nullptr, nullptr}, {nullptr, nullptr}};   // [activation - 1][emit]
 };
 
+// Second convolution in the Winograd domain: F(3,3) along the kernel rows, interpolation points 0, 1, -1, 2 and infinity,
+//   U = G w,  G = [1/2 0 0; -1/2 -1/2 -1/2; -1/6 1/6 -1/6; 1/6 1/3 2/3; 0 0 1]   (in fp64, then rounded)
+void stage1_prepare_weights(const float *blob, float *prepared)
+{
+    static const double G[5][3] = {{0.5, 0, 0}, {-0.5, -0.5, -0.5}, {-1.0 / 6, 1.0 / 6, -1.0 / 6}, {1.0 / 6, 1.0 / 3, 2.0 / 3}, {0, 0, 1}};
+    for (int i = 0; i < 40; ++i) prepared[s1p::W1 + i] = blob[s1::W1 + i];                  // first convolution and its biases
+    for (int row = 0; row < 8 * 4 * 3; ++row)                                                // (k, c, a): one kernel row each
+        for (int pt = 0; pt < 5; ++pt) {
+            const float *w = blob + s1::W2 + row * 3;
+            prepared[s1p::U2 + row * 5 + pt] = (float)(G[pt][0] * (double)w[0] + G[pt][1] * (double)w[1] + G[pt][2] * (double)w[2]);
+        }
+    for (int i = 0; i < 8; ++i) prepared[s1p::B2 + i] = blob[s1::B2 + i];
+    for (int i = 0; i < 73; ++i) prepared[s1p::W3 + i] = blob[s1::W3 + i];                  // fc weights and bias
+}
+
 Stage1Literal *stage1_literal_create(const float *weights)
 {
     static const LiteralImage img = {kStage1LitImage, sizeof(kStage1LitImage), kStage1LitPatch,
-                                     sizeof(kStage1LitPatch) / sizeof(kStage1LitPatch[0]), kS1Params};
+                                     sizeof(kStage1LitPatch) / sizeof(kStage1LitPatch[0]), kS1Prepared};
     LiteralModule *m = literal_acquire(img, weights);
     if (!m) return nullptr;
     Stage1Literal *s = new Stage1Literal();

@@ -7,7 +7,7 @@
 
 using namespace cnnc;
 
-static_assert(kS1Params <= kMaxLiteralWeights, "placeholder range");
+static_assert(kS1Prepared <= kMaxLiteralWeights, "placeholder range");
 
 #define CNNC_S1_LIT(NAME, ACT, EMIT)                                                                                  \
     extern "C" __global__ __launch_bounds__(s1body::kThreads) void NAME(                                               \

@@ -7,7 +7,7 @@
 // of 2 in everything after it, which gives exactly the per-window result at every position:
 //   A_c = f(b1_c + sum w1_c[a][b] X(y+a, x+b))                      conv 3x3, 1 -> 4
 //   M_c = max of A_c over (y..y+1, x..x+1)
-//   C_k = f(b2_k + sum w2_k[c][a][b] M_c(y+2a, x+2b))              conv 3x3, 4 -> 8, spacing 2
+//   C_k = f(b2_k + sum w2_k[c][a][b] M_c(y+2a, x+2b))              conv 3x3, 4 -> 8, spacing 2 (Winograd F(3,3) along rows)
 //   score = b3 + sum w3[k][i][j] C_k(y+2i, x+2j)                    fc over 8x3x3, spacing 2
 //
 // Register blocking: a thread computes four (conv2: three) neighbouring positions at a time, so every
@@ -100,7 +100,7 @@ __device__ __forceinline__ void stage1_tile(const uint8_t *__restrict__ pyr, con
 #pragma unroll
         for (int ch = 0; ch < 4; ++ch)
 #pragma unroll
-            for (int p = 0; p < 4; ++p) acc[ch][p] = wt[s1::B1 + ch];
+            for (int p = 0; p < 4; ++p) acc[ch][p] = wt[s1p::B1 + ch];
 #pragma unroll
         for (int a = 0; a < 3; ++a) {
             const f6 in = load6(sIn + (r + a) * IN_P + x0);
@@ -109,7 +109,7 @@ __device__ __forceinline__ void stage1_tile(const uint8_t *__restrict__ pyr, con
 #pragma unroll
                 for (int ch = 0; ch < 4; ++ch)
 #pragma unroll
-                    for (int p = 0; p < 4; ++p) acc[ch][p] = fmaf(wt[s1::W1 + ch * 9 + a * 3 + b], in.v[p + b], acc[ch][p]);
+                    for (int p = 0; p < 4; ++p) acc[ch][p] = fmaf(wt[s1p::W1 + ch * 9 + a * 3 + b], in.v[p + b], acc[ch][p]);
         }
 #pragma unroll
         for (int ch = 0; ch < 4; ++ch)
@@ -121,14 +121,14 @@ __device__ __forceinline__ void stage1_tile(const uint8_t *__restrict__ pyr, con
         const int r = tid - 192;
         float acc[4];
 #pragma unroll
-        for (int ch = 0; ch < 4; ++ch) acc[ch] = wt[s1::B1 + ch];
+        for (int ch = 0; ch < 4; ++ch) acc[ch] = wt[s1p::B1 + ch];
 #pragma unroll
         for (int a = 0; a < 3; ++a)
 #pragma unroll
             for (int b = 0; b < 3; ++b) {
                 const float v = sIn[(r + a) * IN_P + 40 + b];
 #pragma unroll
-                for (int ch = 0; ch < 4; ++ch) acc[ch] = fmaf(wt[s1::W1 + ch * 9 + a * 3 + b], v, acc[ch]);
+                for (int ch = 0; ch < 4; ++ch) acc[ch] = fmaf(wt[s1p::W1 + ch * 9 + a * 3 + b], v, acc[ch]);
             }
 #pragma unroll
         for (int ch = 0; ch < 4; ++ch) sA[(ch * A_H + r) * A_P + 40] = act_f<ACT>(acc[ch]);
@@ -153,34 +153,43 @@ __device__ __forceinline__ void stage1_tile(const uint8_t *__restrict__ pyr, con
     __syncthreads();
 
     // ---- conv2 (tap spacing 2) + f: 20 rows x 2 parities x 6 groups of three same-parity columns (18 per parity
-    // are needed), all 8 channels: 240 units for the 256 threads
+    // are needed), all 8 channels: 240 units for the 256 threads.  Three neighbouring outputs of a 3-tap row filter
+    // by the Winograd form F(3,3): five multiplications instead of nine,
+    //   m = (G w) * (BT d),  out = AT m summed over input channels and kernel rows before AT is applied,
+    //   BT = [2 -1 -2 1 0; 0 -2 -1 1 0; 0 2 -3 1 0; 0 -1 0 1 0; 0 2 -1 -2 1],  AT = [1 1 1 1 0; 0 1 -1 2 0; 0 1 1 4 1];
+    // the input transform (nine operations per five-vector) is shared by the eight output channels.
     if (tid < C_H * 12) {
         const int r = tid / 12, px = (tid % 12) / 6, j0 = 3 * (tid % 6);
-        float acc[8][3];
-#pragma unroll
-        for (int k = 0; k < 8; ++k)
-#pragma unroll
-            for (int p = 0; p < 3; ++p) acc[k][p] = wt[s1::B2 + k];
+        float m[8][5];
 #pragma unroll
         for (int ch = 0; ch < 4; ++ch)
 #pragma unroll
             for (int a = 0; a < 3; ++a) {
                 const float *mp = sM + (ch * M_H + r + 2 * a) * M_P + px * 20 + j0;
-                float m[5];
+                float d[5];
 #pragma unroll
-                for (int b = 0; b < 5; ++b) m[b] = mp[b];
+                for (int b = 0; b < 5; ++b) d[b] = mp[b];
+                const float v3 = d[3] - d[1];
+                const float v[5] = {fmaf(2.0f, d[0] - d[2], v3), v3 - (d[1] + d[2]), fmaf(3.0f, d[1] - d[2], v3), v3,
+                                    fmaf(-2.0f, v3, d[4] - d[2])};
 #pragma unroll
-                for (int b = 0; b < 3; ++b)
+                for (int k = 0; k < 8; ++k)
 #pragma unroll
-                    for (int k = 0; k < 8; ++k)
-#pragma unroll
-                        for (int p = 0; p < 3; ++p)
-                            acc[k][p] = fmaf(wt[s1::W2 + ((k * 4 + ch) * 3 + a) * 3 + b], m[p + b], acc[k][p]);
+                    for (int p = 0; p < 5; ++p) {
+                        const float u = wt[s1p::U2 + (((k * 4 + ch) * 3 + a) * 5) + p];
+                        // the bias rides on m0 and m4, which enter the first and the last output once each
+                        if (ch == 0 && a == 0) m[k][p] = (p == 0 || p == 4) ? fmaf(u, v[p], wt[s1p::B2 + k]) : u * v[p];
+                        else m[k][p] = fmaf(u, v[p], m[k][p]);
+                    }
             }
 #pragma unroll
-        for (int k = 0; k < 8; ++k)
-#pragma unroll
-            for (int p = 0; p < 3; ++p) sC[(k * C_H + r) * C_P + px * 20 + j0 + p] = act_f<ACT>(acc[k][p]);
+        for (int k = 0; k < 8; ++k) {
+            const float s = m[k][1] + m[k][2], t = m[k][1] - m[k][2];
+            float *cp = sC + (k * C_H + r) * C_P + px * 20 + j0;
+            cp[0] = act_f<ACT>(m[k][0] + s + m[k][3]);
+            cp[1] = act_f<ACT>(fmaf(2.0f, m[k][3], t) + wt[s1p::B2 + k]);
+            cp[2] = act_f<ACT>(fmaf(4.0f, m[k][3], s) + m[k][4]);
+        }
     }
     __syncthreads();
 
@@ -205,7 +214,7 @@ __device__ __forceinline__ void stage1_tile(const uint8_t *__restrict__ pyr, con
                     const f6 c = load6(sC + ((K0 + kk) * C_H + r + 2 * i) * C_P + px * 20 + j0);
 #pragma unroll
                     for (int j = 0; j < 3; ++j) {
-                        const float w = wt[s1::W3 + ((K0 + kk) * 3 + i) * 3 + j];
+                        const float w = wt[s1p::W3 + ((K0 + kk) * 3 + i) * 3 + j];
 #pragma unroll
                         for (int p = 0; p < 4; ++p) acc[p] = fmaf(w, c.v[p + j], acc[p]);
                     }
@@ -223,7 +232,7 @@ __device__ __forceinline__ void stage1_tile(const uint8_t *__restrict__ pyr, con
         const int y = oy + r;
         if (!half) {
             const float4 other = *reinterpret_cast<const float4 *>(sM + 4 * unit);
-            const float b3 = wt[s1::B3];
+            const float b3 = wt[s1p::B3];
             const float sc[4] = {acc[0] + other.x + b3, acc[1] + other.y + b3, acc[2] + other.z + b3, acc[3] + other.w + b3};
             float *row = score + (size_t)L.score_off + (size_t)y * L.ow;
             uint32_t bits = 0;                   // EMIT: this thread's four windows of the row's 32-bit word
