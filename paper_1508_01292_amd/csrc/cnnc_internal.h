@@ -86,6 +86,7 @@ struct StepTimer {
 };
 
 struct Stage1Literal;
+struct ScanLiteral;
 
 }  // namespace cnnc
 
@@ -117,6 +118,7 @@ struct cnnc_ctx {
 
     // first stage in the paper's geometry (27 x 31 window, 4 pixel step): weights, tables and response map
     float *d_scan_wt = nullptr;
+    cnnc::ScanLiteral *scan_literal = nullptr;   // the scan with its weights as instruction literals (or none)
     int scan_act = 0;
     cnnc::ScanLevel *d_scan_levels = nullptr;
     uint32_t *d_scan_tiles = nullptr;

@@ -80,3 +80,36 @@ def test_modules_are_per_weight_set_and_outlive_other_contexts():
     assert_scores(_scoremap(a3, ft), want_a, "a3")
     a3.close()
     b.close()
+
+
+@pytest.mark.parametrize("act", [I.ACT_RATIONAL, I.ACT_SCALED_TANH, I.ACT_TANH])
+def test_scan_literal_build_equals_memory_build(act):
+    """The first stage in the paper's geometry: both builds give the same bits (the memory build is compared with the
+    oracle in tests/test_gpu_scan.py; the literal build is the default there too)."""
+    import torch
+    import paper_1508_01292_amd as P
+    for (w, h, mf, step, seed) in ((640, 480, 24.0, 1.25, 21), (301, 263, 16.0, 1.4, 22)):
+        frame = I.make_frame(w, h, seed)
+        casc = I.default_cascade()
+        net = I.paper_stage1(act)
+        ws = I.draw_scan_weights(net, seed, bias_sd=0.3)
+        ctx = P.Context(casc, I.draw_weights(casc, seed), w, h, 1000)
+        ctx.set_params(mf, step, (0.0, 0.0, 0.0))
+        ctx.scan_set_weights(ws, act)
+        ft = torch.from_numpy(frame).cuda()
+        ctx.build_pyramid(ft)
+        ctx.scan_scoremap()
+        lit = ctx.get_scan_scoremap().copy()
+        ctx.set_literal_weights(False)
+        ctx.scan_scoremap()
+        mem = ctx.get_scan_scoremap().copy()
+        np.testing.assert_array_equal(lit, mem)
+        ref = O.scan_scores(O.build_pyramid(frame, mf, step), net, ws)
+        assert_scores(lit, ref, "scan, literal weights")
+        # another weight set on the same context replaces the module
+        ws2 = I.draw_scan_weights(net, seed + 100)
+        ctx.set_literal_weights(True)
+        ctx.scan_set_weights(ws2, act)
+        ctx.scan_scoremap()
+        assert_scores(ctx.get_scan_scoremap(), O.scan_scores(O.build_pyramid(frame, mf, step), net, ws2), "scan, second weight set")
+        ctx.close()
