@@ -362,13 +362,15 @@ int cnnc_pipe_set_paper(cnnc_pipe *pipe, const float *scan_weights, int n_scan, 
 int cnnc_pipe_fetch_paper(cnnc_pipe *pipe, int64_t ticket, cnnc_rdet *out, int cap, int *n_out);
 const char *cnnc_pipe_last_error(const cnnc_pipe *pipe);
 
-/* Weights as instruction literals (Section 3.4: the code is written for the network it runs).  cnnc_create also
- * prepares a build of the stage-1 kernel in which the context's stage-1 weights are 32-bit literals of the multiply-add
- * instructions instead of values loaded from memory (such instructions issue at up to twice the rate on this GPU);
- * cnnc_stage1_scoremap, cnnc_stage1_survivors and cnnc_detect use it.  Results are bit-identical to the kernel that
- * reads its weights from memory.  cnnc_set_literal_weights(ctx, 0) switches to that kernel, 1 (default) back;
- * cnnc_literal_weights returns 1 when the literal build is in use, 0 when it is switched off or could not be
- * loaded at creation (the context then works as with 0).  Host only. */
+/* Weights as instruction literals (Section 3.4: the code is written for the network it runs).  The kernels whose weights
+ * are the same for every lane of a wave (stage 1; with cnnc_scan_set_weights the 27x31 scan; with
+ * cnnc_select_set_weights the first layers of CNN_2 and CNN_3 in the selective unit) exist in a second build in which
+ * those weights are 32-bit literals of the multiply-add instructions instead of values loaded from memory (such
+ * instructions issue at up to twice the rate on this GPU).  cnnc_create and the two set_weights calls write the
+ * context's weights into a copy of that code and load it; the calls that run those kernels then use it.  Results are
+ * bit-identical to the kernels that read their weights from memory.  cnnc_set_literal_weights(ctx, 0) switches to
+ * those, 1 (default) back; cnnc_literal_weights returns 1 when the literal build of stage 1 is in use, 0 when it is
+ * switched off or could not be loaded at creation (the context then works as with 0).  Host only. */
 int cnnc_set_literal_weights(cnnc_ctx *ctx, int on);
 int cnnc_literal_weights(const cnnc_ctx *ctx);
 

@@ -87,6 +87,7 @@ struct StepTimer {
 
 struct Stage1Literal;
 struct ScanLiteral;
+struct SelectLiteral;
 
 }  // namespace cnnc
 
@@ -129,6 +130,7 @@ struct cnnc_ctx {
 
     // the selective unit in that geometry: networks, list of positions above T_1, per-region records and response maps
     float *d_sel_w2 = nullptr, *d_sel_w3 = nullptr;
+    cnnc::SelectLiteral *sel_literal = nullptr;  // the unit with its first layers' weights as instruction literals (or none)
     float *d_sel_f2 = nullptr, *d_sel_f3 = nullptr;   // their second convolutions in matrix-operand lane order
     int sel_act = 0, sel_rule = 2;           // decision rule: eq. (2) or the weaker eq. (3)
     uint32_t *d_sel_idx = nullptr;

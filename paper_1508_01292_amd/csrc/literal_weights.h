@@ -30,6 +30,12 @@ struct LiteralWeights {
     __device__ constexpr float operator[](int i) const { return __builtin_bit_cast(float, literal_placeholder_bits(i)); }
 };
 
+// The same for weights BASE, BASE + 1, ... of the literal array (a layer inside a larger set of literals).
+template <int BASE>
+struct LiteralWeightsAt {
+    __device__ constexpr float operator[](int i) const { return __builtin_bit_cast(float, literal_placeholder_bits(BASE + i)); }
+};
+
 #ifndef CNNC_LITERAL_DEVICE_ONLY
 // A code object with placeholders, as the build embeds it: the image, and (byte offset, weight index) of every literal.
 struct LiteralImage {

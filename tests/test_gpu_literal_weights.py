@@ -113,3 +113,34 @@ def test_scan_literal_build_equals_memory_build(act):
         ctx.scan_scoremap()
         assert_scores(ctx.get_scan_scoremap(), O.scan_scores(O.build_pyramid(frame, mf, step), net, ws2), "scan, second weight set")
         ctx.close()
+
+
+@pytest.mark.parametrize("act", [I.ACT_RATIONAL, I.ACT_SCALED_TANH, I.ACT_TANH])
+def test_select_literal_build_equals_memory_build(act):
+    """The selective unit: records and both response maps of every listed region are the same bits in both builds (the
+    comparison with the oracle is tests/test_gpu_select.py, which runs the literal build by default)."""
+    import torch
+    import paper_1508_01292_amd as P
+    frame = I.make_frame(481, 363, 31)
+    casc = I.default_cascade()
+    n1, n2, n3 = I.paper_stage1(act), I.paper_stage2(act), I.paper_stage3(act)
+    w1, w2, w3 = (I.draw_scan_weights(n, 40 + k, bias_sd=0.2) for k, n in enumerate((n1, n2, n3)))
+    ctx = P.Context(casc, I.draw_weights(casc, 4), 481, 363, 20000)
+    ctx.set_params(20.0, 1.3, (0.0, 0.0, 0.0))
+    ctx.scan_set_weights(w1, act)
+    ctx.select_set_weights(w2, w3, act)
+    ft = torch.from_numpy(frame).cuda()
+    ctx.build_pyramid(ft)
+    ctx.scan_scoremap()
+    s = ctx.get_scan_scoremap()
+    t1 = float(np.sort(s)[-max(2, s.size // 20)])
+    out = []
+    for on in (True, False):
+        ctx.set_literal_weights(on)
+        ctx.select_run(t1, 0.0, 0.0, 3)
+        recs, m2, m3 = ctx.select_fetch(20000, maps=True)
+        out.append(([(r.index, r.k2, r.k3, r.face) for r in recs], m2.copy(), m3.copy()))
+    assert len(out[0][0]) > 50 and out[0][0] == out[1][0]
+    np.testing.assert_array_equal(out[0][1], out[1][1])
+    np.testing.assert_array_equal(out[0][2], out[1][2])
+    ctx.close()
