@@ -339,7 +339,8 @@ def main():
                                % (cfg["name"], len(frames), cfg["width"], cfg["height"], cfg["min_face"], cfg["scale_step"],
                                   100 * a.q1),
                    "frames_in_flight": F if el_inflight <= el_serial else 1, "windows": n_windows,
-                   "survivors": [n1, n2, n3], "detections": n_det, "prewarm_s": a.prewarm},
+                   "survivors": [n1, n2, n3], "detections": n_det, "prewarm_s": a.prewarm,
+                   "stage1_weights": "instruction literals" if c0.literal_weights() else "memory"},
         "frames_per_s": {"in_flight_%d" % F: fps_inflight, "one_at_a_time": fps_serial},
         "stage1_windows_per_s": n_windows / (ms["stage1"] * 1e-3) if ms["stage1"] > 0 else None,
         "latency_ms_single_frame": latency_ms,
