@@ -211,23 +211,35 @@ __device__ __forceinline__ void s3_conv2_wino4_tile(const float *sP1, float *sP2
     for (int b = 0; b < 8; ++b)
 #pragma unroll
         for (int t = 0; t < NTN; ++t) acc[b][t] = floatx4{0, 0, 0, 0};
-    // filter fragments [k-step][lane][n-tile][8 points]: uniform base + 32-bit lane offset
+    // filter fragments [k-step][lane][n-tile][8 points]: a wave-uniform pointer per k-step (kept in scalar registers:
+    // the empty asm stops the compiler from folding it into a per-lane 64-bit address) + 32-bit lane offset
     const char *ubase = reinterpret_cast<const char *>(UF);
     const uint32_t lane_off = lane * 64 + (NTN == 1 ? nt0 * 32 : 0);
-    auto ldu = [&](int step, int k) {
-        return *reinterpret_cast<const float4 *>(ubase + (size_t)(step * 4096 + k * 16) + lane_off);
+    auto step_ptr = [&](int step) {
+        const char *sp = ubase + step * 4096;
+        asm volatile("" : "+s"(sp));
+        return sp;
+    };
+    // (the pointer comes out of the asm without its address space: say again that it is global memory)
+    typedef const __attribute__((address_space(1))) floatx4 *global_x4_ptr;
+    auto ldu = [&](const char *sp, int k) {
+        const floatx4 v = *(global_x4_ptr)(sp + lane_off + k * 16);
+        return make_float4(v[0], v[1], v[2], v[3]);
     };
     float4 u[2 * NTN], n[2 * NTN];
+    {
+        const char *sp = step_ptr(0);
 #pragma unroll
-    for (int k = 0; k < 2 * NTN; ++k) u[k] = ldu(0, k);
+        for (int k = 0; k < 2 * NTN; ++k) u[k] = ldu(sp, k);
+    }
     float4 c0 = *reinterpret_cast<const float4 *>(dptr), c1 = *reinterpret_cast<const float4 *>(dptr + 4);
 #pragma unroll 1
     for (int a = 0; a < 5; ++a) {                                // kernel row
 #pragma unroll
         for (int cq = 0; cq < 4; ++cq) {                         // input channels 4 cq + g
-            const int nstep = min(a * 4 + cq + 1, 19);
+            const char *np = step_ptr(min(a * 4 + cq + 1, 19));
 #pragma unroll
-            for (int k = 0; k < 2 * NTN; ++k) n[k] = ldu(nstep, k);
+            for (int k = 0; k < 2 * NTN; ++k) n[k] = ldu(np, k);
             const float *nrow = dptr + (cq == 3 ? min(a + 1, 4) * kP1Row + (a == 4 ? 3 : 0) * 4 * kP1Ch
                                                 : a * kP1Row + (cq + 1) * 4 * kP1Ch);
             const float4 m0 = *reinterpret_cast<const float4 *>(nrow), m1 = *reinterpret_cast<const float4 *>(nrow + 4);
