@@ -16,7 +16,7 @@
 // consecutive entries of one parity, and their taps are consecutive too.  The unit sizes are chosen so
 // that every phase fills the 256 threads (250, 240, 240 units, and 128 units by two halves of the channels).
 //
-// WT is what `wt[i]` reads weight i of the stage's blob from: a pointer (wave-uniform scalar loads; a multiply-add
+// WT is what `wt[i]` reads weight i of the prepared array (layout s1p: conv2 in the Winograd domain) from: a pointer (wave-uniform scalar loads; a multiply-add
 // with a scalar-register operand issues at half the rate of one with vector or literal operands on this chip), or
 // LiteralWeights (every weight a distinct constant that the compiler encodes as an instruction literal; the host
 // overwrites those literals with a weight set before it loads the code).
@@ -51,8 +51,8 @@ __device__ __forceinline__ f6 load6(const float *p)
 }
 
 // EMIT = false: every score goes to the score map.  EMIT = true: only windows with score > thr leave the kernel,
-// as one bit per window (a word per 32-window row of the tile, so each word has one writer and needs no clearing)
-// plus the score at the window's place in the map.
+// as one bit per window (a word per 32-window row of the tile, collected in LDS and stored by one thread, so the
+// words in memory have one writer each and need no clearing) plus the score at the window's place in the map.
 template <int ACT, bool EMIT, class WT>
 __device__ __forceinline__ void stage1_tile(const uint8_t *__restrict__ pyr, const LevelDev *__restrict__ levels,
                                             const uint32_t *__restrict__ tiles, const WT wt,
