@@ -176,7 +176,9 @@ def main():
             busy[j] = True
         for j in range(F):
             if busy[j]:
-                n_det = len(ctxs[j].fetch_detections(8192))
+                n = len(ctxs[j].fetch_detections(8192))
+                if j == (n_steps - 1) % F:       # the frame of the last step, as run_serial returns it
+                    n_det = n
         return n_det
 
     def run_serial(n_steps):
