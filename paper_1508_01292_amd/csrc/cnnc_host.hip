@@ -146,8 +146,20 @@ int prepare_layout(cnnc_ctx *c, int w, int h)
                 tiles_pyr.push_back((uint32_t)i);
             }
         }
-        for (int ty = 0; ty * kS1TileH < L.oh; ++ty)
-            for (int tx = 0; tx * kS1TileW < L.ow; ++tx) tiles_s1.push_back(pack_tile((int)l, ty, tx));
+        // Stage-1 tiles of the level, in an order that follows the hardware's hand-out of workgroups: consecutive
+        // workgroups go to the eight XCDs in turn, each with an L2 of its own, so the table positions that fall to
+        // one XCD get a run of tiles that are neighbours in the level and share their halo lines in that L2.
+        {
+            std::vector<uint32_t> row_major;
+            for (int ty = 0; ty * kS1TileH < L.oh; ++ty)
+                for (int tx = 0; tx * kS1TileW < L.ow; ++tx) row_major.push_back(pack_tile((int)l, ty, tx));
+            const size_t first = tiles_s1.size(), m = row_major.size();
+            tiles_s1.resize(first + m);
+            size_t next = 0;
+            for (size_t xcd = 0; xcd < 8; ++xcd)
+                for (size_t p = 0; p < m; ++p)
+                    if (((first + p) & 7) == xcd) tiles_s1[first + p] = row_major[next++];
+        }
     }
 
     s1_tile_of_level[lv.size()] = (int)tiles_s1.size();
