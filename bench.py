@@ -303,6 +303,13 @@ def main():
     try:
         mf, vf, hb = P.cnnc_measure_peaks()
         roof["sustained_on_this_gpu"] = {"mfma_f32_tflops": mf, "valu_f32_tflops": vf, "hbm_copy_gbs": hb}
+        # the two machine facts the kernels' designs lean on (include/cnnc.h, measurement aids)
+        roof["sustained_on_this_gpu"]["issue_ns_per_wave_instruction_and_simd"] = P.cnnc_measure_issue_rates()
+        roof["sustained_on_this_gpu"]["lds_read_ns_per_wave_instruction_and_cu"] = {
+            "b32_consecutive": P.cnnc_measure_lds_read(list(range(64)), 1),
+            "b32_every_second_dword": P.cnnc_measure_lds_read([2 * i for i in range(64)], 1),
+            "b64_consecutive": P.cnnc_measure_lds_read([2 * i for i in range(64)], 2),
+            "b128_consecutive": P.cnnc_measure_lds_read([4 * i for i in range(64)], 4)}
     except Exception as e:       # a probe failure must not lose the benchmark line
         roof["sustained_on_this_gpu"] = {"error": str(e)}
 

@@ -385,6 +385,17 @@ int cnnc_executed_mfma(const cnnc_ctx *ctx, int k, int64_t *per_crop);
  * current device's default stream, allocates and frees 2 GiB, synchronises.  Outputs are host pointers. */
 int cnnc_measure_peaks(double *mfma_f32_tflops, double *valu_f32_tflops, double *hbm_copy_gbs);
 
+/* Measurement aids behind two design choices (weights as literals; the lane orders of LDS reads).  Both run small probe
+ * kernels on the current device's default stream and synchronise; outputs are host pointers.
+ * cnnc_measure_issue_rates: ns per wave instruction and SIMD, four waves per SIMD issuing the same instruction back to
+ *   back on independent registers, into ns[0 .. min(n, 4)): [0] v_fmac_f32 with vector-register operands, [1] with one
+ *   operand in a scalar register, [2] with a 32-bit literal operand, [3] v_rcp_f32.
+ * cnnc_measure_lds_read: ns per wave instruction and compute unit of ds_read_b32 / _b64 / _b128 (width = 1, 2, 4
+ *   dwords) when lane l reads at dword address addr[l] of the workgroup's LDS (addr[l] < 0: lane inactive; otherwise a
+ *   multiple of width and at most 8704; CNNC_E_INVAL else), sixteen waves per compute unit issuing such reads back to back. */
+int cnnc_measure_issue_rates(double *ns, int n);
+int cnnc_measure_lds_read(const int32_t *addr, int width, double *ns_per_instruction);
+
 /* For bindings: sizes in bytes of cnnc_layer, cnnc_stage_desc, cnnc_params, cnnc_det, cnnc_region, the value of
  * CNNC_T_COUNT, and the size of cnnc_rdet, in that order, into out[0 .. n) (host; at most seven are written).
  * Returns how many exist (7). */

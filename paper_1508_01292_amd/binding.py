@@ -20,7 +20,7 @@ EXPORTS = [
     "cnnc_get_survivors", "cnnc_get_stage_scores", "cnnc_survivor_count", "cnnc_set_timing",
     "cnnc_get_timings", "cnnc_set_eval_impl", "cnnc_executed_mfma", "cnnc_measure_peaks", "cnnc_last_error", "cnnc_version",
     "cnnc_stage1_survivors", "cnnc_set_fused_stage1", "cnnc_set_async_chunks", "cnnc_compact_noalloc",
-    "cnnc_set_literal_weights", "cnnc_literal_weights",
+    "cnnc_set_literal_weights", "cnnc_literal_weights", "cnnc_measure_issue_rates", "cnnc_measure_lds_read",
     "cnnc_scan_set_weights", "cnnc_scan_layout", "cnnc_scan_scoremap", "cnnc_get_scan_scoremap",
     "cnnc_select_set_weights", "cnnc_select_set_rule", "cnnc_select_run", "cnnc_select_fetch", "cnnc_select_merge", "cnnc_abi_sizes",
     "cnnc_detect_paper", "cnnc_detect_paper_async", "cnnc_fetch_paper",
@@ -469,6 +469,27 @@ def cnnc_compact_noalloc(values, n: int, thr: float, index, score, count, stream
     return lib().cnnc_compact_noalloc(C.c_void_p(values.data_ptr() if values is not None else 0), C.c_int64(n), C.c_float(thr),
                                       C.c_void_p(index.data_ptr()), C.c_void_p(score.data_ptr()), C.c_int32(cap),
                                       C.c_void_p(count.data_ptr()), _stream(stream))
+
+
+def cnnc_measure_issue_rates():
+    """ns per wave instruction and SIMD (four waves per SIMD) of v_fmac_f32 with vector, scalar-register and literal
+    operands, and of v_rcp_f32."""
+    out = (C.c_double * 4)()
+    rc = lib().cnnc_measure_issue_rates(out, C.c_int(4))
+    if rc != 0:
+        raise CnncError(rc, "cnnc_measure_issue_rates failed")
+    return {"v_fmac_vector_operands": out[0], "v_fmac_scalar_register_operand": out[1], "v_fmac_literal_operand": out[2],
+            "v_rcp_f32": out[3]}
+
+
+def cnnc_measure_lds_read(addr, width: int) -> float:
+    """ns per wave instruction and compute unit of an LDS read of `width` dwords with lane l at dword address addr[l]."""
+    a = (C.c_int32 * 64)(*[int(x) for x in addr])
+    ns = C.c_double(0)
+    rc = lib().cnnc_measure_lds_read(a, C.c_int(width), C.byref(ns))
+    if rc != 0:
+        raise CnncError(rc, "cnnc_measure_lds_read failed")
+    return ns.value
 
 
 def cnnc_measure_peaks():
