@@ -245,11 +245,19 @@ int cnnc_set_eval_impl(cnnc_ctx *ctx, int impl);
  * cnnc_scan_scoremap: needs cnnc_build_pyramid first (CNNC_E_STATE otherwise) and the weights.  Response (j, i)
  *   of level l is the network on the window whose corner is pixel (4 i, 4 j) of that level, pixels entering as
  *   (p - 128) / 128; fp32, flat order (level, row, column).  Enqueued on `stream`.
- * cnnc_get_scan_scoremap: device view of that map and its length. */
+ * cnnc_get_scan_scoremap: device view of that map and its length.
+ * cnnc_scan_set_tile: the scan kernel has two builds, a workgroup per 8 x 8 or per 16 x 16 tile of responses (the
+ *   larger tile computes less of the border that neighbouring tiles compute again; the smaller one gives more workgroups
+ *   on a small frame).  side = 0 (the default): chosen from the frame, 16 when that gives at least 512 tiles; 8 or 16:
+ *   that build.  The responses of the two builds may differ in the last bits (the eleven maps of the output layer are
+ *   summed in four or in two groups).  Anything else: CNNC_E_INVAL.  cnnc_scan_tile returns the side the last
+ *   cnnc_scan_scoremap used (0 before the first). */
 int cnnc_scan_set_weights(cnnc_ctx *ctx, const float *weights, int n_floats, int act);
 int cnnc_scan_layout(cnnc_ctx *ctx, int w, int h, int *n_levels, int32_t *out_w, int32_t *out_h, int64_t *out_off);
 int cnnc_scan_scoremap(cnnc_ctx *ctx, void *stream);
 int cnnc_get_scan_scoremap(cnnc_ctx *ctx, const float **d_scores, int64_t *n);
+int cnnc_scan_set_tile(cnnc_ctx *ctx, int side);
+int cnnc_scan_tile(cnnc_ctx *ctx);
 
 /* ---- The selective unit in the paper's geometry -----------------------------------------------
  * Section 3.3: a window position whose first-stage response exceeded T_1 is read from the original image together

@@ -21,7 +21,7 @@ EXPORTS = [
     "cnnc_get_timings", "cnnc_set_eval_impl", "cnnc_executed_mfma", "cnnc_measure_peaks", "cnnc_last_error", "cnnc_version",
     "cnnc_stage1_survivors", "cnnc_set_fused_stage1", "cnnc_set_async_chunks", "cnnc_compact_noalloc",
     "cnnc_set_literal_weights", "cnnc_literal_weights", "cnnc_measure_issue_rates", "cnnc_measure_lds_read",
-    "cnnc_scan_set_weights", "cnnc_scan_layout", "cnnc_scan_scoremap", "cnnc_get_scan_scoremap",
+    "cnnc_scan_set_weights", "cnnc_scan_layout", "cnnc_scan_scoremap", "cnnc_get_scan_scoremap", "cnnc_scan_set_tile", "cnnc_scan_tile",
     "cnnc_select_set_weights", "cnnc_select_set_rule", "cnnc_select_run", "cnnc_select_fetch", "cnnc_select_merge", "cnnc_abi_sizes",
     "cnnc_detect_paper", "cnnc_detect_paper_async", "cnnc_fetch_paper",
     "cnnc_pipe_create", "cnnc_pipe_destroy", "cnnc_pipe_set_params", "cnnc_pipe_frame_buffer", "cnnc_pipe_submit",
@@ -283,6 +283,13 @@ class Context:
     def scan_scoremap(self, stream=None):
         self._check(lib().cnnc_scan_scoremap(self._h, _stream(stream)))
 
+    def scan_set_tile(self, side: int):
+        """Responses per side of a workgroup's tile: 0 (chosen from the frame), 8 or 16."""
+        self._check(lib().cnnc_scan_set_tile(self._h, C.c_int(side)))
+
+    def scan_tile(self) -> int:
+        return int(lib().cnnc_scan_tile(self._h))
+
     def get_scan_scoremap(self) -> np.ndarray:
         _hiprt().hipDeviceSynchronize()
         p, n = C.c_void_p(0), C.c_int64(0)
@@ -506,7 +513,7 @@ _CTX_CALLS = ("set_params", "pyramid_layout", "build_pyramid", "stage1_scoremap"
               "compact_survivors", "eval_stage", "merge_detections", "detect", "detect_async", "fetch_detections",
               "get_pyramid", "get_scoremap", "get_survivors", "get_stage_scores", "survivor_count", "set_eval_impl",
               "executed_mfma", "set_timing", "get_timings", "scan_set_weights", "scan_layout", "scan_scoremap",
-              "get_scan_scoremap", "select_set_weights", "select_set_rule", "select_run", "select_fetch", "select_merge", "detect_paper",
+              "get_scan_scoremap", "scan_set_tile", "scan_tile", "select_set_weights", "select_set_rule", "select_run", "select_fetch", "select_merge", "detect_paper",
               "detect_paper_async", "fetch_paper", "set_literal_weights", "literal_weights")
 
 

@@ -126,6 +126,7 @@ struct cnnc_ctx {
     float *d_scan_map = nullptr;
     int64_t cap_scan_tiles = 0, cap_scan_map = 0, n_scan = 0;
     int n_scan_tiles = 0, scan_serial = -1;
+    int scan_tile_request = 0, scan_tile_side = 0;   // responses per tile side: asked for (0 = chosen from the frame) and in use
     bool scan_done = false;
 
     // the selective unit in that geometry: networks, list of positions above T_1, per-region records and response maps

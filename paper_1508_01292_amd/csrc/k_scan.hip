@@ -11,17 +11,19 @@ namespace cnnc {
 
 using namespace scanbody;
 
-template <int ACT>
-__global__ __launch_bounds__(kThreads)
+constexpr int64_t kLargeTileMin = 128;       // 16 x 16 tiles from this many on: below, the smaller tiles reach more compute units
+
+template <int ACT, class S>
+__global__ __launch_bounds__(S::kThreads)
 void scan_kernel(const uint8_t *__restrict__ pyr, const ScanLevel *__restrict__ levels, const uint32_t *__restrict__ tiles,
                  const float *__restrict__ wt, float *__restrict__ out)
 {
-    scan_tile<ACT>(pyr, levels, tiles, wt, out);
+    scan_tile<ACT, S>(pyr, levels, tiles, wt, out);
 }
 
 struct ScanLiteral {
     LiteralModule *mod = nullptr;
-    hipFunction_t fn[3] = {nullptr, nullptr, nullptr};       // [activation - 1]
+    hipFunction_t fn[3][2] = {};                             // [activation - 1][0: 8 x 8 tiles, 1: 16 x 16 tiles]
 };
 
 namespace {
@@ -40,12 +42,15 @@ ScanLiteral *scan_literal_create(const float *weights)
     if (!m) return nullptr;
     ScanLiteral *s = new ScanLiteral();
     s->mod = m;
-    static const char *const names[3] = {"cnnc_scan_lit_act1", "cnnc_scan_lit_act2", "cnnc_scan_lit_act3"};
+    static const char *const names[3][2] = {{"cnnc_scan_lit_act1_t8", "cnnc_scan_lit_act1_t16"},
+                                            {"cnnc_scan_lit_act2_t8", "cnnc_scan_lit_act2_t16"},
+                                            {"cnnc_scan_lit_act3_t8", "cnnc_scan_lit_act3_t16"}};
     for (int a = 0; a < 3; ++a)
-        if (!(s->fn[a] = literal_function(m, names[a]))) {
-            scan_literal_destroy(s);
-            return nullptr;
-        }
+        for (int t = 0; t < 2; ++t)
+            if (!(s->fn[a][t] = literal_function(m, names[a][t]))) {
+                scan_literal_destroy(s);
+                return nullptr;
+            }
     return s;
 }
 }  // namespace
@@ -59,7 +64,8 @@ namespace {
 
 // Response-map geometry of the current pyramid: level l gives ((w - 27) / 4 + 1) x ((h - 31) / 4 + 1) responses,
 // none when it is smaller than the window.
-void scan_geometry(const std::vector<LevelDev> &lv, std::vector<ScanLevel> &sl, std::vector<uint32_t> *tiles, int64_t &total)
+void scan_geometry(const std::vector<LevelDev> &lv, std::vector<ScanLevel> &sl, std::vector<uint32_t> *tiles, int64_t &total,
+                   int tile_side = 8)
 {
     sl.clear();
     total = 0;
@@ -69,8 +75,8 @@ void scan_geometry(const std::vector<LevelDev> &lv, std::vector<ScanLevel> &sl, 
         if (S.w >= kWinW && S.h >= kWinH) { S.ow = (S.w - kWinW) / kStep + 1; S.oh = (S.h - kWinH) / kStep + 1; }
         total += (int64_t)S.ow * S.oh;
         if (tiles)
-            for (int ty = 0; ty * TO < S.oh; ++ty)
-                for (int tx = 0; tx * TO < S.ow; ++tx) tiles->push_back(pack_tile((int)l, ty, tx));
+            for (int ty = 0; ty * tile_side < S.oh; ++ty)
+                for (int tx = 0; tx * tile_side < S.ow; ++tx) tiles->push_back(pack_tile((int)l, ty, tx));
         sl.push_back(S);
     }
 }
@@ -106,6 +112,22 @@ int cnnc_scan_set_weights(cnnc_ctx *c, const float *weights, int n_floats, int a
     return CNNC_OK;
 }
 
+int cnnc_scan_set_tile(cnnc_ctx *c, int side)
+{
+    if (!c) return CNNC_E_INVAL;
+    if (side != 0 && side != 8 && side != 16) return fail(c, CNNC_E_INVAL, "tile side must be 0 (chosen from the frame), 8 or 16");
+    if (side != c->scan_tile_request) {
+        c->scan_tile_request = side;
+        c->scan_serial = -1;                                     // the tile table is rebuilt by the next scan
+    }
+    return CNNC_OK;
+}
+
+int cnnc_scan_tile(cnnc_ctx *c)
+{
+    return c ? c->scan_tile_side : CNNC_E_INVAL;
+}
+
 int cnnc_scan_layout(cnnc_ctx *c, int w, int h, int *n_levels, int32_t *out_w, int32_t *out_h, int64_t *out_off)
 {
     if (!c || !n_levels) return CNNC_E_INVAL;
@@ -135,7 +157,16 @@ int cnnc_scan_scoremap(cnnc_ctx *c, void *stream)
         std::vector<ScanLevel> sl;
         std::vector<uint32_t> tiles;
         int64_t total = 0;
-        scan_geometry(c->levels, sl, &tiles, total);
+        // Tiles of 16 x 16 responses do a third less arithmetic per response; they are taken when there are enough of
+        // them for two workgroups on every compute unit, otherwise 8 x 8 tiles spread the frame over more of the chip.
+        int side = c->scan_tile_request;
+        if (side == 0) {
+            scan_geometry(c->levels, sl, &tiles, total, 16);
+            side = (int64_t)tiles.size() >= kLargeTileMin ? 16 : 8;
+            if (side != 16) tiles.clear();
+        }
+        if (tiles.empty()) scan_geometry(c->levels, sl, &tiles, total, side);
+        c->scan_tile_side = side;
         HIP_TRY(c, hipStreamSynchronize(c->last_stream));        // the old tables may still be in use
         if (!c->d_scan_levels) HIP_TRY(c, hipMalloc((void **)&c->d_scan_levels, sizeof(ScanLevel) * CNNC_MAX_LEVELS));
         if ((int64_t)tiles.size() > c->cap_scan_tiles) {
@@ -158,17 +189,22 @@ int cnnc_scan_scoremap(cnnc_ctx *c, void *stream)
     c->last_stream = st;
     if (c->n_scan_tiles > 0) {
         ScopedTimer tm(c, CNNC_T_SCAN, st);
-        dim3 grid(c->n_scan_tiles), block(kThreads);
+        const bool large = c->scan_tile_side == 16;
+        const unsigned threads = large ? Shape16::kThreads : Shape8::kThreads;
+        dim3 grid(c->n_scan_tiles), block(threads);
         if (c->scan_literal && c->use_literals) {
             const uint8_t *pyr = c->d_pyr;
             const ScanLevel *levels = c->d_scan_levels;
             const uint32_t *tiles = c->d_scan_tiles;
             float *out = c->d_scan_map;
             void *args[] = {&pyr, &levels, &tiles, &out};
-            HIP_TRY(c, hipModuleLaunchKernel(c->scan_literal->fn[c->scan_act - 1], (unsigned)c->n_scan_tiles, 1, 1, kThreads, 1, 1, 0, st, args, nullptr));
+            HIP_TRY(c, hipModuleLaunchKernel(c->scan_literal->fn[c->scan_act - 1][large ? 1 : 0], (unsigned)c->n_scan_tiles, 1, 1, threads, 1, 1, 0, st, args, nullptr));
         } else
-#define CNNC_SCAN(ACT) \
-    hipLaunchKernelGGL(scan_kernel<ACT>, grid, block, 0, st, c->d_pyr, c->d_scan_levels, c->d_scan_tiles, c->d_scan_wt, c->d_scan_map)
+#define CNNC_SCAN(ACT)                                                                                                        \
+    do {                                                                                                                      \
+        if (large) hipLaunchKernelGGL((scan_kernel<ACT, Shape16>), grid, block, 0, st, c->d_pyr, c->d_scan_levels, c->d_scan_tiles, c->d_scan_wt, c->d_scan_map); \
+        else hipLaunchKernelGGL((scan_kernel<ACT, Shape8>), grid, block, 0, st, c->d_pyr, c->d_scan_levels, c->d_scan_tiles, c->d_scan_wt, c->d_scan_map);       \
+    } while (0)
         switch (c->scan_act) {
         case CNNC_ACT_RATIONAL: CNNC_SCAN(CNNC_ACT_RATIONAL); break;
         case CNNC_ACT_SCALED_TANH: CNNC_SCAN(CNNC_ACT_SCALED_TANH); break;

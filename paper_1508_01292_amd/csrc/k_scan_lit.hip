@@ -8,14 +8,17 @@ using namespace cnnc;
 
 static_assert(scanbody::kScanParams <= kMaxLiteralWeights, "placeholder range");
 
-#define CNNC_SCAN_LIT(NAME, ACT)                                                                                       \
-    extern "C" __global__ __launch_bounds__(scanbody::kThreads) void NAME(                                             \
+#define CNNC_SCAN_LIT(NAME, ACT, SHAPE)                                                                                \
+    extern "C" __global__ __launch_bounds__(scanbody::SHAPE::kThreads) void NAME(                                      \
         const uint8_t *__restrict__ pyr, const ScanLevel *__restrict__ levels, const uint32_t *__restrict__ tiles,     \
         float *__restrict__ out)                                                                                       \
     {                                                                                                                  \
-        scanbody::scan_tile<ACT>(pyr, levels, tiles, LiteralWeights{}, out);                                           \
+        scanbody::scan_tile<ACT, scanbody::SHAPE>(pyr, levels, tiles, LiteralWeights{}, out);                          \
     }
 
-CNNC_SCAN_LIT(cnnc_scan_lit_act1, CNNC_ACT_RATIONAL)
-CNNC_SCAN_LIT(cnnc_scan_lit_act2, CNNC_ACT_SCALED_TANH)
-CNNC_SCAN_LIT(cnnc_scan_lit_act3, CNNC_ACT_TANH)
+CNNC_SCAN_LIT(cnnc_scan_lit_act1_t8, CNNC_ACT_RATIONAL, Shape8)
+CNNC_SCAN_LIT(cnnc_scan_lit_act2_t8, CNNC_ACT_SCALED_TANH, Shape8)
+CNNC_SCAN_LIT(cnnc_scan_lit_act3_t8, CNNC_ACT_TANH, Shape8)
+CNNC_SCAN_LIT(cnnc_scan_lit_act1_t16, CNNC_ACT_RATIONAL, Shape16)
+CNNC_SCAN_LIT(cnnc_scan_lit_act2_t16, CNNC_ACT_SCALED_TANH, Shape16)
+CNNC_SCAN_LIT(cnnc_scan_lit_act3_t16, CNNC_ACT_TANH, Shape16)

@@ -98,12 +98,16 @@ def test_scan_literal_build_equals_memory_build(act):
         ctx.scan_set_weights(ws, act)
         ft = torch.from_numpy(frame).cuda()
         ctx.build_pyramid(ft)
-        ctx.scan_scoremap()
-        lit = ctx.get_scan_scoremap().copy()
-        ctx.set_literal_weights(False)
-        ctx.scan_scoremap()
-        mem = ctx.get_scan_scoremap().copy()
-        np.testing.assert_array_equal(lit, mem)
+        for side in (16, 8):                                   # both tile shapes of the kernel have both builds
+            ctx.scan_set_tile(side)
+            ctx.set_literal_weights(True)
+            ctx.scan_scoremap()
+            lit = ctx.get_scan_scoremap().copy()
+            ctx.set_literal_weights(False)
+            ctx.scan_scoremap()
+            mem = ctx.get_scan_scoremap().copy()
+            np.testing.assert_array_equal(lit, mem)
+        ctx.scan_set_tile(0)
         ref = O.scan_scores(O.build_pyramid(frame, mf, step), net, ws)
         assert_scores(lit, ref, "scan, literal weights")
         # another weight set on the same context replaces the module

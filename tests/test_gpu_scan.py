@@ -22,10 +22,20 @@ def _scan_case(frame, min_face, step, act, seed, bias_sd=0.0, name=""):
     blob = I.draw_scan_weights(net, seed, bias_sd=bias_sd)
     ctx.scan_set_weights(blob, act)
     ctx.build_pyramid(torch.from_numpy(frame).cuda())
-    ctx.scan_scoremap()
-    got = ctx.get_scan_scoremap()
     pyr = O.build_pyramid(frame, min_face, step)
     want = O.scan_scores(pyr, net, blob)
+    # both builds of the kernel (a workgroup per 8 x 8 and per 16 x 16 responses), then the one chosen from the frame
+    maps = {}
+    for side in (8, 16, 0):
+        ctx.scan_set_tile(side)
+        ctx.scan_scoremap()
+        assert ctx.scan_tile() == (side or ctx.scan_tile()) and ctx.scan_tile() in (8, 16)
+        maps[side] = ctx.get_scan_scoremap()
+        assert maps[side].size == want.size
+        e = np.abs(maps[side].astype(np.float64) - want)
+        assert np.all(e <= ATOL + RTOL * np.abs(want)), "tile side %d: max err %g" % (side, e.max())
+    assert np.array_equal(maps[8], maps[16]), "a response is summed in the same order whatever the tile"
+    got = maps[0]
     lay = ctx.scan_layout(frame.shape[1], frame.shape[0])
     sizes = [(max(0, (l.shape[0] - 31) // 4 + 1), max(0, (l.shape[1] - 27) // 4 + 1)) if min(l.shape[0] - 31, l.shape[1] - 27) >= 0
              else (0, 0) for l in pyr.levels]
@@ -66,6 +76,17 @@ def test_scan_uhd_headline_frame():
     frame = I.make_frame(c["width"], c["height"], I.config_seed(2))
     got, want, *_ = _scan_case(frame, c["min_face"], c["scale_step"], I.ACT_RATIONAL, I.config_seed(2), name="uhd")
     assert want.size > 40000
+    import paper_1508_01292_amd as P           # a frame of this size is scanned in 16 x 16 tiles, a small one in 8 x 8
+    casc = I.default_cascade()
+    ctx = P.Context(casc, I.draw_weights(casc, 2), c["width"], c["height"], 1024)
+    import torch
+    for cfg, side in ((c, 16), (I.CONFIGS[0], 8)):
+        ctx.set_params(cfg["min_face"], cfg["scale_step"], (0.0, 0.0, 0.0))
+        ctx.scan_set_weights(I.draw_scan_weights(I.paper_stage1(), 2), 1)
+        ctx.build_pyramid(torch.from_numpy(I.make_frame(cfg["width"], cfg["height"], 2)).cuda())
+        ctx.scan_scoremap()
+        assert ctx.scan_tile() == side
+    ctx.close()
 
 
 def test_scan_degenerate_and_call_order():
@@ -83,6 +104,9 @@ def test_scan_degenerate_and_call_order():
     with pytest.raises(P.CnncError):                 # activation kind
         ctx.scan_set_weights(blob, 0)
     ctx.scan_set_weights(blob, 1)
+    with pytest.raises(P.CnncError):                 # tile side
+        ctx.scan_set_tile(12)
+    assert ctx.scan_tile() == 0
     with pytest.raises(P.CnncError):                 # no pyramid yet
         ctx.scan_scoremap()
     with pytest.raises(P.CnncError):                 # no map yet
@@ -100,6 +124,10 @@ def test_scan_degenerate_and_call_order():
     assert got.size == 1
     win = (one.astype(np.float64) - 128) / 128
     assert abs(float(got[0]) - O.scan_window(net, blob, win)) <= ATOL
+    ctx.scan_set_tile(16)
+    ctx.scan_scoremap()
+    assert np.array_equal(ctx.get_scan_scoremap(), got)
+    ctx.scan_set_tile(0)
     # the same context still runs the cascade's own stage 1 on that pyramid
     ctx.stage1_scoremap()
     assert ctx.get_scoremap().size == O.pyramid_layout(27, 31, 12.0, 1.25).score_off[-1]
