@@ -67,11 +67,18 @@ namespace {
 constexpr int kPaperFastDets = 2048;      // detections of the whole-path call that come back with the counters
 
 // B operand of a network's second convolution in lane order: [n tile][k step][lane], lane (g = lane / 16, j = lane % 16)
-// holds the weight of tap k = 4 step + g (k = 9 c + 3 a + b) for map n = 16 tile + j; zero beyond K and C2.
+// holds the weight of tap k = 4 step + g (k = 9 c + 3 a + b) for map n = 16 tile + j; zero beyond K and C2.  Behind it
+// the weights of the output convolution as [c2][8 kernel rows][8] (a row's seven, then a zero), for 16-byte loads.
+size_t fragment_floats(int c1, int c2) { return (size_t)2 * conv2_steps(c1) * 64 + (size_t)c2 * kK3H * kOutRowPad; }
+
 void conv2_fragments(const float *blob, int c1, int c2, std::vector<float> &f)
 {
-    const int K = c1 * 9, KS = conv2_steps(c1), W2 = c1 * 17;
-    f.assign((size_t)2 * KS * 64, 0.0f);
+    const int K = c1 * 9, KS = conv2_steps(c1), W2 = c1 * 17, W3 = W2 + c2 * K + c2;
+    f.assign(fragment_floats(c1, c2), 0.0f);
+    for (int k = 0; k < c2; ++k)
+        for (int a = 0; a < kK3H; ++a)
+            for (int b = 0; b < kK3W; ++b)
+                f[(size_t)2 * KS * 64 + ((size_t)k * kK3H + a) * kOutRowPad + b] = blob[W3 + (k * kK3H + a) * kK3W + b];
     for (int nt = 0; nt < 2; ++nt)
         for (int st = 0; st < KS; ++st)
             for (int lane = 0; lane < 64; ++lane) {
@@ -121,8 +128,8 @@ int cnnc_select_set_weights(cnnc_ctx *c, const float *w2, int n2, const float *w
         const size_t cap = (size_t)c->max_surv;
         HIP_TRY(c, hipMalloc((void **)&c->d_sel_w2, sizeof(float) * kNet2Params));
         HIP_TRY(c, hipMalloc((void **)&c->d_sel_w3, sizeof(float) * kNet3Params));
-        HIP_TRY(c, hipMalloc((void **)&c->d_sel_f2, sizeof(float) * 2 * conv2_steps(kNet2C1) * 64));
-        HIP_TRY(c, hipMalloc((void **)&c->d_sel_f3, sizeof(float) * 2 * conv2_steps(kNet3C1) * 64));
+        HIP_TRY(c, hipMalloc((void **)&c->d_sel_f2, sizeof(float) * fragment_floats(kNet2C1, kNet2C2)));
+        HIP_TRY(c, hipMalloc((void **)&c->d_sel_f3, sizeof(float) * fragment_floats(kNet3C1, kNet3C2)));
         HIP_TRY(c, hipMalloc((void **)&c->d_sel_idx, sizeof(uint32_t) * cap));
         HIP_TRY(c, hipMalloc((void **)&c->d_sel_sc, sizeof(float) * cap));
         HIP_TRY(c, hipMalloc((void **)&c->d_sel_rec, sizeof(cnnc_region) * cap));

@@ -87,7 +87,7 @@ __device__ void conv1_pool(const float *in, float *out, const W1T w)
 // GEMM rows = positions of the 22 x 24 map, sixteen a tile = four pooling blocks with their four positions each, so
 // that a lane's four result registers are one block and the pooling stays in registers; K = C1 x 9 taps in steps of
 // four (padded with zero weights), N = the C2 maps in two tiles of sixteen.  132 pooling blocks = 33 tiles, dealt
-// round-robin to the waves and taken two at a time.  frag: the B operand in lane order, [n tile][k step][64].
+// round-robin to the waves and taken two at a time.  frag: the B operand in lane order, [n tile][k step][64] (the output layer's weights follow it).
 constexpr int kConv2Tiles = kP2W * kP2H / 4;
 static_assert(kConv2Tiles * 4 == kP2W * kP2H && kConv2Tiles == 33, "pooling blocks come in fours");
 constexpr int conv2_steps(int c1) { return (c1 * 9 + 3) / 4; }
@@ -145,29 +145,47 @@ __device__ void conv2_pool_mfma(const float *in, float *out, const float *__rest
     __syncthreads();
 }
 
-// The output convolution (7 x 8 kernel over [C2][12][kP2P]) -> 25 responses in res[25].  Ten groups of threads split
-// the input maps; their partial sums meet in LDS.
+// The output convolution (7 x 8 kernel over [C2][12][kP2P]) -> 25 responses in res[25].  A lane takes one row of five
+// responses of one input map: per kernel row it reads the twelve values of a map row once (three 16-byte reads) for
+// 35 multiply-adds, where a lane per response would read one value per multiply-add and be bound by LDS.  Lane =
+// 8 x (map of the wave) + response row; a wave has up to eight maps, which are summed with three exchanges between
+// lanes, and the four waves' sums meet in LDS.  wq: the layer's weights as [C2][8][8] (kernel rows padded to eight).
+constexpr int kOutRowPad = 8;
 template <int C2>
-__device__ void conv_out(const float *in, const float *__restrict__ w, const float *__restrict__ bias, float *part, float *res)
+__device__ void conv_out(const float *in, const float *__restrict__ wq, const float *__restrict__ bias, float *part, float *res)
 {
-    const int tid = threadIdx.x;
-    if (tid < 10 * kMap) {
-        const int o = tid % kMap, grp = tid / kMap, v = o / kMapW, u = o % kMapW;
-        float acc = 0.0f;
-        for (int k = grp; k < C2; k += 10)
+    static_assert(kK3W < kOutRowPad && kMapW - 1 + kK3W <= kP2P && kP2P == 12 && C2 <= 32 && kThreads == 256, "row of a map in three reads");
+    constexpr int kPer = (C2 + 3) / 4;                           // maps per wave
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int v = lane & 7, kk = lane >> 3, k = wave * kPer + kk;
+    float acc[kMapW];
 #pragma unroll
-            for (int a = 0; a < kK3H; ++a)
+    for (int u = 0; u < kMapW; ++u) acc[u] = 0.0f;
+    if (v < kMapH && kk < kPer && k < C2) {
 #pragma unroll
-                for (int b = 0; b < kK3W; ++b)
-                    acc = fmaf(w[(k * kK3H + a) * kK3W + b], in[(k * kP2H + v + a) * kP2P + u + b], acc);
-        part[grp * kMap + o] = acc;
+        for (int a = 0; a < kK3H; ++a) {
+            const floatx4 *row = reinterpret_cast<const floatx4 *>(in + (k * kP2H + v + a) * kP2P);
+            const floatx4 *wr = reinterpret_cast<const floatx4 *>(wq + (k * kK3H + a) * kOutRowPad);
+            const floatx4 x0 = row[0], x1 = row[1], x2 = row[2], w0 = wr[0], w1 = wr[1];
+            const float x[12] = {x0[0], x0[1], x0[2], x0[3], x1[0], x1[1], x1[2], x1[3], x2[0], x2[1], x2[2], x2[3]};
+            const float w[kOutRowPad] = {w0[0], w0[1], w0[2], w0[3], w1[0], w1[1], w1[2], w1[3]};
+#pragma unroll
+            for (int b = 0; b < kK3W; ++b)
+#pragma unroll
+                for (int u = 0; u < kMapW; ++u) acc[u] = fmaf(w[b], x[u + b], acc[u]);
+        }
     }
+#pragma unroll
+    for (int u = 0; u < kMapW; ++u) {
+        acc[u] += __shfl_xor(acc[u], 8, 64);
+        acc[u] += __shfl_xor(acc[u], 16, 64);
+        acc[u] += __shfl_xor(acc[u], 32, 64);
+    }
+    if (lane < kMapH)
+#pragma unroll
+        for (int u = 0; u < kMapW; ++u) part[wave * kMap + lane * kMapW + u] = acc[u];
     __syncthreads();
-    if (tid < kMap) {
-        float s = bias[0];
-        for (int g = 0; g < 10; ++g) s += part[g * kMap + tid];
-        res[tid] = s;
-    }
+    if (tid < kMap) res[tid] = ((part[tid] + part[kMap + tid]) + (part[2 * kMap + tid] + part[3 * kMap + tid])) + bias[0];
     __syncthreads();
 }
 
@@ -177,11 +195,11 @@ __device__ void region_net(const float *sReg, float *sP1, float *sP2, float *sPa
                            const float *__restrict__ frag, float *res)
 {
     constexpr int W1 = 0, B1 = W1 + C1 * 16, W2 = B1 + C1, B2 = W2 + C2 * C1 * 9, W3 = B2 + C2, B3 = W3 + C2 * kK3W * kK3H;
-    (void)W2;
+    (void)W2; (void)W3;
     static_assert(W1 == 0 && B1 == C1 * 16, "the first layer's weights and biases open the blob");
     conv1_pool<C1, MIRROR, ACT>(sReg, sP1, w1);
     conv2_pool_mfma<C1, C2, ACT>(sP1, sP2, frag, wt + B2);
-    conv_out<C2>(sP2, wt + W3, wt + B3, sPart, res);
+    conv_out<C2>(sP2, frag + 2 * conv2_steps(C1) * 64, wt + B3, sPart, res);
 }
 
 // region + mirror -> combined map in sComb[25], written to `map`, and the count of responses above thr.
@@ -222,7 +240,7 @@ __device__ __forceinline__ void select_regions(const uint8_t *__restrict__ frame
     // the partial sums of the output convolution live in the first map buffer, which is idle by then.
     __shared__ float sReg[kRegH * kRegP];
     __shared__ float sP1[kC1Max * kP1H * kP1W];
-    __shared__ float sP2[kC2Max * kP2H * kP2P];
+    __shared__ __attribute__((aligned(16))) float sP2[kC2Max * kP2H * kP2P];
     __shared__ float sRes[2 * kMap];
     __shared__ int sC0;
     float *sPart = sP1;
@@ -230,7 +248,7 @@ __device__ __forceinline__ void select_regions(const uint8_t *__restrict__ frame
     int *sHist = reinterpret_cast<int *>(sP2) + 128;
     uint8_t *sPix = reinterpret_cast<uint8_t *>(sP2 + 128 + 256);
     static_assert(kRegW + kRegH <= 128 && (128 + 256) * 4 + kRegW * kRegH <= (int)sizeof(float) * kC2Max * kP2H * kP2P &&
-                  10 * kMap <= kC1Max * kP1H * kP1W, "scratch arrays fit in the map buffers");
+                  4 * kMap <= kC1Max * kP1H * kP1W, "scratch arrays fit in the map buffers");
     const int tid = threadIdx.x;
     const int n = min(*d_n, n_max);
     for (int s = blockIdx.x; s < n; s += gridDim.x) {
