@@ -86,8 +86,8 @@ __device__ void conv1_pool(const float *in, float *out, const W1T w)
 // conv 3x3 C1 -> C2 + 2x2 max-pool + bias + f on the matrix cores (it is 70 % of a network's arithmetic).
 // GEMM rows = positions of the 22 x 24 map, sixteen a tile = four pooling blocks with their four positions each, so
 // that a lane's four result registers are one block and the pooling stays in registers; K = C1 x 9 taps in steps of
-// four (padded with zero weights), N = the C2 maps in two tiles of sixteen.  132 pooling blocks = 33 tiles, dealt
-// round-robin to the waves and taken two at a time.  frag: the B operand in lane order, [n tile][k step][64] (the output layer's weights follow it).
+// four (padded with zero weights), N = the C2 maps in two tiles of sixteen.  132 pooling blocks = 33 tiles: a wave takes
+// eight of them, two at a time, and the last tile's two halves (of output maps) go to two waves.  frag: the B operand in lane order, [n tile][k step][64] (the output layer's weights follow it).
 constexpr int kConv2Tiles = kP2W * kP2H / 4;
 static_assert(kConv2Tiles * 4 == kP2W * kP2H && kConv2Tiles == 33, "pooling blocks come in fours");
 constexpr int conv2_steps(int c1) { return (c1 * 9 + 3) / 4; }
@@ -101,7 +101,7 @@ __device__ void conv2_pool_mfma(const float *in, float *out, const float *__rest
     // opaque per call: otherwise the weight fragments and tap offsets of all four network passes are hoisted out of
     // the loop over regions and kept alive across it, which spills 40 registers per lane
     asm volatile("" : "+v"(lane));
-    const int wave = threadIdx.x >> 6, g = lane >> 4, i = lane & 15;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), g = lane >> 4, i = lane & 15;
     float bf[2][KS];
     int koff[KS];
 #pragma unroll
@@ -113,13 +113,14 @@ __device__ void conv2_pool_mfma(const float *in, float *out, const float *__rest
     }
     const int sub_off = ((i >> 1) & 1) * kP1W + (i & 1);          // position (i % 4) inside its pooling block
     const float bias0 = bias[i], bias1 = 16 + i < C2 ? bias[16 + i] : 0.0f;
-    for (int t0 = wave; t0 < kConv2Tiles; t0 += 8) {
+    static_assert(kConv2Tiles == 33 && kThreads == 256, "four waves: eight tiles each in pairs, and the last tile's two halves");
+#pragma unroll 1
+    for (int t0 = wave; t0 < kConv2Tiles - 1; t0 += 8) {
         floatx4 acc[2][2];
         int base[2];
 #pragma unroll
         for (int v = 0; v < 2; ++v) {
-            const int t = min(t0 + 4 * v, kConv2Tiles - 1);      // past the end: the last tile again, not stored
-            const int pb = 4 * t + (i >> 2), by = pb / kP2W, bx = pb % kP2W;
+            const int pb = 4 * (t0 + 4 * v) + (i >> 2), by = pb / kP2W, bx = pb % kP2W;
             base[v] = 2 * by * kP1W + 2 * bx + sub_off;
             acc[v][0] = acc[v][1] = floatx4{0.0f, 0.0f, 0.0f, 0.0f};
         }
@@ -133,13 +134,27 @@ __device__ void conv2_pool_mfma(const float *in, float *out, const float *__rest
             }
 #pragma unroll
         for (int v = 0; v < 2; ++v) {
-            const int t = t0 + 4 * v;
-            if (t >= kConv2Tiles) continue;
-            const int pb = 4 * t + g, by = pb / kP2W, bx = pb % kP2W;               // lane (g, i): block g of the tile, map i
+            const int pb = 4 * (t0 + 4 * v) + g, by = pb / kP2W, bx = pb % kP2W;    // lane (g, i): block g of the tile, map i
             const floatx4 lo = acc[v][0], hi = acc[v][1];
             out[(i * kP2H + by) * kP2P + bx] = act_f<ACT>(fmaxf(fmaxf(lo[0], lo[1]), fmaxf(lo[2], lo[3])) + bias0);
             if (16 + i < C2)
                 out[((16 + i) * kP2H + by) * kP2P + bx] = act_f<ACT>(fmaxf(fmaxf(hi[0], hi[1]), fmaxf(hi[2], hi[3])) + bias1);
+        }
+    }
+    if (wave < 2) {                                              // the thirty-third tile: wave 0 its first sixteen maps, wave 1 the rest
+        constexpr int t = kConv2Tiles - 1;
+        const int pa = 4 * t + (i >> 2), base = 2 * (pa / kP2W) * kP1W + 2 * (pa % kP2W) + sub_off;
+        const int pb = 4 * t + g, by = pb / kP2W, bx = pb % kP2W;
+        floatx4 acc = floatx4{0.0f, 0.0f, 0.0f, 0.0f};
+        if (wave == 0) {
+#pragma unroll
+            for (int st = 0; st < KS; ++st) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(in[base + koff[st]], bf[0][st], acc, 0, 0, 0);
+            out[(i * kP2H + by) * kP2P + bx] = act_f<ACT>(fmaxf(fmaxf(acc[0], acc[1]), fmaxf(acc[2], acc[3])) + bias0);
+        } else {
+#pragma unroll
+            for (int st = 0; st < KS; ++st) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(in[base + koff[st]], bf[1][st], acc, 0, 0, 0);
+            if (16 + i < C2)
+                out[((16 + i) * kP2H + by) * kP2P + bx] = act_f<ACT>(fmaxf(fmaxf(acc[0], acc[1]), fmaxf(acc[2], acc[3])) + bias1);
         }
     }
     __syncthreads();
