@@ -85,6 +85,60 @@ class Detection(C.Structure):
                     neighbors=self.neighbors, index=self.index)
 
 
+class Records:
+    """The n records a call wrote, kept as the block of host memory the library filled.  len(), indexing and iteration
+    give ctypes structures that view that memory (made when asked for, so a caller that only counts pays nothing per
+    record); `array` is the same memory as a numpy structured array."""
+    __slots__ = ("_raw", "_ctype", "_n")
+
+    def __init__(self, ctype, cap: int):
+        self._ctype, self._n = ctype, 0
+        self._raw = np.empty(max(int(cap), 1) * C.sizeof(ctype), np.uint8)      # not cleared: the library writes it
+
+    def _pointer(self):
+        return self._raw.ctypes.data_as(C.c_void_p)
+
+    def _filled(self, n: int, cap: int):
+        self._n = max(0, min(int(n), int(cap)))
+        used = self._n * C.sizeof(self._ctype)
+        if 2 * used < self._raw.size:
+            self._raw = self._raw[:max(used, 1)].copy()
+        return self
+
+    def __len__(self):
+        return self._n
+
+    def __getitem__(self, i):
+        if isinstance(i, slice):
+            return [self[k] for k in range(*i.indices(self._n))]
+        if i < 0:
+            i += self._n
+        if not 0 <= i < self._n:
+            raise IndexError(i)
+        return self._ctype.from_buffer(self._raw, i * C.sizeof(self._ctype))
+
+    def __iter__(self):
+        for i in range(self._n):
+            yield self[i]
+
+    @property
+    def array(self) -> np.ndarray:
+        return self._raw[:self._n * C.sizeof(self._ctype)].view(np.dtype(self._ctype))
+
+    def __eq__(self, other):
+        """Equal to a sequence of the same length whose elements are the same records (structures or their dicts)."""
+        if isinstance(other, Records):
+            return self._ctype is other._ctype and self._n == other._n and bool(np.array_equal(self.array, other.array))
+        try:
+            if len(other) != self._n:
+                return False
+        except TypeError:
+            return NotImplemented
+        return all(a.as_dict() == (b.as_dict() if hasattr(b, "as_dict") else b) for a, b in zip(self, other))
+
+    __hash__ = None
+
+
 _lib = None
 _hip = None
 
@@ -212,26 +266,26 @@ class Context:
     def eval_stage(self, k: int, stream=None):
         self._check(lib().cnnc_eval_stage(self._h, C.c_int(k), _stream(stream)))
 
-    def merge_detections(self, cap: int = 4096, stream=None) -> List[Detection]:
-        out = (Detection * cap)()
+    def merge_detections(self, cap: int = 4096, stream=None) -> Records:
+        out = Records(Detection, cap)
         n = C.c_int(0)
-        self._check(lib().cnnc_merge_detections(self._h, out, C.c_int(cap), C.byref(n), _stream(stream)))
-        return list(out[:n.value])
+        self._check(lib().cnnc_merge_detections(self._h, out._pointer(), C.c_int(cap), C.byref(n), _stream(stream)))
+        return out._filled(n.value, cap)
 
-    def detect(self, frame, cap: int = 4096) -> List[Detection]:
-        out = (Detection * cap)()
+    def detect(self, frame, cap: int = 4096) -> Records:
+        out = Records(Detection, cap)
         n = C.c_int(0)
-        self._check(lib().cnnc_detect(self._h, *self._frame_args(frame), out, C.c_int(cap), C.byref(n)))
-        return list(out[:n.value])
+        self._check(lib().cnnc_detect(self._h, *self._frame_args(frame), out._pointer(), C.c_int(cap), C.byref(n)))
+        return out._filled(n.value, cap)
 
     def detect_async(self, frame, stream=None):
         self._check(lib().cnnc_detect_async(self._h, *self._frame_args(frame), _stream(stream)))
 
-    def fetch_detections(self, cap: int = 4096) -> List[Detection]:
-        out = (Detection * cap)()
+    def fetch_detections(self, cap: int = 4096) -> Records:
+        out = Records(Detection, cap)
         n = C.c_int(0)
-        self._check(lib().cnnc_fetch_detections(self._h, out, C.c_int(cap), C.byref(n)))
-        return list(out[:n.value])
+        self._check(lib().cnnc_fetch_detections(self._h, out._pointer(), C.c_int(cap), C.byref(n)))
+        return out._filled(n.value, cap)
 
     # -- views (copied to the host) -----------------------------------------------------------
     def get_pyramid(self) -> np.ndarray:
@@ -307,14 +361,14 @@ class Context:
 
     def select_fetch(self, cap: int = 65536, maps: bool = False):
         """Records of the positions that passed T_1 (list of Region); with maps=True also the two (n, 5, 5) response maps."""
-        out = (Region * cap)()
+        out = Records(Region, cap)
         n = C.c_int(0)
         m2 = np.zeros((cap, 5, 5), np.float32) if maps else None
         m3 = np.zeros((cap, 5, 5), np.float32) if maps else None
-        self._check(lib().cnnc_select_fetch(self._h, out, C.c_int(cap), C.byref(n),
+        self._check(lib().cnnc_select_fetch(self._h, out._pointer(), C.c_int(cap), C.byref(n),
                                             m2.ctypes.data_as(C.c_void_p) if maps else C.c_void_p(0),
                                             m3.ctypes.data_as(C.c_void_p) if maps else C.c_void_p(0)))
-        recs = list(out[:n.value])
+        recs = out._filled(n.value, cap)
         return (recs, m2[:n.value], m3[:n.value]) if maps else recs
 
     def select_set_rule(self, rule: int):
@@ -322,11 +376,11 @@ class Context:
 
     def select_merge(self, iou: float = 0.3, min_neighbors: int = 1, cap: int = 4096, stream=None):
         """Greedy merge of the regions the last select_run accepted (list of RegionDetection, kept order)."""
-        out = (RegionDetection * cap)()
+        out = Records(RegionDetection, cap)
         n = C.c_int(0)
-        self._check(lib().cnnc_select_merge(self._h, C.c_float(iou), C.c_int(min_neighbors), out, C.c_int(cap),
+        self._check(lib().cnnc_select_merge(self._h, C.c_float(iou), C.c_int(min_neighbors), out._pointer(), C.c_int(cap),
                                             C.byref(n), _stream(stream)))
-        return list(out[:n.value])
+        return out._filled(n.value, cap)
 
     @staticmethod
     def _paper_params(t1, t2, t3, t_nn, iou, min_neighbors):
@@ -335,11 +389,11 @@ class Context:
     def detect_paper(self, frame, t1: float, t2: float, t3: float, t_nn: int, iou: float = 0.3, min_neighbors: int = 1,
                      cap: int = 4096):
         """The whole path in the paper's geometry on one frame (list of RegionDetection, kept order)."""
-        out = (RegionDetection * cap)()
+        out = Records(RegionDetection, cap)
         n = C.c_int(0)
         p = self._paper_params(t1, t2, t3, t_nn, iou, min_neighbors)
-        self._check(lib().cnnc_detect_paper(self._h, *self._frame_args(frame), C.byref(p), out, C.c_int(cap), C.byref(n)))
-        return list(out[:n.value])
+        self._check(lib().cnnc_detect_paper(self._h, *self._frame_args(frame), C.byref(p), out._pointer(), C.c_int(cap), C.byref(n)))
+        return out._filled(n.value, cap)
 
     def detect_paper_async(self, frame, t1: float, t2: float, t3: float, t_nn: int, iou: float = 0.3, min_neighbors: int = 1,
                            stream=None):
@@ -347,10 +401,10 @@ class Context:
         self._check(lib().cnnc_detect_paper_async(self._h, *self._frame_args(frame), C.byref(p), _stream(stream)))
 
     def fetch_paper(self, cap: int = 4096):
-        out = (RegionDetection * cap)()
+        out = Records(RegionDetection, cap)
         n = C.c_int(0)
-        self._check(lib().cnnc_fetch_paper(self._h, out, C.c_int(cap), C.byref(n)))
-        return list(out[:n.value])
+        self._check(lib().cnnc_fetch_paper(self._h, out._pointer(), C.c_int(cap), C.byref(n)))
+        return out._filled(n.value, cap)
 
     def set_literal_weights(self, on: bool):
         self._check(lib().cnnc_set_literal_weights(self._h, C.c_int(1 if on else 0)))
@@ -439,11 +493,11 @@ class Pipe:
             self._check(lib().cnnc_pipe_submit(self._h, frame.ctypes.data_as(C.c_void_p), C.c_int(frame.strides[0]), C.byref(t)))
         return t.value
 
-    def fetch(self, ticket: int, cap: int = 4096) -> List[Detection]:
-        out = (Detection * cap)()
+    def fetch(self, ticket: int, cap: int = 4096) -> Records:
+        out = Records(Detection, cap)
         n = C.c_int(0)
-        self._check(lib().cnnc_pipe_fetch(self._h, C.c_int64(ticket), out, C.c_int(cap), C.byref(n)))
-        return list(out[:n.value])
+        self._check(lib().cnnc_pipe_fetch(self._h, C.c_int64(ticket), out._pointer(), C.c_int(cap), C.byref(n)))
+        return out._filled(n.value, cap)
 
     def set_paper(self, scan_weights: np.ndarray, w2: np.ndarray, w3: np.ndarray, t1: float, t2: float, t3: float, t_nn: int,
                   iou: float = 0.3, min_neighbors: int = 1, rule: int = 2, scan_act: int = 1, select_act: int = 1):
@@ -454,11 +508,11 @@ class Pipe:
                                               b.ctypes.data_as(C.c_void_p), C.c_int(b.size), c.ctypes.data_as(C.c_void_p),
                                               C.c_int(c.size), C.c_int(select_act), C.c_int(rule), C.byref(pp)))
 
-    def fetch_paper(self, ticket: int, cap: int = 4096) -> List[RegionDetection]:
-        out = (RegionDetection * cap)()
+    def fetch_paper(self, ticket: int, cap: int = 4096) -> Records:
+        out = Records(RegionDetection, cap)
         n = C.c_int(0)
-        self._check(lib().cnnc_pipe_fetch_paper(self._h, C.c_int64(ticket), out, C.c_int(cap), C.byref(n)))
-        return list(out[:n.value])
+        self._check(lib().cnnc_pipe_fetch_paper(self._h, C.c_int64(ticket), out._pointer(), C.c_int(cap), C.byref(n)))
+        return out._filled(n.value, cap)
 
 
 def cnnc_abi_sizes():

@@ -76,3 +76,26 @@ def test_struct_sizes_and_step_names_match_the_library():
     sizes = B.cnnc_abi_sizes()
     assert sizes == (C.sizeof(B._Layer), C.sizeof(B._StageDesc), C.sizeof(B._Params), C.sizeof(B.Detection),
                      C.sizeof(B.Region), len(B.STEP_NAMES), C.sizeof(B.RegionDetection))
+
+
+def test_records_view_the_memory_the_library_fills():
+    """The binding hands back what a call wrote as one block; records are made from it only when asked for."""
+    import numpy as np
+    from paper_1508_01292_amd.binding import Detection, RegionDetection, Records
+    r = Records(Detection, 64)
+    assert C.sizeof(Detection) == 32 and r._raw.size == 64 * 32
+    words = np.frombuffer(r._raw, np.int32)
+    words[:24] = np.arange(24)                        # what a C call would leave: three records
+    assert r._filled(3, 64) is r and len(r) == 3 and r._raw.size == 96          # the unused tail is given back
+    assert [d.x for d in r] == [0, 8, 16] and r[2].index == 22 and r[-1].y == 17
+    assert [d.as_dict()["neighbors"] for d in r[1:]] == [13, 21]
+    assert r.array.dtype.names[:3] == ("x", "y", "size") and list(r.array["level"]) == [4, 12, 20]
+    with pytest.raises(IndexError):
+        r[3]
+    empty = Records(RegionDetection, 0)._filled(0, 0)
+    assert len(empty) == 0 and not empty and list(empty) == []
+    assert len(Records(Detection, 4)._filled(9, 4)) == 4                         # never more than the capacity
+    assert empty == [] and r == [d.as_dict() for d in r] and r == list(r) and r != [] and r != list(r)[:2]
+    twin = Records(Detection, 3)
+    twin._raw[:] = r._raw
+    assert twin._filled(3, 3) == r
