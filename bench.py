@@ -156,7 +156,9 @@ def main():
     F = max(1, a.inflight)
     max_surv = max(32768, 1 << int(np.ceil(np.log2(2 * max(1, len(tr.idx1))))))
     ctxs = [P.Context(casc, W, cfg["width"], cfg["height"], max_surv) for _ in range(F)]
-    streams = [torch.cuda.Stream() for _ in range(F)]
+    # streams that are destroyed again before the ingest legs: a process has four hardware queues, and streams left alive
+    # (torch's are pooled and never destroyed) would make the ring's four streams share queues among themselves
+    streams = [P.Stream() for _ in range(F)]
     for c in ctxs:
         c.set_params(cfg["min_face"], cfg["scale_step"], tr.thr)
         if a.eval_impl is not None:
@@ -262,7 +264,7 @@ def main():
 
     paper = None
     if not a.no_paper_path:
-        make_pipe = None if a.no_ingest else (lambda: P.Pipe(casc, W, cfg["width"], cfg["height"], max_surv, depth=F + 1, use_graph=False))
+        make_pipe = None if a.no_ingest else (lambda: P.Pipe(casc, W, cfg["width"], cfg["height"], max_surv, depth=F + 1, use_graph=True))
         paper = paper_geometry_legs(a, ctxs, streams, dev_frame, frame, cfg, seed, tr, I, O, np, torch, time, tflops, make_pipe)
 
     kernels = {
@@ -316,6 +318,9 @@ def main():
     # frames from pinned host memory through the ingest ring: copy in + path + results out, PCIe included
     ingest = {}
     D = F + 1                                    # one slot more than frames computing: its copy runs ahead
+    torch.cuda.synchronize()
+    for s in streams:
+        s.close()
     for use_graph in (() if a.no_ingest else (False, True)):
         pipe = P.Pipe(casc, W, cfg["width"], cfg["height"], max_surv, depth=D, use_graph=use_graph)
         pipe.set_params(cfg["min_face"], cfg["scale_step"], tr.thr)
@@ -454,6 +459,9 @@ def paper_geometry_legs(a, ctxs, streams, dev_frame, frame, cfg, seed, tr, I, O,
     # the same path fed from pinned host memory through the ingest ring (PCIe included; never the headline value)
     fps_paper_ingest = None
     if make_pipe is not None:
+        torch.cuda.synchronize()
+        for s in streams:                             # see the note where they are created
+            s.close()
         pipe = make_pipe()
         pipe.set_params(cfg["min_face"], cfg["scale_step"], (0.0, 0.0, 0.0))
         pipe.set_paper(w_scan, w2_sel, w3_sel, t1_scan, t2_sel, t3_sel, 5, 0.3, 1)
@@ -492,7 +500,8 @@ def paper_geometry_legs(a, ctxs, streams, dev_frame, frame, cfg, seed, tr, I, O,
         "merge": {"detections": len(sel_det), "ms_per_call_with_wait_and_readback": ms_sel_merge},
         "whole_path_ms_per_frame_one_at_a_time": ms_paper_frame,
         "whole_path_frames_per_s_%d_in_flight" % F: 1e3 / ms_paper_inflight,
-        "whole_path_frames_per_s_from_pinned_host_memory": fps_paper_ingest}
+        "whole_path_frames_per_s_from_pinned_host_memory": fps_paper_ingest,
+        "whole_path_ingest_ring": None if make_pipe is None else {"slots": F + 1, "lanes": min(F + 1, 3), "graphs": True}}
 
 
 if __name__ == "__main__":

@@ -22,7 +22,10 @@
  *     and only lends read-only device pointers through the cnnc_get_* calls (valid until the next
  *     call that changes the frame size or parameters, or cnnc_destroy).
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Work is enqueued on
- *     it and not waited for, except where a function says it synchronises.
+ *     it and not waited for, except where a function says it synchronises.  A context remembers the
+ *     stream of its last enqueue until a call that waits for it (cnnc_merge_detections,
+ *     cnnc_fetch_detections, cnnc_detect, cnnc_survivor_count on that stream, cnnc_select_fetch,
+ *     cnnc_select_merge, cnnc_fetch_paper, cnnc_detect_paper); after such a call the stream may be destroyed.
  *   - Calls on one context must not overlap in time; use one context per stream / thread.
  *   - The flat window index g orders all stage-1 windows of a frame by (level, y, x):
  *     g = score_off[level] + y * (lvl_w[level] - 11) + x.
@@ -197,7 +200,7 @@ int cnnc_fetch_detections(cnnc_ctx *ctx, cnnc_det *out, int cap, int *n_out);
  * chunk on the caller's stream, stages 2 and 3 of a chunk start on a second stream as soon as that chunk's survivors
  * are listed, ordered by HIP events only; the merge follows the last chunk and the caller's stream then waits for it,
  * so the call keeps its contract (work enqueued, cnnc_fetch_detections waits).  Survivor lists and detections are
- * exactly those of chunks = 1.  The second stream belongs to the context (default priority).  On one GPU whose later
+ * exactly those of chunks = 1.  The second stream belongs to the context (default priority; it exists while chunks > 1: the call that sets chunks > 1 creates it, the call that sets 1 waits for it and destroys it).  On one GPU whose later
  * stages already fill the chip the overlap buys less than the extra launches and cross-stream waits cost, so 1 is
  * the default; the mode is there for cascades whose first stage dominates, as in the paper.
  * Ignored (one stream) with cnnc_set_eval_impl(0) or cnnc_set_fused_stage1(1), and inside cnnc_pipe graphs. */
@@ -337,10 +340,16 @@ int cnnc_fetch_paper(cnnc_ctx *ctx, cnnc_rdet *out, int cap, int *n_out);
 
 /* ---- Frame ingest from host memory ------------------------------------------------------------
  * The paper's detector is fed video (Section 4.2) and overlaps its stages (Section 3.4, asynchronous mode).
- * A pipe is a ring of `depth` slots (1..16); each slot owns a context, a HIP stream, a pinned host frame
- * (w * h bytes, row pitch w) and a device frame, so the host-to-device copy of one frame overlaps the kernels of
- * the others.  use_graph != 0: from a slot's second frame on, its copy + kernels + read-back run as one captured
- * HIP graph launch.  All frames of a pipe have the size given at creation.  One thread per pipe.
+ * A pipe is a ring of `depth` slots (1..16), each a pinned host frame (w * h bytes, row pitch w) and a device frame,
+ * feeding min(depth, 3) lanes, each a context with a HIP stream of its own (not synchronising with the default stream);
+ * the host-to-device copies are enqueued on the device's default stream, whose hardware queue no lane shares (work the
+ * caller puts on the default stream delays them, nothing else).  Up to `depth` frames are in flight: at most one per lane is being processed (or keeps its results in
+ * the lane's context until fetched), the others are copied in and start when a fetch frees a lane.  So with
+ * depth = lanes + 1 the copy of the next frame is hidden behind the kernels of the others (more compute streams than
+ * three share hardware queues on this GPU and lower the throughput).  use_graph != 0: from a lane's second frame on,
+ * a frame's kernels + read-back run as one captured HIP graph launch (one graph per slot and lane; the copy in front of
+ * it stays a plain asynchronous copy, which the DMA engine carries out).  All frames of a pipe have the size given at
+ * creation.  One thread per pipe.  Memory: min(depth, 3) contexts plus depth device and pinned frames.
  *
  * cnnc_pipe_frame_buffer: the pinned buffer the next submit will send (that of the free slot that has been free
  *   longest), for producers that write frames in place; valid until the next submit or fetch.  CNNC_E_STATE when
@@ -349,12 +358,14 @@ int cnnc_fetch_paper(cnnc_ctx *ctx, cnnc_rdet *out, int cap, int *n_out);
  *   host pointer: its w x h bytes (row pitch `pitch`) are copied into the buffer first.  Enqueues and returns a
  *   ticket; CNNC_E_STATE when every slot is in flight.
  * cnnc_pipe_fetch: waits for the frame with that ticket and returns its detections like cnnc_detect
- *   (CNNC_E_OVERFLOW rules included); frees the slot.  Tickets may be fetched in any order.
- * cnnc_pipe_set_params: for every slot; CNNC_E_STATE while frames are in flight.
+ *   (CNNC_E_OVERFLOW rules included); frees the slot and starts the frame that has waited longest for a lane.  Tickets
+ *   may be fetched in any order: if the frame still waits for a lane, the results of frames submitted earlier are taken
+ *   out of their lanes into host memory (and handed out when their tickets are fetched) until it has run.
+ * cnnc_pipe_set_params: for every lane; CNNC_E_STATE while frames are in flight.
  * cnnc_pipe_set_paper: from now on submit runs the path in the paper's geometry (cnnc_detect_paper_async: pyramid,
  *   27x31 scan, selective unit, merge; Section 3.3) instead of the cascade of cnnc_detect_async.  Arguments as for
  *   cnnc_scan_set_weights, cnnc_select_set_weights, cnnc_select_set_rule and cnnc_detect_paper, applied to every
- *   slot; the host arrays are copied.  CNNC_E_STATE while frames are in flight.  Results then come through
+ *   lane; the host arrays are copied.  CNNC_E_STATE while frames are in flight.  Results then come through
  *   cnnc_pipe_fetch_paper (as cnnc_fetch_paper; cnnc_pipe_fetch answers CNNC_E_STATE on such a pipe and
  *   cnnc_pipe_fetch_paper on any other). */
 typedef struct cnnc_pipe cnnc_pipe;

@@ -4,10 +4,10 @@ The work is done by hand-written HIP kernels in libcnnc.so (C ABI: include/cnnc.
 package is only the ctypes binding: it marshals arguments and never computes a step itself.
 """
 from . import binding as _b
-from .binding import (EXPORTS, STEP_NAMES, CnncError, Context, Detection, Pipe, Region, RegionDetection, lib,
+from .binding import (EXPORTS, STEP_NAMES, CnncError, Context, Detection, Pipe, Records, Region, RegionDetection, Stream, lib,
                       library_path)
 
-__all__ = ["CnncError", "Context", "Detection", "Pipe", "Region", "RegionDetection", "lib", "library_path", "EXPORTS",
+__all__ = ["CnncError", "Context", "Detection", "Pipe", "Records", "Region", "RegionDetection", "Stream", "lib", "library_path", "EXPORTS",
            "STEP_NAMES"]
 for _n in dir(_b):
     if _n.startswith("cnnc_"):

@@ -171,6 +171,35 @@ def _hiprt():
     return _hip
 
 
+class Stream:
+    """A HIP stream of default priority that does not synchronise with the null stream, for callers that want to destroy
+    their streams again: a process has few hardware queues, streams that stay alive keep their share of them, and the
+    streams of a Pipe created later then have to share queues among themselves."""
+
+    def __init__(self):
+        h = C.c_void_p(0)
+        rc = _hiprt().hipStreamCreateWithFlags(C.byref(h), C.c_uint(1))          # hipStreamNonBlocking
+        if rc != 0 or not h.value:
+            raise CnncError(-4, "hipStreamCreateWithFlags failed (%d)" % rc)
+        self.cuda_stream = h.value
+
+    def synchronize(self):
+        if self.cuda_stream and _hiprt().hipStreamSynchronize(C.c_void_p(self.cuda_stream)) != 0:
+            raise CnncError(-4, "hipStreamSynchronize failed")
+
+    def close(self):
+        if self.cuda_stream:
+            _hiprt().hipStreamSynchronize(C.c_void_p(self.cuda_stream))
+            _hiprt().hipStreamDestroy(C.c_void_p(self.cuda_stream))
+            self.cuda_stream = 0
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
 def _stream(s) -> C.c_void_p:
     if s is None:
         return C.c_void_p(0)

@@ -176,7 +176,7 @@ int prepare_layout(cnnc_ctx *c, int w, int h)
     }
 
     // buffers may be in use by work still queued on the last stream
-    HIP_TRY(c, hipStreamSynchronize(c->last_stream));
+    HIP_TRY(c, wait_last_stream(c));
     int rc;
     int64_t cap_levels = c->d_levels ? CNNC_MAX_LEVELS : 0;
     if ((rc = ensure(c, c->d_levels, cap_levels, CNNC_MAX_LEVELS))) return rc;
@@ -224,7 +224,7 @@ using Timed = cnnc::ScopedTimer;
 
 int fetch(cnnc_ctx *c, cnnc_det *out, int cap, int *n_out)
 {
-    HIP_TRY(c, hipStreamSynchronize(c->last_stream));
+    HIP_TRY(c, wait_last_stream(c));
     const Counters &k = *c->h_cnt;
     // The detections made from the (possibly truncated) lists are handed over in every case; an overflow is reported
     // after the copy, so that "contents up to the capacity are valid" holds for this call too.
@@ -349,7 +349,6 @@ int cnnc_create(cnnc_ctx **out, const cnnc_stage_desc stages[3], int max_w, int 
     }
     for (int s = 0; s < 2; ++s)
         if (hipMalloc((void **)&c->d_eval[s], sizeof(float) * (size_t)max_survivors) != hipSuccess) return bail(CNNC_E_NOMEM);
-    if (hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking) != hipSuccess) return bail(CNNC_E_HIP);
     for (int k = 0; k < kMaxLevelChunks; ++k)
         if (hipEventCreateWithFlags(&c->ev_s1[k], hipEventDisableTiming) != hipSuccess) return bail(CNNC_E_HIP);
     if (hipEventCreateWithFlags(&c->ev_done, hipEventDisableTiming) != hipSuccess) return bail(CNNC_E_HIP);
@@ -642,7 +641,19 @@ int cnnc_set_async_chunks(cnnc_ctx *c, int chunks)
 {
     if (!c) return CNNC_E_INVAL;
     if (chunks < 1 || chunks > kMaxLevelChunks) return fail(c, CNNC_E_INVAL, "chunks must be 1..8");
-    if (chunks != c->async_chunks) { c->async_chunks = chunks; c->layout_valid = false; c->progress = 0; }
+    if (chunks == c->async_chunks) return CNNC_OK;
+    // The second stream exists only while it is used: a process has few hardware queues, and every stream that is alive
+    // keeps its share of them whether it carries work or not.
+    HIP_TRY(c, wait_last_stream(c));
+    if (chunks > 1 && !c->side) HIP_TRY(c, hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking));
+    if (chunks == 1 && c->side) {
+        HIP_TRY(c, hipStreamSynchronize(c->side));
+        HIP_TRY(c, hipStreamDestroy(c->side));
+        c->side = nullptr;
+    }
+    c->async_chunks = chunks;
+    c->layout_valid = false;
+    c->progress = 0;
     return CNNC_OK;
 }
 
@@ -728,6 +739,7 @@ int cnnc_survivor_count(cnnc_ctx *c, int stage, int *n, void *stream)
     hipStream_t st = (hipStream_t)stream;
     HIP_TRY(c, hipMemcpyAsync(c->h_cnt, c->d_cnt, sizeof(Counters), hipMemcpyDeviceToHost, st));
     HIP_TRY(c, hipStreamSynchronize(st));
+    if (c->last_stream == st) c->last_stream = nullptr;
     *n = c->h_cnt->n[stage - 1];
     return *n > c->max_surv ? fail(c, CNNC_E_OVERFLOW, "survivor list truncated") : CNNC_OK;
 }
@@ -757,7 +769,7 @@ int cnnc_set_timing(cnnc_ctx *c, int on)
 int cnnc_get_timings(cnnc_ctx *c, double *ms_sum, int32_t *calls)
 {
     if (!c) return CNNC_E_INVAL;
-    HIP_TRY(c, hipStreamSynchronize(c->last_stream));
+    HIP_TRY(c, wait_last_stream(c));
     for (int s = 0; s < CNNC_T_COUNT; ++s) {
         StepTimer &t = c->timers[s];
         for (size_t i = 0; i < t.begin.size(); ++i) {

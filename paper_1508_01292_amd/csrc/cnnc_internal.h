@@ -180,7 +180,7 @@ struct cnnc_ctx {
     const uint8_t *d_frame = nullptr;
     int fw = 0, fh = 0, fpitch = 0;
     int progress = 0;                        // bit mask of completed steps for CNNC_E_STATE checks
-    hipStream_t last_stream = nullptr;
+    hipStream_t last_stream = nullptr;       // stream of the last enqueue; the default stream again once it has been waited for
 
     // asynchronous mode inside a frame: chunks of pyramid levels, stage 1 of a chunk on the caller's stream while the
     // later stages of earlier chunks run on a stream of the context, ordered by events only
@@ -247,6 +247,15 @@ struct ScopedTimer {
 int fail(cnnc_ctx *c, int code, const std::string &msg);
 int hip_fail(cnnc_ctx *c, hipError_t e, const char *what);
 int compute_levels(const cnnc_ctx *c, int w, int h, std::vector<LevelDev> &lv, int64_t &pyr_bytes, int64_t &n_windows);
+// Waits for the stream the context last enqueued on and forgets it: from then on the context holds no reference to a
+// stream of the caller, who may destroy it.
+inline hipError_t wait_last_stream(cnnc_ctx *c)
+{
+    const hipError_t e = hipStreamSynchronize(c->last_stream);
+    c->last_stream = nullptr;
+    return e;
+}
+
 void scan_release(cnnc_ctx *c);
 void select_release(cnnc_ctx *c);
 size_t eval2_frag_floats();

@@ -101,7 +101,7 @@ int cnnc_scan_set_weights(cnnc_ctx *c, const float *weights, int n_floats, int a
     if (!c) return CNNC_E_INVAL;
     if (!weights || n_floats != kScanParams) return fail(c, CNNC_E_INVAL, "the scanning network has 806 parameters");
     if (act < CNNC_ACT_RATIONAL || act > CNNC_ACT_TANH) return fail(c, CNNC_E_INVAL, "activation kind must be 1, 2 or 3");
-    HIP_TRY(c, hipStreamSynchronize(c->last_stream));            // a scan may still be reading the old weights
+    HIP_TRY(c, wait_last_stream(c));            // a scan may still be reading the old weights
     if (!c->d_scan_wt) HIP_TRY(c, hipMalloc((void **)&c->d_scan_wt, sizeof(float) * kScanParams));
     HIP_TRY(c, hipMemcpy(c->d_scan_wt, weights, sizeof(float) * kScanParams, hipMemcpyHostToDevice));
     scan_literal_destroy(c->scan_literal);
@@ -167,7 +167,7 @@ int cnnc_scan_scoremap(cnnc_ctx *c, void *stream)
         }
         if (tiles.empty()) scan_geometry(c->levels, sl, &tiles, total, side);
         c->scan_tile_side = side;
-        HIP_TRY(c, hipStreamSynchronize(c->last_stream));        // the old tables may still be in use
+        HIP_TRY(c, wait_last_stream(c));        // the old tables may still be in use
         if (!c->d_scan_levels) HIP_TRY(c, hipMalloc((void **)&c->d_scan_levels, sizeof(ScanLevel) * CNNC_MAX_LEVELS));
         if ((int64_t)tiles.size() > c->cap_scan_tiles) {
             if (c->d_scan_tiles) { HIP_TRY(c, hipFree(c->d_scan_tiles)); c->d_scan_tiles = nullptr; c->cap_scan_tiles = 0; }

@@ -123,7 +123,7 @@ int cnnc_select_set_weights(cnnc_ctx *c, const float *w2, int n2, const float *w
     if (!w2 || !w3 || n2 != kNet2Params || n3 != kNet3Params)
         return fail(c, CNNC_E_INVAL, "the selective unit's networks have 1836 and 2942 parameters");
     if (act < CNNC_ACT_RATIONAL || act > CNNC_ACT_TANH) return fail(c, CNNC_E_INVAL, "activation kind must be 1, 2 or 3");
-    HIP_TRY(c, hipStreamSynchronize(c->last_stream));
+    HIP_TRY(c, wait_last_stream(c));
     if (!c->d_sel_w2) {
         const size_t cap = (size_t)c->max_surv;
         HIP_TRY(c, hipMalloc((void **)&c->d_sel_w2, sizeof(float) * kNet2Params));
@@ -218,7 +218,7 @@ int cnnc_select_fetch(cnnc_ctx *c, cnnc_region *out, int cap, int *n_out, float 
     if (!n_out || cap < 0 || (!out && cap > 0)) return fail(c, CNNC_E_INVAL, "null output");
     if (!c->sel_done) return fail(c, CNNC_E_STATE, "cnnc_select_run has not been called for this frame");
     HIP_TRY(c, hipMemcpyAsync(c->h_sel_cnt, c->d_sel_cnt, sizeof(int32_t), hipMemcpyDeviceToHost, c->last_stream));
-    HIP_TRY(c, hipStreamSynchronize(c->last_stream));
+    HIP_TRY(c, wait_last_stream(c));
     const int total = *c->h_sel_cnt;
     *n_out = total;
     const int have = std::min(total, c->max_surv), m = std::min(have, cap);
@@ -243,7 +243,7 @@ int cnnc_select_merge(cnnc_ctx *c, float iou, int min_neighbors, cnnc_rdet *out,
     c->last_stream = st;
     HIP_TRY(c, launch_merge_regions(c, iou, min_neighbors, st));
     HIP_TRY(c, hipMemcpyAsync(c->h_sel_cnt, c->d_sel_cnt, sizeof(int32_t) * 3, hipMemcpyDeviceToHost, st));
-    HIP_TRY(c, hipStreamSynchronize(st));
+    HIP_TRY(c, wait_last_stream(c));
     *n_out = 0;
     if (c->h_sel_cnt[0] > c->max_surv) return fail(c, CNNC_E_OVERFLOW, "more positions passed T_1 than the context's survivor capacity");
     if (c->h_sel_cnt[1] > c->merge_cap) return fail(c, CNNC_E_OVERFLOW, "more regions accepted than the merge can take");
@@ -257,7 +257,7 @@ int cnnc_select_merge(cnnc_ctx *c, float iou, int min_neighbors, cnnc_rdet *out,
 // ---- the whole path in the paper's geometry: pyramid, scan, selective unit, merge (Section 3.3) ----------------
 static int paper_fetch(cnnc_ctx *c, cnnc_rdet *out, int cap, int *n_out)
 {
-    HIP_TRY(c, hipStreamSynchronize(c->last_stream));
+    HIP_TRY(c, wait_last_stream(c));
     *n_out = 0;
     if (c->h_sel_cnt[0] > c->max_surv) return fail(c, CNNC_E_OVERFLOW, "more positions passed T_1 than the context's survivor capacity");
     if (c->h_sel_cnt[1] > c->merge_cap) return fail(c, CNNC_E_OVERFLOW, "more regions accepted than the merge can take");

@@ -35,14 +35,15 @@ def test_pipe_matches_single_context_and_oracle(use_graph):
     tr5 = O.detect(frames[5], casc, W, cfg["min_face"], cfg["scale_step"], thr=tr0.thr)
     assert [(d["index"], d["neighbors"]) for d in want[5]] == [(d["index"], d["neighbors"]) for d in tr5.det]
 
-    pipe = P.Pipe(casc, W, w, h, 100000, depth=3, use_graph=use_graph)
+    # four slots on three lanes: a frame is always copied in ahead and meets every lane in turn
+    pipe = P.Pipe(casc, W, w, h, 100000, depth=4, use_graph=use_graph)
     pipe.set_params(cfg["min_face"], cfg["scale_step"], tr0.thr)
-    print("pipe graph=%s: 3 slots, 3 passes over %d frames" % (use_graph, len(frames)), flush=True)
+    print("pipe graph=%s: 4 slots, 3 passes over %d frames" % (use_graph, len(frames)), flush=True)
     got = {}
     tickets = []
     order = list(range(len(frames))) + list(reversed(range(len(frames)))) + list(range(len(frames)))
     for k, fi in enumerate(order):
-        if len(tickets) == 3:
+        if len(tickets) == 4:
             t, f0 = tickets.pop(0)
             got.setdefault(f0, []).append([d.as_dict() for d in pipe.fetch(t, 8192)])
         if k % 2:
@@ -113,6 +114,45 @@ def test_pipe_errors_and_parameter_change():
     assert e.value.code == -3
     assert len(pipe.fetch(pipe.submit(frame))) == len(tr2.det)
     pipe.close()
+
+
+@pytest.mark.parametrize("use_graph", [False, True])
+def test_pipe_more_slots_than_lanes_fetched_in_any_order(use_graph):
+    """Five slots on three lanes: two frames wait for a lane.  Asking for a waiting frame first sets the results of
+    running ones aside; they are handed out later, unchanged."""
+    import torch
+    import paper_1508_01292_amd as P
+    casc = I.default_cascade()
+    W = I.draw_weights(casc, 9)
+    frames = [I.make_frame(320, 240, 90 + k) for k in range(5)]
+    tr = O.detect(frames[0], casc, W, 24.0, 1.25)
+    ctx = P.Context(casc, W, 320, 240, 20000)
+    ctx.set_params(24.0, 1.25, tr.thr)
+    want = [[d.as_dict() for d in ctx.detect(torch.from_numpy(f).cuda(), 8192)] for f in frames]
+    assert [(d["index"], d["neighbors"]) for d in want[0]] == [(d["index"], d["neighbors"]) for d in tr.det]
+    assert len({len(x) for x in want}) > 1, "the frames must be told apart by their results"
+    pipe = P.Pipe(casc, W, 320, 240, 20000, depth=5, use_graph=use_graph)
+    pipe.set_params(24.0, 1.25, tr.thr)
+    for rnd, fetch_order in enumerate(([4, 0, 3, 1, 2], [3, 4, 2, 1, 0], [0, 1, 2, 3, 4], [2, 4, 0, 1, 3])):
+        t = [pipe.submit(f) for f in frames]
+        with pytest.raises(P.CnncError) as e:         # ring full
+            pipe.submit(frames[0])
+        assert e.value.code == -5
+        for k in fetch_order:
+            assert [d.as_dict() for d in pipe.fetch(t[k], 8192)] == want[k], "round %d frame %d" % (rnd, k)
+        with pytest.raises(P.CnncError):              # all fetched
+            pipe.fetch(t[0])
+    # a set-aside frame keeps its overflow rule: too small an array at fetch time reports it, and the slot is free again
+    t = [pipe.submit(f) for f in frames]
+    assert [d.as_dict() for d in pipe.fetch(t[4], 8192)] == want[4]
+    with pytest.raises(P.CnncError) as e:
+        pipe.fetch(t[0], cap=1)
+    assert e.value.code == -3
+    for k in (1, 2, 3):
+        assert [d.as_dict() for d in pipe.fetch(t[k], 8192)] == want[k]
+    assert [d.as_dict() for d in pipe.fetch(pipe.submit(frames[2]), 8192)] == want[2]
+    pipe.close()
+    ctx.close()
 
 
 @pytest.mark.parametrize("use_graph", [False, True])
