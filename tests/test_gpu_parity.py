@@ -343,6 +343,47 @@ def test_async_contexts_on_streams_match_synchronous_results():
         c.close()
 
 
+def test_a_context_lets_go_of_the_callers_stream_once_it_has_waited_for_it():
+    """A stream of the caller may be destroyed after a call that waits for it (fetch, merge, survivor count, the
+    synchronous calls): the context refers to it no longer, so calls that wait for earlier work, a change of frame size
+    and the end of the context all work afterwards."""
+    import paper_1508_01292_amd as P
+    torch = _torch()
+    casc = I.default_cascade()
+    W = I.draw_weights(casc, 3)
+    frames = [I.make_frame(320, 240, 30 + k) for k in range(3)]
+    ctx = _ctx(casc, W, 320, 240)
+    ctx.set_params(24, 1.25, (0.4, -0.2, 0.0))
+    dev = [torch.from_numpy(f).cuda() for f in frames]
+    want = [[d.as_dict() for d in ctx.detect(t, 8192)] for t in dev]
+    for rnd in range(2):
+        for k, t in enumerate(dev):
+            st = P.Stream()
+            ctx.detect_async(t, st)
+            got = [d.as_dict() for d in ctx.fetch_detections(8192)]
+            st.close()
+            assert st.cuda_stream == 0 and got == want[k]
+        # step by step on a stream that is gone after the count was read
+        st = P.Stream()
+        ctx.build_pyramid(dev[0], st)
+        ctx.stage1_scoremap(st)
+        ctx.compact_survivors(1, 0.4, st)
+        n1 = ctx.survivor_count(1, st)
+        st.close()
+        assert n1 > 0
+        ctx.set_timing(True)
+        ctx.get_timings()                                 # waits for "the last stream"
+        ctx.set_timing(False)
+        small = I.make_frame(200, 150, 5)                 # another frame size: buffers are rebuilt after a wait
+        assert len(ctx.detect(torch.from_numpy(small).cuda(), 8192)) >= 0
+        assert [d.as_dict() for d in ctx.detect(dev[1], 8192)] == want[1]
+    st = P.Stream()
+    ctx.detect_async(dev[2], st)
+    assert [d.as_dict() for d in ctx.fetch_detections(8192)] == want[2]
+    st.close()
+    ctx.close()
+
+
 def test_fhd_stream_three_survival_quantiles_async():
     """The 16-frame 1920x1080 stream (0..200 ellipses per frame), thresholds pooled over the stream at three
     stage-1 survival quantiles, frames in flight on three streams.  Every frame's detections are compared with
