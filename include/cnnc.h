@@ -251,10 +251,9 @@ int cnnc_set_eval_impl(cnnc_ctx *ctx, int impl);
  * cnnc_get_scan_scoremap: device view of that map and its length.
  * cnnc_scan_set_tile: the scan kernel has two builds, a workgroup per 8 x 8 or per 16 x 16 tile of responses (the
  *   larger tile computes less of the border that neighbouring tiles compute again; the smaller one gives more workgroups
- *   on a small frame).  side = 0 (the default): chosen from the frame, 16 when that gives at least 512 tiles; 8 or 16:
- *   that build.  The responses of the two builds may differ in the last bits (the eleven maps of the output layer are
- *   summed in four or in two groups).  Anything else: CNNC_E_INVAL.  cnnc_scan_tile returns the side the last
- *   cnnc_scan_scoremap used (0 before the first). */
+ *   on a small frame).  side = 0 (the default): chosen from the frame, 16 when that gives at least 128 tiles; 8 or 16:
+ *   that build.  Both builds sum every response in the same order and give the same bits.  Anything else:
+ *   CNNC_E_INVAL.  cnnc_scan_tile returns the side the last cnnc_scan_scoremap used (0 before the first). */
 int cnnc_scan_set_weights(cnnc_ctx *ctx, const float *weights, int n_floats, int act);
 int cnnc_scan_layout(cnnc_ctx *ctx, int w, int h, int *n_levels, int32_t *out_w, int32_t *out_h, int64_t *out_off);
 int cnnc_scan_scoremap(cnnc_ctx *ctx, void *stream);
