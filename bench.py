@@ -10,7 +10,8 @@ already resident in device memory.  Prints ONE JSON line.
 Every timed leg is preceded by an untimed, time-based pre-warm of the same loop (--prewarm seconds) so that a short
 run (--steps 20) measures the same state of the GPU as a long one; the W warm-up steps follow it and the K timed
 steps are bracketed by device synchronisation.  The headline is timed twice over exactly K steps, with F frames in
-flight on F contexts / streams and one frame at a time; `value` is the faster and both are reported.
+flight on F contexts / streams (with plain launches, and through the ring with one captured graph per frame) and one frame at
+a time; `value` is the fastest and all are reported.
 """
 import argparse
 import json
@@ -212,7 +213,26 @@ def main():
     el_serial, n_det_serial = timed_leg(run_serial, 4)
     assert n_det == n_det_serial
     fps_inflight, fps_serial = a.steps / el_inflight, a.steps / el_serial
-    elapsed = min(el_inflight, el_serial)
+    # the same F frames in flight, resident in device memory, through the ring (cnnc_pipe_submit_device): a frame is one
+    # captured graph launch instead of sixteen or more launches, which counts where the host's calls are the limit
+    ring = P.Pipe(casc, W, cfg["width"], cfg["height"], max_surv, depth=F, use_graph=True)
+    ring.set_params(cfg["min_face"], cfg["scale_step"], tr.thr)
+
+    def run_ring(n_steps):
+        q, n = [], 0
+        for i in range(n_steps):
+            if len(q) == F:
+                n = len(ring.fetch(q.pop(0), 8192))
+            q.append(ring.submit_device(dev_frames[i % len(dev_frames)]))
+        for t in q:
+            n = len(ring.fetch(t, 8192))
+        return n
+
+    el_ring, n_det_ring = timed_leg(run_ring, 4 * F)
+    assert n_det_ring == n_det
+    ring.close()
+    fps_ring = a.steps / el_ring
+    elapsed = min(el_inflight, el_serial, el_ring)
     fps = a.steps / elapsed
     latency_ms = el_serial / a.steps * 1e3
     # asynchronous mode inside a frame: stage 1 of the next chunk of pyramid levels overlaps stages 2-3 of the last one
@@ -352,10 +372,13 @@ def main():
         "config": {"workload": "%s: %d %dx%d uint8 frame(s), min face %g px, scale step %g, %g%% / 20%% survival quantiles, T3 = 0"
                                % (cfg["name"], len(frames), cfg["width"], cfg["height"], cfg["min_face"], cfg["scale_step"],
                                   100 * a.q1),
-                   "frames_in_flight": F if el_inflight <= el_serial else 1, "windows": n_windows,
+                   "frames_in_flight": 1 if el_serial <= min(el_inflight, el_ring) else F,
+                   "launches": "one at a time" if el_serial <= min(el_inflight, el_ring) else
+                               ("one captured graph per frame" if el_ring < el_inflight else "plain launches"),
+                   "windows": n_windows,
                    "survivors": [n1, n2, n3], "detections": n_det, "prewarm_s": a.prewarm,
                    "stage1_weights": "instruction literals" if c0.literal_weights() else "memory"},
-        "frames_per_s": {"in_flight_%d" % F: fps_inflight, "one_at_a_time": fps_serial},
+        "frames_per_s": {"in_flight_%d" % F: fps_inflight, "in_flight_%d_graphs" % F: fps_ring, "one_at_a_time": fps_serial},
         "stage1_windows_per_s": n_windows / (ms["stage1"] * 1e-3) if ms["stage1"] > 0 else None,
         "latency_ms_single_frame": latency_ms,
         "latency_ms_per_frame_of_stream": per_frame,

@@ -356,6 +356,11 @@ int cnnc_fetch_paper(cnnc_ctx *ctx, cnnc_rdet *out, int cap, int *n_out);
  * cnnc_pipe_submit: h_frame = NULL or the pointer from cnnc_pipe_frame_buffer: send the buffer as it is; any other
  *   host pointer: its w x h bytes (row pitch `pitch`) are copied into the buffer first.  Enqueues and returns a
  *   ticket; CNNC_E_STATE when every slot is in flight.
+ * cnnc_pipe_submit_device: the same for a frame that is in device memory already (w x h bytes, row pitch `pitch`):
+ *   nothing is copied.  The frame must be complete when the call is made (written by work the caller has waited
+ *   for) and stay unchanged until its ticket is fetched; it takes a slot like any other frame.  With use_graph the path
+ *   is captured per (frame address, pitch, lane) and replayed whenever that address comes again (48 such graphs are
+ *   kept; frames at further addresses run without one).
  * cnnc_pipe_fetch: waits for the frame with that ticket and returns its detections like cnnc_detect
  *   (CNNC_E_OVERFLOW rules included); frees the slot and starts the frame that has waited longest for a lane.  Tickets
  *   may be fetched in any order: if the frame still waits for a lane, the results of frames submitted earlier are taken
@@ -374,6 +379,7 @@ int cnnc_pipe_destroy(cnnc_pipe *pipe);
 int cnnc_pipe_set_params(cnnc_pipe *pipe, const cnnc_params *p);
 int cnnc_pipe_frame_buffer(cnnc_pipe *pipe, uint8_t **h_frame);
 int cnnc_pipe_submit(cnnc_pipe *pipe, const uint8_t *h_frame, int pitch, int64_t *ticket);
+int cnnc_pipe_submit_device(cnnc_pipe *pipe, const uint8_t *d_frame, int pitch, int64_t *ticket);
 int cnnc_pipe_fetch(cnnc_pipe *pipe, int64_t ticket, cnnc_det *out, int cap, int *n_out);
 int cnnc_pipe_set_paper(cnnc_pipe *pipe, const float *scan_weights, int n_scan, int scan_act, const float *w2, int n2,
                         const float *w3, int n3, int select_act, int rule, const cnnc_paper_params *p);

@@ -24,7 +24,7 @@ EXPORTS = [
     "cnnc_scan_set_weights", "cnnc_scan_layout", "cnnc_scan_scoremap", "cnnc_get_scan_scoremap", "cnnc_scan_set_tile", "cnnc_scan_tile",
     "cnnc_select_set_weights", "cnnc_select_set_rule", "cnnc_select_run", "cnnc_select_fetch", "cnnc_select_merge", "cnnc_abi_sizes",
     "cnnc_detect_paper", "cnnc_detect_paper_async", "cnnc_fetch_paper",
-    "cnnc_pipe_create", "cnnc_pipe_destroy", "cnnc_pipe_set_params", "cnnc_pipe_frame_buffer", "cnnc_pipe_submit",
+    "cnnc_pipe_create", "cnnc_pipe_destroy", "cnnc_pipe_set_params", "cnnc_pipe_frame_buffer", "cnnc_pipe_submit", "cnnc_pipe_submit_device",
     "cnnc_pipe_fetch", "cnnc_pipe_set_paper", "cnnc_pipe_fetch_paper", "cnnc_pipe_last_error",
 ]
 STEP_NAMES = ["pyramid", "stage1", "compact1", "stage2", "compact2", "stage3", "compact3", "merge",
@@ -478,6 +478,7 @@ class Pipe:
     def __init__(self, cascade, weights, w: int, h: int, max_survivors: int, depth: int = 3, use_graph: bool = True):
         self._h = C.c_void_p(0)
         self._keep = []
+        self._frames = {}            # device frames of tickets not fetched yet (kept alive for the library)
         self.w, self.h, self.depth = w, h, depth
         rc = lib().cnnc_pipe_create(C.byref(self._h), _stage_descs(cascade, weights, self._keep), C.c_int(w), C.c_int(h),
                                     C.c_int(max_survivors), C.c_int(depth), C.c_int(1 if use_graph else 0))
@@ -522,7 +523,19 @@ class Pipe:
             self._check(lib().cnnc_pipe_submit(self._h, frame.ctypes.data_as(C.c_void_p), C.c_int(frame.strides[0]), C.byref(t)))
         return t.value
 
+    def submit_device(self, frame) -> int:
+        """A frame that is on the device already (2-D uint8 tensor of the pipe's size): nothing is copied.  The caller
+        keeps it alive and unchanged until its ticket is fetched."""
+        if frame.dtype.__str__() != "torch.uint8" or frame.dim() != 2 or not frame.is_cuda or frame.stride(1) != 1 or \
+                tuple(frame.shape) != (self.h, self.w):
+            raise ValueError("frame must be a 2-D uint8 device tensor of the pipe's size with unit column stride")
+        t = C.c_int64(0)
+        self._check(lib().cnnc_pipe_submit_device(self._h, C.c_void_p(frame.data_ptr()), C.c_int(frame.stride(0)), C.byref(t)))
+        self._frames[t.value] = frame
+        return t.value
+
     def fetch(self, ticket: int, cap: int = 4096) -> Records:
+        self._frames.pop(ticket, None)
         out = Records(Detection, cap)
         n = C.c_int(0)
         self._check(lib().cnnc_pipe_fetch(self._h, C.c_int64(ticket), out._pointer(), C.c_int(cap), C.byref(n)))
@@ -538,6 +551,7 @@ class Pipe:
                                               C.c_int(c.size), C.c_int(select_act), C.c_int(rule), C.byref(pp)))
 
     def fetch_paper(self, ticket: int, cap: int = 4096) -> Records:
+        self._frames.pop(ticket, None)
         out = Records(RegionDetection, cap)
         n = C.c_int(0)
         self._check(lib().cnnc_pipe_fetch_paper(self._h, C.c_int64(ticket), out._pointer(), C.c_int(cap), C.byref(n)))

@@ -40,6 +40,8 @@ struct Slot {
     hipEvent_t copied = nullptr;  // the frame has arrived in d_frame
     hipGraph_t graph[kLanes] = {};         // the path on this slot's device frame, captured on each lane's stream
     hipGraphExec_t exec[kLanes] = {};
+    const uint8_t *ext_frame = nullptr;    // a frame of the caller's that is on the device already (cnnc_pipe_submit_device)
+    int ext_pitch = 0;
     SlotState state = FREE;
     int lane = -1;                // while RUNNING
     int64_t ticket = -1;
@@ -48,6 +50,15 @@ struct Slot {
     int held_n = 0, held_rc = CNNC_OK;
     std::string held_err;
 };
+
+// The path on a device frame of the caller's, captured per frame address and lane.
+struct FrameGraph {
+    const uint8_t *d_frame = nullptr;
+    int pitch = 0, lane = 0;
+    hipGraph_t graph = nullptr;
+    hipGraphExec_t exec = nullptr;
+};
+constexpr size_t kMaxFrameGraphs = 48;       // (address, lane) pairs beyond that many run without a graph
 
 struct Lane {
     cnnc_ctx *ctx = nullptr;
@@ -62,6 +73,7 @@ struct cnnc_pipe {
     std::vector<Slot> slots;
     std::vector<Lane> lanes;
     std::vector<int> waiting;      // slots whose frames are copied in (or on their way) and wait for a lane, in submit order
+    std::vector<FrameGraph> frame_graphs;
     int w = 0, h = 0;
     bool use_graph = false;
     bool paper = false;            // submit runs the path in the paper's geometry (cnnc_pipe_set_paper)
@@ -101,6 +113,15 @@ bool in_flight(const cnnc_pipe *p)
     return false;
 }
 
+void drop_frame_graphs(cnnc_pipe *p)
+{
+    for (FrameGraph &g : p->frame_graphs) {
+        if (g.exec) (void)hipGraphExecDestroy(g.exec);
+        if (g.graph) (void)hipGraphDestroy(g.graph);
+    }
+    p->frame_graphs.clear();
+}
+
 void drop_graphs(Slot &s)
 {
     for (int l = 0; l < kLanes; ++l) {
@@ -112,8 +133,10 @@ void drop_graphs(Slot &s)
 // The whole path + results out for the frame in slot s, on the lane's stream.
 int enqueue_path(cnnc_pipe *p, Lane &l, Slot &s)
 {
-    const int rc = p->paper ? cnnc_detect_paper_async(l.ctx, s.d_frame, p->w, p->h, p->w, &p->pp, l.st)
-                            : cnnc_detect_async(l.ctx, s.d_frame, p->w, p->h, p->w, l.st);
+    const uint8_t *frame = s.ext_frame ? s.ext_frame : s.d_frame;
+    const int pitch = s.ext_frame ? s.ext_pitch : p->w;
+    const int rc = p->paper ? cnnc_detect_paper_async(l.ctx, frame, p->w, p->h, pitch, &p->pp, l.st)
+                            : cnnc_detect_async(l.ctx, frame, p->w, p->h, pitch, l.st);
     if (rc) return pfail(p, rc, std::string("detect: ") + cnnc_last_error(l.ctx));
     return CNNC_OK;
 }
@@ -126,28 +149,44 @@ int dispatch(cnnc_pipe *p)
         if (l.running >= 0) continue;
         const int si = p->waiting.front();
         Slot &s = p->slots[(size_t)si];
-        PIPE_HIP(p, hipStreamWaitEvent(l.st, s.copied, 0));
+        if (!s.ext_frame) PIPE_HIP(p, hipStreamWaitEvent(l.st, s.copied, 0));
         int rc = CNNC_OK;
-        if (!p->use_graph || l.runs == 0) {
-            // eager; a lane's first frame always is, so that every table and buffer exists before a capture
+        hipGraphExec_t *exec = &s.exec[li];
+        hipGraph_t *graph = &s.graph[li];
+        bool eager = !p->use_graph || l.runs == 0;               // a lane's first frame always is, so that every table and
+                                                                 // buffer exists before a capture
+        if (!eager && s.ext_frame) {                             // graphs of the caller's frames: by address and lane
+            FrameGraph *fg = nullptr;
+            for (FrameGraph &g : p->frame_graphs)
+                if (g.d_frame == s.ext_frame && g.pitch == s.ext_pitch && g.lane == (int)li) fg = &g;
+            if (!fg && p->frame_graphs.size() < kMaxFrameGraphs) {
+                FrameGraph g;
+                g.d_frame = s.ext_frame; g.pitch = s.ext_pitch; g.lane = (int)li;
+                p->frame_graphs.push_back(g);
+                fg = &p->frame_graphs.back();
+            }
+            if (fg) { exec = &fg->exec; graph = &fg->graph; }
+            else eager = true;                                   // more frame addresses than graphs are kept for
+        }
+        if (eager) {
             rc = enqueue_path(p, l, s);
         } else {
-            if (!s.exec[li]) {
+            if (!*exec) {
                 PIPE_HIP(p, hipStreamBeginCapture(l.st, hipStreamCaptureModeThreadLocal));
                 rc = enqueue_path(p, l, s);
                 hipGraph_t g = nullptr;
                 const hipError_t e = hipStreamEndCapture(l.st, &g);
                 if (rc == CNNC_OK && e != hipSuccess) rc = pfail(p, CNNC_E_HIP, std::string("hipStreamEndCapture: ") + hipGetErrorString(e));
                 if (rc) { if (g) (void)hipGraphDestroy(g); return rc; }
-                const hipError_t ei = hipGraphInstantiate(&s.exec[li], g, nullptr, nullptr, 0);
+                const hipError_t ei = hipGraphInstantiate(exec, g, nullptr, nullptr, 0);
                 if (ei != hipSuccess) {
                     (void)hipGraphDestroy(g);
-                    s.exec[li] = nullptr;
+                    *exec = nullptr;
                     return pfail(p, CNNC_E_HIP, std::string("hipGraphInstantiate: ") + hipGetErrorString(ei));
                 }
-                s.graph[li] = g;
+                *graph = g;
             }
-            PIPE_HIP(p, hipGraphLaunch(s.exec[li], l.st));
+            PIPE_HIP(p, hipGraphLaunch(*exec, l.st));
             l.ctx->last_stream = l.st;                           // what the captured calls would have noted: the fetch waits for it
         }
         if (rc) return rc;
@@ -227,6 +266,7 @@ int cnnc_pipe_destroy(cnnc_pipe *p)
         if (s.copied && s.state != FREE) (void)hipEventSynchronize(s.copied);      // a copy may still be reading the pinned frame
     for (Lane &l : p->lanes)
         if (l.st) (void)hipStreamSynchronize(l.st);
+    drop_frame_graphs(p);
     for (Slot &s : p->slots) {
         drop_graphs(s);
         if (s.copied) (void)hipEventDestroy(s.copied);
@@ -279,6 +319,7 @@ int cnnc_pipe_set_params(cnnc_pipe *p, const cnnc_params *prm)
         l.runs = 0;
     }
     for (Slot &s : p->slots) drop_graphs(s);       // thresholds and geometry are baked into the captured launches
+    drop_frame_graphs(p);
     return CNNC_OK;
 }
 
@@ -295,6 +336,7 @@ int cnnc_pipe_set_paper(cnnc_pipe *p, const float *scan_w, int n_scan, int scan_
         l.runs = 0;
     }
     for (Slot &s : p->slots) drop_graphs(s);       // another sequence of launches; thresholds are baked into a captured one
+    drop_frame_graphs(p);
     p->pp = *pp;
     p->paper = true;
     return CNNC_OK;
@@ -309,6 +351,22 @@ int cnnc_pipe_frame_buffer(cnnc_pipe *p, uint8_t **h_frame)
     return CNNC_OK;
 }
 
+// The slot joins the frames that wait for a lane and gets its ticket; a free lane takes it at once.
+static int enter_ring(cnnc_pipe *p, Slot &s, int64_t *ticket)
+{
+    const int si = (int)(&s - p->slots.data());
+    p->waiting.push_back(si);
+    s.state = WAITING;
+    s.ticket = p->next_ticket++;
+    *ticket = s.ticket;
+    const int rc = dispatch(p);
+    if (rc && s.state == WAITING) {                              // could not be started: the slot is free again
+        p->waiting.erase(std::find(p->waiting.begin(), p->waiting.end(), si));
+        s.state = FREE;
+    }
+    return rc;
+}
+
 int cnnc_pipe_submit(cnnc_pipe *p, const uint8_t *h_frame, int pitch, int64_t *ticket)
 {
     if (!p || !ticket) return CNNC_E_INVAL;
@@ -321,16 +379,19 @@ int cnnc_pipe_submit(cnnc_pipe *p, const uint8_t *h_frame, int pitch, int64_t *t
     }
     PIPE_HIP(p, hipMemcpyAsync(s.d_frame, s.h_frame, (size_t)p->w * p->h, hipMemcpyHostToDevice, kCopyStream));
     PIPE_HIP(p, hipEventRecord(s.copied, kCopyStream));
-    p->waiting.push_back((int)(fs - p->slots.data()));
-    s.state = WAITING;
-    s.ticket = p->next_ticket++;
-    *ticket = s.ticket;
-    const int rc = dispatch(p);
-    if (rc && s.state == WAITING) {                              // could not be started: the slot is free again
-        p->waiting.erase(std::find(p->waiting.begin(), p->waiting.end(), (int)(fs - p->slots.data())));
-        s.state = FREE;
-    }
-    return rc;
+    s.ext_frame = nullptr;
+    return enter_ring(p, s, ticket);
+}
+
+int cnnc_pipe_submit_device(cnnc_pipe *p, const uint8_t *d_frame, int pitch, int64_t *ticket)
+{
+    if (!p || !ticket) return CNNC_E_INVAL;
+    if (!d_frame || pitch < p->w) return pfail(p, CNNC_E_INVAL, "null frame or pitch < width");
+    Slot *fs = free_slot(p);
+    if (!fs) return pfail(p, CNNC_E_STATE, "every slot is in flight: fetch a frame first");
+    fs->ext_frame = d_frame;
+    fs->ext_pitch = pitch;
+    return enter_ring(p, *fs, ticket);
 }
 
 int cnnc_pipe_fetch(cnnc_pipe *p, int64_t ticket, cnnc_det *out, int cap, int *n_out)

@@ -142,6 +142,22 @@ def test_pipe_more_slots_than_lanes_fetched_in_any_order(use_graph):
             assert [d.as_dict() for d in pipe.fetch(t[k], 8192)] == want[k], "round %d frame %d" % (rnd, k)
         with pytest.raises(P.CnncError):              # all fetched
             pipe.fetch(t[0])
+    # frames that are on the device already go through the same ring without a copy (graphs by frame address and lane),
+    # mixed with frames from host memory
+    import torch
+    dev = [torch.from_numpy(f).cuda() for f in frames]
+    wide = torch.zeros((240, 384), dtype=torch.uint8, device="cuda")       # a frame with a row pitch of its own
+    wide[:, :320] = dev[1]
+    torch.cuda.synchronize()
+    for rnd in range(3):
+        t = [pipe.submit_device(dev[0]), pipe.submit(frames[3]), pipe.submit_device(wide[:, :320]), pipe.submit_device(dev[2]),
+             pipe.submit_device(dev[0])]
+        for k, fi in ((3, 2), (0, 0), (4, 0), (1, 3), (2, 1)):
+            assert [d.as_dict() for d in pipe.fetch(t[k], 8192)] == want[fi], "device frames, round %d ticket %d" % (rnd, k)
+    with pytest.raises(ValueError):
+        pipe.submit_device(dev[0][:-1])
+    with pytest.raises(ValueError):
+        pipe.submit_device(dev[0].cpu())
     # a set-aside frame keeps its overflow rule: too small an array at fetch time reports it, and the slot is free again
     t = [pipe.submit(f) for f in frames]
     assert [d.as_dict() for d in pipe.fetch(t[4], 8192)] == want[4]
