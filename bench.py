@@ -221,7 +221,7 @@ def main():
     def run_ring(n_steps):
         q, n = [], 0
         for i in range(n_steps):
-            if len(q) == F:
+            if len(q) == ring.depth:
                 n = len(ring.fetch(q.pop(0), 8192))
             q.append(ring.submit_device(dev_frames[i % len(dev_frames)]))
         for t in q:
