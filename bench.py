@@ -480,7 +480,7 @@ def paper_geometry_legs(a, ctxs, streams, dev_frame, frame, cfg, seed, tr, I, O,
     torch.cuda.synchronize()
     ms_paper_inflight = (time.perf_counter() - t0) / n_fly * 1e3
     # the same path fed from pinned host memory through the ingest ring (PCIe included; never the headline value)
-    fps_paper_ingest = None
+    fps_paper_ingest = fps_paper_ring = None
     if make_pipe is not None:
         torch.cuda.synchronize()
         for s in streams:                             # see the note where they are created
@@ -506,6 +506,20 @@ def paper_geometry_legs(a, ctxs, streams, dev_frame, frame, cfg, seed, tr, I, O,
         n_pipe_det = run_pipe(n_fly)
         fps_paper_ingest = n_fly / (time.perf_counter() - t0)
         assert n_pipe_det == n_paper_det
+
+        def run_pipe_resident(n_steps):               # the same ring fed with the frame that is on the device already
+            q = []
+            for _ in range(n_steps):
+                if len(q) == D:
+                    pipe.fetch_paper(q.pop(0), 32768)
+                q.append(pipe.submit_device(dev_frame))
+            return [len(pipe.fetch_paper(t, 32768)) for t in q][-1]
+
+        run_pipe_resident(D if few else 10 * D)
+        t0 = time.perf_counter()
+        n_pipe_det = run_pipe_resident(n_fly)
+        fps_paper_ring = n_fly / (time.perf_counter() - t0)
+        assert n_pipe_det == n_paper_det
         pipe.close()
     sel_flop = 2.0 * sum(2 * SEL_MAC_CNN2 + (2 * SEL_MAC_CNN3 if r.k2 > 0 else 0) for r in sel)
     c0.detect(dev_frame, 8192)           # leaves the context with the cascade's own survivor lists again
@@ -523,6 +537,7 @@ def paper_geometry_legs(a, ctxs, streams, dev_frame, frame, cfg, seed, tr, I, O,
         "merge": {"detections": len(sel_det), "ms_per_call_with_wait_and_readback": ms_sel_merge},
         "whole_path_ms_per_frame_one_at_a_time": ms_paper_frame,
         "whole_path_frames_per_s_%d_in_flight" % F: 1e3 / ms_paper_inflight,
+        "whole_path_frames_per_s_3_in_flight_graphs": fps_paper_ring,
         "whole_path_frames_per_s_from_pinned_host_memory": fps_paper_ingest,
         "whole_path_ingest_ring": None if make_pipe is None else {"slots": F + 1, "lanes": min(F + 1, 3), "graphs": True}}
 
